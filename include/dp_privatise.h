@@ -1,0 +1,182 @@
+/*
+ * dp_privatise.h -- C ABI of the MI355X (gfx950) DPSGD gradient-privatisation library.
+ *
+ * What it computes (NanoBatch Privacy, arxiv 2109.12191, Section 2, first equation):
+ *
+ *     g_t = 1/|B| * ( N(0, sigma^2 C^2 I) + sum_{x_j in B} clip(grad L(theta, x_j), C) )
+ *
+ * with clip(g, C) = g * min(1, C / ||g||_2), the sum accumulated over micro-steps
+ * (Section 2, gradient accumulation), and optionally one bound C_g = C / sqrt(M) per group
+ * of parameter tensors instead of one global bound (Section 3.5).
+ *
+ * The path is split into the calls below; a caller runs, per micro-step,
+ *   dp_per_example_grad  (per layer)      -> per-example, per-layer squared norms
+ *   dp_norms                              -> per-example, per-group squared norms
+ *   dp_clip_accumulate[_recompute] (per layer) -> acc += sum_i f_i * g_i
+ * and once per optimiser step, per parameter tensor,
+ *   dp_add_noise_finalize                 -> (acc + sigma*C*z) / |B|
+ *
+ * Conventions shared by every entry point
+ *   - Pointers marked [device] are device memory owned by the caller, valid until the
+ *     stream has executed the enqueued work.  Activations, gradients, accumulators, outputs
+ *     and workspaces must be 16-byte aligned; the small per-example vectors (squared norms,
+ *     factors, group ids, raw random words) need 4-byte alignment only.  Pointers marked [host] are
+ *     read before the call returns.  The library allocates, frees and synchronises nothing
+ *     and never changes the current device.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously; calls return at once.
+ *   - Every argument is validated on the host before anything is launched.  On error no
+ *     work is enqueued, the code says why, and dp_last_error() gives a sentence
+ *     (thread-local).  Nothing aborts or throws.
+ *   - Parameter-gradient tensors use the framework layout: conv [cout, cin, kh, kw],
+ *     dense [out, in], GroupNorm scale/shift [c]; fp32.
+ *   - Activations x and output gradients dy: NCHW ([n, c, h, w]) for conv / GroupNorm,
+ *     [n, tokens, features] for dense; fp32 or bf16 (dp_dtype).  All arithmetic
+ *     accumulates in fp32.
+ */
+#ifndef DP_PRIVATISE_H
+#define DP_PRIVATISE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DP_OK = 0,
+    DP_ERR_INVALID_ARG = 1,   /* null / misaligned pointer, non-positive size, NaN, C <= 0, sigma < 0 ... */
+    DP_ERR_UNSUPPORTED = 2,   /* a layout, dtype or layer geometry this build has no kernel for          */
+    DP_ERR_WORKSPACE = 3,     /* workspace missing or smaller than dp_workspace_bytes()                   */
+    DP_ERR_DEVICE = 4         /* the HIP runtime refused a launch                                         */
+} dp_status;
+
+typedef enum { DP_DENSE = 0, DP_CONV2D = 1, DP_GN_AFFINE = 2 } dp_kind;
+typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
+typedef enum { DP_NCHW = 0, DP_NHWC = 1 } dp_layout;   /* DP_NHWC: DP_ERR_UNSUPPORTED in this build */
+
+/* One parameterised layer and the micro-batch it is evaluated on.
+ *   dense     : x [n, h, cin], dy [n, h, cout]; h = tokens per example, w = 1
+ *   conv2d    : x [n, cin, h, w], dy [n, cout, oh, ow], oh = (h + 2 pad - kh)/stride + 1;
+ *               cross-correlation, zero padding, dilation 1, groups 1
+ *   gn_affine : x [n, cin, h, w] is the input of the GroupNorm (before normalisation),
+ *               dy [n, cin, h, w]; cout == cin; statistics per (example, group) over
+ *               (cin/gn_groups)*h*w elements, biased variance, xhat = (x-mean)/sqrt(var+eps);
+ *               the "weight" is the scale gamma, the "bias" the shift beta (always present). */
+typedef struct dp_layer_desc {
+    int kind;        /* dp_kind   */
+    int in_dtype;    /* dp_dtype of x and dy */
+    int layout;      /* dp_layout */
+    int n;           /* examples in this micro-step, >= 1 */
+    int cin, cout, h, w;
+    int kh, kw, stride, pad;     /* conv2d only; ignored otherwise */
+    int has_bias;                /* conv2d / dense */
+    int gn_groups;               /* gn_affine only */
+    float gn_eps;                /* gn_affine only */
+} dp_layer_desc;
+
+typedef void *dp_stream;   /* a hipStream_t */
+
+/* Which call a workspace is sized for. */
+typedef enum { DP_WS_PER_EXAMPLE_GRAD = 0, DP_WS_RECOMPUTE = 1 } dp_ws_use;
+
+/* Number of weight / bias parameters of a layer (0 on a bad descriptor).  Pure host. */
+size_t dp_weight_count(const dp_layer_desc *desc /*[host]*/);
+size_t dp_bias_count(const dp_layer_desc *desc /*[host]*/);
+
+/* Bytes of device workspace the given call needs for this descriptor (pure host; 0 on a
+ * bad descriptor).  DP_WS_PER_EXAMPLE_GRAD: one float per (example, output tile).
+ * DP_WS_RECOMPUTE: up to a few copies of the layer's parameter tensor when the examples are
+ * cut into ranges to fill the chip, plus n*2*cin floats for GroupNorm layers.  The workspace
+ * carries partial sums so that reductions run in a fixed order: the same inputs give the
+ * same bits on every call.                                                                   */
+size_t dp_workspace_bytes(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_use*/);
+
+/* H1 (+ the layer's share of H2): per-example weight gradients of one layer
+ * (Section 2: "per-example gradients are computed"), from each example's input activation
+ * and output gradient:
+ *   conv   dW_i[co,ci,kh,kw] = sum_{oh,ow} dY_i[co,oh,ow] * Xpad_i[ci, oh*s+kh-p, ow*s+kw-p]
+ *          db_i[co] = sum_{oh,ow} dY_i[co,oh,ow]
+ *   dense  dW_i[o,k] = sum_t dY_i[t,o] * X_i[t,k];   db_i[o] = sum_t dY_i[t,o]
+ *   gn     dgamma_i[c] = sum_{h,w} dY_i[c,h,w] * xhat_i[c,h,w];  dbeta_i[c] = sum dY_i[c,h,w]
+ * x, dy      [device] inputs as described by desc.
+ * g_w        [device] fp32, example i's weight gradient at g_w + i*stride_w, overwritten;
+ *            NULL = do not materialise (norms only).
+ * g_b        [device] fp32, example i's bias gradient at g_b + i*stride_b, overwritten; must be
+ *            given exactly when g_w is given and the layer has a bias.
+ * g_stride   elements between consecutive examples' rows in g_w and in g_b; 0 means packed
+ *            (stride_w = dp_weight_count, stride_b = dp_bias_count).  A non-zero value lets
+ *            all tensors of a model share one [n, P_total] matrix; it must be a multiple of 4
+ *            and at least the tensor's size.
+ * sqnorm     [device] [n] fp32, overwritten with ||dW_i||^2 + ||db_i||^2, reduced inside the
+ *            contraction's epilogue (the gradients are not read back); may be NULL only if
+ *            g_w is given.
+ * ws         [device] workspace of at least dp_workspace_bytes(desc, DP_WS_PER_EXAMPLE_GRAD).  */
+dp_status dp_per_example_grad(const dp_layer_desc *desc /*[host]*/, const void *x, const void *dy,
+                              float *g_w, float *g_b, size_t g_stride, float *sqnorm,
+                              void *ws, size_t ws_bytes, dp_stream stream);
+
+/* H2: per-example squared norms per clipping group (Section 2: one global norm;
+ * Section 3.5: one norm per group):
+ *   group_sqnorm[g, i] = sum over layers l with group_of_layer[l] == g of layer_sqnorm[l, i],
+ * summed in increasing l.
+ * layer_sqnorm   [device] [n_layers, n] fp32
+ * group_of_layer [device] [n_layers] int32, each in [0, n_groups) (not checked on the host;
+ *                out-of-range entries are ignored by the kernel)
+ * group_sqnorm   [device] [n_groups, n] fp32, overwritten                                    */
+dp_status dp_norms(const float *layer_sqnorm, const int32_t *group_of_layer, int n_layers, int n,
+                   int n_groups, float *group_sqnorm, dp_stream stream);
+
+/* H3, for observability (H4 evaluates the same expression itself):
+ *   f[i] = min(1, clip_c / sqrt(sqnorm[i])), and 1 where sqnorm[i] == 0 or clip_c = +inf.
+ * sqnorm, f  [device] [n] fp32.  clip_c > 0 (may be +inf).                                   */
+dp_status dp_clip_factors(const float *sqnorm, float clip_c, int n, float *f, dp_stream stream);
+
+/* H4, materialised form: acc[e] += sum_{i<n} f_i * g[i, e]   (Section 2: "clipped gradients
+ * are accumulated over the entire batch"; called once per micro-step it is the gradient
+ * accumulation over micro-steps).
+ * g        [device] fp32 per-example gradients, example i's p values at g + i*g_stride
+ *          (g_stride = 0 means p; several tensors of one clipping group that sit side by
+ *          side in a [n, P_total] matrix can be accumulated by one call)
+ * sqnorm   [device] [n] fp32 squared norms of the clipping group this tensor belongs to
+ * acc      [device] [p] fp32, read and written; the caller zeroes it when a step starts      */
+dp_status dp_clip_accumulate(const float *g, size_t g_stride, const float *sqnorm, float clip_c, int n,
+                             size_t p, float *acc, dp_stream stream);
+
+/* H4, recomputing form: the same sum without per-example gradients in memory,
+ *   acc_w += sum_i f_i * dW_i,  acc_b += sum_i f_i * db_i,
+ * evaluated as one contraction over (example, position) with dY_i scaled by f_i as it is
+ * staged (for bf16 inputs the scaled value is rounded to bf16 once more).
+ * acc_b may be NULL only when the layer has no bias.  ws as for DP_WS_RECOMPUTE.             */
+dp_status dp_clip_accumulate_recompute(const dp_layer_desc *desc /*[host]*/, const void *x, const void *dy,
+                                       const float *sqnorm, float clip_c, float *acc_w, float *acc_b,
+                                       void *ws, size_t ws_bytes, dp_stream stream);
+
+/* H5: out[e] = (acc[e] + sigma * clip_total * z_e) / total_batch  (Section 2, first equation),
+ * z_e iid N(0,1) from Philox4x32-10: elements 4q..4q+3 come from the call with counter
+ * (q mod 2^32, q div 2^32, tensor_id, step mod 2^32) and key (seed mod 2^32, seed div 2^32);
+ * each 32-bit word r gives u = ((r >> 9) + 0.5) * 2^-23; (u0,u1) -> z0 = R cos(2 pi u1),
+ * z1 = R sin(2 pi u1), R = sqrt(-2 ln u0); (u2,u3) -> z2, z3.  The result does not depend on
+ * the launch geometry.  sigma == 0 evaluates no random numbers.  out may alias acc.
+ * clip_total = sqrt(sum_g C_g^2), the bound on the whole clipped gradient.
+ * acc, out  [device] [p] fp32.  sigma >= 0, clip_total > 0 and finite, total_batch >= 1.       */
+dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,
+                                uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
+                                dp_stream stream);
+
+/* The raw 32-bit Philox word behind each element of the stream above (diagnostic; lets a
+ * test compare the integer stream bit for bit).  raw [device] [p] uint32.                      */
+dp_status dp_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id,
+                        dp_stream stream);
+
+/* Sentence describing the last error on this thread ("" if none).  Never NULL. */
+const char *dp_last_error(void);
+
+/* "major.minor gfx950" */
+const char *dp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,165 @@
+"""ctypes binding of libdp_privatise.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+DP_OK, DP_ERR_INVALID_ARG, DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE, DP_ERR_DEVICE = range(5)
+DP_DENSE, DP_CONV2D, DP_GN_AFFINE = 0, 1, 2
+DP_F32, DP_BF16 = 0, 1
+DP_NCHW, DP_NHWC = 0, 1
+DP_WS_PER_EXAMPLE_GRAD, DP_WS_RECOMPUTE = 0, 1
+
+_STATUS_NAMES = {1: "DP_ERR_INVALID_ARG", 2: "DP_ERR_UNSUPPORTED", 3: "DP_ERR_WORKSPACE", 4: "DP_ERR_DEVICE"}
+_KINDS = {"dense": DP_DENSE, "conv": DP_CONV2D, "gn": DP_GN_AFFINE}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdp_privatise.so")
+_lib = None
+
+
+class DpError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+class LayerDesc(C.Structure):
+    """Mirror of dp_layer_desc."""
+    _fields_ = [("kind", C.c_int), ("in_dtype", C.c_int), ("layout", C.c_int), ("n", C.c_int),
+                ("cin", C.c_int), ("cout", C.c_int), ("h", C.c_int), ("w", C.c_int),
+                ("kh", C.c_int), ("kw", C.c_int), ("stride", C.c_int), ("pad", C.c_int),
+                ("has_bias", C.c_int), ("gn_groups", C.c_int), ("gn_eps", C.c_float)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the HIP library.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2109_12191_amd.build` "
+                           "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = C.CDLL(_LIB_PATH)
+    vp, sz, u64, u32, fl, it = C.c_void_p, C.c_size_t, C.c_uint64, C.c_uint32, C.c_float, C.c_int
+    dpp = C.POINTER(LayerDesc)
+    sigs = {
+        "dp_weight_count": (sz, [dpp]),
+        "dp_bias_count": (sz, [dpp]),
+        "dp_workspace_bytes": (sz, [dpp, it]),
+        "dp_per_example_grad": (it, [dpp, vp, vp, vp, vp, sz, vp, vp, sz, vp]),
+        "dp_norms": (it, [vp, vp, it, it, it, vp, vp]),
+        "dp_clip_factors": (it, [vp, fl, it, vp, vp]),
+        "dp_clip_accumulate": (it, [vp, sz, vp, fl, it, sz, vp, vp]),
+        "dp_clip_accumulate_recompute": (it, [dpp, vp, vp, vp, fl, vp, vp, vp, sz, vp]),
+        "dp_add_noise_finalize": (it, [vp, vp, sz, fl, fl, u64, u64, u64, u32, vp]),
+        "dp_philox_raw": (it, [vp, sz, u64, u64, u32, vp]),
+        "dp_last_error": (C.c_char_p, []),
+        "dp_version": (C.c_char_p, []),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+EXPORTED = ("dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_per_example_grad", "dp_norms",
+            "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_recompute", "dp_add_noise_finalize",
+            "dp_philox_raw", "dp_last_error", "dp_version")
+
+
+def make_desc(layer, n: int, dtype: str = "f32", layout: int = DP_NCHW) -> LayerDesc:
+    """dp_layer_desc from a workload layer (anything with kind/cin/cout/h/w/kh/kw/stride/pad/...)."""
+    return LayerDesc(_KINDS[layer.kind], DP_BF16 if dtype == "bf16" else DP_F32, layout, n,
+                     layer.cin, layer.cout, layer.h, layer.w, layer.kh, layer.kw, layer.stride, layer.pad,
+                     int(bool(layer.has_bias)), layer.gn_groups, float(layer.gn_eps))
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int):
+    if status != DP_OK:
+        raise DpError(status, dp_last_error())
+
+
+def dp_last_error() -> str:
+    return load_library().dp_last_error().decode()
+
+
+def dp_version() -> str:
+    return load_library().dp_version().decode()
+
+
+def dp_weight_count(desc: LayerDesc) -> int:
+    return int(load_library().dp_weight_count(C.byref(desc)))
+
+
+def dp_bias_count(desc: LayerDesc) -> int:
+    return int(load_library().dp_bias_count(C.byref(desc)))
+
+
+def dp_workspace_bytes(desc: LayerDesc, use: int = DP_WS_PER_EXAMPLE_GRAD) -> int:
+    return int(load_library().dp_workspace_bytes(C.byref(desc), use))
+
+
+def dp_per_example_grad(desc, x, dy, g_w, g_b, sqnorm, ws, g_stride: int = 0, ws_bytes: Optional[int] = None,
+                        stream=None):
+    _check(load_library().dp_per_example_grad(C.byref(desc), _ptr(x), _ptr(dy), _ptr(g_w), _ptr(g_b), g_stride,
+                                              _ptr(sqnorm), _ptr(ws),
+                                              _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream)))
+
+
+def dp_norms(layer_sqnorm, group_of_layer, n_layers: int, n: int, n_groups: int, group_sqnorm, stream=None):
+    _check(load_library().dp_norms(_ptr(layer_sqnorm), _ptr(group_of_layer), n_layers, n, n_groups,
+                                   _ptr(group_sqnorm), _stream(stream)))
+
+
+def dp_clip_factors(sqnorm, clip_c: float, n: int, f, stream=None):
+    _check(load_library().dp_clip_factors(_ptr(sqnorm), clip_c, n, _ptr(f), _stream(stream)))
+
+
+def dp_clip_accumulate(g, sqnorm, clip_c: float, n: int, p: int, acc, g_stride: int = 0, stream=None):
+    _check(load_library().dp_clip_accumulate(_ptr(g), g_stride, _ptr(sqnorm), clip_c, n, p, _ptr(acc),
+                                             _stream(stream)))
+
+
+def dp_clip_accumulate_recompute(desc, x, dy, sqnorm, clip_c: float, acc_w, acc_b, ws,
+                                 ws_bytes: Optional[int] = None, stream=None):
+    _check(load_library().dp_clip_accumulate_recompute(C.byref(desc), _ptr(x), _ptr(dy), _ptr(sqnorm), clip_c,
+                                                       _ptr(acc_w), _ptr(acc_b), _ptr(ws),
+                                                       _nbytes(ws) if ws_bytes is None else ws_bytes,
+                                                       _stream(stream)))
+
+
+def dp_add_noise_finalize(acc, out, p: int, sigma: float, clip_total: float, total_batch: int, seed: int,
+                          step: int, tensor_id: int, stream=None):
+    _check(load_library().dp_add_noise_finalize(_ptr(acc), _ptr(out), p, sigma, clip_total, total_batch, seed,
+                                                step, tensor_id, _stream(stream)))
+
+
+def dp_philox_raw(raw, p: int, seed: int, step: int, tensor_id: int, stream=None):
+    _check(load_library().dp_philox_raw(_ptr(raw), p, seed, step, tensor_id, _stream(stream)))

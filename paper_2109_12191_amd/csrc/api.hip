@@ -1,0 +1,269 @@
+// C ABI of libdp_privatise: argument validation (all on the host, before any launch) and
+// dispatch to the kernels.  See include/dp_privatise.h for the contract of every call.
+#include "internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace dp {
+
+static thread_local char g_err[512] = "";
+
+dp_status fail(dp_status code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+dp_status check_launch(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(DP_ERR_DEVICE, "%s: launch failed: %s", what, hipGetErrorString(e));
+    return DP_OK;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validate a descriptor and derive its geometry.  Limits keep every index in 32 bits inside
+// the kernels: per-example tensors below 2^31 elements.
+static dp_status make_geo(const dp_layer_desc *d, Geo &g)
+{
+    if (!d) return fail(DP_ERR_INVALID_ARG, "descriptor is NULL");
+    if (d->kind != DP_DENSE && d->kind != DP_CONV2D && d->kind != DP_GN_AFFINE)
+        return fail(DP_ERR_INVALID_ARG, "unknown layer kind %d", d->kind);
+    if (d->in_dtype != DP_F32 && d->in_dtype != DP_BF16)
+        return fail(DP_ERR_INVALID_ARG, "unknown input dtype %d", d->in_dtype);
+    if (d->layout == DP_NHWC) return fail(DP_ERR_UNSUPPORTED, "NHWC activations are not supported by this build");
+    if (d->layout != DP_NCHW) return fail(DP_ERR_INVALID_ARG, "unknown layout %d", d->layout);
+    if (d->n < 1) return fail(DP_ERR_INVALID_ARG, "n = %d examples (need >= 1)", d->n);
+    if (d->cin < 1 || d->cout < 1 || d->h < 1 || d->w < 1)
+        return fail(DP_ERR_INVALID_ARG, "non-positive dimension (cin %d cout %d h %d w %d)", d->cin, d->cout, d->h, d->w);
+    memset(&g, 0, sizeof(g));
+    g.kind = d->kind; g.bf16 = d->in_dtype == DP_BF16; g.n = d->n;
+    g.cin = d->cin; g.cout = d->cout; g.h = d->h; g.w = d->w;
+    g.kh = g.kw = 1; g.stride = 1; g.pad = 0; g.oh = d->h; g.ow = d->w;
+    g.has_bias = d->has_bias ? 1 : 0;
+    if (d->kind == DP_CONV2D) {
+        if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
+            return fail(DP_ERR_INVALID_ARG, "bad conv geometry (kh %d kw %d stride %d pad %d)", d->kh, d->kw, d->stride, d->pad);
+        if (d->h + 2 * d->pad < d->kh || d->w + 2 * d->pad < d->kw)
+            return fail(DP_ERR_INVALID_ARG, "kernel %dx%d larger than padded input %dx%d", d->kh, d->kw, d->h + 2 * d->pad, d->w + 2 * d->pad);
+        if (d->kh > 255 || d->kw > 255 || d->pad > 255 || d->h > 16384 || d->w > 16384)
+            return fail(DP_ERR_UNSUPPORTED, "conv geometry beyond kernel limits (k, pad <= 255; h, w <= 16384)");
+        g.kh = d->kh; g.kw = d->kw; g.stride = d->stride; g.pad = d->pad;
+        g.oh = (d->h + 2 * d->pad - d->kh) / d->stride + 1;
+        g.ow = (d->w + 2 * d->pad - d->kw) / d->stride + 1;
+        g.pw = (size_t)d->cout * d->cin * d->kh * d->kw;
+        g.pb = g.has_bias ? (size_t)d->cout : 0;
+        g.x_elems = (size_t)d->cin * d->h * d->w;
+        g.dy_elems = (size_t)d->cout * g.oh * g.ow;
+    } else if (d->kind == DP_DENSE) {
+        if (d->w != 1) return fail(DP_ERR_INVALID_ARG, "dense layer: w must be 1 (h = tokens), got %d", d->w);
+        g.pw = (size_t)d->cout * d->cin;
+        g.pb = g.has_bias ? (size_t)d->cout : 0;
+        g.x_elems = (size_t)d->h * d->cin;
+        g.dy_elems = (size_t)d->h * d->cout;
+    } else {
+        if (d->cout != d->cin) return fail(DP_ERR_INVALID_ARG, "GroupNorm: cout (%d) must equal cin (%d)", d->cout, d->cin);
+        if (d->gn_groups < 1 || d->cin % d->gn_groups != 0)
+            return fail(DP_ERR_INVALID_ARG, "GroupNorm: %d groups do not divide %d channels", d->gn_groups, d->cin);
+        if (!(d->gn_eps >= 0.0f) || !std::isfinite(d->gn_eps))
+            return fail(DP_ERR_INVALID_ARG, "GroupNorm: eps must be finite and >= 0");
+        g.gn_groups = d->gn_groups; g.gn_eps = d->gn_eps; g.has_bias = 1;
+        g.pw = (size_t)d->cin; g.pb = (size_t)d->cin;
+        g.x_elems = g.dy_elems = (size_t)d->cin * d->h * d->w;
+    }
+    const size_t lim = (size_t)1 << 31;
+    if (g.x_elems >= lim || g.dy_elems >= lim || g.pw >= lim)
+        return fail(DP_ERR_UNSUPPORTED, "per-example tensor of 2^31 elements or more");
+    if ((size_t)d->n > 65535 && d->kind != DP_CONV2D)
+        return fail(DP_ERR_UNSUPPORTED, "more than 65535 examples per call for dense / GroupNorm layers");
+    return DP_OK;
+}
+
+static size_t ws_bytes_for(const Geo &g, int mode)
+{
+    size_t b;
+    if (g.kind == DP_CONV2D) b = conv_ws_bytes(g, mode);
+    else if (g.kind == DP_DENSE) b = dense_ws_bytes(g, mode);
+    else b = gn_ws_bytes(g, mode);
+    return (b + 15) & ~(size_t)15;
+}
+
+// Tensors that are read or written with 16-byte accesses need 16-byte alignment; the small
+// per-example vectors (norms, factors, group ids, raw words) are accessed word by word.
+static dp_status check_ptr(const void *p, const char *name, bool required, unsigned align = 16)
+{
+    if (!p) return required ? fail(DP_ERR_INVALID_ARG, "%s is NULL", name) : DP_OK;
+    if (reinterpret_cast<uintptr_t>(p) & (align - 1))
+        return fail(DP_ERR_INVALID_ARG, "%s is not %u-byte aligned", name, align);
+    return DP_OK;
+}
+
+static dp_status check_clip(float clip_c)
+{
+    if (std::isnan(clip_c) || !(clip_c > 0.0f)) return fail(DP_ERR_INVALID_ARG, "clip_c must be > 0 (may be +inf)");
+    return DP_OK;
+}
+
+static dp_status check_ws(const Geo &g, int mode, const void *ws, size_t ws_bytes)
+{
+    const size_t need = ws_bytes_for(g, mode);
+    if (need == 0) return DP_OK;
+    if (!ws) return fail(DP_ERR_WORKSPACE, "workspace is NULL; %zu bytes needed", need);
+    if (!aligned16(ws)) return fail(DP_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+    if (ws_bytes < need) return fail(DP_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
+    return DP_OK;
+}
+
+}  // namespace dp
+
+using namespace dp;
+
+#define DP_TRY(expr) do { dp_status st__ = (expr); if (st__ != DP_OK) return st__; } while (0)
+
+extern "C" {
+
+const char *dp_last_error(void) { return g_err; }
+const char *dp_version(void) { return "0.1 gfx950"; }
+
+size_t dp_weight_count(const dp_layer_desc *desc)
+{
+    Geo g;
+    return make_geo(desc, g) == DP_OK ? g.pw : 0;
+}
+
+size_t dp_bias_count(const dp_layer_desc *desc)
+{
+    Geo g;
+    return make_geo(desc, g) == DP_OK ? g.pb : 0;
+}
+
+size_t dp_workspace_bytes(const dp_layer_desc *desc, int use)
+{
+    Geo g;
+    if (make_geo(desc, g) != DP_OK) return 0;
+    if (use != DP_WS_PER_EXAMPLE_GRAD && use != DP_WS_RECOMPUTE) {
+        fail(DP_ERR_INVALID_ARG, "unknown workspace use %d", use);
+        return 0;
+    }
+    return ws_bytes_for(g, use == DP_WS_RECOMPUTE ? MODE_WEIGHTED : MODE_NORM);
+}
+
+dp_status dp_per_example_grad(const dp_layer_desc *desc, const void *x, const void *dy, float *g_w, float *g_b,
+                              size_t g_stride, float *sqnorm, void *ws, size_t ws_bytes, dp_stream stream)
+{
+    Geo g;
+    DP_TRY(make_geo(desc, g));
+    DP_TRY(check_ptr(x, "x", true));
+    DP_TRY(check_ptr(dy, "dy", true));
+    DP_TRY(check_ptr(g_w, "g_w", false));
+    DP_TRY(check_ptr(g_b, "g_b", false));
+    DP_TRY(check_ptr(sqnorm, "sqnorm", false, 4));
+    if (!g_w && !sqnorm) return fail(DP_ERR_INVALID_ARG, "nothing to compute: g_w and sqnorm are both NULL");
+    if (g_w && g.pb && !g_b) return fail(DP_ERR_INVALID_ARG, "g_w given but g_b is NULL for a layer with a bias");
+    if (!g_w && g_b) return fail(DP_ERR_INVALID_ARG, "g_b given without g_w");
+    if (g_stride) {
+        if (g_stride % 4) return fail(DP_ERR_INVALID_ARG, "g_stride must be a multiple of 4");
+        if (g_stride < g.pw || g_stride < g.pb) return fail(DP_ERR_INVALID_ARG, "g_stride smaller than the tensor");
+    }
+    DP_TRY(check_ws(g, MODE_NORM, ws, ws_bytes));
+    const int mode = g_w ? MODE_MATERIALISE : MODE_NORM;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    g_err[0] = 0;
+    if (g.kind == DP_CONV2D) return launch_conv(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
+    if (g.kind == DP_DENSE) return launch_dense(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
+    return launch_gn(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
+}
+
+dp_status dp_norms(const float *layer_sqnorm, const int32_t *group_of_layer, int n_layers, int n, int n_groups,
+                   float *group_sqnorm, dp_stream stream)
+{
+    DP_TRY(check_ptr(layer_sqnorm, "layer_sqnorm", true, 4));
+    DP_TRY(check_ptr(group_of_layer, "group_of_layer", true, 4));
+    DP_TRY(check_ptr(group_sqnorm, "group_sqnorm", true, 4));
+    if (n_layers < 1 || n < 1 || n_groups < 1)
+        return fail(DP_ERR_INVALID_ARG, "n_layers (%d), n (%d) and n_groups (%d) must be >= 1", n_layers, n, n_groups);
+    if (n_groups > 65535) return fail(DP_ERR_UNSUPPORTED, "more than 65535 clipping groups");
+    g_err[0] = 0;
+    return launch_norms(layer_sqnorm, group_of_layer, n_layers, n, n_groups, group_sqnorm, static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_clip_factors(const float *sqnorm, float clip_c, int n, float *f, dp_stream stream)
+{
+    DP_TRY(check_ptr(sqnorm, "sqnorm", true, 4));
+    DP_TRY(check_ptr(f, "f", true, 4));
+    DP_TRY(check_clip(clip_c));
+    if (n < 1) return fail(DP_ERR_INVALID_ARG, "n = %d (need >= 1)", n);
+    g_err[0] = 0;
+    return launch_clip_factors(sqnorm, clip_c, n, f, static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_clip_accumulate(const float *g, size_t g_stride, const float *sqnorm, float clip_c, int n, size_t p,
+                             float *acc, dp_stream stream)
+{
+    DP_TRY(check_ptr(g, "g", true));
+    DP_TRY(check_ptr(sqnorm, "sqnorm", true, 4));
+    DP_TRY(check_ptr(acc, "acc", true));
+    DP_TRY(check_clip(clip_c));
+    if (n < 1) return fail(DP_ERR_INVALID_ARG, "n = %d (need >= 1)", n);
+    if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0 parameters");
+    if (g_stride == 0) g_stride = p;
+    if (g_stride < p) return fail(DP_ERR_INVALID_ARG, "g_stride smaller than p");
+    if (p >= ((size_t)1 << 40)) return fail(DP_ERR_UNSUPPORTED, "p too large");
+    g_err[0] = 0;
+    return launch_clip_accumulate(g, g_stride, sqnorm, clip_c, n, p, acc, static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_clip_accumulate_recompute(const dp_layer_desc *desc, const void *x, const void *dy, const float *sqnorm,
+                                       float clip_c, float *acc_w, float *acc_b, void *ws, size_t ws_bytes,
+                                       dp_stream stream)
+{
+    Geo g;
+    DP_TRY(make_geo(desc, g));
+    DP_TRY(check_ptr(x, "x", true));
+    DP_TRY(check_ptr(dy, "dy", true));
+    DP_TRY(check_ptr(sqnorm, "sqnorm", true, 4));
+    DP_TRY(check_ptr(acc_w, "acc_w", true));
+    DP_TRY(check_ptr(acc_b, "acc_b", g.pb != 0));
+    if (!g.pb && acc_b) return fail(DP_ERR_INVALID_ARG, "acc_b given for a layer without bias");
+    DP_TRY(check_clip(clip_c));
+    DP_TRY(check_ws(g, MODE_WEIGHTED, ws, ws_bytes));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    g_err[0] = 0;
+    if (g.kind == DP_CONV2D) return launch_conv(g, MODE_WEIGHTED, x, dy, acc_w, acc_b, 0, nullptr, sqnorm, clip_c, ws, s);
+    if (g.kind == DP_DENSE) return launch_dense(g, MODE_WEIGHTED, x, dy, acc_w, acc_b, 0, nullptr, sqnorm, clip_c, ws, s);
+    return launch_gn(g, MODE_WEIGHTED, x, dy, acc_w, acc_b, 0, nullptr, sqnorm, clip_c, ws, s);
+}
+
+dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,
+                                uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
+                                dp_stream stream)
+{
+    DP_TRY(check_ptr(acc, "acc", true));
+    DP_TRY(check_ptr(out, "out", true));
+    if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0 parameters");
+    if (std::isnan(sigma) || sigma < 0.0f || std::isinf(sigma)) return fail(DP_ERR_INVALID_ARG, "sigma must be finite and >= 0");
+    if (!(clip_total > 0.0f) || !std::isfinite(clip_total)) return fail(DP_ERR_INVALID_ARG, "clip_total must be finite and > 0");
+    if (total_batch < 1) return fail(DP_ERR_INVALID_ARG, "total_batch = 0");
+    if (p >= ((size_t)1 << 40)) return fail(DP_ERR_UNSUPPORTED, "p too large");
+    g_err[0] = 0;
+    return launch_noise_finalize(acc, out, p, sigma, clip_total, total_batch, seed, step, tensor_id,
+                                 static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id, dp_stream stream)
+{
+    DP_TRY(check_ptr(raw, "raw", true, 4));
+    if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0");
+    if (p >= ((size_t)1 << 40)) return fail(DP_ERR_UNSUPPORTED, "p too large");
+    g_err[0] = 0;
+    return launch_philox_raw(raw, p, seed, step, tensor_id, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

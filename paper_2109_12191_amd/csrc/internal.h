@@ -1,0 +1,113 @@
+// Internal declarations shared by the translation units of libdp_privatise (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/dp_privatise.h"
+
+namespace dp {
+
+// ---- error reporting (api.hip) ---------------------------------------------------------
+dp_status fail(dp_status code, const char *fmt, ...);
+dp_status check_launch(const char *what);
+
+// ---- geometry of a validated descriptor ------------------------------------------------
+struct Geo {
+    int kind, bf16, n;
+    int cin, cout, h, w, kh, kw, stride, pad, oh, ow;
+    int has_bias, gn_groups;
+    float gn_eps;
+    size_t pw, pb;          // weight / bias parameter counts
+    size_t x_elems, dy_elems;   // per example
+};
+
+// Contraction modes of the conv / dense kernels.
+enum Mode { MODE_NORM = 0, MODE_MATERIALISE = 1, MODE_WEIGHTED = 2 };
+
+// Tiling plan of the conv contraction for one descriptor (host side, contract.hip).
+struct ConvPlan {
+    int big;            // 1: 128x128 workgroup tile, 0: 64x64
+    int tiles_m, tiles_n;
+    int splits;         // MODE_WEIGHTED: number of example ranges reduced through the workspace
+};
+ConvPlan conv_plan(const Geo &g, int mode);
+size_t conv_ws_bytes(const Geo &g, int mode);
+dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
+                      size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
+                      hipStream_t s);
+
+size_t dense_ws_bytes(const Geo &g, int mode);
+dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
+                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
+                       hipStream_t s);
+
+size_t gn_ws_bytes(const Geo &g, int mode);
+dp_status launch_gn(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
+                    size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
+                    hipStream_t s);
+
+// streaming kernels (stream_kernels.hip)
+dp_status launch_sum_partials(const float *partials, int n, int per_example, float *sqnorm, hipStream_t s);
+dp_status launch_norms(const float *layer_sqnorm, const int32_t *group_of_layer, int n_layers, int n,
+                       int n_groups, float *group_sqnorm, hipStream_t s);
+dp_status launch_clip_factors(const float *sqnorm, float clip_c, int n, float *f, hipStream_t s);
+dp_status launch_clip_accumulate(const float *g, size_t stride, const float *sqnorm, float clip_c, int n,
+                                 size_t p, float *acc, hipStream_t s);
+dp_status launch_add_partial_sums(const float *parts, int n_parts, size_t slice, size_t pw, float *acc_w,
+                                  float *acc_b, hipStream_t s);
+dp_status launch_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,
+                                uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
+                                hipStream_t s);
+dp_status launch_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id,
+                            hipStream_t s);
+
+// ---- device helpers --------------------------------------------------------------------
+#if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC__)
+
+// min(1, C / sqrt(n2)); 1 for a zero gradient or an infinite bound.
+__device__ __forceinline__ float clip_factor(float n2, float clip_c)
+{
+    if (!(n2 > 0.0f)) return 1.0f;
+    const float r = clip_c / sqrtf(n2);     // +inf / x = +inf -> 1
+    return r < 1.0f ? r : 1.0f;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Sum over a workgroup of `NW` waves; result valid in every thread.  `red` holds NW floats.
+template <int NW>
+__device__ __forceinline__ float block_sum(float v, float *red)
+{
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[wave] = v;
+    __syncthreads();
+    float t = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) t += red[i];
+    return t;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b)
+{
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// round to nearest, ties to even (finite inputs)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+#endif
+
+}  // namespace dp

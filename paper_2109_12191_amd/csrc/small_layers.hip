@@ -1,0 +1,234 @@
+// Per-example gradients of dense layers and GroupNorm affine parameters (H1 for the layer
+// kinds that are not convolutions).  With one token per example a dense weight gradient is
+// the rank-one product dy_i (x) x_i: there is no contraction to put on MFMA, the kernel is a
+// streaming outer product.  GroupNorm scale/shift gradients are two reductions over each
+// channel of x and dy.
+#include "internal.h"
+
+namespace dp {
+
+template <bool BF16> struct In;
+template <> struct In<true> {
+    typedef uint16_t type;
+    static __device__ __forceinline__ float ld(const uint16_t *p) { return bf16_bits_to_float(*p); }
+};
+template <> struct In<false> {
+    typedef float type;
+    static __device__ __forceinline__ float ld(const float *p) { return *p; }
+};
+
+// ------------------------------------------------------------------------------------------
+// dense: dW_i[o,k] = sum_t dY_i[t,o] X_i[t,k];  db_i[o] = sum_t dY_i[t,o]
+// Workgroup tile: DR rows (o) x 256 columns (k); a thread owns one column, so x loads and
+// gradient stores are coalesced along k and dy values are wave-uniform.
+constexpr int DR = 16;
+
+struct DenseArgs {
+    const void *x, *dy;
+    float *out_w, *out_b;
+    size_t out_stride_w, out_stride_b;
+    float *partials;
+    const float *group_sqnorm;
+    float clip_c;
+    int n, tokens, cin, cout, has_bias;
+    int tiles_k, tiles_o;
+};
+
+template <bool BF16, bool WEIGHTED>
+__global__ void __launch_bounds__(256) dense_kernel(const DenseArgs a)
+{
+    typedef typename In<BF16>::type E;
+    __shared__ float red[4];
+    const int tile_k = blockIdx.x, tile_o = blockIdx.y;
+    const int k = tile_k * 256 + threadIdx.x;
+    const int o0 = tile_o * DR;
+    const bool k_ok = k < a.cin;
+    const E *xg = static_cast<const E *>(a.x), *dyg = static_cast<const E *>(a.dy);
+    const int i_begin = WEIGHTED ? 0 : blockIdx.z;
+    const int i_end = WEIGHTED ? a.n : blockIdx.z + 1;
+    const bool bias_thread = a.has_bias && tile_k == 0 && threadIdx.x < DR && o0 + threadIdx.x < a.cout;
+
+    float acc[DR];
+#pragma unroll
+    for (int r = 0; r < DR; ++r) acc[r] = 0.0f;
+    float accb = 0.0f;
+
+    for (int i = i_begin; i < i_end; ++i) {
+        const float f = WEIGHTED ? clip_factor(a.group_sqnorm[i], a.clip_c) : 1.0f;
+        const E *xi = xg + (size_t)i * a.tokens * a.cin;
+        const E *dyi = dyg + (size_t)i * a.tokens * a.cout;
+        for (int t = 0; t < a.tokens; ++t) {
+            const float xv = k_ok ? In<BF16>::ld(xi + (size_t)t * a.cin + k) * f : 0.0f;
+#pragma unroll
+            for (int r = 0; r < DR; ++r) {
+                const int o = o0 + r;
+                const float d = (o < a.cout) ? In<BF16>::ld(dyi + (size_t)t * a.cout + o) : 0.0f;
+                acc[r] += d * xv;
+            }
+            if (bias_thread) accb += In<BF16>::ld(dyi + (size_t)t * a.cout + o0 + threadIdx.x) * f;
+        }
+    }
+
+    if constexpr (!WEIGHTED) {
+        const int i = i_begin;
+        float ss = 0.0f;
+#pragma unroll
+        for (int r = 0; r < DR; ++r) {
+            ss += acc[r] * acc[r];
+            if (a.out_w && k_ok && o0 + r < a.cout)
+                a.out_w[(size_t)i * a.out_stride_w + (size_t)(o0 + r) * a.cin + k] = acc[r];
+        }
+        if (bias_thread) {
+            ss += accb * accb;
+            if (a.out_w) a.out_b[(size_t)i * a.out_stride_b + o0 + threadIdx.x] = accb;
+        }
+        const float tot = block_sum<4>(ss, red);
+        if (threadIdx.x == 0)
+            a.partials[(size_t)i * (a.tiles_k * a.tiles_o) + tile_o * a.tiles_k + tile_k] = tot;
+    } else {
+#pragma unroll
+        for (int r = 0; r < DR; ++r)
+            if (k_ok && o0 + r < a.cout) a.out_w[(size_t)(o0 + r) * a.cin + k] += acc[r];
+        if (bias_thread) a.out_b[o0 + threadIdx.x] += accb;
+    }
+}
+
+size_t dense_ws_bytes(const Geo &g, int mode)
+{
+    if (mode == MODE_WEIGHTED) return 0;
+    const size_t tiles = (size_t)((g.cin + 255) / 256) * ((g.cout + DR - 1) / DR);
+    return (size_t)g.n * tiles * sizeof(float);
+}
+
+dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
+                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
+                       hipStream_t s)
+{
+    DenseArgs a;
+    a.x = x; a.dy = dy; a.out_w = out_w; a.out_b = out_b;
+    a.out_stride_w = out_stride ? out_stride : g.pw;
+    a.out_stride_b = out_stride ? out_stride : g.pb;
+    a.partials = static_cast<float *>(ws);
+    a.group_sqnorm = group_sqnorm; a.clip_c = clip_c;
+    a.n = g.n; a.tokens = g.h; a.cin = g.cin; a.cout = g.cout; a.has_bias = g.has_bias;
+    a.tiles_k = (g.cin + 255) / 256;
+    a.tiles_o = (g.cout + DR - 1) / DR;
+    const bool weighted = mode == MODE_WEIGHTED;
+    const dim3 grid(a.tiles_k, a.tiles_o, weighted ? 1 : g.n);
+    if (g.bf16) {
+        if (weighted) hipLaunchKernelGGL((dense_kernel<true, true>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((dense_kernel<true, false>), grid, dim3(256), 0, s, a);
+    } else {
+        if (weighted) hipLaunchKernelGGL((dense_kernel<false, true>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((dense_kernel<false, false>), grid, dim3(256), 0, s, a);
+    }
+    dp_status st = check_launch("dense");
+    if (st != DP_OK || weighted || !sqnorm) return st;
+    return launch_sum_partials(a.partials, g.n, a.tiles_k * a.tiles_o, sqnorm, s);
+}
+
+// ------------------------------------------------------------------------------------------
+// GroupNorm affine: one workgroup per (example, group).  Mean and biased variance of the
+// group's (C/G)*H*W elements in two passes (the group is L2-resident after the first), then
+// each wave takes channels of the group in turn and reduces sum dy*xhat and sum dy with
+// shuffles.
+struct GnArgs {
+    const void *x, *dy;
+    float *out_w, *out_b;           // [n, stride] rows of dgamma / dbeta (may be null)
+    size_t out_stride_w, out_stride_b;
+    float *partials;                // [n, groups]
+    int n, c, hw, groups;
+    float eps;
+};
+
+template <bool BF16>
+__global__ void __launch_bounds__(256) gn_affine_kernel(const GnArgs a)
+{
+    typedef typename In<BF16>::type E;
+    __shared__ float red[4];
+    const int grp = blockIdx.x, i = blockIdx.y;
+    const int cg = a.c / a.groups;
+    const size_t first = ((size_t)i * a.c + (size_t)grp * cg) * a.hw;
+    const int cnt = cg * a.hw;
+    const E *xg = static_cast<const E *>(a.x) + first;
+    const E *dyg = static_cast<const E *>(a.dy) + first;
+
+    float s = 0.0f;
+    for (int p = threadIdx.x; p < cnt; p += 256) s += In<BF16>::ld(xg + p);
+    const float mean = block_sum<4>(s, red) / (float)cnt;
+    float v = 0.0f;
+    for (int p = threadIdx.x; p < cnt; p += 256) {
+        const float d = In<BF16>::ld(xg + p) - mean;
+        v += d * d;
+    }
+    const float var = block_sum<4>(v, red) / (float)cnt;
+    const float rstd = 1.0f / sqrtf(var + a.eps);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float ss = 0.0f;
+    for (int cl = wave; cl < cg; cl += 4) {
+        const E *xc = xg + (size_t)cl * a.hw, *dc = dyg + (size_t)cl * a.hw;
+        float sg = 0.0f, sb = 0.0f;
+        for (int p = lane; p < a.hw; p += 64) {
+            const float d = In<BF16>::ld(dc + p);
+            sg += d * ((In<BF16>::ld(xc + p) - mean) * rstd);
+            sb += d;
+        }
+        sg = wave_sum(sg);
+        sb = wave_sum(sb);
+        if (lane == 0) {
+            const int c = grp * cg + cl;
+            ss += sg * sg + sb * sb;
+            if (a.out_w) {
+                a.out_w[(size_t)i * a.out_stride_w + c] = sg;
+                a.out_b[(size_t)i * a.out_stride_b + c] = sb;
+            }
+        }
+    }
+    const float tot = block_sum<4>(ss, red);
+    if (threadIdx.x == 0) a.partials[(size_t)i * a.groups + grp] = tot;
+}
+
+size_t gn_ws_bytes(const Geo &g, int mode)
+{
+    size_t b = (size_t)g.n * g.gn_groups * sizeof(float);
+    b = (b + 15) & ~(size_t)15;
+    if (mode == MODE_WEIGHTED) b += (size_t)g.n * 2 * g.cin * sizeof(float);
+    return b;
+}
+
+dp_status launch_gn(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
+                    size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
+                    hipStream_t s)
+{
+    GnArgs a;
+    a.x = x; a.dy = dy;
+    a.partials = static_cast<float *>(ws);
+    a.n = g.n; a.c = g.cin; a.hw = g.h * g.w; a.groups = g.gn_groups; a.eps = g.gn_eps;
+    const bool weighted = mode == MODE_WEIGHTED;
+    float *gw = out_w, *gb = out_b;
+    if (weighted) {
+        const size_t head = (((size_t)g.n * g.gn_groups * sizeof(float)) + 15) & ~(size_t)15;
+        gw = reinterpret_cast<float *>(static_cast<char *>(ws) + head);
+        gb = gw + (size_t)g.n * g.cin;
+        a.out_stride_w = a.out_stride_b = (size_t)g.cin;
+    } else {
+        a.out_stride_w = out_stride ? out_stride : g.pw;
+        a.out_stride_b = out_stride ? out_stride : g.pb;
+    }
+    a.out_w = gw; a.out_b = gb;
+    const dim3 grid(g.gn_groups, g.n);
+    if (g.bf16) hipLaunchKernelGGL(gn_affine_kernel<true>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(gn_affine_kernel<false>, grid, dim3(256), 0, s, a);
+    dp_status st = check_launch("gn_affine");
+    if (st != DP_OK) return st;
+    if (weighted) {
+        st = launch_clip_accumulate(gw, (size_t)g.cin, group_sqnorm, clip_c, g.n, (size_t)g.cin, out_w, s);
+        if (st != DP_OK) return st;
+        return launch_clip_accumulate(gb, (size_t)g.cin, group_sqnorm, clip_c, g.n, (size_t)g.cin, out_b, s);
+    }
+    if (!sqnorm) return st;
+    return launch_sum_partials(a.partials, g.n, g.gn_groups, sqnorm, s);
+}
+
+}  // namespace dp

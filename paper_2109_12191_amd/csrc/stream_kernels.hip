@@ -1,0 +1,260 @@
+// Streaming kernels of the privatisation path: norm bookkeeping, clip-scale-accumulate,
+// and Philox noise + finalize.  All are HBM-bound by design: 16-byte accesses, one pass.
+#include "internal.h"
+
+namespace dp {
+
+// ------------------------------------------------------------------------------------------
+// sqnorm[i] = sum_t partials[i, t], t in increasing order (fixed order => reproducible bits).
+__global__ void __launch_bounds__(256) sum_partials_kernel(const float *__restrict__ partials, int n,
+                                                            int per_example, float *__restrict__ sqnorm)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float *p = partials + (size_t)i * per_example;
+    float s = 0.0f;
+    for (int t = 0; t < per_example; ++t) s += p[t];
+    sqnorm[i] = s;
+}
+
+dp_status launch_sum_partials(const float *partials, int n, int per_example, float *sqnorm, hipStream_t s)
+{
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partials, n, per_example,
+                       sqnorm);
+    return check_launch("sum_partials");
+}
+
+// ------------------------------------------------------------------------------------------
+// H2: group_sqnorm[g, i] = sum_{l : group_of_layer[l] == g} layer_sqnorm[l, i], l increasing.
+__global__ void __launch_bounds__(256) norms_kernel(const float *__restrict__ layer_sqnorm,
+                                                     const int32_t *__restrict__ group_of_layer, int n_layers,
+                                                     int n, int n_groups, float *__restrict__ group_sqnorm)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int g = blockIdx.y;
+    if (i >= n) return;
+    float s = 0.0f;
+    for (int l = 0; l < n_layers; ++l)
+        if (group_of_layer[l] == g) s += layer_sqnorm[(size_t)l * n + i];
+    group_sqnorm[(size_t)g * n + i] = s;
+}
+
+dp_status launch_norms(const float *layer_sqnorm, const int32_t *group_of_layer, int n_layers, int n,
+                       int n_groups, float *group_sqnorm, hipStream_t s)
+{
+    hipLaunchKernelGGL(norms_kernel, dim3((n + 255) / 256, n_groups), dim3(256), 0, s, layer_sqnorm,
+                       group_of_layer, n_layers, n, n_groups, group_sqnorm);
+    return check_launch("norms");
+}
+
+// ------------------------------------------------------------------------------------------
+// H3
+__global__ void __launch_bounds__(256) clip_factors_kernel(const float *__restrict__ sqnorm, float clip_c, int n,
+                                                            float *__restrict__ f)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) f[i] = clip_factor(sqnorm[i], clip_c);
+}
+
+dp_status launch_clip_factors(const float *sqnorm, float clip_c, int n, float *f, hipStream_t s)
+{
+    hipLaunchKernelGGL(clip_factors_kernel, dim3((n + 255) / 256), dim3(256), 0, s, sqnorm, clip_c, n, f);
+    return check_launch("clip_factors");
+}
+
+// ------------------------------------------------------------------------------------------
+// H4 (materialised form): acc[e] += sum_i f_i g[i, e].
+// Each thread owns VEC consecutive parameters and walks the examples in order (fixed order =>
+// reproducible bits); consecutive threads touch consecutive 16-byte pieces of one example's
+// row, so every wave load is a full 1 KiB run.  `stride` is the distance between rows.
+constexpr int CA_FMAX = 1024;   // clip factors staged in LDS per pass over the examples
+
+template <int VEC>
+__global__ void __launch_bounds__(256) clip_accumulate_kernel(const float *__restrict__ g, size_t stride,
+                                                               const float *__restrict__ sqnorm, float clip_c,
+                                                               int n, size_t p, float *__restrict__ acc)
+{
+    __shared__ float fs[CA_FMAX];
+    const size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * VEC;
+    float s[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) s[v] = 0.0f;
+
+    for (int base = 0; base < n; base += CA_FMAX) {
+        const int cnt = min(CA_FMAX, n - base);
+        __syncthreads();
+        for (int j = threadIdx.x; j < cnt; j += 256) fs[j] = clip_factor(sqnorm[base + j], clip_c);
+        __syncthreads();
+        if (e < p) {
+            const float *row = g + (size_t)base * stride + e;
+            int j = 0;
+            if constexpr (VEC == 4) {
+                for (; j + 4 <= cnt; j += 4) {
+                    const float4 a = *reinterpret_cast<const float4 *>(row + (size_t)(j + 0) * stride);
+                    const float4 b = *reinterpret_cast<const float4 *>(row + (size_t)(j + 1) * stride);
+                    const float4 c = *reinterpret_cast<const float4 *>(row + (size_t)(j + 2) * stride);
+                    const float4 d = *reinterpret_cast<const float4 *>(row + (size_t)(j + 3) * stride);
+                    const float f0 = fs[j], f1 = fs[j + 1], f2 = fs[j + 2], f3 = fs[j + 3];
+                    s[0] += f0 * a.x; s[1] += f0 * a.y; s[2] += f0 * a.z; s[3] += f0 * a.w;
+                    s[0] += f1 * b.x; s[1] += f1 * b.y; s[2] += f1 * b.z; s[3] += f1 * b.w;
+                    s[0] += f2 * c.x; s[1] += f2 * c.y; s[2] += f2 * c.z; s[3] += f2 * c.w;
+                    s[0] += f3 * d.x; s[1] += f3 * d.y; s[2] += f3 * d.z; s[3] += f3 * d.w;
+                }
+                for (; j < cnt; ++j) {
+                    const float4 a = *reinterpret_cast<const float4 *>(row + (size_t)j * stride);
+                    const float f0 = fs[j];
+                    s[0] += f0 * a.x; s[1] += f0 * a.y; s[2] += f0 * a.z; s[3] += f0 * a.w;
+                }
+            } else {
+                for (; j < cnt; ++j) s[0] += fs[j] * row[(size_t)j * stride];
+            }
+        }
+    }
+    if (e >= p) return;
+    if constexpr (VEC == 4) {
+        float4 a = *reinterpret_cast<float4 *>(acc + e);
+        a.x += s[0]; a.y += s[1]; a.z += s[2]; a.w += s[3];
+        *reinterpret_cast<float4 *>(acc + e) = a;
+    } else {
+        acc[e] += s[0];
+    }
+}
+
+dp_status launch_clip_accumulate(const float *g, size_t stride, const float *sqnorm, float clip_c, int n, size_t p,
+                                 float *acc, hipStream_t s)
+{
+    const bool vec4 = (p % 4 == 0) && (stride % 4 == 0);
+    const size_t threads = vec4 ? p / 4 : p;
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    if (vec4)
+        hipLaunchKernelGGL(clip_accumulate_kernel<4>, dim3(blocks), dim3(256), 0, s, g, stride, sqnorm, clip_c, n, p,
+                           acc);
+    else
+        hipLaunchKernelGGL(clip_accumulate_kernel<1>, dim3(blocks), dim3(256), 0, s, g, stride, sqnorm, clip_c, n, p,
+                           acc);
+    return check_launch("clip_accumulate");
+}
+
+// Combine the example ranges of the recomputing form: each of n_parts workspace slices holds
+// [weights (pw) | bias (slice - pw)]; acc_w[e] += sum_k parts[k, e], k increasing; likewise acc_b.
+__global__ void __launch_bounds__(256) add_partial_sums_kernel(const float *__restrict__ parts, int n_parts,
+                                                                size_t slice, size_t pw, float *__restrict__ acc_w,
+                                                                float *__restrict__ acc_b)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= slice) return;
+    float s = 0.0f;
+    for (int k = 0; k < n_parts; ++k) s += parts[(size_t)k * slice + e];
+    if (e < pw) acc_w[e] += s;
+    else acc_b[e - pw] += s;
+}
+
+dp_status launch_add_partial_sums(const float *parts, int n_parts, size_t slice, size_t pw, float *acc_w,
+                                  float *acc_b, hipStream_t s)
+{
+    hipLaunchKernelGGL(add_partial_sums_kernel, dim3((unsigned)((slice + 255) / 256)), dim3(256), 0, s, parts,
+                       n_parts, slice, pw, acc_w, acc_b);
+    return check_launch("add_partial_sums");
+}
+
+// ------------------------------------------------------------------------------------------
+// H5: Philox4x32-10 (Salmon et al., SC'11) + Box-Muller + finalize.
+struct Philox4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                 uint32_t k1)
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += W0;               // the bump after the last round is unused
+        k1 += W1;
+    }
+    return Philox4{c0, c1, c2, c3};
+}
+
+__device__ __forceinline__ float uniform_open(uint32_t r)
+{
+    return ((float)(r >> 9) + 0.5f) * 1.1920928955078125e-07f;     // 2^-23; exact in fp32, in (0,1)
+}
+
+__device__ __forceinline__ void box_muller(uint32_t ra, uint32_t rb, float &z0, float &z1)
+{
+    const float radius = sqrtf(-2.0f * logf(uniform_open(ra)));
+    float sn, cs;
+    sincospif(2.0f * uniform_open(rb), &sn, &cs);                   // 2u is exact; argument in (0,2)
+    z0 = radius * cs;
+    z1 = radius * sn;
+}
+
+// One thread per Philox call = 4 consecutive parameters (one 16-byte load, one 16-byte store).
+template <bool NOISE>
+__global__ void __launch_bounds__(256) noise_finalize_kernel(const float *__restrict__ acc, float *__restrict__ out,
+                                                              size_t p, float scale, float inv_batch, uint32_t k0,
+                                                              uint32_t k1, uint32_t step_lo, uint32_t tensor_id)
+{
+    const uint64_t q = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t e = (size_t)q * 4;
+    if (e >= p) return;
+    float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if constexpr (NOISE) {
+        const Philox4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), tensor_id, step_lo, k0, k1);
+        box_muller(r.x, r.y, z[0], z[1]);
+        box_muller(r.z, r.w, z[2], z[3]);
+    }
+    if (e + 4 <= p) {
+        const float4 a = *reinterpret_cast<const float4 *>(acc + e);
+        float4 o;
+        o.x = (a.x + scale * z[0]) * inv_batch;
+        o.y = (a.y + scale * z[1]) * inv_batch;
+        o.z = (a.z + scale * z[2]) * inv_batch;
+        o.w = (a.w + scale * z[3]) * inv_batch;
+        *reinterpret_cast<float4 *>(out + e) = o;
+    } else {
+        for (int j = 0; e + j < p; ++j) out[e + j] = (acc[e + j] + scale * z[j]) * inv_batch;
+    }
+}
+
+dp_status launch_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,
+                                uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
+                                hipStream_t s)
+{
+    const size_t calls = (p + 3) / 4;
+    const unsigned blocks = (unsigned)((calls + 255) / 256);
+    const float scale = sigma * clip_total;
+    const float inv_batch = 1.0f / (float)total_batch;
+    if (sigma > 0.0f)
+        hipLaunchKernelGGL(noise_finalize_kernel<true>, dim3(blocks), dim3(256), 0, s, acc, out, p, scale, inv_batch,
+                           (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, tensor_id);
+    else
+        hipLaunchKernelGGL(noise_finalize_kernel<false>, dim3(blocks), dim3(256), 0, s, acc, out, p, 0.0f, inv_batch,
+                           0u, 0u, 0u, 0u);
+    return check_launch("noise_finalize");
+}
+
+__global__ void __launch_bounds__(256) philox_raw_kernel(uint32_t *__restrict__ raw, size_t p, uint32_t k0,
+                                                          uint32_t k1, uint32_t step_lo, uint32_t tensor_id)
+{
+    const uint64_t q = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t e = (size_t)q * 4;
+    if (e >= p) return;
+    const Philox4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), tensor_id, step_lo, k0, k1);
+    const uint32_t v[4] = {r.x, r.y, r.z, r.w};
+    for (int j = 0; j < 4 && e + j < p; ++j) raw[e + j] = v[j];
+}
+
+dp_status launch_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id, hipStream_t s)
+{
+    const size_t calls = (p + 3) / 4;
+    hipLaunchKernelGGL(philox_raw_kernel, dim3((unsigned)((calls + 255) / 256)), dim3(256), 0, s, raw, p,
+                       (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, tensor_id);
+    return check_launch("philox_raw");
+}
+
+}  // namespace dp

@@ -1,0 +1,164 @@
+"""Sequencing of the C-ABI calls for one optimiser step of a layer set.
+
+This class owns device buffers (allocated through torch) and issues the library calls in
+order; it performs no arithmetic of its own.  Per micro-step:
+    dp_per_example_grad (every layer)  ->  dp_norms  ->  dp_clip_accumulate (materialised
+    layers) and dp_clip_accumulate_recompute (the rest);
+once per optimiser step: dp_add_noise_finalize per parameter tensor.
+
+Each layer uses one of the two forms of the clipped sum.  "materialise" keeps the layer's
+per-example gradients of the micro-step in a [n, P] matrix (written by the contraction's
+epilogue, read once by the streaming accumulate); "recompute" keeps nothing and runs a
+second, clip-factor-weighted contraction.  `mode="auto"` picks per layer whichever moves
+fewer bytes / flops; early conv layers (few parameters, large feature maps) materialise,
+late ones (many parameters, tiny feature maps) recompute.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+_HBM = 8.0e12
+_MFMA = {"bf16": 2.5e15, "f32": 157.3e12}
+
+
+def _pad4(v: int) -> int:
+    return (v + 3) & ~3
+
+
+class PrivatiseStep:
+    def __init__(self, wl, device: str = "cuda:0", mode: str = "auto"):
+        B.load_library()
+        self.wl = wl
+        self.device = torch.device(device)
+        self.layers = list(wl.layers)
+        self.n = wl.n
+        L = len(self.layers)
+        self.descs = [B.make_desc(l, wl.n, wl.dtype) for l in self.layers]
+        self.pw = [B.dp_weight_count(d) for d in self.descs]
+        self.pb = [B.dp_bias_count(d) for d in self.descs]
+        self.group_of_layer = list(wl.group_of_layer)
+        self.group_clip = [float(c) for c in wl.group_clip]
+        self.n_groups = wl.n_groups
+        self.form = [self._choose(l, mode) for l in self.layers]
+
+        # flat parameter vector: materialised layers first (their columns double as the
+        # layout of the per-example gradient matrix), then the recomputed ones
+        order = [i for i in range(L) if self.form[i] == "materialise"] + \
+                [i for i in range(L) if self.form[i] == "recompute"]
+        self.off_w = [0] * L
+        self.off_b = [0] * L
+        pos = 0
+        self.p_mat = 0
+        for i in order:
+            self.off_w[i] = pos
+            pos += _pad4(self.pw[i])
+            self.off_b[i] = pos
+            pos += _pad4(self.pb[i])
+            if self.form[i] == "materialise":
+                self.p_mat = pos
+        self.p_total = max(pos, 4)
+        dev = self.device
+        f32 = torch.float32
+        self.acc = torch.zeros(self.p_total, dtype=f32, device=dev)
+        self.out = torch.zeros(self.p_total, dtype=f32, device=dev)
+        self.g = torch.zeros((self.n, self.p_mat), dtype=f32, device=dev) if self.p_mat else None
+        self.layer_sqnorm = torch.zeros((L, self.n), dtype=f32, device=dev)
+        self.group_sqnorm = torch.zeros((self.n_groups, self.n), dtype=f32, device=dev)
+        self.group_of_layer_dev = torch.tensor(self.group_of_layer, dtype=torch.int32, device=dev)
+        ws = 16
+        for d, form in zip(self.descs, self.form):
+            ws = max(ws, B.dp_workspace_bytes(d, B.DP_WS_PER_EXAMPLE_GRAD))
+            if form == "recompute":
+                ws = max(ws, B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
+        self.micro_steps_done = 0
+
+    def _choose(self, layer, mode: str) -> str:
+        if mode in ("materialise", "recompute"):
+            return mode
+        if mode != "auto":
+            raise ValueError(mode)
+        esize = 2 if self.wl.dtype == "bf16" else 4
+        p = layer.pw + layer.pb
+        materialise = 8.0 * p / _HBM                       # write + read one fp32 gradient
+        recompute = max(layer.flops / (0.4 * _MFMA[self.wl.dtype]), layer.in_bytes(esize) / _HBM)
+        return "materialise" if materialise <= recompute else "recompute"
+
+    # ---- views of one layer's tensors in the flat vectors
+    def acc_w(self, li: int) -> torch.Tensor:
+        return self.acc[self.off_w[li]: self.off_w[li] + self.pw[li]]
+
+    def acc_b(self, li: int) -> Optional[torch.Tensor]:
+        return self.acc[self.off_b[li]: self.off_b[li] + self.pb[li]] if self.pb[li] else None
+
+    def out_w(self, li: int) -> torch.Tensor:
+        return self.out[self.off_w[li]: self.off_w[li] + self.pw[li]]
+
+    def out_b(self, li: int) -> Optional[torch.Tensor]:
+        return self.out[self.off_b[li]: self.off_b[li] + self.pb[li]] if self.pb[li] else None
+
+    def begin_step(self):
+        self.acc.zero_()
+        self.micro_steps_done = 0
+
+    def micro_step(self, inputs: Sequence):
+        """inputs: per layer (x, dy) device tensors of the workload's dtype, n examples each."""
+        L = len(self.layers)
+        gs = self.p_mat
+        for li in range(L):
+            x, dy = inputs[li]
+            if self.form[li] == "materialise":
+                g_w = self.g[:, self.off_w[li]:]
+                g_b = self.g[:, self.off_b[li]:] if self.pb[li] else None
+                B.dp_per_example_grad(self.descs[li], x, dy, g_w.data_ptr(),
+                                      g_b.data_ptr() if g_b is not None else None,
+                                      self.layer_sqnorm[li], self.ws, g_stride=gs, ws_bytes=self.ws.numel())
+            else:
+                B.dp_per_example_grad(self.descs[li], x, dy, None, None, self.layer_sqnorm[li], self.ws,
+                                      ws_bytes=self.ws.numel())
+        B.dp_norms(self.layer_sqnorm, self.group_of_layer_dev, L, self.n, self.n_groups, self.group_sqnorm)
+        if self.p_mat:
+            if self.n_groups == 1:
+                # one clipping group: every materialised tensor shares the factors -> one pass
+                B.dp_clip_accumulate(self.g, self.group_sqnorm[0], self.group_clip[0], self.n, self.p_mat,
+                                     self.acc, g_stride=gs)
+            else:
+                for li in range(L):
+                    if self.form[li] != "materialise":
+                        continue
+                    g = self.group_of_layer[li]
+                    span = _pad4(self.pw[li]) + _pad4(self.pb[li])
+                    B.dp_clip_accumulate(self.g[:, self.off_w[li]:].data_ptr(), self.group_sqnorm[g],
+                                         self.group_clip[g], self.n, span,
+                                         self.acc[self.off_w[li]:].data_ptr(), g_stride=gs)
+        for li in range(L):
+            if self.form[li] != "recompute":
+                continue
+            x, dy = inputs[li]
+            g = self.group_of_layer[li]
+            B.dp_clip_accumulate_recompute(self.descs[li], x, dy, self.group_sqnorm[g], self.group_clip[g],
+                                           self.acc_w(li).data_ptr(),
+                                           self.acc_b(li).data_ptr() if self.pb[li] else None,
+                                           self.ws, ws_bytes=self.ws.numel())
+        self.micro_steps_done += 1
+
+    def finalize(self):
+        wl = self.wl
+        for li in range(len(self.layers)):
+            B.dp_add_noise_finalize(self.acc_w(li).data_ptr(), self.out_w(li).data_ptr(), self.pw[li], wl.sigma,
+                                    wl.clip_total, wl.total_batch, wl.philox_seed, wl.step, 2 * li)
+            if self.pb[li]:
+                B.dp_add_noise_finalize(self.acc_b(li).data_ptr(), self.out_b(li).data_ptr(), self.pb[li],
+                                        wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step,
+                                        2 * li + 1)
+
+    def run(self, inputs_per_micro_step: Sequence[Sequence]):
+        self.begin_step()
+        for inputs in inputs_per_micro_step:
+            self.micro_step(inputs)
+        self.finalize()
+        return self.out

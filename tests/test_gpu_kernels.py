@@ -1,0 +1,253 @@
+"""GPU parity, kernel by kernel: each C-ABI call against the fp64 CPU oracle on the same
+seeded inputs, element by element (sizes the oracle finishes in seconds, spanning several
+tiles and ragged tails)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2109_12191_amd as dp
+from gpu_util import BF16_TOL, F32_TOL, assert_close, dev, host
+from workloads import Layer, conv, dense, gn_affine, to_bf16_grid
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(layer, n, seed, dtype, x_abs=False, dy_std=0.05):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((n,) + tuple(layer.x_shape)).astype(np.float32)
+    if x_abs:
+        x = np.abs(x)
+    dy = (rng.standard_normal((n,) + tuple(layer.dy_shape)) * dy_std).astype(np.float32)
+    if dtype == "bf16":
+        x, dy = to_bf16_grid(x), to_bf16_grid(dy)
+    return x, dy
+
+
+def _oracle_grads(layer, x, dy):
+    gw, gb, n2 = [], [], []
+    for i in range(x.shape[0]):
+        w, b = oracle.example_grad(layer, x[i], dy[i])
+        gw.append(w.reshape(-1))
+        gb.append(b if b is not None else np.zeros(0))
+        n2.append(oracle.sqnorm(w) + (oracle.sqnorm(b) if b is not None else 0.0))
+    return np.stack(gw), np.stack(gb), np.array(n2)
+
+
+def _run_per_example(layer, x, dy, dtype, materialise=True, g_stride=0):
+    n = x.shape[0]
+    d = dp.make_desc(layer, n, dtype)
+    pw, pb = dp.dp_weight_count(d), dp.dp_bias_count(d)
+    assert (pw, pb) == (layer.pw, layer.pb)
+    ws = torch.empty(max(16, dp.dp_workspace_bytes(d)), dtype=torch.uint8, device="cuda:0")
+    sq = torch.full((n,), -1.0, device="cuda:0")
+    xd, dyd = dev(x, dtype), dev(dy, dtype)
+    if not materialise:
+        dp.dp_per_example_grad(d, xd, dyd, None, None, sq, ws)
+        torch.cuda.synchronize()
+        return None, None, host(sq)
+    if g_stride:
+        g = torch.full((n, g_stride), 7.0, device="cuda:0")
+        off_b = (pw + 3) & ~3
+        dp.dp_per_example_grad(d, xd, dyd, g.data_ptr(), g[:, off_b:].data_ptr() if pb else None, sq, ws,
+                               g_stride=g_stride)
+        torch.cuda.synchronize()
+        gh = host(g)
+        assert np.all(gh[:, off_b + pb:] == 7.0) and np.all(gh[:, pw:off_b] == 7.0)   # nothing else touched
+        return gh[:, :pw], gh[:, off_b:off_b + pb], host(sq)
+    gw = torch.full((n, pw), 7.0, device="cuda:0")
+    gb = torch.full((n, max(pb, 1)), 7.0, device="cuda:0")
+    dp.dp_per_example_grad(d, xd, dyd, gw, gb if pb else None, sq, ws)
+    torch.cuda.synchronize()
+    return host(gw), host(gb)[:, :pb], host(sq)
+
+
+CONV_CASES = [
+    # name, layer, n
+    ("3x3 s1 ragged tiles", Layer("conv", 20, 70, 12, 12, 3, 3, 1, 1, False), 3),
+    ("3x3 s1 bias small", Layer("conv", 3, 16, 10, 9, 3, 3, 1, 1, True), 4),
+    ("3x3 s2 big", Layer("conv", 40, 200, 15, 15, 3, 3, 2, 1, False), 2),
+    ("1x1 s1 direct S=196", conv(150, 130, 1, 1, 14), 3),
+    ("1x1 s1 direct S=49 bias", conv(96, 72, 1, 1, 7, bias=True), 3),
+    ("1x1 s1 direct S=225 odd", conv(33, 65, 1, 1, 15), 2),
+    ("1x1 s2", conv(48, 80, 1, 2, 14), 2),
+    ("7x7 s2 cin3", conv(3, 64, 7, 2, 32), 2),
+    ("5x3 rect nopad", Layer("conv", 6, 9, 11, 13, 5, 3, 1, 0, True), 2),
+    ("long K several chunks", conv(8, 24, 3, 1, 40, bias=True), 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name,layer,n", CONV_CASES, ids=[c[0] for c in CONV_CASES])
+def test_conv_per_example_grad_and_norm(name, layer, n, dtype):
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
+    x, dy = _inputs(layer, n, 101, dtype)
+    ref_w, ref_b, ref_n2 = _oracle_grads(layer, x, dy)
+    gw, gb, sq = _run_per_example(layer, x, dy, dtype)
+    for i in range(n):
+        assert_close(gw[i], ref_w[i], tol, f"{name} dW[{i}]")
+        if layer.pb:
+            assert_close(gb[i], ref_b[i], tol, f"{name} db[{i}]")
+    assert np.allclose(sq, ref_n2, rtol=tol, atol=0), (sq, ref_n2)
+    # norms-only call gives the same norms bit for bit (same kernel, no store)
+    _, _, sq2 = _run_per_example(layer, x, dy, dtype, materialise=False)
+    assert np.array_equal(sq, sq2)
+
+
+def test_conv_strided_gradient_matrix_layout():
+    layer = Layer("conv", 5, 9, 8, 8, 3, 3, 1, 1, True)
+    x, dy = _inputs(layer, 3, 103, "f32")
+    ref_w, ref_b, ref_n2 = _oracle_grads(layer, x, dy)
+    gw, gb, sq = _run_per_example(layer, x, dy, "f32", g_stride=432)   # 405 -> pad 408, +9 bias, slack
+    assert_close(gw, ref_w, F32_TOL, "strided dW")
+    assert_close(gb, ref_b, F32_TOL, "strided db")
+    assert np.allclose(sq, ref_n2, rtol=F32_TOL)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layer", [dense(784, 256), dense(256, 10), dense(300, 37, tokens=3), dense(5, 3, bias=False)],
+                         ids=["784x256", "256x10", "300x37xT3", "5x3nobias"])
+def test_dense_per_example_grad_and_norm(layer, dtype):
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
+    x, dy = _inputs(layer, 5, 107, dtype)
+    ref_w, ref_b, ref_n2 = _oracle_grads(layer, x, dy)
+    gw, gb, sq = _run_per_example(layer, x, dy, dtype)
+    assert_close(gw, ref_w, tol, "dense dW")
+    if layer.pb:
+        assert_close(gb, ref_b, tol, "dense db")
+    assert np.allclose(sq, ref_n2, rtol=tol)
+    _, _, sq2 = _run_per_example(layer, x, dy, dtype, materialise=False)
+    assert np.array_equal(sq, sq2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("c,hw,groups", [(16, 32, 8), (64, 8, 8), (24, 5, 3), (32, 7, 32)])
+def test_groupnorm_affine_grad_and_norm(c, hw, groups, dtype):
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
+    layer = gn_affine(c, hw, groups)
+    x, dy = _inputs(layer, 4, 109, dtype)
+    x = x * 1.5 + 0.25
+    if dtype == "bf16":
+        x = to_bf16_grid(x)
+    ref_w, ref_b, ref_n2 = _oracle_grads(layer, x, dy)
+    gw, gb, sq = _run_per_example(layer, x, dy, dtype)
+    assert_close(gw, ref_w, tol, "dgamma")
+    assert_close(gb, ref_b, tol, "dbeta")
+    assert np.allclose(sq, ref_n2, rtol=tol)
+
+
+def test_norms_and_clip_factors():
+    rng = np.random.default_rng(5)
+    L, n, G = 7, 37, 3
+    layer_sq = rng.uniform(0.0, 4.0, (L, n)).astype(np.float32)
+    layer_sq[:, 5] = 0.0
+    grp = np.array([0, 2, 1, 1, 0, 2, 2], dtype=np.int32)
+    out = torch.full((G, n), -1.0, device="cuda:0")
+    dp.dp_norms(dev(layer_sq), torch.from_numpy(grp).cuda(), L, n, G, out)
+    got = host(out)
+    ref = np.stack([layer_sq[grp == g].astype(np.float64).sum(0) for g in range(G)])
+    assert np.allclose(got, ref, rtol=1e-6)
+    for c in (0.5, 1.7, math.inf):
+        f = torch.empty(n, device="cuda:0")
+        dp.dp_clip_factors(out[1], c, n, f)
+        ref_f = np.array([oracle.clip_factor(v, c) for v in got[1]])
+        assert np.allclose(host(f), ref_f, rtol=1e-6)
+        assert host(f)[5] == 1.0
+
+
+@pytest.mark.parametrize("n,p,stride", [(16, 36928, 0), (5, 1001, 0), (33, 4096, 4100), (3, 7, 8), (1100, 64, 0)])
+def test_clip_accumulate_materialised(n, p, stride):
+    rng = np.random.default_rng(11)
+    s = stride or p
+    g = rng.standard_normal((n, s)).astype(np.float32)
+    n2 = (rng.uniform(0.2, 3.0, n) ** 2).astype(np.float32)
+    n2[0] = 0.0
+    acc0 = rng.standard_normal(p).astype(np.float32)
+    c = 1.0
+    f = np.array([oracle.clip_factor(float(v), c) for v in n2])
+    ref = acc0.astype(np.float64) + (f[:, None] * g[:, :p].astype(np.float64)).sum(0)
+    acc = dev(acc0)
+    dp.dp_clip_accumulate(dev(g), dev(n2), c, n, p, acc, g_stride=stride)
+    assert_close(host(acc), ref, F32_TOL, "clip_accumulate")
+    # twice the same call from the same start gives the same bits (fixed summation order)
+    acc2 = dev(acc0)
+    dp.dp_clip_accumulate(dev(g), dev(n2), c, n, p, acc2, g_stride=stride)
+    assert torch.equal(acc, acc2)
+
+
+RECOMPUTE_CASES = [
+    ("conv 3x3 bias", Layer("conv", 20, 70, 12, 12, 3, 3, 1, 1, True), 9),
+    ("conv 1x1 S=49", conv(96, 136, 1, 1, 7), 6),
+    ("conv 3x3 s2", conv(24, 40, 3, 2, 14), 5),
+    ("conv small long K", conv(8, 24, 3, 1, 40, bias=True), 3),
+    ("dense", dense(300, 37, tokens=2), 7),
+    ("dense fc", dense(784, 256), 6),
+    ("gn", gn_affine(16, 9, 4), 6),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name,layer,n", RECOMPUTE_CASES, ids=[c[0] for c in RECOMPUTE_CASES])
+def test_clip_accumulate_recompute(name, layer, n, dtype):
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
+    x, dy = _inputs(layer, n, 113, dtype)
+    rng = np.random.default_rng(17)
+    n2 = (rng.uniform(0.3, 2.5, n) ** 2).astype(np.float32)     # both branches of the clip
+    n2[1] = 0.0
+    c = 1.0
+    f = np.array([oracle.clip_factor(float(v), c) for v in n2])
+    acc0_w = rng.standard_normal(layer.pw).astype(np.float32) * 0.01
+    acc0_b = rng.standard_normal(max(layer.pb, 1)).astype(np.float32) * 0.01
+    ref_w = acc0_w.astype(np.float64) + oracle.weighted_sum_elems(layer, x, dy, f, np.arange(layer.pw))
+    d = dp.make_desc(layer, n, dtype)
+    ws = torch.empty(max(16, dp.dp_workspace_bytes(d, dp.DP_WS_RECOMPUTE)), dtype=torch.uint8, device="cuda:0")
+    aw, ab = dev(acc0_w), dev(acc0_b)
+    dp.dp_clip_accumulate_recompute(d, dev(x, dtype), dev(dy, dtype), dev(n2), c, aw, ab if layer.pb else None, ws)
+    # compare the increment (the part the call computes) as well as the total
+    assert_close(host(aw) - acc0_w, ref_w - acc0_w, tol, f"{name} acc_w increment")
+    if layer.pb:
+        ref_b = acc0_b[:layer.pb].astype(np.float64) + oracle.weighted_sum_elems(layer, x, dy, f, np.arange(layer.pb),
+                                                                                  bias=True)
+        assert_close(host(ab)[:layer.pb] - acc0_b[:layer.pb], ref_b - acc0_b[:layer.pb], tol, f"{name} acc_b increment")
+
+
+def test_philox_integer_stream_is_bit_exact():
+    for seed, step, tid, p in [(0, 0, 0, 1), (0, 0, 0, 3), (0, 0, 1, 1027), (0x123456789ABCDEF, 0x100000005, 77, 4096),
+                               (2**64 - 1, 2**40 + 3, 2**32 - 1, 65537), (42, 7, 3, 1_000_001)]:
+        raw = torch.zeros(p, dtype=torch.int32, device="cuda:0")
+        dp.dp_philox_raw(raw, p, seed, step, tid)
+        got = raw.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, oracle.noise_raw(seed, step, tid, p)), (seed, step, tid, p)
+
+
+@pytest.mark.parametrize("p", [1, 6, 4099, 203_530])
+def test_noise_finalize_matches_oracle(p):
+    rng = np.random.default_rng(19)
+    acc = rng.standard_normal(p).astype(np.float32)
+    sigma, c, b, seed, step, tid = 1.1, 1.5, 256, 9, 4, 6
+    ref = oracle.noise_finalize(acc.astype(np.float64), sigma, c, b, seed, step, tid)
+    a = dev(acc)
+    out = torch.empty(p, device="cuda:0")
+    dp.dp_add_noise_finalize(a, out, p, sigma, c, b, seed, step, tid)
+    assert_close(host(out), ref, F32_TOL, "finalize")
+    # noise alone (acc = 0): the normals themselves
+    z = torch.zeros(p, device="cuda:0")
+    dp.dp_add_noise_finalize(z, z, p, 1.0, 1.0, 1, seed, step, tid)       # in place
+    assert_close(host(z), oracle.noise_normal(seed, step, tid, p), F32_TOL, "normals")
+    # sigma = 0: plain division
+    out0 = torch.empty(p, device="cuda:0")
+    dp.dp_add_noise_finalize(a, out0, p, 0.0, c, b, seed, step, tid)
+    assert_close(host(out0), acc.astype(np.float64) / b, 1e-6, "sigma=0")
+
+
+def test_noise_moments_match_sigma_c_within_one_percent():
+    p = 2_000_000
+    sigma, c, b = 1.1, 1.0, 32
+    out = torch.empty(p, device="cuda:0")
+    dp.dp_add_noise_finalize(torch.zeros(p, device="cuda:0"), out, p, sigma, c, b, 0, 0, 0)
+    z = host(out) * b
+    assert abs(z.std() / (sigma * c) - 1.0) < 0.01
+    assert abs(z.mean()) < 0.01 * sigma * c
+    assert abs(np.mean(z ** 2) / (sigma * c) ** 2 - 1.0) < 0.01

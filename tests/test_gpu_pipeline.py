@@ -1,0 +1,99 @@
+"""GPU parity of the whole path (all five steps through the C ABI) against the fp64 oracle,
+on the five workloads -- full size where the oracle finishes in seconds, otherwise the same
+layer structure on smaller feature maps / fewer examples."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2109_12191_amd as dp
+from gpu_util import BF16_TOL, F32_TOL, assert_close, dev, host
+from workloads import get_workload, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_both(wl, mode):
+    steps = [make_inputs(wl, m) for m in range(wl.accum)]
+    ref = oracle.privatise(wl, steps)
+    ps = dp.PrivatiseStep(wl, mode=mode)
+    ps.begin_step()
+    n2_gpu = []
+    for inputs in steps:
+        ps.micro_step([(dev(x, wl.dtype), dev(dy, wl.dtype)) for x, dy in inputs])
+        n2_gpu.append(host(ps.group_sqnorm).T.copy())          # [n, G]
+    acc_gpu = ps.acc.clone()
+    ps.finalize()
+    torch.cuda.synchronize()
+    return ref, ps, n2_gpu, acc_gpu
+
+
+def _check(wl, mode):
+    tol = F32_TOL if wl.dtype == "f32" else BF16_TOL
+    ref, ps, n2_gpu, acc_gpu = _run_both(wl, mode)
+    # H2: squared norms per example and group
+    for m in range(wl.accum):
+        assert np.allclose(n2_gpu[m], ref["n2"][m], rtol=tol, atol=0), f"n2 micro-step {m}"
+    # H4: clipped sum before noise, tensor by tensor
+    for li, l in enumerate(wl.layers):
+        a = host(acc_gpu[ps.off_w[li]: ps.off_w[li] + ps.pw[li]])
+        assert_close(a, ref["acc_w"][li], tol, f"acc_w[{li}] {l.name} ({ps.form[li]})")
+        if l.pb:
+            b = host(acc_gpu[ps.off_b[li]: ps.off_b[li] + ps.pb[li]])
+            assert_close(b, ref["acc_b"][li], tol, f"acc_b[{li}] {l.name}")
+    # H5: final output
+    for li, l in enumerate(wl.layers):
+        assert_close(host(ps.out_w(li)), ref["out_w"][li], tol, f"out_w[{li}] {l.name}")
+        if l.pb:
+            assert_close(host(ps.out_b(li)), ref["out_b"][li], tol, f"out_b[{li}] {l.name}")
+    return ps
+
+
+@pytest.mark.parametrize("mode", ["auto", "materialise", "recompute"])
+def test_mlp_workload_full_size(mode):
+    _check(get_workload("mlp"), mode)
+
+
+@pytest.mark.parametrize("mode", ["auto", "recompute"])
+def test_conv3x3_workload_full_size(mode):
+    _check(get_workload("conv3x3"), mode)
+
+
+@pytest.mark.parametrize("mode", ["auto", "recompute"])
+def test_resnet20_workload(mode):
+    # config 3 at full size: 39 layers, 256 examples
+    _check(get_workload("resnet20"), mode)
+
+
+@pytest.mark.parametrize("mode", ["auto", "materialise", "recompute"])
+def test_resnet50_layer_set_small_maps(mode):
+    # all 54 layers with their real channel counts, 64x64 input instead of 224x224
+    ps = _check(get_workload("resnet50", n=4, accum=2, hw=64), mode)
+    if mode == "auto":
+        assert "materialise" in ps.form or "recompute" in ps.form
+
+
+def test_resnet50_nano_per_layer_clipping_small_maps():
+    wl = get_workload("resnet50_nano", accum=4, hw=64)
+    assert wl.n == 1 and wl.n_groups == 54
+    _check(wl, "auto")
+
+
+def test_split_and_resume_gives_same_bits():
+    """State between micro-steps is only the accumulator: copy it out and in mid-step."""
+    wl = get_workload("conv3x3", n=4, accum=3, hw=14)
+    steps = [[(dev(x), dev(dy)) for x, dy in make_inputs(wl, m)] for m in range(3)]
+    a = dp.PrivatiseStep(wl)
+    a.run(steps)
+    b = dp.PrivatiseStep(wl)
+    b.begin_step()
+    b.micro_step(steps[0])
+    saved = b.acc.clone()
+    c = dp.PrivatiseStep(wl)
+    c.begin_step()
+    c.acc.copy_(saved)
+    c.micro_step(steps[1])
+    c.micro_step(steps[2])
+    c.finalize()
+    torch.cuda.synchronize()
+    assert torch.equal(a.out, c.out)

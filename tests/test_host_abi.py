@@ -1,0 +1,133 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and
+rejects bad arguments on the host before anything could be launched (no GPU needed; no
+compute call is made with valid arguments here)."""
+import math
+import os
+import re
+
+import pytest
+
+import paper_2109_12191_amd as dp
+from paper_2109_12191_amd import binding as B
+from workloads import conv, dense, gn_affine, get_workload
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000          # a non-null, 16-byte aligned "device pointer" that is never dereferenced
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dp.lib_path()):
+        from paper_2109_12191_amd.build import build
+        build(verbose=False)
+    return dp.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "dp_privatise.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dp_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTED)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert "gfx950" in dp.dp_version()
+
+
+def test_parameter_counts_and_workspace_are_pure_host(lib):
+    d = dp.make_desc(conv(64, 64, 3, 1, 56, bias=True), 16)
+    assert dp.dp_weight_count(d) == 64 * 64 * 9 and dp.dp_bias_count(d) == 64
+    assert dp.dp_workspace_bytes(d, dp.DP_WS_PER_EXAMPLE_GRAD) >= 16 * 4
+    d = dp.make_desc(dense(2048, 1000), 32, "bf16")
+    assert dp.dp_weight_count(d) == 2048000 and dp.dp_bias_count(d) == 1000
+    d = dp.make_desc(gn_affine(64, 8, 8), 4)
+    assert dp.dp_weight_count(d) == 64 and dp.dp_bias_count(d) == 64
+    assert dp.dp_workspace_bytes(d, dp.DP_WS_RECOMPUTE) >= 4 * 2 * 64 * 4
+    # the ResNet-50 layer set adds up to the published parameter count
+    wl = get_workload("resnet50")
+    total = sum(dp.dp_weight_count(dp.make_desc(l, 1, "bf16")) + dp.dp_bias_count(dp.make_desc(l, 1, "bf16"))
+                for l in wl.layers)
+    assert total == 25_503_912
+    bad = dp.make_desc(conv(8, 8, 3, 1, 8), 0)
+    assert dp.dp_weight_count(bad) == 0 and dp.dp_workspace_bytes(bad) == 0
+
+
+def _raises(status, fn, *a, **k):
+    with pytest.raises(dp.DpError) as ei:
+        fn(*a, **k)
+    assert ei.value.status == status, str(ei.value)
+    assert dp.dp_last_error() != ""
+    return str(ei.value)
+
+
+def test_per_example_grad_argument_errors(lib):
+    good = dp.make_desc(conv(8, 8, 3, 1, 8, bias=True), 4)
+    ws = dp.dp_workspace_bytes(good)
+    call = lambda d, x=FAKE, dy=FAKE, gw=FAKE, gb=FAKE, sq=FAKE, w=FAKE, wb=ws, gs=0: dp.dp_per_example_grad(
+        d, x, dy, gw, gb, sq, w, g_stride=gs, ws_bytes=wb, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, call, good, x=None)
+    _raises(B.DP_ERR_INVALID_ARG, call, good, dy=None)
+    _raises(B.DP_ERR_INVALID_ARG, call, good, x=FAKE + 4)                 # misaligned
+    _raises(B.DP_ERR_INVALID_ARG, call, good, gw=None, gb=None, sq=None)  # nothing to compute
+    _raises(B.DP_ERR_INVALID_ARG, call, good, gb=None)                    # bias layer needs g_b with g_w
+    _raises(B.DP_ERR_INVALID_ARG, call, good, gw=None)                    # g_b without g_w
+    _raises(B.DP_ERR_INVALID_ARG, call, good, gs=6)                       # stride not a multiple of 4
+    _raises(B.DP_ERR_INVALID_ARG, call, good, gs=8)                       # stride smaller than the tensor
+    _raises(B.DP_ERR_WORKSPACE, call, good, w=None)
+    _raises(B.DP_ERR_WORKSPACE, call, good, wb=ws - 1)
+    for field, val in (("n", 0), ("cin", 0), ("cout", -1), ("h", 0), ("kh", 0), ("stride", 0), ("pad", -1),
+                       ("kind", 7), ("in_dtype", 5), ("layout", 9)):
+        d = dp.make_desc(conv(8, 8, 3, 1, 8, bias=True), 4)
+        setattr(d, field, val)
+        _raises(B.DP_ERR_INVALID_ARG, call, d)
+    d = dp.make_desc(conv(8, 8, 3, 1, 8), 4)
+    d.layout = dp.DP_NHWC
+    _raises(B.DP_ERR_UNSUPPORTED, call, d)
+    d = dp.make_desc(conv(8, 8, 3, 1, 8), 4)
+    d.kh = 20                                                             # kernel larger than padded input
+    _raises(B.DP_ERR_INVALID_ARG, call, d)
+    d = dp.make_desc(gn_affine(6, 4, 4), 2)                               # groups do not divide channels
+    _raises(B.DP_ERR_INVALID_ARG, call, d)
+    d = dp.make_desc(dense(8, 4), 2)
+    d.w = 3
+    _raises(B.DP_ERR_INVALID_ARG, call, d)
+
+
+def test_streaming_calls_argument_errors(lib):
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_norms, None, FAKE, 2, 4, 1, FAKE, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_norms, FAKE, FAKE, 0, 4, 1, FAKE, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_norms, FAKE, FAKE, 2, 4, 0, FAKE, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_factors, FAKE, 0.0, 4, FAKE, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_factors, FAKE, float("nan"), 4, FAKE, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_accumulate, FAKE, FAKE, -1.0, 4, 16, FAKE, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_accumulate, FAKE, FAKE, 1.0, 0, 16, FAKE, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_accumulate, FAKE, FAKE, 1.0, 4, 0, FAKE, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_accumulate, FAKE, FAKE, 1.0, 4, 16, FAKE, g_stride=8, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_accumulate, FAKE, FAKE, 1.0, 4, 16, None, stream=0)
+    fin = lambda **k: dp.dp_add_noise_finalize(k.get("acc", FAKE), k.get("out", FAKE), k.get("p", 16),
+                                               k.get("sigma", 1.0), k.get("c", 1.0), k.get("b", 8), 0, 0, 0, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, fin, acc=None)
+    _raises(B.DP_ERR_INVALID_ARG, fin, out=FAKE + 8)
+    _raises(B.DP_ERR_INVALID_ARG, fin, p=0)
+    _raises(B.DP_ERR_INVALID_ARG, fin, sigma=-0.1)
+    _raises(B.DP_ERR_INVALID_ARG, fin, sigma=float("nan"))
+    _raises(B.DP_ERR_INVALID_ARG, fin, c=0.0)
+    _raises(B.DP_ERR_INVALID_ARG, fin, c=math.inf)
+    _raises(B.DP_ERR_INVALID_ARG, fin, b=0)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_philox_raw, None, 16, 0, 0, 0, stream=0)
+
+
+def test_recompute_argument_errors(lib):
+    d = dp.make_desc(conv(8, 8, 3, 1, 8, bias=True), 64)
+    ws = dp.dp_workspace_bytes(d, dp.DP_WS_RECOMPUTE)
+    assert ws > 0
+    call = lambda sq=FAKE, c=1.0, aw=FAKE, ab=FAKE, w=FAKE, wb=ws: dp.dp_clip_accumulate_recompute(
+        d, FAKE, FAKE, sq, c, aw, ab, w, ws_bytes=wb, stream=0)
+    _raises(B.DP_ERR_INVALID_ARG, call, sq=None)
+    _raises(B.DP_ERR_INVALID_ARG, call, c=0.0)
+    _raises(B.DP_ERR_INVALID_ARG, call, aw=None)
+    _raises(B.DP_ERR_INVALID_ARG, call, ab=None)          # bias layer
+    _raises(B.DP_ERR_WORKSPACE, call, w=None)
+    _raises(B.DP_ERR_WORKSPACE, call, wb=16)
+    nb = dp.make_desc(conv(8, 8, 3, 1, 8), 4)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_accumulate_recompute, nb, FAKE, FAKE, FAKE, 1.0, FAKE, FAKE, FAKE,
+            ws_bytes=1 << 20, stream=0)                    # acc_b for a layer without bias
