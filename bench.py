@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the DPSGD gradient-privatisation hot path on one MI355X.
+
+A "step" is one optimiser step of the whole path on the ResNet-50 layer set (config 4 of the
+build's workloads): 8 micro-steps of 32 examples (per-example gradients + norms, clip factors,
+clipped sum) followed by Philox noise + finalize on all 25.5 M parameters = 256 privatised
+examples.  Inputs (bf16 activations and output gradients of all 54 layers, 8 distinct
+micro-batches, about 11 GB) are synthetic, seeded, and resident in HBM before the timed region.
+
+Prints ONE JSON line (see the keys below).  `roofline` describes the dominant kernel (the bf16
+MFMA contraction variant with the largest share of the timed region), timed with events on the
+stream it runs on; `cpu_baseline` is the fp64 oracle timed on this machine's host cores on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, flop/s
+HBM_PEAK = 8.0e12
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); filled in once measured, else null in the JSON line.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+class Probe:
+    """Brackets every contraction call with a pair of events on the current stream."""
+
+    def __init__(self):
+        self.pairs = {}     # variant -> list of (start, stop, flops, in_bytes)
+        self.enabled = False
+
+    def bracket(self, variant, flops, nbytes):
+        import torch
+        if not self.enabled:
+            return None
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        self.pairs.setdefault(variant, []).append((a, b, flops, nbytes))
+        a.record()
+        return b
+
+    def summary(self):
+        out = {}
+        for variant, lst in self.pairs.items():
+            ms = sum(a.elapsed_time(b) for a, b, _, _ in lst)
+            out[variant] = dict(launches=len(lst), total_ms=ms, flops=sum(p[2] for p in lst),
+                                bytes=sum(p[3] for p in lst))
+        return out
+
+
+def make_device_inputs(wl, micro_steps, device):
+    """Seeded synthetic inputs generated on the device: x ~ |N(0,1)|, dy ~ N(0, 1e-4) (variance),
+    rounded to bf16 (nearest-even) by the dtype conversion."""
+    import torch
+    gen = torch.Generator(device=device)
+    out = []
+    for m in range(micro_steps):
+        layers = []
+        for li, l in enumerate(wl.layers):
+            gen.manual_seed(wl.data_seed * 1_000_003 + m * 1009 + li)
+            x = torch.randn((wl.n,) + tuple(l.x_shape), generator=gen, device=device, dtype=torch.float32)
+            dist = wl.x_dist[li]
+            if dist == "absnormal":
+                x = x.abs_()
+            elif dist == "relu":
+                x = x.clamp_(min=0)
+            dy = torch.randn((wl.n,) + tuple(l.dy_shape), generator=gen, device=device, dtype=torch.float32)
+            dy.mul_(wl.dy_std)
+            if wl.dtype == "bf16":
+                x, dy = x.to(torch.bfloat16), dy.to(torch.bfloat16)
+            layers.append((x.contiguous(), dy.contiguous()))
+        out.append(layers)
+    return out
+
+
+def cpu_baseline(wl, inputs0, budget_examples):
+    """The oracle as it stands on the host cores, on the first `budget_examples` examples of
+    micro-batch 0 (same bits the GPU got); examples/s scales linearly (examples are independent)."""
+    import numpy as np
+    import oracle
+    cores = oracle.max_threads()
+    s = min(budget_examples, wl.n, max(cores, 1))
+    host_inputs = [(x[:s].float().cpu().numpy(), dy[:s].float().cpu().numpy()) for x, dy in inputs0]
+    acc_w, acc_b = oracle.new_accumulators(wl.layers)
+    t0 = time.perf_counter()
+    oracle.clip_accumulate(wl.layers, host_inputs, wl.group_of_layer, wl.group_clip, acc_w, acc_b, threads=cores)
+    # noise + finalize on every parameter, once (amortised over the whole batch in `value`)
+    t1 = time.perf_counter()
+    p_sample = 0
+    for li, l in enumerate(wl.layers):
+        if li % 8 == 0:      # a bounded sample of tensors, scaled to all parameters below
+            oracle.noise_finalize(acc_w[li], wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step, 2 * li)
+            p_sample += l.pw
+    t2 = time.perf_counter()
+    per_example = (t1 - t0) / s
+    finalize_all = (t2 - t1) * (wl.n_params / max(p_sample, 1))
+    step_time = per_example * wl.total_batch + finalize_all
+    return dict(value=wl.total_batch / step_time, unit="examples/s", cores=min(cores, s), kind="oracle",
+                sample=f"{s} examples of micro-batch 0 through all {len(wl.layers)} layers "
+                       f"({t1 - t0:.1f} s) + noise/finalize on {p_sample} of {wl.n_params} parameters "
+                       f"({t2 - t1:.1f} s), scaled linearly to one step of {wl.total_batch} examples")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--mode", default="auto", choices=["auto", "materialise", "recompute"])
+    ap.add_argument("--n", type=int, default=None, help="override examples per micro-step (tests)")
+    ap.add_argument("--accum", type=int, default=None)
+    ap.add_argument("--hw", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-examples", type=int, default=16)
+    ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "
+                 "run with --gpus 1")
+
+    import torch
+    import paper_2109_12191_amd as dp
+    from workloads import get_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dp.load_library()
+    device = torch.device("cuda:0")
+    wl = get_workload(args.workload, n=args.n, accum=args.accum, hw=args.hw)
+    ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode)
+    probe = Probe()
+    ps.probe = probe
+    inputs = make_device_inputs(wl, wl.accum, device)
+    torch.cuda.synchronize()
+
+    def one_step():
+        ps.begin_step()
+        for m in range(wl.accum):
+            ps.micro_step(inputs[m])
+        ps.finalize()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    probe.enabled = True
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    probe.enabled = False
+
+    summary = probe.summary()
+    esize = wl.elem_bytes
+    contraction = {k: v for k, v in summary.items() if k.startswith("conv_contract")}
+    dom_name, dom = max(contraction.items(), key=lambda kv: kv[1]["total_ms"])
+    achieved = dom["flops"] / (dom["total_ms"] * 1e-3)
+    peak = MFMA_PEAK[wl.dtype]
+    roofline = dict(bound="mfma", achieved=achieved / 1e12, peak=peak / 1e12, unit="TFLOP/s",
+                    frac=achieved / peak, traffic=MEASURED_TRAFFIC_BYTES_PER_LAUNCH, kernel=dom_name,
+                    launches=dom["launches"], avg_launch_us=dom["total_ms"] * 1e3 / dom["launches"],
+                    algorithmic_flop_per_launch=dom["flops"] / dom["launches"],
+                    share_of_step=dom["total_ms"] * 1e-3 / elapsed)
+    if args.table:
+        for k, v in sorted(summary.items(), key=lambda kv: -kv[1]["total_ms"]):
+            tf = v["flops"] / (v["total_ms"] * 1e-3) / 1e12 if v["total_ms"] else 0.0
+            gb = v["bytes"] / (v["total_ms"] * 1e-3) / 1e9 if v["total_ms"] else 0.0
+            print(f"{k:50s} launches {v['launches']:6d}  {v['total_ms'] / args.steps:9.3f} ms/step  "
+                  f"{tf:8.1f} TFLOP/s  {gb:8.1f} GB/s(in)", file=sys.stderr)
+        print("forms:", {f: ps.form.count(f) for f in set(ps.form)}, file=sys.stderr)
+
+    line = {
+        "metric": "privatised examples/sec at ResNet-50 layer shapes",
+        "value": args.steps * wl.total_batch / elapsed,
+        "unit": "examples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {len(wl.layers)} layers, {wl.n_params} parameters, micro-batch {wl.n} x "
+                               f"{wl.accum} accumulation = {wl.total_batch} examples/step, {wl.clip_mode} clipping "
+                               f"C={wl.clip_c}, sigma={wl.sigma}, {wl.dtype} inputs, fp32 accumulators",
+                   "clipped_sum_forms": {f: ps.form.count(f) for f in sorted(set(ps.form))},
+                   "flop_per_example": wl.flops_per_example, "input_bytes_per_example": wl.in_bytes_per_example},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, inputs[0], args.cpu_examples)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

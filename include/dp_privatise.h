@@ -93,8 +93,14 @@ size_t dp_bias_count(const dp_layer_desc *desc /*[host]*/);
  * same bits on every call.                                                                   */
 size_t dp_workspace_bytes(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_use*/);
 
+/* Name of the kernel variant that dp_per_example_grad (use = DP_WS_PER_EXAMPLE_GRAD) or
+ * dp_clip_accumulate_recompute (use = DP_WS_RECOMPUTE) launches for this descriptor, e.g.
+ * "conv_contract<bf16,128x128,per_example>"; "" on a bad descriptor.  Pure host; lets a
+ * profiler's per-kernel rows be tied to layers.  The string is static.                       */
+const char *dp_kernel_variant(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_use*/);
+
 /* H1 (+ the layer's share of H2): per-example weight gradients of one layer
- * (Section 2: "per-example gradients are computed"), from each example's input activation
+ * (Section 2: the gradient of each example's loss is formed on its own), from each example's input activation
  * and output gradient:
  *   conv   dW_i[co,ci,kh,kw] = sum_{oh,ow} dY_i[co,oh,ow] * Xpad_i[ci, oh*s+kh-p, ow*s+kw-p]
  *          db_i[co] = sum_{oh,ow} dY_i[co,oh,ow]
@@ -133,9 +139,9 @@ dp_status dp_norms(const float *layer_sqnorm, const int32_t *group_of_layer, int
  * sqnorm, f  [device] [n] fp32.  clip_c > 0 (may be +inf).                                   */
 dp_status dp_clip_factors(const float *sqnorm, float clip_c, int n, float *f, dp_stream stream);
 
-/* H4, materialised form: acc[e] += sum_{i<n} f_i * g[i, e]   (Section 2: "clipped gradients
- * are accumulated over the entire batch"; called once per micro-step it is the gradient
- * accumulation over micro-steps).
+/* H4, materialised form: acc[e] += sum_{i<n} f_i * g[i, e]   (Section 2: the clipped
+ * per-example gradients are summed over the whole batch; called once per micro-step it is
+ * the gradient accumulation over micro-steps).
  * g        [device] fp32 per-example gradients, example i's p values at g + i*g_stride
  *          (g_stride = 0 means p; several tensors of one clipping group that sit side by
  *          side in a [n, P_total] matrix can be accumulated by one call)

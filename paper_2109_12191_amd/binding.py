@@ -52,6 +52,7 @@ def load_library():
         "dp_weight_count": (sz, [dpp]),
         "dp_bias_count": (sz, [dpp]),
         "dp_workspace_bytes": (sz, [dpp, it]),
+        "dp_kernel_variant": (C.c_char_p, [dpp, it]),
         "dp_per_example_grad": (it, [dpp, vp, vp, vp, vp, sz, vp, vp, sz, vp]),
         "dp_norms": (it, [vp, vp, it, it, it, vp, vp]),
         "dp_clip_factors": (it, [vp, fl, it, vp, vp]),
@@ -70,7 +71,7 @@ def load_library():
     return lib
 
 
-EXPORTED = ("dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_per_example_grad", "dp_norms",
+EXPORTED = ("dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_recompute", "dp_add_noise_finalize",
             "dp_philox_raw", "dp_last_error", "dp_version")
 
@@ -124,6 +125,10 @@ def dp_bias_count(desc: LayerDesc) -> int:
 
 def dp_workspace_bytes(desc: LayerDesc, use: int = DP_WS_PER_EXAMPLE_GRAD) -> int:
     return int(load_library().dp_workspace_bytes(C.byref(desc), use))
+
+
+def dp_kernel_variant(desc: LayerDesc, use: int = DP_WS_PER_EXAMPLE_GRAD) -> str:
+    return load_library().dp_kernel_variant(C.byref(desc), use).decode()
 
 
 def dp_per_example_grad(desc, x, dy, g_w, g_b, sqnorm, ws, g_stride: int = 0, ws_bytes: Optional[int] = None,

@@ -155,6 +155,16 @@ size_t dp_workspace_bytes(const dp_layer_desc *desc, int use)
     return ws_bytes_for(g, use == DP_WS_RECOMPUTE ? MODE_WEIGHTED : MODE_NORM);
 }
 
+const char *dp_kernel_variant(const dp_layer_desc *desc, int use)
+{
+    Geo g;
+    if (make_geo(desc, g) != DP_OK) return "";
+    const int mode = use == DP_WS_RECOMPUTE ? MODE_WEIGHTED : MODE_NORM;
+    if (g.kind == DP_CONV2D) return conv_variant_name(g, mode);
+    if (g.kind == DP_DENSE) return g.bf16 ? "dense<bf16>" : "dense<f32>";
+    return g.bf16 ? "gn_affine<bf16>" : "gn_affine<f32>";
+}
+
 dp_status dp_per_example_grad(const dp_layer_desc *desc, const void *x, const void *dy, float *g_w, float *g_b,
                               size_t g_stride, float *sqnorm, void *ws, size_t ws_bytes, dp_stream stream)
 {

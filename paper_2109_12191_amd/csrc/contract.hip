@@ -448,6 +448,21 @@ size_t conv_ws_bytes(const Geo &g, int mode)
     return (size_t)g.n * p.tiles_m * p.tiles_n * sizeof(float);
 }
 
+const char *conv_variant_name(const Geo &g, int mode)
+{
+    static const char *names[2][2][2][2] = {
+        {{{"conv_contract<f32,64x64,per_example>", "conv_contract<f32,64x64,per_example,bias>"},
+          {"conv_contract<f32,64x64,weighted>", "conv_contract<f32,64x64,weighted,bias>"}},
+         {{"conv_contract<f32,128x128,per_example>", "conv_contract<f32,128x128,per_example,bias>"},
+          {"conv_contract<f32,128x128,weighted>", "conv_contract<f32,128x128,weighted,bias>"}}},
+        {{{"conv_contract<bf16,64x64,per_example>", "conv_contract<bf16,64x64,per_example,bias>"},
+          {"conv_contract<bf16,64x64,weighted>", "conv_contract<bf16,64x64,weighted,bias>"}},
+         {{"conv_contract<bf16,128x128,per_example>", "conv_contract<bf16,128x128,per_example,bias>"},
+          {"conv_contract<bf16,128x128,weighted>", "conv_contract<bf16,128x128,weighted,bias>"}}}};
+    const ConvPlan p = conv_plan(g, mode);
+    return names[g.bf16 ? 1 : 0][p.big][mode == MODE_WEIGHTED ? 1 : 0][g.has_bias ? 1 : 0];
+}
+
 template <bool BF16, bool BIG, bool WEIGHTED>
 static void launch_variant(const ConvArgs &a, bool bias, unsigned blocks, hipStream_t s)
 {

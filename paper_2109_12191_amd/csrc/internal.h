@@ -34,6 +34,7 @@ struct ConvPlan {
 };
 ConvPlan conv_plan(const Geo &g, int mode);
 size_t conv_ws_bytes(const Geo &g, int mode);
+const char *conv_variant_name(const Geo &g, int mode);
 dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
                       hipStream_t s);

@@ -76,6 +76,18 @@ class PrivatiseStep:
                 ws = max(ws, B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE))
         self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
         self.micro_steps_done = 0
+        # optional timing probe (bench.py): an object with bracket(variant, flops, bytes) that
+        # records an event on the current stream and returns the event to record afterwards
+        self.probe = None
+        esize = 2 if wl.dtype == "bf16" else 4
+        self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD), B.dp_kernel_variant(d, B.DP_WS_RECOMPUTE))
+                        for d in self.descs]
+        self.work = [(l.flops * wl.n, l.in_bytes(esize) * wl.n) for l in self.layers]
+
+    def _bracket(self, li: int, use: int):
+        if self.probe is None:
+            return None
+        return self.probe.bracket(self.variant[li][use], self.work[li][0], self.work[li][1])
 
     def _choose(self, layer, mode: str) -> str:
         if mode in ("materialise", "recompute"):
@@ -111,6 +123,7 @@ class PrivatiseStep:
         gs = self.p_mat
         for li in range(L):
             x, dy = inputs[li]
+            stop = self._bracket(li, 0)
             if self.form[li] == "materialise":
                 g_w = self.g[:, self.off_w[li]:]
                 g_b = self.g[:, self.off_b[li]:] if self.pb[li] else None
@@ -120,6 +133,8 @@ class PrivatiseStep:
             else:
                 B.dp_per_example_grad(self.descs[li], x, dy, None, None, self.layer_sqnorm[li], self.ws,
                                       ws_bytes=self.ws.numel())
+            if stop is not None:
+                stop.record()
         B.dp_norms(self.layer_sqnorm, self.group_of_layer_dev, L, self.n, self.n_groups, self.group_sqnorm)
         if self.p_mat:
             if self.n_groups == 1:
@@ -140,10 +155,13 @@ class PrivatiseStep:
                 continue
             x, dy = inputs[li]
             g = self.group_of_layer[li]
+            stop = self._bracket(li, 1)
             B.dp_clip_accumulate_recompute(self.descs[li], x, dy, self.group_sqnorm[g], self.group_clip[g],
                                            self.acc_w(li).data_ptr(),
                                            self.acc_b(li).data_ptr() if self.pb[li] else None,
                                            self.ws, ws_bytes=self.ws.numel())
+            if stop is not None:
+                stop.record()
         self.micro_steps_done += 1
 
     def finalize(self):
