@@ -126,7 +126,7 @@ dp_status dp_per_example_grad(const dp_layer_desc *desc /*[host]*/, const void *
 /* H2: per-example squared norms per clipping group (Section 2: one global norm;
  * Section 3.5: one norm per group):
  *   group_sqnorm[g, i] = sum over layers l with group_of_layer[l] == g of layer_sqnorm[l, i],
- * summed in increasing l.
+ * summed in a fixed order (the same bits on every call).
  * layer_sqnorm   [device] [n_layers, n] fp32
  * group_of_layer [device] [n_layers] int32, each in [0, n_groups) (not checked on the host;
  *                out-of-range entries are ignored by the kernel)

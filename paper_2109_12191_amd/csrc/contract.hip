@@ -4,50 +4,69 @@
 //     D_i[m, j] = sum_k A_i[m, k] * B_i[j, k]
 //     m = output channel (Cout rows), j = (ci, kh, kw) flattened (J = Cin*KH*KW columns, the
 //     framework's [Cout, Cin, KH, KW] weight layout read as a Cout x J matrix),
-//     k = output position (oh, ow) flattened (S = OH*OW, the contraction),
-//     A_i[m, k] = dY_i[m, k]               -- contiguous in k in NCHW
-//     B_i[j, k] = Xpad_i[ci, oh*s+kh-p, ow*s+kw-p]  (zero outside the image).
+//     k = output position (oh, ow), the contraction,
+//     A_i[m, k] = dY_i[m, oh, ow]                      -- contiguous along ow in NCHW
+//     B_i[j, k] = Xpad_i[ci, oh*s+kh-p, ow*s+kw-p]     -- zero outside the image.
 //
-// One workgroup (4 waves) owns one MT x NT tile of D.  It walks K in chunks: each chunk of A
-// and of the im2col view of B is staged through LDS with K contiguous (the operand order
-// v_mfma_f32_32x32x16_bf16 / v_mfma_f32_32x32x2_f32 want), then every wave runs its share of
-// 32x32 MFMA tiles out of LDS.  Three things can happen to a finished tile:
+// K is laid out "row padded": k' = oh * OWp + ow with OWp = OW rounded up to the 16-byte
+// piece (8 bf16 / 4 fp32), so that a piece never straddles two image rows and every piece of
+// either operand is a run of consecutive (or stride-2) elements of one row of one tensor.
+// A 1x1 stride-1 conv is passed in as the degenerate geometry H = 1, W = S (one long row).
+//
+// One workgroup (4 waves) owns one MT x NT tile of D and walks chunks of 128 bytes of K per
+// row.  Each thread stages 16-byte pieces: one dword-aligned 16-byte global load (+1 dword
+// when the run starts on an odd bf16), a funnel shift, and an edge mask; stride-2 rows are
+// de-interleaved in registers.  Pieces go to LDS with K contiguous (the operand order of
+// v_mfma_f32_32x32x16_bf16 / v_mfma_f32_32x32x2_f32) and every wave runs its 32x32 MFMA
+// tiles out of LDS while the next chunk's loads are in flight.
+//
+// What happens to a finished tile:
 //   * per-example mode: its squares are summed in registers and reduced with wavefront
-//     shuffles to one partial per (example, tile) -- the gradient never goes back to HBM for
-//     the norm -- and, if asked, the tile is also stored (materialised per-example gradient);
+//     shuffles to one partial per (example, tile) -- the gradient is never re-read for the
+//     norm -- and, if asked, the tile is stored (materialised per-example gradient).  A
+//     workgroup may take several examples in a row (short K) so loads stream across example
+//     boundaries, or a slice of one example's K (long K, few tiles); slices meet in a
+//     workspace and the last one to arrive adds them in fixed order and runs the epilogue.
 //   * weighted mode: K runs over (example, position) with dY_i scaled by the clip factor f_i
-//     while it is staged, so the tile is sum_i f_i dW_i; it is added to the accumulator.
+//     while it is staged, so the tile is sum_i f_i dW_i; example ranges meet the same way and
+//     the sum is added to the accumulator.
 // The bias gradient db_i[m] = sum_k dY_i[m, k] rides along as one more MFMA against a
 // register of ones in the workgroups of tile column 0.
 #include "internal.h"
+
+#include <cstdio>
+#include <type_traits>
 
 namespace dp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // 16 bytes, dword aligned
 
 constexpr int THREADS = 256;
 constexpr int PITCH = 144;            // bytes per LDS row: 128 data + 16 pad (odd multiple of 16 B:
                                       // 8 consecutive rows hit 8 distinct 16-byte bank groups)
-constexpr int ROW_BYTES = 128;        // K-chunk per row: 64 bf16 or 32 fp32
 
 struct ConvArgs {
     const void *x, *dy;
-    float *out_w, *out_b;             // per-example: g_w / g_b (may be null); weighted: acc or ws slices
-    size_t out_stride_w, out_stride_b;  // per-example row stride / weighted per-split stride
+    float *out_w, *out_b;             // per-example: g_w / g_b (may be null); weighted: accumulators
+    size_t out_stride_w, out_stride_b;  // per-example row stride
     float *partials;                  // per-example: [n, tiles] partial squared norms
     const float *group_sqnorm;        // weighted: [n]
     float clip_c;
+    float *ws_part;                   // split partial tiles
     int n, cin, cout, h, w, kh, kw, stride, pad, oh, ow;
     int J, S;
     int tiles_m, tiles_n;
-    int ex_per_split, splits;
-    int accumulate;                   // weighted: 1 = out += tile, 0 = out = tile (workspace slice)
-    int va, vb;                       // elements per 16-byte-or-smaller vector access of A / B rows
-    int b_direct;                     // 1x1, stride 1, no padding: B is a plain matrix
+    int kcolsp;                       // OW rounded up to a piece
+    int chunks_per_ex;                // ceil(OH * kcolsp / KC)
+    int ksplit;                       // per-example: K slices per (example, tile); weighted: example ranges
+    int chunks_per_split;             // per-example mode
+    int ex_per_split;                 // weighted mode
+    int ex_per_wg;                    // per-example mode, ksplit == 1: consecutive examples per workgroup
+    int force_slow;                   // stride other than 1 or 2: stage every chunk element by element
 };
 
-// Entry of the per-tile column table used by the im2col gather.
 struct ColInfo {
     int off;        // ci*H*W + (kh-p)*W + (kw-p)
     short dh, dw;   // kh-p, kw-p; dh = -30000 marks a column beyond J
@@ -56,122 +75,96 @@ struct ColInfo {
 template <bool BF16> struct ElemTraits;
 template <> struct ElemTraits<true> {
     typedef uint16_t type;
-    static constexpr int KC = 64;      // elements per K-chunk
-    static constexpr int ESIZE = 2;
+    static constexpr int KC = 64;      // elements per K-chunk (128 bytes)
+    static constexpr int EPP = 8;      // elements per 16-byte piece
 };
 template <> struct ElemTraits<false> {
     typedef float type;
     static constexpr int KC = 32;
-    static constexpr int ESIZE = 4;
+    static constexpr int EPP = 4;
 };
 
-// Stage ROWS x KC elements of a K-contiguous matrix (row r at base + r*row_stride) into
-// registers as raw dwords.  Thread t owns the 16-byte pieces {t + 256*q}; piece c covers row
-// c / 8, bytes (c % 8)*16 .. +15 of the row's 128-byte chunk.  V = elements per global load.
-// Rows >= rows_valid and k >= k_valid read as zero.
-template <bool BF16, int ROWS, int V>
-__device__ __forceinline__ void load_rows(uint32_t (&st)[ROWS * ROW_BYTES / 4 / THREADS],
-                                          const typename ElemTraits<BF16>::type *base, size_t row_stride,
-                                          int rows_valid, int k0, int k_valid)
+__device__ __forceinline__ uint32_t funnel(uint32_t hi, uint32_t lo, uint32_t bits)
 {
-    typedef typename ElemTraits<BF16>::type E;
-    constexpr int ES = ElemTraits<BF16>::ESIZE;
-    constexpr int PIECES = ROWS * 8 / THREADS;        // 16-byte pieces per thread
-    constexpr int EPP = 16 / ES;                      // elements per piece
-#pragma unroll
-    for (int q = 0; q < PIECES; ++q) {
-        const int c = threadIdx.x + THREADS * q;
-        const int row = c >> 3;
-        const int k = k0 + (c & 7) * EPP;
-        const E *src = base + (size_t)row * row_stride + k;
-        const bool row_ok = row < rows_valid;
-        if constexpr (V == EPP) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row_ok && k < k_valid) v = *reinterpret_cast<const uint4 *>(src);
-            st[q * 4 + 0] = v.x; st[q * 4 + 1] = v.y; st[q * 4 + 2] = v.z; st[q * 4 + 3] = v.w;
-        } else if constexpr (V * ES == 8) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                uint2 v = make_uint2(0, 0);
-                if (row_ok && k + h * V < k_valid) v = *reinterpret_cast<const uint2 *>(src + h * V);
-                st[q * 4 + 2 * h] = v.x; st[q * 4 + 2 * h + 1] = v.y;
-            }
-        } else {
-            // element-wise
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                if constexpr (BF16) {
-                    uint32_t lo = 0, hi = 0;
-                    if (row_ok && k + 2 * d < k_valid) lo = src[2 * d];
-                    if (row_ok && k + 2 * d + 1 < k_valid) hi = src[2 * d + 1];
-                    st[q * 4 + d] = lo | (hi << 16);
-                } else {
-                    uint32_t v = 0;
-                    if (row_ok && k + d < k_valid) v = __float_as_uint(src[d]);
-                    st[q * 4 + d] = v;
-                }
-            }
-        }
-    }
+    return (uint32_t)((((uint64_t)hi << 32) | lo) >> bits);
 }
 
-template <bool BF16, int ROWS>
-__device__ __forceinline__ void load_rows_any(uint32_t (&st)[ROWS * ROW_BYTES / 4 / THREADS],
-                                              const typename ElemTraits<BF16>::type *base, size_t row_stride,
-                                              int rows_valid, int k0, int k_valid, int v)
+// Keep elements lo <= i < hi of a piece, zero the rest (an empty range zeroes everything).
+template <bool BF16>
+__device__ __forceinline__ void mask_piece(uint32_t (&v)[4], int lo, int hi)
 {
-    constexpr int EPP = 16 / ElemTraits<BF16>::ESIZE;
-    if (v == EPP) load_rows<BF16, ROWS, EPP>(st, base, row_stride, rows_valid, k0, k_valid);
-    else if (v == EPP / 2) load_rows<BF16, ROWS, EPP / 2>(st, base, row_stride, rows_valid, k0, k_valid);
-    else load_rows<BF16, ROWS, 1>(st, base, row_stride, rows_valid, k0, k_valid);
-}
-
-// im2col gather of ROWS columns-of-D x KC positions for a general conv.
-template <bool BF16, int ROWS>
-__device__ __forceinline__ void gather_rows(uint32_t (&st)[ROWS * ROW_BYTES / 4 / THREADS],
-                                            const typename ElemTraits<BF16>::type *xi, const ColInfo *cols,
-                                            const ConvArgs &a, int k0)
-{
-    constexpr int ES = ElemTraits<BF16>::ESIZE;
-    constexpr int PIECES = ROWS * 8 / THREADS;
-    constexpr int EPP = 16 / ES;
-    // positions of this thread's piece are the same for all its rows: decode them once
-    const int kbase = k0 + (threadIdx.x & 7) * EPP;
-    int ihs[EPP], iws[EPP];
+    constexpr int EPP = ElemTraits<BF16>::EPP;
+    if (lo <= 0 && hi >= EPP) return;
+    const int l = min(max(lo, 0), EPP), h = min(max(hi, l), EPP);
+    const uint32_t bits = ((1u << h) - 1u) & ~((1u << l) - 1u);
 #pragma unroll
-    for (int e = 0; e < EPP; ++e) {
-        const int k = kbase + e;
-        const int oh = k / a.ow, ow = k - oh * a.ow;
-        ihs[e] = (k < a.S) ? oh * a.stride : -60000;      // pushes ih out of range
-        iws[e] = ow * a.stride;
-    }
-#pragma unroll
-    for (int q = 0; q < PIECES; ++q) {
-        const int row = (threadIdx.x >> 3) + (THREADS / 8) * q;
-        const ColInfo ci = cols[row];
-        uint32_t v[EPP];
-#pragma unroll
-        for (int e = 0; e < EPP; ++e) {
-            const int ih = ihs[e] + ci.dh, iw = iws[e] + ci.dw;
-            const bool ok = (unsigned)ih < (unsigned)a.h && (unsigned)iw < (unsigned)a.w;
-            const int idx = ok ? ci.off + ihs[e] * a.w + iws[e] : 0;
-            if constexpr (BF16) {
-                const uint32_t t = xi[idx];
-                v[e] = ok ? t : 0u;
-            } else {
-                const float t = xi[idx];
-                v[e] = ok ? __float_as_uint(t) : 0u;
-            }
-        }
+    for (int d = 0; d < 4; ++d) {
         if constexpr (BF16) {
-#pragma unroll
-            for (int d = 0; d < 4; ++d) st[q * 4 + d] = v[2 * d] | (v[2 * d + 1] << 16);
+            const uint32_t m = ((bits >> (2 * d)) & 1u ? 0x0000FFFFu : 0u) | ((bits >> (2 * d + 1)) & 1u ? 0xFFFF0000u : 0u);
+            v[d] &= m;
         } else {
-#pragma unroll
-            for (int d = 0; d < 4; ++d) st[q * 4 + d] = v[d];
+            if (!((bits >> d) & 1u)) v[d] = 0u;
         }
     }
 }
+
+// One 16-byte piece = elements src[i * STRIDE], i in [lo, hi) (others zero), packed K-contiguous.
+// It is produced in two steps so that every load of a chunk is in flight before any is used:
+//   piece_load : whole dwords around the run -- one dword-aligned 16-byte load plus the next
+//                dword for stride 1 (the run may start on an odd bf16), two 16-byte loads for
+//                stride 2.  No branches.  Up to 32 bytes from the run's start are touched: the
+//                caller only uses this where that stays inside the tensor, and passes a harmless
+//                address when the piece is empty.
+//   piece_finish : funnel shift / de-interleave and the edge mask, in registers.
+template <bool BF16, int STRIDE> constexpr int raw_n() { return (STRIDE == 1) ? (BF16 ? 5 : 4) : 8; }
+template <int N> struct Raw { uint32_t d[N]; };
+
+template <bool BF16, int STRIDE>
+__device__ __forceinline__ Raw<raw_n<BF16, STRIDE>()> piece_load(const typename ElemTraits<BF16>::type *src)
+{
+    Raw<raw_n<BF16, STRIDE>()> out;
+    uint32_t *raw = out.d;
+    uintptr_t addr = reinterpret_cast<uintptr_t>(src);
+    if constexpr (BF16) addr &= ~(uintptr_t)3;                      // dword aligned; bit 1 of src is the shift
+    const uint32_t *pw = reinterpret_cast<const uint32_t *>(addr);
+    const u32x4_a4 a = *reinterpret_cast<const u32x4_a4 *>(pw);
+    raw[0] = a.x; raw[1] = a.y; raw[2] = a.z; raw[3] = a.w;
+    if constexpr (STRIDE == 1) {
+        if constexpr (BF16) raw[4] = pw[4];
+    } else {
+        const u32x4_a4 b = *reinterpret_cast<const u32x4_a4 *>(pw + 4);
+        raw[4] = b.x; raw[5] = b.y; raw[6] = b.z; raw[7] = b.w;
+    }
+    return out;
+}
+
+template <bool BF16, int STRIDE>
+__device__ __forceinline__ void piece_finish(uint32_t (&v)[4], const Raw<raw_n<BF16, STRIDE>()> &in, uint32_t odd,
+                                             int lo, int hi)
+{
+    const uint32_t *raw = in.d;
+    if constexpr (BF16) {
+        const uint32_t bits = odd * 16u;
+        if constexpr (STRIDE == 1) {
+            v[0] = funnel(raw[1], raw[0], bits);
+            v[1] = funnel(raw[2], raw[1], bits);
+            v[2] = funnel(raw[3], raw[2], bits);
+            v[3] = funnel(raw[4], raw[3], bits);
+        } else {                                                    // low or high halves of 8 dwords
+            v[0] = ((raw[0] >> bits) & 0xFFFFu) | ((raw[1] >> bits) << 16);
+            v[1] = ((raw[2] >> bits) & 0xFFFFu) | ((raw[3] >> bits) << 16);
+            v[2] = ((raw[4] >> bits) & 0xFFFFu) | ((raw[5] >> bits) << 16);
+            v[3] = ((raw[6] >> bits) & 0xFFFFu) | ((raw[7] >> bits) << 16);
+        }
+    } else {
+        if constexpr (STRIDE == 1) { v[0] = raw[0]; v[1] = raw[1]; v[2] = raw[2]; v[3] = raw[3]; }
+        else { v[0] = raw[0]; v[1] = raw[2]; v[2] = raw[4]; v[3] = raw[6]; }
+    }
+    mask_piece<BF16>(v, lo, hi);
+}
+
+// ceil(a / b) for b > 0 and any sign of a
+__device__ __forceinline__ int ceil_div(int a, int b) { return (a >= 0) ? (a + b - 1) / b : -((-a) / b); }
 
 template <bool BF16, int N>
 __device__ __forceinline__ void scale_regs(uint32_t (&st)[N], float f)
@@ -179,62 +172,180 @@ __device__ __forceinline__ void scale_regs(uint32_t (&st)[N], float f)
 #pragma unroll
     for (int d = 0; d < N; ++d) {
         if constexpr (BF16) {
-            const float lo = __uint_as_float(st[d] << 16) * f;
-            const float hi = __uint_as_float(st[d] & 0xFFFF0000u) * f;
-            st[d] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            const f32x2 p = {__uint_as_float(st[d] << 16) * f, __uint_as_float(st[d] & 0xFFFF0000u) * f};
+            st[d] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));   // nearest-even, one instruction
         } else {
             st[d] = __float_as_uint(__uint_as_float(st[d]) * f);
         }
     }
 }
 
-template <int ROWS>
-__device__ __forceinline__ void store_rows(const uint32_t (&st)[ROWS * ROW_BYTES / 4 / THREADS], char *lds)
+// Epilogue of one finished tile held in the MFMA accumulator layout (full K of one example, or
+// the weighted sum over examples): squared norm + optional store, or add into the accumulator.
+template <int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS, int NACC>
+__device__ __forceinline__ void tile_epilogue(const f32x16 (&acc)[NACC], const ConvArgs &a, int i, int tile, int tiles,
+                                              int m0, int n0, int wm, int wn, int lane, bool bias_here, float *red)
 {
-    constexpr int PIECES = ROWS * 8 / THREADS;
+    if constexpr (!WEIGHTED) {
+        float ss = 0.0f;
+        const bool store = a.out_w != nullptr;
 #pragma unroll
-    for (int q = 0; q < PIECES; ++q) {
-        const int c = threadIdx.x + THREADS * q;
-        *reinterpret_cast<uint4 *>(lds + (c >> 3) * PITCH + (c & 7) * 16) =
-            make_uint4(st[q * 4], st[q * 4 + 1], st[q * 4 + 2], st[q * 4 + 3]);
+        for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int j = n0 + (wn * TN + tn) * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v = acc[tm * TN + tn][r];
+                    ss += v * v;                      // rows / columns beyond the matrix are exact zeros
+                    if (store) {
+                        const int m = m0 + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                        if (m < a.cout && j < a.J) a.out_w[(size_t)i * a.out_stride_w + (size_t)m * a.J + j] = v;
+                    }
+                }
+            }
+            if constexpr (BIAS) {
+                if (bias_here && (lane & 31) == 0) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float v = acc[TM * TN + tm][r];
+                        ss += v * v;
+                        const int m = m0 + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                        if (store && m < a.cout) a.out_b[(size_t)i * a.out_stride_b + m] = v;
+                    }
+                }
+            }
+        }
+        const float tot = block_sum<4>(ss, red);
+        if (threadIdx.x == 0) a.partials[(size_t)i * tiles + tile] = tot;
+    } else {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int j = n0 + (wn * TN + tn) * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                    if (m < a.cout && j < a.J) a.out_w[(size_t)m * a.J + j] += acc[tm * TN + tn][r];
+                }
+            }
+            if constexpr (BIAS) {
+                if (bias_here && (lane & 31) == 0) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = m0 + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                        if (m < a.cout) a.out_b[m] += acc[TM * TN + tm][r];
+                    }
+                }
+            }
+        }
     }
 }
 
-// MT = NT = 128 (BIG) or 64; 2x2 waves; each wave TM x TN tiles of 32x32.
-template <bool BF16, bool BIG, bool WEIGHTED, bool BIAS>
-__global__ void __launch_bounds__(THREADS) conv_contract_kernel(const ConvArgs a)
+// Workgroup tile MT x NT = (WAVES_M*TM*32) x (WAVES_N*TN*32), WAVES_M*WAVES_N = 4 waves.
+// Element-by-element staging of one operand's chunk straight into LDS, touching only valid
+// elements.  Used for the few chunks whose whole-dword reads could leave the tensor (first rows
+// of the first example, last rows of the last example), for tensors too small to have slack, and
+// for strides other than 1 and 2.  Compact on purpose: it is rarely taken.
+template <bool BF16, int ROWS, bool WEIGHTED>
+__device__ __noinline__ void slow_stage_a(char *lds, const typename ElemTraits<BF16>::type *dy_i, int cout, int S,
+                                          int oh_n, int ow_n, int kcolsp, int m0, int k0, float f)
+{
+    struct { int cout, S, oh, ow, kcolsp; } a = {cout, S, oh_n, ow_n, kcolsp};
+    typedef typename ElemTraits<BF16>::type E;
+    constexpr int KC = ElemTraits<BF16>::KC;
+    for (int idx = threadIdx.x; idx < ROWS * KC; idx += THREADS) {
+        const int row = idx / KC, kk = idx - row * KC;
+        const int kprime = k0 + kk;
+        const int oh = kprime / a.kcolsp, ow = kprime - oh * a.kcolsp;
+        const int m = m0 + row;
+        E val = 0;
+        if (m < a.cout && oh < a.oh && ow < a.ow) {
+            val = dy_i[(size_t)m * a.S + (size_t)oh * a.ow + ow];
+            if constexpr (WEIGHTED) {
+                if constexpr (BF16) val = float_to_bf16_bits(bf16_bits_to_float(val) * f);
+                else val = val * f;
+            }
+        }
+        *reinterpret_cast<E *>(lds + row * PITCH + kk * (int)sizeof(E)) = val;
+    }
+}
+
+template <bool BF16, int ROWS>
+__device__ __noinline__ void slow_stage_b(char *lds, const typename ElemTraits<BF16>::type *x_i, const ColInfo *cols,
+                                          int h, int w, int oh_n, int ow_n, int stride, int kcolsp, int k0)
+{
+    struct { int h, w, oh, ow, stride, kcolsp; } a = {h, w, oh_n, ow_n, stride, kcolsp};
+    typedef typename ElemTraits<BF16>::type E;
+    constexpr int KC = ElemTraits<BF16>::KC;
+    for (int idx = threadIdx.x; idx < ROWS * KC; idx += THREADS) {
+        const int row = idx / KC, kk = idx - row * KC;
+        const int kprime = k0 + kk;
+        const int oh = kprime / a.kcolsp, ow = kprime - oh * a.kcolsp;
+        const ColInfo ci = cols[row];
+        const int ih = oh * a.stride + ci.dh, iw = ow * a.stride + ci.dw;
+        E val = 0;
+        if (oh < a.oh && ow < a.ow && (unsigned)ih < (unsigned)a.h && (unsigned)iw < (unsigned)a.w)
+            val = x_i[ci.off + oh * a.stride * a.w + ow * a.stride];
+        *reinterpret_cast<E *>(lds + row * PITCH + kk * (int)sizeof(E)) = val;
+    }
+}
+
+// LOADER 0: the geometry is one long row per channel whose length is a multiple of the piece
+// (1x1 stride-1 conv with S % 8 == 0 for bf16): every piece is a single aligned 16-byte load.
+// LOADER 1 / 2: general geometry with stride 1 / 2 (any other stride runs LOADER 1 with every
+// chunk staged element by element).
+template <bool BF16, int WAVES_M, int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS, int LOADER>
+__global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArgs a)
 {
     typedef typename ElemTraits<BF16>::type E;
     constexpr int KC = ElemTraits<BF16>::KC;
-    constexpr int MT = BIG ? 128 : 64, NT = MT;
-    constexpr int TM = BIG ? 2 : 1, TN = TM;
-    constexpr int WT = 32 * TM;                         // wave tile edge
-    constexpr int REGS = MT * ROW_BYTES / 4 / THREADS;  // staging dwords per operand per thread
+    constexpr int EPP = ElemTraits<BF16>::EPP;
+    constexpr int MT = WAVES_M * TM * 32, NT = WAVES_N * TN * 32;
+    constexpr int PA = MT / 32, PB = NT / 32;           // 16-byte pieces per thread per chunk
+    constexpr int NACC = TM * TN + (BIAS ? TM : 0);     // 32x32 accumulator tiles per wave
+    static_assert(WAVES_M * WAVES_N == 4, "four waves");
 
-    __shared__ __attribute__((aligned(16))) char sA[MT * PITCH];
-    __shared__ __attribute__((aligned(16))) char sB[NT * PITCH];
+    __shared__ __attribute__((aligned(16))) char sA[2 * MT * PITCH];     // two buffers each
+    __shared__ __attribute__((aligned(16))) char sB[2 * NT * PITCH];
     __shared__ ColInfo cols[NT];
     __shared__ float red[4];
 
-    // ---- which tile / example range: consecutive hardware workgroup ids rotate over the 8
-    // XCDs, so id -> (id % 8) * per_xcd + id / 8 keeps the tiles of one example (which share
-    // its A and B rows) on one XCD's L2.
+    // ---- which tile and which slice of work.  Consecutive hardware workgroup ids rotate over
+    // the 8 XCDs, so id -> (id % 8) * per_xcd + id / 8 puts runs of consecutive logical ids
+    // (the slices of one tile; the tiles of one example) behind one XCD's L2.
     const int tiles = a.tiles_m * a.tiles_n;
-    const int units = WEIGHTED ? a.splits : a.n;
-    const int total = tiles * units;
+    int total, tile, unit;
+    if constexpr (WEIGHTED) {
+        total = tiles * a.ksplit;
+    } else {
+        const int ex_groups = (a.n + a.ex_per_wg - 1) / a.ex_per_wg;
+        total = ex_groups * tiles * a.ksplit;
+    }
     const int per_xcd = (total + 7) >> 3;
     const int wg = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (wg >= total) return;
-    const int unit = wg / tiles;
-    const int tile = wg - unit * tiles;
+    int split;
+    if constexpr (WEIGHTED) {
+        tile = wg / a.ksplit;               // slices of one tile are neighbours
+        split = wg - tile * a.ksplit;
+        unit = 0;
+    } else {
+        split = wg % a.ksplit;
+        const int r = wg / a.ksplit;
+        unit = r / tiles;                   // example group
+        tile = r - unit * tiles;
+    }
     const int tile_m = tile / a.tiles_n, tile_n = tile - tile_m * a.tiles_n;
     const int m0 = tile_m * MT, n0 = tile_n * NT;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WAVES_N, wn = wave - wm * WAVES_N;
 
-    // column table for the gather
-    if (!a.b_direct && threadIdx.x < NT) {
+    if (threadIdx.x < NT) {
         const int j = n0 + threadIdx.x;
         ColInfo c;
         if (j < a.J) {
@@ -251,51 +362,208 @@ __global__ void __launch_bounds__(THREADS) conv_contract_kernel(const ConvArgs a
     }
     __syncthreads();
 
-    const int i_begin = WEIGHTED ? unit * a.ex_per_split : unit;
-    const int i_end = WEIGHTED ? min(a.n, i_begin + a.ex_per_split) : unit + 1;
-    const int chunks_per_ex = (a.S + KC - 1) / KC;
-    const int n_chunks = (i_end - i_begin) * chunks_per_ex;
+    // ---- the stream of chunks this workgroup walks
+    int i_begin, i_end, c_begin, c_end;     // examples [i_begin, i_end), chunks [c_begin, c_end) of each
+    if constexpr (WEIGHTED) {
+        i_begin = split * a.ex_per_split;
+        i_end = min(a.n, i_begin + a.ex_per_split);
+        c_begin = 0;
+        c_end = a.chunks_per_ex;
+    } else {
+        i_begin = unit * a.ex_per_wg;
+        i_end = min(a.n, i_begin + a.ex_per_wg);
+        c_begin = split * a.chunks_per_split;
+        c_end = min(a.chunks_per_ex, c_begin + a.chunks_per_split);
+    }
+    const int cpe = c_end - c_begin;
+    const int n_chunks = (i_end - i_begin) * cpe;
 
     const size_t x_ex = (size_t)a.cin * a.h * a.w, dy_ex = (size_t)a.cout * a.S;
     const E *xg = static_cast<const E *>(a.x), *dyg = static_cast<const E *>(a.dy);
 
-    f32x16 acc[TM][TN];
-    f32x16 accb[TM];
+    // per-thread constants of the staging map: piece c = tid + 256 q -> row c / 8, K-piece c % 8
+    const int kp = (threadIdx.x & 7) * EPP;
+    const int row0 = threadIdx.x >> 3;
+    int a_row_off[PA];                       // (m0 + row) * S, or -1 beyond Cout
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.0f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) accb[tm][r] = 0.0f;
+    for (int q = 0; q < PA; ++q) {
+        const int m = m0 + row0 + 32 * q;
+        a_row_off[q] = (m < a.cout) ? m * a.S : -1;
     }
+
+    f32x16 acc[NACC];
+#pragma unroll
+    for (int t = 0; t < NACC; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
     const bool bias_here = BIAS && tile_n == 0 && wn == 0;
 
-    uint32_t stA[REGS], stB[REGS];
-    auto fetch = [&](int chunk) {
-        const int i = i_begin + chunk / chunks_per_ex;
-        const int k0 = (chunk - (chunk / chunks_per_ex) * chunks_per_ex) * KC;
-        load_rows_any<BF16, MT>(stA, dyg + (size_t)i * dy_ex + (size_t)m0 * a.S, (size_t)a.S, a.cout - m0, k0, a.S,
-                                a.va);
-        if constexpr (WEIGHTED) scale_regs<BF16, REGS>(stA, clip_factor(a.group_sqnorm[i], a.clip_c));
-        if (a.b_direct)
-            load_rows_any<BF16, NT>(stB, xg + (size_t)i * x_ex + (size_t)n0 * a.S, (size_t)a.S, a.J - n0, k0, a.S,
-                                    a.vb);
-        else
-            gather_rows<BF16, NT>(stB, xg + (size_t)i * x_ex, cols, a, k0);
+    // Raw loaded dwords of a chunk in flight and, per piece, the packed (odd, lo, hi) needed to
+    // finish it.  Two sets: while chunk c is in the MFMAs, chunk c+1 waits in one set and the
+    // loads of chunk c+2 are issued into the other.
+    constexpr int LS = (LOADER == 2) ? 2 : 1;
+    constexpr int RA = (LOADER == 0) ? 4 : raw_n<BF16, 1>();
+    constexpr int RB = (LOADER == 0) ? 4 : raw_n<BF16, LS>();
+    struct RawSet {
+        Raw<RA> ra[PA];
+        Raw<RB> rb[PB];
+        uint32_t ma[PA], mb[PB];
+    };
+    RawSet set0, set1;
+
+    // Which chunks cannot use whole-dword reads (all wave-uniform).
+    const bool flat_tail = (LOADER == 0) && (a.S % EPP != 0);
+    const bool all_slow = (LOADER != 0 || flat_tail) && (a.force_slow || x_ex < 512 || dy_ex < 512);
+    const int risk_a = (16 + a.ow - 1) / a.ow;          // trailing output rows within 32 bytes of a channel's end
+    const int risk_b = (16 + a.w - 1) / a.w;            // trailing input rows likewise
+    auto locate = [&](int chunk, int &i, int &k0) {
+        const int ie = chunk / cpe;
+        i = i_begin + ie;
+        k0 = (c_begin + chunk - ie * cpe) * KC;
+    };
+    auto is_slow_a = [&](int i, int k0) -> bool {
+        if constexpr (LOADER == 0) {
+            return flat_tail && (all_slow || (i == a.n - 1 && tile_m == a.tiles_m - 1 && k0 + KC >= a.S));
+        } else {
+            const int oh_hi = min(a.oh - 1, (k0 + KC - 1) / a.kcolsp);
+            return all_slow || (i == a.n - 1 && tile_m == a.tiles_m - 1 && oh_hi >= a.oh - risk_a);
+        }
+    };
+    auto is_slow_b = [&](int i, int k0) -> bool {
+        if constexpr (LOADER == 0) {
+            return flat_tail && (all_slow || (i == a.n - 1 && tile_n == a.tiles_n - 1 && k0 + KC >= a.S));
+        } else {
+            const int oh_lo = k0 / a.kcolsp;
+            const int oh_hi = min(a.oh - 1, (k0 + KC - 1) / a.kcolsp);
+            return all_slow || (i == 0 && tile_n == 0 && oh_lo * a.stride <= a.pad) ||
+                   (i == a.n - 1 && tile_n == a.tiles_n - 1 && oh_hi * a.stride + (a.kh - 1 - a.pad) >= a.h - risk_b);
+        }
     };
 
-    if (n_chunks > 0) fetch(0);
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
-        __syncthreads();                       // everyone is done reading the previous chunk
-        store_rows<MT>(stA, sA);
-        store_rows<NT>(stB, sB);
-        __syncthreads();
-        if (chunk + 1 < n_chunks) fetch(chunk + 1);   // global loads fly while the MFMAs run
+    // Issue every global load of a chunk (no use of the data here, so no wait either).
+    auto fetch = [&](int chunk, RawSet &R) {
+        int i, k0;
+        locate(chunk, i, k0);
+        const int kprime = k0 + kp;
+        if constexpr (LOADER == 0) {
+            // one long row per channel; pieces are dword aligned (16-byte aligned when S % EPP == 0);
+            // only the last piece of a row can be partial, and only A is masked for it
+            const int hi = min(EPP, a.S - kprime);
+            if (!is_slow_a(i, k0)) {
+                const E *pa_ = dyg + (size_t)i * dy_ex + kprime;
+#pragma unroll
+                for (int q = 0; q < PA; ++q) {
+                    u32x4_a4 v = {0u, 0u, 0u, 0u};
+                    if (hi > 0 && a_row_off[q] >= 0) v = *reinterpret_cast<const u32x4_a4 *>(pa_ + a_row_off[q]);
+                    R.ra[q].d[0] = v.x; R.ra[q].d[1] = v.y; R.ra[q].d[2] = v.z; R.ra[q].d[3] = v.w;
+                    R.ma[q] = (uint32_t)max(hi, 0);
+                }
+            }
+            if (!is_slow_b(i, k0)) {
+                const E *pb_ = xg + (size_t)i * x_ex + kprime;
+#pragma unroll
+                for (int q = 0; q < PB; ++q) {
+                    const int j = n0 + row0 + 32 * q;
+                    u32x4_a4 v = {0u, 0u, 0u, 0u};
+                    if (hi > 0 && j < a.J) v = *reinterpret_cast<const u32x4_a4 *>(pb_ + (size_t)j * a.S);
+                    R.rb[q].d[0] = v.x; R.rb[q].d[1] = v.y; R.rb[q].d[2] = v.z; R.rb[q].d[3] = v.w;
+                }
+            }
+        } else {
+            const int oh = kprime / a.kcolsp, ow0 = kprime - oh * a.kcolsp;
+            const bool k_ok = oh < a.oh;
+            if (!is_slow_a(i, k0)) {
+                // A: dY_i[m, oh, ow0 .. ow0+EPP)
+                const E *ex_a = dyg + (size_t)i * dy_ex;
+                const int koff = k_ok ? oh * a.ow + ow0 : 0;
+                const int hi_a = k_ok ? min(a.ow - ow0, EPP) : 0;
+#pragma unroll
+                for (int q = 0; q < PA; ++q) {
+                    const bool ok = a_row_off[q] >= 0 && hi_a > 0;
+                    const E *src = ex_a + (ok ? a_row_off[q] + koff : 0);
+                    R.ra[q] = piece_load<BF16, 1>(src);
+                    R.ma[q] = ((uint32_t)(reinterpret_cast<uintptr_t>(src) >> 1) & 1u) | ((uint32_t)(ok ? hi_a : 0) << 16);
+                }
+            }
+            if (!is_slow_b(i, k0)) {
+                // B: X_i[ci, oh*s + dh, (ow0 + e)*s + dw]; only the image edge is masked here,
+                // positions past OW meet the zeros of A
+                const E *ex_b = xg + (size_t)i * x_ex;
+                const int ihs = oh * a.stride, iws = ow0 * a.stride;
+                const int koff = ihs * a.w + iws;
+#pragma unroll
+                for (int q = 0; q < PB; ++q) {
+                    const ColInfo ci = cols[row0 + 32 * q];
+                    const int ih = ihs + ci.dh;
+                    const int first = iws + ci.dw;                          // input column of e = 0
+                    int lo, hi;
+                    if constexpr (LOADER == 1) { lo = -first; hi = a.w - first; }
+                    else { lo = (1 - first) >> 1; hi = (a.w - first + 1) >> 1; }      // ceil(-first/2), ceil((W-first)/2)
+                    lo = min(max(lo, 0), EPP);
+                    hi = min(max(hi, lo), EPP);
+                    const bool ok = k_ok && (unsigned)ih < (unsigned)a.h && hi > lo;
+                    const E *src = ex_b + (ok ? ci.off + koff : 0);
+                    R.rb[q] = piece_load<BF16, LS>(src);
+                    R.mb[q] = ((uint32_t)(reinterpret_cast<uintptr_t>(src) >> 1) & 1u) | ((uint32_t)lo << 8) |
+                              ((uint32_t)(ok ? hi : lo) << 16);
+                }
+            }
+        }
+    };
 
-        const char *pa = sA + (wm * WT + (lane & 31)) * PITCH + (lane >> 5) * 16;
-        const char *pb = sB + (wn * WT + (lane & 31)) * PITCH + (lane >> 5) * 16;
+    // Finish the fetched pieces in registers and put the chunk into one LDS buffer (element by
+    // element for the chunks that may not use whole-dword reads).
+    auto stage = [&](int chunk, const RawSet &R, char *bufA, char *bufB) {
+        int i, k0;
+        locate(chunk, i, k0);
+        float f = 1.0f;
+        if constexpr (WEIGHTED) f = clip_factor(a.group_sqnorm[i], a.clip_c);
+        if (is_slow_a(i, k0)) {
+            slow_stage_a<BF16, MT, WEIGHTED>(bufA, dyg + (size_t)i * dy_ex, a.cout, a.S, a.oh, a.ow, a.kcolsp, m0, k0, f);
+        } else {
+#pragma unroll
+            for (int q = 0; q < PA; ++q) {
+                uint32_t v[4];
+                if constexpr (LOADER == 0) {
+                    v[0] = R.ra[q].d[0]; v[1] = R.ra[q].d[1]; v[2] = R.ra[q].d[2]; v[3] = R.ra[q].d[3];
+                    mask_piece<BF16>(v, 0, (int)R.ma[q]);
+                } else {
+                    piece_finish<BF16, 1>(v, R.ra[q], R.ma[q] & 1u, 0, (int)(R.ma[q] >> 16));
+                }
+                if constexpr (WEIGHTED) scale_regs<BF16, 4>(v, f);
+                *reinterpret_cast<uint4 *>(bufA + (row0 + 32 * q) * PITCH + (threadIdx.x & 7) * 16) =
+                    make_uint4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        if (is_slow_b(i, k0)) {
+            slow_stage_b<BF16, NT>(bufB, xg + (size_t)i * x_ex, cols, a.h, a.w, a.oh, a.ow, a.stride, a.kcolsp, k0);
+        } else {
+#pragma unroll
+            for (int q = 0; q < PB; ++q) {
+                uint32_t v[4];
+                if constexpr (LOADER == 0) { v[0] = R.rb[q].d[0]; v[1] = R.rb[q].d[1]; v[2] = R.rb[q].d[2]; v[3] = R.rb[q].d[3]; }
+                else piece_finish<BF16, LS>(v, R.rb[q], R.mb[q] & 1u, (int)((R.mb[q] >> 8) & 0xFFu), (int)(R.mb[q] >> 16));
+                *reinterpret_cast<uint4 *>(bufB + (row0 + 32 * q) * PITCH + (threadIdx.x & 7) * 16) =
+                    make_uint4(v[0], v[1], v[2], v[3]);
+            }
+        }
+    };
+
+    auto finish = [&](int i) {
+        // The epilogue may sit inside the chunk loop (several examples per workgroup).  Its index
+        // arithmetic is loop-invariant; passing the tile origin through an opaque copy keeps the
+        // compiler from hoisting ~100 registers of addresses across the MFMA loop.
+        int m0v = __builtin_amdgcn_readfirstlane(m0), n0v = __builtin_amdgcn_readfirstlane(n0);
+        asm volatile("" : "+s"(m0v), "+s"(n0v));
+        tile_epilogue<WAVES_N, TM, TN, WEIGHTED, BIAS>(acc, a, i, tile, tiles, m0v, n0v, wm, wn, lane, bias_here, red);
+    };
+
+    // MFMAs of one chunk out of one LDS buffer; then, in per-example mode without K slices, the
+    // epilogue of an example whose K has run out.
+    int chunk_in_ex = 0, ex = i_begin;
+    auto compute = [&](const char *bufA, const char *bufB) {
+        const char *pa = bufA + (wm * TM * 32 + (lane & 31)) * PITCH + (lane >> 5) * 16;
+        const char *pb = bufB + (wn * TN * 32 + (lane & 31)) * PITCH + (lane >> 5) * 16;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {       // 4 x 32 bytes of K per row
             uint4 fa[TM], fb[TN];
@@ -309,13 +577,13 @@ __global__ void __launch_bounds__(THREADS) conv_contract_kernel(const ConvArgs a
                     const bf16x8 va = __builtin_bit_cast(bf16x8, fa[tm]);
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            va, __builtin_bit_cast(bf16x8, fb[tn]), acc[tm][tn], 0, 0, 0);
+                        acc[tm * TN + tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            va, __builtin_bit_cast(bf16x8, fb[tn]), acc[tm * TN + tn], 0, 0, 0);
                     if constexpr (BIAS) {
                         if (bias_here) {
                             const uint4 one = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
-                            accb[tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, one),
-                                                                               accb[tm], 0, 0, 0);
+                            acc[TM * TN + tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                va, __builtin_bit_cast(bf16x8, one), acc[TM * TN + tm], 0, 0, 0);
                         }
                     }
                 }
@@ -330,207 +598,312 @@ __global__ void __launch_bounds__(THREADS) conv_contract_kernel(const ConvArgs a
                                              __uint_as_float(fb[tn].z), __uint_as_float(fb[tn].w)};
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bv[e], acc[tm][tn], 0, 0, 0);
+                            acc[tm * TN + tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bv[e], acc[tm * TN + tn], 0, 0, 0);
                     }
                     if constexpr (BIAS) {
                         if (bias_here) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e)
-                                accb[tm] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], 1.0f, accb[tm], 0, 0, 0);
+                                acc[TM * TN + tm] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], 1.0f, acc[TM * TN + tm], 0, 0, 0);
                         }
                     }
                 }
             }
         }
-
-    }
-
-    if constexpr (!WEIGHTED) {
-        // ---- epilogue of one example's tile: squared norm in registers, optional store
-        const int i = i_begin;
-        float ss = 0.0f;
-        const bool store = a.out_w != nullptr;
+        if constexpr (!WEIGHTED) {
+            if (a.ksplit == 1 && ++chunk_in_ex == cpe) {
+                finish(ex);
+                ++ex;
+                chunk_in_ex = 0;
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
+                for (int t = 0; t < NACC; ++t)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int j = n0 + wn * WT + tn * 32 + (lane & 31);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float v = acc[tm][tn][r];
-                    ss += v * v;                  // rows/columns beyond the matrix are exact zeros
-                    if (store) {
-                        const int m = m0 + wm * WT + tm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                        if (m < a.cout && j < a.J)
-                            a.out_w[(size_t)i * a.out_stride_w + (size_t)m * a.J + j] = v;
-                    }
-                }
-            }
-            if constexpr (BIAS) {
-                if (bias_here && (lane & 31) == 0) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float v = accb[tm][r];
-                        ss += v * v;
-                        const int m = m0 + wm * WT + tm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                        if (store && m < a.cout) a.out_b[(size_t)i * a.out_stride_b + m] = v;
-                    }
-                }
+                    for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
             }
         }
-        const float tot = block_sum<4>(ss, red);
-        if (threadIdx.x == 0) a.partials[(size_t)i * tiles + tile] = tot;
+    };
+
+    // ---- software pipeline, one barrier per chunk:
+    //   loads of chunk c+2 are issued, chunk c runs out of LDS buffer c%2, chunk c+1 (whose loads
+    //   were issued one step earlier) is finished into buffer (c+1)%2, barrier.
+    char *a0 = sA, *a1 = sA + MT * PITCH, *b0 = sB, *b1 = sB + NT * PITCH;
+    if (n_chunks > 0) fetch(0, set0);
+    if (n_chunks > 1) fetch(1, set1);
+    if (n_chunks > 0) stage(0, set0, a0, b0);
+    __syncthreads();
+    for (int chunk = 0; chunk < n_chunks; chunk += 2) {
+        if (chunk + 2 < n_chunks) fetch(chunk + 2, set0);
+        compute(a0, b0);
+        if (chunk + 1 < n_chunks) stage(chunk + 1, set1, a1, b1);
+        __syncthreads();
+        if (chunk + 1 >= n_chunks) break;
+        if (chunk + 3 < n_chunks) fetch(chunk + 3, set1);
+        compute(a1, b1);
+        if (chunk + 2 < n_chunks) stage(chunk + 2, set0, a0, b0);
+        __syncthreads();
     }
 
-    if constexpr (WEIGHTED) {
-        float *ow = a.out_w + (size_t)unit * a.out_stride_w;
-        float *ob = a.out_b ? a.out_b + (size_t)unit * a.out_stride_b : nullptr;
+    if (a.ksplit == 1) {
+        if constexpr (WEIGHTED) finish(0);
+        return;
+    }
+
+    // ---- slices of one tile meet in the workspace; a second kernel (conv_fixup_kernel) adds
+    // them in slice order and runs the epilogue.  Plain stores: the kernel boundary orders them.
+    const int group = WEIGHTED ? tile : (unit * tiles + tile);     // ex_per_wg == 1 when K is sliced
+    float *mine = a.ws_part + ((size_t)group * a.ksplit + split) * (NACC * 16 * THREADS);
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
+    for (int t = 0; t < NACC; ++t)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int j = n0 + wn * WT + tn * 32 + (lane & 31);
+        for (int r = 0; r < 16; ++r) mine[(t * 16 + r) * THREADS + threadIdx.x] = acc[t][r];
+}
+
+// One workgroup per group of slices: add the partial tiles in slice order (same bits every
+// run), then the same epilogue as the unsliced case.
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS>
+__global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const ConvArgs a)
+{
+    constexpr int MT = WAVES_M * TM * 32, NT = WAVES_N * TN * 32;
+    constexpr int NACC = TM * TN + (BIAS ? TM : 0);
+    __shared__ float red[4];
+    const int tiles = a.tiles_m * a.tiles_n;
+    const int group = blockIdx.x;
+    const int i = WEIGHTED ? 0 : group / tiles;
+    const int tile = WEIGHTED ? group : group - i * tiles;
+    const int tile_m = tile / a.tiles_n, tile_n = tile - tile_m * a.tiles_n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WAVES_N, wn = wave - wm * WAVES_N;
+    f32x16 acc[NACC];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * WT + tm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                    if (m < a.cout && j < a.J) {
-                        float *p = ow + (size_t)m * a.J + j;
-                        *p = a.accumulate ? *p + acc[tm][tn][r] : acc[tm][tn][r];
-                    }
-                }
-            }
-            if constexpr (BIAS) {
-                if (bias_here && (lane & 31) == 0) {
+    for (int t = 0; t < NACC; ++t)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int m = m0 + wm * WT + tm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                        if (m < a.cout) ob[m] = a.accumulate ? ob[m] + accb[tm][r] : accb[tm][r];
-                    }
-                }
-            }
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+    // slice order is fixed; four slices' worth of loads are in flight per accumulator tile
+    const size_t slice = (size_t)NACC * 16 * THREADS;
+    const float *base = a.ws_part + (size_t)group * a.ksplit * slice + threadIdx.x;
+#pragma unroll
+    for (int t = 0; t < NACC; ++t) {
+        int s = 0;
+        for (; s + 4 <= a.ksplit; s += 4) {
+            float tmp[4][16];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmp[u][r] = base[(size_t)(s + u) * slice + (t * 16 + r) * THREADS];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] += tmp[u][r];
+        }
+        for (; s < a.ksplit; ++s) {
+            float tmp[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tmp[r] = base[(size_t)s * slice + (t * 16 + r) * THREADS];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] += tmp[r];
         }
     }
+    tile_epilogue<WAVES_N, TM, TN, WEIGHTED, BIAS>(acc, a, i, tile, tiles, tile_m * MT, tile_n * NT, wm, wn, lane,
+                                                  BIAS && tile_n == 0 && wn == 0, red);
 }
 
 // ------------------------------------------------------------------------------------ host
 
-static int pow2_divisor(int s, int vmax)
+enum TileShape { T64 = 0, T128 = 1, T256x64 = 2, T64x256 = 3 };
+static const int kTileM[4] = {64, 128, 256, 64};
+static const int kTileN[4] = {64, 128, 64, 256};
+static const char *kTileName[4] = {"64x64", "128x128", "256x64", "64x256"};
+
+struct FullPlan {
+    int shape, tiles_m, tiles_n;
+    int kcolsp, chunks_per_ex;
+    int ksplit, chunks_per_split, ex_per_split, ex_per_wg;
+    int nacc;               // accumulator tiles per wave
+    int groups;             // groups of slices (counters)
+    size_t part_floats;     // floats of partial tiles in the workspace
+    // geometry as the kernel sees it (1x1 stride-1 convs are flattened to one long row)
+    int h, w, oh, ow;
+};
+
+static FullPlan full_plan(const Geo &g, int mode)
 {
-    int v = vmax;
-    while (v > 1 && (s % v) != 0) v >>= 1;
-    return v;
+    FullPlan p;
+    const int J = g.cin * g.kh * g.kw;
+    const int S = g.oh * g.ow;
+    const bool flat = (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0);
+    p.h = flat ? 1 : g.h; p.w = flat ? S : g.w; p.oh = flat ? 1 : g.oh; p.ow = flat ? S : g.ow;
+    const int epp = g.bf16 ? 8 : 4, kc = g.bf16 ? 64 : 32;
+    p.kcolsp = (p.ow + epp - 1) / epp * epp;
+    p.chunks_per_ex = (int)(((long long)p.oh * p.kcolsp + kc - 1) / kc);
+
+    p.shape = (g.cout > 64 && J > 64) ? T128 : T64;
+    p.tiles_m = (g.cout + kTileM[p.shape] - 1) / kTileM[p.shape];
+    p.tiles_n = (J + kTileN[p.shape] - 1) / kTileN[p.shape];
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int per_wave_tiles = (p.shape == T64) ? 1 : 4;
+    p.nacc = per_wave_tiles + (g.has_bias ? (p.shape == T64 ? 1 : 2) : 0);
+    const size_t tile_floats = (size_t)p.nacc * 16 * THREADS;
+
+    p.ksplit = 1; p.chunks_per_split = p.chunks_per_ex; p.ex_per_split = g.n; p.ex_per_wg = 1;
+    if (mode == MODE_WEIGHTED) {
+        // example ranges: enough workgroups to fill the chip, with the partial tiles that are
+        // written and read back (cache-resident in practice) kept below ~100 MB
+        const double in_bytes = (double)g.n * (double)(g.x_elems + g.dy_elems) * (g.bf16 ? 2 : 4);
+        (void)in_bytes;
+        long long want = (512 + tiles - 1) / tiles;
+        const long long cap = (long long)(96.0e6 / (4.0 * (double)tiles * (double)tile_floats));
+        if (want > cap) want = cap;
+        if (want > g.n) want = g.n;
+        if (want < 1) want = 1;
+        p.ex_per_split = (int)((g.n + want - 1) / want);
+        p.ksplit = (g.n + p.ex_per_split - 1) / p.ex_per_split;
+        p.groups = tiles;
+    } else {
+        const long long units = (long long)g.n * tiles;
+        if (units < 512 && p.chunks_per_ex >= 8) {
+            long long want = (768 + units - 1) / units;
+            if (want > p.chunks_per_ex / 4) want = p.chunks_per_ex / 4;
+            if (want < 1) want = 1;
+            p.chunks_per_split = (int)((p.chunks_per_ex + want - 1) / want);
+            p.ksplit = (p.chunks_per_ex + p.chunks_per_split - 1) / p.chunks_per_split;
+        } else if (units > 1536 && p.chunks_per_ex <= 4) {
+            long long e = units / 1024;
+            if (e > 8) e = 8;
+            if (e > g.n) e = g.n;
+            p.ex_per_wg = (int)(e < 1 ? 1 : e);
+        }
+        p.groups = g.n * tiles;
+    }
+    p.part_floats = (p.ksplit > 1) ? (size_t)p.groups * p.ksplit * tile_floats : 0;
+    return p;
 }
 
 ConvPlan conv_plan(const Geo &g, int mode)
 {
+    const FullPlan f = full_plan(g, mode);
     ConvPlan p;
-    const int J = g.cin * g.kh * g.kw;
-    p.big = (g.cout > 64 && J > 64) ? 1 : 0;
-    const int t = p.big ? 128 : 64;
-    p.tiles_m = (g.cout + t - 1) / t;
-    p.tiles_n = (J + t - 1) / t;
-    p.splits = 1;
-    if (mode == MODE_WEIGHTED) {
-        const int tiles = p.tiles_m * p.tiles_n;
-        int want = (256 + tiles - 1) / tiles;
-        if (want > g.n) want = g.n;
-        if (want < 1) want = 1;
-        const int per = (g.n + want - 1) / want;
-        p.splits = (g.n + per - 1) / per;
-    }
+    p.big = f.shape;
+    p.tiles_m = f.tiles_m; p.tiles_n = f.tiles_n; p.splits = f.ksplit;
     return p;
 }
 
+// workspace: [norm partials n*tiles floats (per-example mode)] [partial tiles]
+static size_t align16(size_t b) { return (b + 15) & ~(size_t)15; }
+
 size_t conv_ws_bytes(const Geo &g, int mode)
 {
-    const ConvPlan p = conv_plan(g, mode);
-    if (mode == MODE_WEIGHTED) return p.splits > 1 ? (size_t)p.splits * (g.pw + g.pb) * sizeof(float) : 0;
-    return (size_t)g.n * p.tiles_m * p.tiles_n * sizeof(float);
+    const FullPlan f = full_plan(g, mode);
+    size_t b = 0;
+    if (mode != MODE_WEIGHTED) b += align16((size_t)g.n * f.tiles_m * f.tiles_n * sizeof(float));
+    if (f.ksplit > 1) b += f.part_floats * sizeof(float);
+    return b;
 }
 
 const char *conv_variant_name(const Geo &g, int mode)
 {
-    static const char *names[2][2][2][2] = {
-        {{{"conv_contract<f32,64x64,per_example>", "conv_contract<f32,64x64,per_example,bias>"},
-          {"conv_contract<f32,64x64,weighted>", "conv_contract<f32,64x64,weighted,bias>"}},
-         {{"conv_contract<f32,128x128,per_example>", "conv_contract<f32,128x128,per_example,bias>"},
-          {"conv_contract<f32,128x128,weighted>", "conv_contract<f32,128x128,weighted,bias>"}}},
-        {{{"conv_contract<bf16,64x64,per_example>", "conv_contract<bf16,64x64,per_example,bias>"},
-          {"conv_contract<bf16,64x64,weighted>", "conv_contract<bf16,64x64,weighted,bias>"}},
-         {{"conv_contract<bf16,128x128,per_example>", "conv_contract<bf16,128x128,per_example,bias>"},
-          {"conv_contract<bf16,128x128,weighted>", "conv_contract<bf16,128x128,weighted,bias>"}}}};
-    const ConvPlan p = conv_plan(g, mode);
-    return names[g.bf16 ? 1 : 0][p.big][mode == MODE_WEIGHTED ? 1 : 0][g.has_bias ? 1 : 0];
+    static char names[2][4][2][2][64];
+    static bool init = false;
+    if (!init) {
+        for (int b = 0; b < 2; ++b)
+            for (int s = 0; s < 4; ++s)
+                for (int w = 0; w < 2; ++w)
+                    for (int bi = 0; bi < 2; ++bi)
+                        snprintf(names[b][s][w][bi], 64, "conv_contract<%s,%s,%s%s>", b ? "bf16" : "f32", kTileName[s],
+                                 w ? "weighted" : "per_example", bi ? ",bias" : "");
+        init = true;
+    }
+    const FullPlan f = full_plan(g, mode);
+    return names[g.bf16 ? 1 : 0][f.shape][mode == MODE_WEIGHTED ? 1 : 0][g.has_bias ? 1 : 0];
 }
 
-template <bool BF16, bool BIG, bool WEIGHTED>
-static void launch_variant(const ConvArgs &a, bool bias, unsigned blocks, hipStream_t s)
+template <int WM, int WN, int TM, int TN>
+static void launch_fixup(const ConvArgs &a, bool weighted, bool bias, unsigned groups, hipStream_t s)
 {
-    if (bias)
-        hipLaunchKernelGGL((conv_contract_kernel<BF16, BIG, WEIGHTED, true>), dim3(blocks), dim3(THREADS), 0, s, a);
-    else
-        hipLaunchKernelGGL((conv_contract_kernel<BF16, BIG, WEIGHTED, false>), dim3(blocks), dim3(THREADS), 0, s, a);
+    if (weighted) {
+        if (bias) hipLaunchKernelGGL((conv_fixup_kernel<WM, WN, TM, TN, true, true>), dim3(groups), dim3(THREADS), 0, s, a);
+        else hipLaunchKernelGGL((conv_fixup_kernel<WM, WN, TM, TN, true, false>), dim3(groups), dim3(THREADS), 0, s, a);
+    } else {
+        if (bias) hipLaunchKernelGGL((conv_fixup_kernel<WM, WN, TM, TN, false, true>), dim3(groups), dim3(THREADS), 0, s, a);
+        else hipLaunchKernelGGL((conv_fixup_kernel<WM, WN, TM, TN, false, false>), dim3(groups), dim3(THREADS), 0, s, a);
+    }
+}
+
+template <bool BF16, int WM, int WN, int TM, int TN, int SIMPLE>
+static void launch_shape2(const ConvArgs &a, bool weighted, bool bias, unsigned blocks, hipStream_t s)
+{
+    if (weighted) {
+        if (bias) hipLaunchKernelGGL((conv_contract_kernel<BF16, WM, WN, TM, TN, true, true, SIMPLE>), dim3(blocks), dim3(THREADS), 0, s, a);
+        else hipLaunchKernelGGL((conv_contract_kernel<BF16, WM, WN, TM, TN, true, false, SIMPLE>), dim3(blocks), dim3(THREADS), 0, s, a);
+    } else {
+        if (bias) hipLaunchKernelGGL((conv_contract_kernel<BF16, WM, WN, TM, TN, false, true, SIMPLE>), dim3(blocks), dim3(THREADS), 0, s, a);
+        else hipLaunchKernelGGL((conv_contract_kernel<BF16, WM, WN, TM, TN, false, false, SIMPLE>), dim3(blocks), dim3(THREADS), 0, s, a);
+    }
+}
+
+template <bool BF16, int WM, int WN, int TM, int TN>
+static void launch_shape(const ConvArgs &a, int loader, bool weighted, bool bias, unsigned blocks, hipStream_t s)
+{
+    if (loader == 0) launch_shape2<BF16, WM, WN, TM, TN, 0>(a, weighted, bias, blocks, s);
+    else if (loader == 1) launch_shape2<BF16, WM, WN, TM, TN, 1>(a, weighted, bias, blocks, s);
+    else launch_shape2<BF16, WM, WN, TM, TN, 2>(a, weighted, bias, blocks, s);
 }
 
 dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
                       hipStream_t s)
 {
-    const ConvPlan p = conv_plan(g, mode);
+    const FullPlan f = full_plan(g, mode);
+    const bool weighted = mode == MODE_WEIGHTED;
     ConvArgs a;
     a.x = x; a.dy = dy;
-    a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = g.h; a.w = g.w; a.kh = g.kh; a.kw = g.kw;
-    a.stride = g.stride; a.pad = g.pad; a.oh = g.oh; a.ow = g.ow;
+    a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = f.h; a.w = f.w; a.kh = g.kh; a.kw = g.kw;
+    a.stride = g.stride; a.pad = g.pad; a.oh = f.oh; a.ow = f.ow;
     a.J = g.cin * g.kh * g.kw;
     a.S = g.oh * g.ow;
-    a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n;
-    a.splits = p.splits;
-    a.ex_per_split = (g.n + p.splits - 1) / p.splits;
+    a.tiles_m = f.tiles_m; a.tiles_n = f.tiles_n;
+    a.kcolsp = f.kcolsp; a.chunks_per_ex = f.chunks_per_ex;
+    a.ksplit = f.ksplit; a.chunks_per_split = f.chunks_per_split;
+    a.ex_per_split = f.ex_per_split; a.ex_per_wg = f.ex_per_wg;
     a.group_sqnorm = group_sqnorm; a.clip_c = clip_c;
-    a.b_direct = (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0) ? 1 : 0;
-    const int vmax = g.bf16 ? 8 : 4;
-    a.va = pow2_divisor(a.S, vmax);
-    a.vb = a.b_direct ? pow2_divisor(g.h * g.w, vmax) : 1;
+    a.out_w = out_w; a.out_b = out_b;
+    a.out_stride_w = out_stride ? out_stride : g.pw;
+    a.out_stride_b = out_stride ? out_stride : g.pb;
+    const int tiles = f.tiles_m * f.tiles_n;
+    char *w = static_cast<char *>(ws);
     a.partials = nullptr;
-    a.accumulate = 0;
-    const int tiles = p.tiles_m * p.tiles_n;
-    int units;
-    if (mode == MODE_WEIGHTED) {
-        units = p.splits;
-        if (p.splits == 1) {
-            a.out_w = out_w; a.out_b = out_b; a.out_stride_w = 0; a.out_stride_b = 0; a.accumulate = 1;
-        } else {
-            float *w = static_cast<float *>(ws);
-            a.out_w = w; a.out_stride_w = g.pw + g.pb;
-            a.out_b = w + g.pw; a.out_stride_b = g.pw + g.pb;
+    if (!weighted) {
+        a.partials = reinterpret_cast<float *>(w);
+        w += align16((size_t)g.n * tiles * sizeof(float));
+    }
+    a.ws_part = (f.ksplit > 1) ? reinterpret_cast<float *>(w) : nullptr;
+    long long total;
+    if (weighted) total = (long long)tiles * f.ksplit;
+    else total = (long long)((g.n + f.ex_per_wg - 1) / f.ex_per_wg) * tiles * f.ksplit;
+    const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
+    const bool bias = g.has_bias != 0;
+    const bool flat = (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0);
+    const int loader = (flat && (!g.bf16 || a.S % 2 == 0)) ? 0 : (g.stride == 2 ? 2 : 1);
+    a.force_slow = (g.stride > 2) ? 1 : 0;
+    if (g.bf16) {
+        switch (f.shape) {
+        case T64: launch_shape<true, 2, 2, 1, 1>(a, loader, weighted, bias, blocks, s); break;
+        default: launch_shape<true, 2, 2, 2, 2>(a, loader, weighted, bias, blocks, s); break;
         }
     } else {
-        units = g.n;
-        a.out_w = out_w; a.out_b = out_b;
-        a.out_stride_w = out_stride ? out_stride : g.pw;
-        a.out_stride_b = out_stride ? out_stride : g.pb;
-        a.partials = static_cast<float *>(ws);
-    }
-    const unsigned blocks = (unsigned)(((tiles * units + 7) / 8) * 8);
-    const bool bias = g.has_bias != 0;
-    const bool weighted = mode == MODE_WEIGHTED;
-    if (g.bf16) {
-        if (p.big) { if (weighted) launch_variant<true, true, true>(a, bias, blocks, s); else launch_variant<true, true, false>(a, bias, blocks, s); }
-        else       { if (weighted) launch_variant<true, false, true>(a, bias, blocks, s); else launch_variant<true, false, false>(a, bias, blocks, s); }
-    } else {
-        if (p.big) { if (weighted) launch_variant<false, true, true>(a, bias, blocks, s); else launch_variant<false, true, false>(a, bias, blocks, s); }
-        else       { if (weighted) launch_variant<false, false, true>(a, bias, blocks, s); else launch_variant<false, false, false>(a, bias, blocks, s); }
+        if (f.shape == T64) launch_shape<false, 2, 2, 1, 1>(a, loader, weighted, bias, blocks, s);
+        else launch_shape<false, 2, 2, 2, 2>(a, loader, weighted, bias, blocks, s);
     }
     dp_status st = check_launch("conv_contract");
     if (st != DP_OK) return st;
-    if (weighted) {
-        if (p.splits > 1) {
-            // slices hold [w | b] back to back; w and b accumulators are separate tensors
-            st = launch_add_partial_sums(static_cast<float *>(ws), p.splits, g.pw + g.pb, g.pw, out_w, out_b, s);
+    if (f.ksplit > 1) {
+        switch (f.shape) {
+        case T64: launch_fixup<2, 2, 1, 1>(a, weighted, bias, f.groups, s); break;
+        default: launch_fixup<2, 2, 2, 2>(a, weighted, bias, f.groups, s); break;
         }
-    } else if (sqnorm) {
-        st = launch_sum_partials(static_cast<float *>(ws), g.n, tiles, sqnorm, s);
+        st = check_launch("conv_fixup");
+        if (st != DP_OK) return st;
     }
+    if (!weighted && sqnorm) st = launch_sum_partials(a.partials, g.n, tiles, sqnorm, s);
     return st;
 }
 

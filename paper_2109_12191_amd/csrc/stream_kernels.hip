@@ -5,45 +5,50 @@
 namespace dp {
 
 // ------------------------------------------------------------------------------------------
-// sqnorm[i] = sum_t partials[i, t], t in increasing order (fixed order => reproducible bits).
+// sqnorm[i] = sum_t partials[i, t].  One wavefront per example: lane l adds tiles l, l+64, ...
+// in order, then a fixed xor-shuffle tree combines the lanes (same bits on every run).
 __global__ void __launch_bounds__(256) sum_partials_kernel(const float *__restrict__ partials, int n,
                                                             int per_example, float *__restrict__ sqnorm)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     if (i >= n) return;
     const float *p = partials + (size_t)i * per_example;
     float s = 0.0f;
-    for (int t = 0; t < per_example; ++t) s += p[t];
-    sqnorm[i] = s;
+    for (int t = lane; t < per_example; t += 64) s += p[t];
+    s = wave_sum(s);
+    if (lane == 0) sqnorm[i] = s;
 }
 
 dp_status launch_sum_partials(const float *partials, int n, int per_example, float *sqnorm, hipStream_t s)
 {
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partials, n, per_example,
-                       sqnorm);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((n + 3) / 4), dim3(256), 0, s, partials, n, per_example, sqnorm);
     return check_launch("sum_partials");
 }
 
 // ------------------------------------------------------------------------------------------
-// H2: group_sqnorm[g, i] = sum_{l : group_of_layer[l] == g} layer_sqnorm[l, i], l increasing.
+// H2: group_sqnorm[g, i] = sum_{l : group_of_layer[l] == g} layer_sqnorm[l, i].  One wavefront
+// per (group, example): lane l takes layers l, l+64, ... in order, then the fixed shuffle tree.
 __global__ void __launch_bounds__(256) norms_kernel(const float *__restrict__ layer_sqnorm,
                                                      const int32_t *__restrict__ group_of_layer, int n_layers,
                                                      int n, int n_groups, float *__restrict__ group_sqnorm)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     const int g = blockIdx.y;
     if (i >= n) return;
     float s = 0.0f;
-    for (int l = 0; l < n_layers; ++l)
+    for (int l = lane; l < n_layers; l += 64)
         if (group_of_layer[l] == g) s += layer_sqnorm[(size_t)l * n + i];
-    group_sqnorm[(size_t)g * n + i] = s;
+    s = wave_sum(s);
+    if (lane == 0) group_sqnorm[(size_t)g * n + i] = s;
 }
 
 dp_status launch_norms(const float *layer_sqnorm, const int32_t *group_of_layer, int n_layers, int n,
                        int n_groups, float *group_sqnorm, hipStream_t s)
 {
-    hipLaunchKernelGGL(norms_kernel, dim3((n + 255) / 256, n_groups), dim3(256), 0, s, layer_sqnorm,
-                       group_of_layer, n_layers, n, n_groups, group_sqnorm);
+    hipLaunchKernelGGL(norms_kernel, dim3((n + 3) / 4, n_groups), dim3(256), 0, s, layer_sqnorm, group_of_layer,
+                       n_layers, n, n_groups, group_sqnorm);
     return check_launch("norms");
 }
 

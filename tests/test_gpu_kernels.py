@@ -76,6 +76,13 @@ CONV_CASES = [
     ("7x7 s2 cin3", conv(3, 64, 7, 2, 32), 2),
     ("5x3 rect nopad", Layer("conv", 6, 9, 11, 13, 5, 3, 1, 0, True), 2),
     ("long K several chunks", conv(8, 24, 3, 1, 40, bias=True), 2),
+    ("tall tile 256x64", conv(40, 200, 1, 1, 12), 3),
+    ("wide tile 64x256", conv(30, 48, 3, 1, 12, bias=True), 3),
+    ("wide tile long K sliced", conv(24, 64, 3, 1, 56), 1),
+    ("many examples per workgroup", conv(8, 8, 1, 1, 4, bias=True), 1700),
+    ("3x3 s1 odd width 7", conv(72, 136, 3, 1, 7), 5),
+    ("3x3 s2 odd width 15->8", conv(16, 80, 3, 2, 15), 3),
+    ("stride 3", Layer("conv", 6, 10, 14, 17, 3, 3, 3, 1, False), 2),
 ]
 
 
@@ -182,6 +189,9 @@ RECOMPUTE_CASES = [
     ("conv 1x1 S=49", conv(96, 136, 1, 1, 7), 6),
     ("conv 3x3 s2", conv(24, 40, 3, 2, 14), 5),
     ("conv small long K", conv(8, 24, 3, 1, 40, bias=True), 3),
+    ("conv many examples", conv(64, 200, 1, 1, 7), 40),
+    ("conv wide tile", conv(30, 48, 3, 1, 12, bias=True), 6),
+    ("conv tall tile", conv(40, 200, 1, 1, 12), 6),
     ("dense", dense(300, 37, tokens=2), 7),
     ("dense fc", dense(784, 256), 6),
     ("gn", gn_affine(16, 9, 4), 6),
