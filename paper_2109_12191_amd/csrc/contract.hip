@@ -381,7 +381,8 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
     const size_t x_ex = (size_t)a.cin * a.h * a.w, dy_ex = (size_t)a.cout * a.S;
     const E *xg = static_cast<const E *>(a.x), *dyg = static_cast<const E *>(a.dy);
 
-    // per-thread constants of the staging map: piece c = tid + 256 q -> row c / 8, K-piece c % 8
+    // per-thread constants of the staging map: piece c = tid + 256 q -> row c / 8, K-piece c % 8.
+    // Everything that does not change from chunk to chunk is computed here, once.
     const int kp = (threadIdx.x & 7) * EPP;
     const int row0 = threadIdx.x >> 3;
     int a_row_off[PA];                       // (m0 + row) * S, or -1 beyond Cout
@@ -389,6 +390,19 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
     for (int q = 0; q < PA; ++q) {
         const int m = m0 + row0 + 32 * q;
         a_row_off[q] = (m < a.cout) ? m * a.S : -1;
+    }
+    int b_off[PB], b_dhw[PB];                // B rows: element offset of the tap, packed (dh, dw)
+#pragma unroll
+    for (int q = 0; q < PB; ++q) {
+        if constexpr (LOADER == 0) {
+            const int j = n0 + row0 + 32 * q;
+            b_off[q] = (j < a.J) ? j * a.S : -1;
+            b_dhw[q] = 0;
+        } else {
+            const ColInfo ci = cols[row0 + 32 * q];
+            b_off[q] = ci.off;
+            b_dhw[q] = ((int)ci.dh << 16) | ((int)ci.dw & 0xFFFF);
+        }
     }
 
     f32x16 acc[NACC];
@@ -408,48 +422,57 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
         Raw<RA> ra[PA];
         Raw<RB> rb[PB];
         uint32_t ma[PA], mb[PB];
+        int i, c;                            // example and chunk (within the example) held by this set
     };
     RawSet set0, set1;
 
-    // Which chunks cannot use whole-dword reads (all wave-uniform).
+    // Which chunks cannot use whole-dword reads: thresholds on the chunk index within an example,
+    // computed once (all wave-uniform).
     const bool flat_tail = (LOADER == 0) && (a.S % EPP != 0);
     const bool all_slow = (LOADER != 0 || flat_tail) && (a.force_slow || x_ex < 512 || dy_ex < 512);
-    const int risk_a = (16 + a.ow - 1) / a.ow;          // trailing output rows within 32 bytes of a channel's end
-    const int risk_b = (16 + a.w - 1) / a.w;            // trailing input rows likewise
-    auto locate = [&](int chunk, int &i, int &k0) {
-        const int ie = chunk / cpe;
-        i = i_begin + ie;
-        k0 = (c_begin + chunk - ie * cpe) * KC;
-    };
-    auto is_slow_a = [&](int i, int k0) -> bool {
-        if constexpr (LOADER == 0) {
-            return flat_tail && (all_slow || (i == a.n - 1 && tile_m == a.tiles_m - 1 && k0 + KC >= a.S));
-        } else {
-            const int oh_hi = min(a.oh - 1, (k0 + KC - 1) / a.kcolsp);
-            return all_slow || (i == a.n - 1 && tile_m == a.tiles_m - 1 && oh_hi >= a.oh - risk_a);
+    int slow_a_from = 0x7FFFFFFF, slow_b_from = 0x7FFFFFFF, slow_b_until = -1;
+    if constexpr (LOADER == 0) {
+        if (flat_tail) slow_a_from = slow_b_from = (a.S - 1) / KC;       // the chunk that holds the row's tail
+    } else {
+        const int risk_a = (16 + a.ow - 1) / a.ow;      // trailing output rows within 32 bytes of a channel's end
+        const int risk_b = (16 + a.w - 1) / a.w;        // trailing input rows likewise
+        const int ta = (a.oh - risk_a) * a.kcolsp - KC + 1;              // first chunk reaching output row OH - risk_a
+        slow_a_from = ta <= 0 ? 0 : (ta + KC - 1) / KC;
+        const int need = a.h - risk_b - (a.kh - 1 - a.pad);             // input row reached by the lowest tap
+        const int ohb = need <= 0 ? 0 : (need + a.stride - 1) / a.stride;
+        if (ohb <= a.oh - 1) {
+            const int tb = ohb * a.kcolsp - KC + 1;
+            slow_b_from = tb <= 0 ? 0 : (tb + KC - 1) / KC;
         }
+        slow_b_until = ((a.pad / a.stride + 1) * a.kcolsp - 1) / KC;    // chunks touching rows that reach the top padding
+    }
+    auto is_slow_a = [&](int i, int c) -> bool {
+        return all_slow || (i == a.n - 1 && tile_m == a.tiles_m - 1 && c >= slow_a_from);
     };
-    auto is_slow_b = [&](int i, int k0) -> bool {
-        if constexpr (LOADER == 0) {
-            return flat_tail && (all_slow || (i == a.n - 1 && tile_n == a.tiles_n - 1 && k0 + KC >= a.S));
-        } else {
-            const int oh_lo = k0 / a.kcolsp;
-            const int oh_hi = min(a.oh - 1, (k0 + KC - 1) / a.kcolsp);
-            return all_slow || (i == 0 && tile_n == 0 && oh_lo * a.stride <= a.pad) ||
-                   (i == a.n - 1 && tile_n == a.tiles_n - 1 && oh_hi * a.stride + (a.kh - 1 - a.pad) >= a.h - risk_b);
-        }
+    auto is_slow_b = [&](int i, int c) -> bool {
+        return all_slow || (i == a.n - 1 && tile_n == a.tiles_n - 1 && c >= slow_b_from) ||
+               (i == 0 && tile_n == 0 && c <= slow_b_until);
     };
 
-    // Issue every global load of a chunk (no use of the data here, so no wait either).
-    auto fetch = [&](int chunk, RawSet &R) {
-        int i, k0;
-        locate(chunk, i, k0);
-        const int kprime = k0 + kp;
+    // Position of the next chunk to fetch: example, chunk within it, and this thread's (oh, ow0);
+    // advanced incrementally (no division in the loop).
+    int f_i = i_begin, f_c = c_begin;
+    const int kprime0 = c_begin * KC + kp;
+    const int oh0 = (LOADER == 0) ? 0 : kprime0 / a.kcolsp;
+    const int ow00 = (LOADER == 0) ? kprime0 : kprime0 - oh0 * a.kcolsp;
+    const int step_oh = (LOADER == 0) ? 0 : KC / a.kcolsp, step_ow = (LOADER == 0) ? KC : KC - step_oh * a.kcolsp;
+    int f_oh = oh0, f_ow = ow00;
+
+    // Issue every global load of the next chunk (no use of the data here, so no wait either).
+    auto fetch = [&](RawSet &R) {
+        const int i = f_i, c = f_c;
+        R.i = i; R.c = c;
         if constexpr (LOADER == 0) {
             // one long row per channel; pieces are dword aligned (16-byte aligned when S % EPP == 0);
             // only the last piece of a row can be partial, and only A is masked for it
+            const int kprime = f_ow;
             const int hi = min(EPP, a.S - kprime);
-            if (!is_slow_a(i, k0)) {
+            if (!is_slow_a(i, c)) {
                 const E *pa_ = dyg + (size_t)i * dy_ex + kprime;
 #pragma unroll
                 for (int q = 0; q < PA; ++q) {
@@ -459,20 +482,19 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
                     R.ma[q] = (uint32_t)max(hi, 0);
                 }
             }
-            if (!is_slow_b(i, k0)) {
+            if (!is_slow_b(i, c)) {
                 const E *pb_ = xg + (size_t)i * x_ex + kprime;
 #pragma unroll
                 for (int q = 0; q < PB; ++q) {
-                    const int j = n0 + row0 + 32 * q;
                     u32x4_a4 v = {0u, 0u, 0u, 0u};
-                    if (hi > 0 && j < a.J) v = *reinterpret_cast<const u32x4_a4 *>(pb_ + (size_t)j * a.S);
+                    if (hi > 0 && b_off[q] >= 0) v = *reinterpret_cast<const u32x4_a4 *>(pb_ + b_off[q]);
                     R.rb[q].d[0] = v.x; R.rb[q].d[1] = v.y; R.rb[q].d[2] = v.z; R.rb[q].d[3] = v.w;
                 }
             }
         } else {
-            const int oh = kprime / a.kcolsp, ow0 = kprime - oh * a.kcolsp;
+            const int oh = f_oh, ow0 = f_ow;
             const bool k_ok = oh < a.oh;
-            if (!is_slow_a(i, k0)) {
+            if (!is_slow_a(i, c)) {
                 // A: dY_i[m, oh, ow0 .. ow0+EPP)
                 const E *ex_a = dyg + (size_t)i * dy_ex;
                 const int koff = k_ok ? oh * a.ow + ow0 : 0;
@@ -485,7 +507,7 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
                     R.ma[q] = ((uint32_t)(reinterpret_cast<uintptr_t>(src) >> 1) & 1u) | ((uint32_t)(ok ? hi_a : 0) << 16);
                 }
             }
-            if (!is_slow_b(i, k0)) {
+            if (!is_slow_b(i, c)) {
                 // B: X_i[ci, oh*s + dh, (ow0 + e)*s + dw]; only the image edge is masked here,
                 // positions past OW meet the zeros of A
                 const E *ex_b = xg + (size_t)i * x_ex;
@@ -493,32 +515,36 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
                 const int koff = ihs * a.w + iws;
 #pragma unroll
                 for (int q = 0; q < PB; ++q) {
-                    const ColInfo ci = cols[row0 + 32 * q];
-                    const int ih = ihs + ci.dh;
-                    const int first = iws + ci.dw;                          // input column of e = 0
+                    const int ih = ihs + (b_dhw[q] >> 16);
+                    const int first = iws + (int)(short)(b_dhw[q] & 0xFFFF);   // input column of e = 0
                     int lo, hi;
                     if constexpr (LOADER == 1) { lo = -first; hi = a.w - first; }
                     else { lo = (1 - first) >> 1; hi = (a.w - first + 1) >> 1; }      // ceil(-first/2), ceil((W-first)/2)
                     lo = min(max(lo, 0), EPP);
                     hi = min(max(hi, lo), EPP);
                     const bool ok = k_ok && (unsigned)ih < (unsigned)a.h && hi > lo;
-                    const E *src = ex_b + (ok ? ci.off + koff : 0);
+                    const E *src = ex_b + (ok ? b_off[q] + koff : 0);
                     R.rb[q] = piece_load<BF16, LS>(src);
                     R.mb[q] = ((uint32_t)(reinterpret_cast<uintptr_t>(src) >> 1) & 1u) | ((uint32_t)lo << 8) |
                               ((uint32_t)(ok ? hi : lo) << 16);
                 }
             }
         }
+        // advance to the next chunk of this workgroup's stream
+        ++f_c;
+        f_oh += step_oh;
+        f_ow += step_ow;
+        if (LOADER != 0 && f_ow >= a.kcolsp) { f_ow -= a.kcolsp; ++f_oh; }
+        if (f_c == c_end) { f_c = c_begin; ++f_i; f_oh = oh0; f_ow = ow00; }
     };
 
     // Finish the fetched pieces in registers and put the chunk into one LDS buffer (element by
     // element for the chunks that may not use whole-dword reads).
-    auto stage = [&](int chunk, const RawSet &R, char *bufA, char *bufB) {
-        int i, k0;
-        locate(chunk, i, k0);
+    auto stage = [&](const RawSet &R, char *bufA, char *bufB) {
+        const int i = R.i, c = R.c, k0 = c * KC;
         float f = 1.0f;
         if constexpr (WEIGHTED) f = clip_factor(a.group_sqnorm[i], a.clip_c);
-        if (is_slow_a(i, k0)) {
+        if (is_slow_a(i, c)) {
             slow_stage_a<BF16, MT, WEIGHTED>(bufA, dyg + (size_t)i * dy_ex, a.cout, a.S, a.oh, a.ow, a.kcolsp, m0, k0, f);
         } else {
 #pragma unroll
@@ -535,7 +561,7 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
                     make_uint4(v[0], v[1], v[2], v[3]);
             }
         }
-        if (is_slow_b(i, k0)) {
+        if (is_slow_b(i, c)) {
             slow_stage_b<BF16, NT>(bufB, xg + (size_t)i * x_ex, cols, a.h, a.w, a.oh, a.ow, a.stride, a.kcolsp, k0);
         } else {
 #pragma unroll
@@ -627,19 +653,19 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
     //   loads of chunk c+2 are issued, chunk c runs out of LDS buffer c%2, chunk c+1 (whose loads
     //   were issued one step earlier) is finished into buffer (c+1)%2, barrier.
     char *a0 = sA, *a1 = sA + MT * PITCH, *b0 = sB, *b1 = sB + NT * PITCH;
-    if (n_chunks > 0) fetch(0, set0);
-    if (n_chunks > 1) fetch(1, set1);
-    if (n_chunks > 0) stage(0, set0, a0, b0);
+    if (n_chunks > 0) fetch(set0);
+    if (n_chunks > 1) fetch(set1);
+    if (n_chunks > 0) stage(set0, a0, b0);
     __syncthreads();
     for (int chunk = 0; chunk < n_chunks; chunk += 2) {
-        if (chunk + 2 < n_chunks) fetch(chunk + 2, set0);
+        if (chunk + 2 < n_chunks) fetch(set0);
         compute(a0, b0);
-        if (chunk + 1 < n_chunks) stage(chunk + 1, set1, a1, b1);
+        if (chunk + 1 < n_chunks) stage(set1, a1, b1);
         __syncthreads();
         if (chunk + 1 >= n_chunks) break;
-        if (chunk + 3 < n_chunks) fetch(chunk + 3, set1);
+        if (chunk + 3 < n_chunks) fetch(set1);
         compute(a1, b1);
-        if (chunk + 2 < n_chunks) stage(chunk + 2, set0, a0, b0);
+        if (chunk + 2 < n_chunks) stage(set0, a0, b0);
         __syncthreads();
     }
 

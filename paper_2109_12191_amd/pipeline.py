@@ -30,7 +30,7 @@ def _pad4(v: int) -> int:
 
 
 class PrivatiseStep:
-    def __init__(self, wl, device: str = "cuda:0", mode: str = "auto"):
+    def __init__(self, wl, device: str = "cuda:0", mode: str = "auto", streams: int = 1):
         B.load_library()
         self.wl = wl
         self.device = torch.device(device)
@@ -69,12 +69,19 @@ class PrivatiseStep:
         self.layer_sqnorm = torch.zeros((L, self.n), dtype=f32, device=dev)
         self.group_sqnorm = torch.zeros((self.n_groups, self.n), dtype=f32, device=dev)
         self.group_of_layer_dev = torch.tensor(self.group_of_layer, dtype=torch.int32, device=dev)
-        ws = 16
-        for d, form in zip(self.descs, self.form):
-            ws = max(ws, B.dp_workspace_bytes(d, B.DP_WS_PER_EXAMPLE_GRAD))
-            if form == "recompute":
-                ws = max(ws, B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE))
-        self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
+        # Workspaces.  With one stream all calls share one buffer (they run in order); with side
+        # streams the layers of a phase run concurrently, so each layer gets its own.
+        self.n_streams = max(1, int(streams))
+        need = [max(16, B.dp_workspace_bytes(d, B.DP_WS_PER_EXAMPLE_GRAD),
+                    B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE) if form == "recompute" else 0)
+                for d, form in zip(self.descs, self.form)]
+        if self.n_streams == 1:
+            shared = torch.empty(max(need), dtype=torch.uint8, device=dev)
+            self.ws_of = [shared] * L
+        else:
+            self.ws_of = [torch.empty(b, dtype=torch.uint8, device=dev) for b in need]
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
+        self.graph = None
         self.micro_steps_done = 0
         # optional timing probe (bench.py): an object with bracket(variant, flops, bytes) that
         # records an event on the current stream and returns the event to record afterwards
@@ -117,25 +124,45 @@ class PrivatiseStep:
         self.acc.zero_()
         self.micro_steps_done = 0
 
+    def _stream_of(self, li: int):
+        return self.side[li % self.n_streams] if self.side else None
+
+    def _fork(self):
+        main = torch.cuda.current_stream()
+        for st in self.side:
+            st.wait_stream(main)
+
+    def _join(self):
+        main = torch.cuda.current_stream()
+        for st in self.side:
+            main.wait_stream(st)
+
     def micro_step(self, inputs: Sequence):
-        """inputs: per layer (x, dy) device tensors of the workload's dtype, n examples each."""
+        """inputs: per layer (x, dy) device tensors of the workload's dtype, n examples each.
+        Layers of one phase are independent; with side streams they are spread over them and the
+        phases are separated by joins on the current stream."""
         L = len(self.layers)
         gs = self.p_mat
+        self._fork()
         for li in range(L):
             x, dy = inputs[li]
+            st = self._stream_of(li)
+            ws = self.ws_of[li]
             stop = self._bracket(li, 0)
             if self.form[li] == "materialise":
                 g_w = self.g[:, self.off_w[li]:]
                 g_b = self.g[:, self.off_b[li]:] if self.pb[li] else None
                 B.dp_per_example_grad(self.descs[li], x, dy, g_w.data_ptr(),
                                       g_b.data_ptr() if g_b is not None else None,
-                                      self.layer_sqnorm[li], self.ws, g_stride=gs, ws_bytes=self.ws.numel())
+                                      self.layer_sqnorm[li], ws, g_stride=gs, ws_bytes=ws.numel(), stream=st)
             else:
-                B.dp_per_example_grad(self.descs[li], x, dy, None, None, self.layer_sqnorm[li], self.ws,
-                                      ws_bytes=self.ws.numel())
+                B.dp_per_example_grad(self.descs[li], x, dy, None, None, self.layer_sqnorm[li], ws,
+                                      ws_bytes=ws.numel(), stream=st)
             if stop is not None:
                 stop.record()
+        self._join()
         B.dp_norms(self.layer_sqnorm, self.group_of_layer_dev, L, self.n, self.n_groups, self.group_sqnorm)
+        self._fork()
         if self.p_mat:
             if self.n_groups == 1:
                 # one clipping group: every materialised tensor shares the factors -> one pass
@@ -150,18 +177,23 @@ class PrivatiseStep:
                     B.dp_clip_accumulate(self.g[:, self.off_w[li]:].data_ptr(), self.group_sqnorm[g],
                                          self.group_clip[g], self.n, span,
                                          self.acc[self.off_w[li]:].data_ptr(), g_stride=gs)
+        k = 0
         for li in range(L):
             if self.form[li] != "recompute":
                 continue
             x, dy = inputs[li]
             g = self.group_of_layer[li]
+            ws = self.ws_of[li]
+            st = self.side[k % self.n_streams] if self.side else None
+            k += 1
             stop = self._bracket(li, 1)
             B.dp_clip_accumulate_recompute(self.descs[li], x, dy, self.group_sqnorm[g], self.group_clip[g],
                                            self.acc_w(li).data_ptr(),
                                            self.acc_b(li).data_ptr() if self.pb[li] else None,
-                                           self.ws, ws_bytes=self.ws.numel())
+                                           ws, ws_bytes=ws.numel(), stream=st)
             if stop is not None:
                 stop.record()
+        self._join()
         self.micro_steps_done += 1
 
     def finalize(self):
@@ -179,4 +211,21 @@ class PrivatiseStep:
         for inputs in inputs_per_micro_step:
             self.micro_step(inputs)
         self.finalize()
+        return self.out
+
+    def capture(self, inputs_per_micro_step: Sequence[Sequence]):
+        """Record one whole optimiser step on these (persistent) input tensors into a HIP graph:
+        replay() then re-issues every launch without host work.  Only kernels are recorded (the
+        accumulator is cleared by a fill kernel, never by a memset node)."""
+        assert self.probe is None or not getattr(self.probe, "enabled", False)
+        self.run(inputs_per_micro_step)          # warm-up outside capture (lazy module loads)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.run(inputs_per_micro_step)
+        self.graph = graph
+        return graph
+
+    def replay(self):
+        self.graph.replay()
         return self.out
