@@ -1,0 +1,462 @@
+// Per-example weight gradients of 3x3, stride-1, pad-1 convolutions (bf16) from raw image rows.
+//
+// Same contraction as the general kernel (H1 of the path; per example i
+//     dW_i[co, ci, kh, kw] = sum_{oh, ow} dY_i[co, oh, ow] * Xpad_i[ci, oh + kh - 1, ow + kw - 1]),
+// but the nine taps of one input channel are nine shifted views of the SAME rows of X, so a
+// workgroup stages each row once and builds all nine MFMA operands from it:
+//
+//   * a workgroup owns 64 output channels x 64 input channels x 9 taps of one example (four
+//     waves, each 32 co x 32 ci x 9 taps = nine 32x32 accumulator tiles) and walks chunks of R
+//     output rows;
+//   * per chunk it stages dY[64 co][R rows] (K-contiguous, rows padded to OWP = W rounded up to
+//     8) and X[64 ci][R + 2 rows][WP = OWP + 8 columns] into LDS; X is stored with column
+//     c = iw + 1, zeros for iw = -1, iw >= W and rows outside the image, so every tap reads
+//     plain in-range LDS;
+//   * per 16 values of K a lane reads 16 bytes of dY and, per kernel row kh, 20 bytes of X
+//     starting at column ow0: tap kw = 0 is dwords 0..3, kw = 1 the same five dwords shifted by
+//     one element, kw = 2 dwords 1..4 -- nine MFMAs from four LDS reads.
+//
+// Against the general kernel this cuts global/L2 reads of X by ~9x (each row is fetched once
+// per workgroup instead of once per tap) and LDS reads per MFMA by ~3x.
+//
+// K may be sliced over workgroups (few tiles, long K): slices store their accumulators in the
+// workspace and a second kernel adds them in slice order, so results are run-to-run identical.
+#include "internal.h"
+#include "pieces.h"
+
+#include <cstdio>
+
+namespace dp {
+
+namespace {
+
+constexpr int C3_THREADS = 256;
+
+struct C3Args {
+    const uint16_t *x, *dy;
+    float *out_w;                     // per-example gradients (may be null) or, weighted, the accumulator
+    size_t out_stride;
+    float *partials;                  // [n, tiles] partial squared norms
+    float *ws_part;                   // sliced K / example ranges: accumulators in register layout
+    const float *group_sqnorm;        // weighted: [n]
+    float clip_c;
+    int n, cin, cout, h;
+    int tiles_co, tiles_ci;
+    int chunks;                       // ceil(H / R)
+    int ksplit, chunks_per_split;     // per-example mode: K slices
+    int ex_per_split;                 // weighted mode: examples per workgroup (ksplit = example ranges)
+};
+
+constexpr int odd16(int bytes) { return ((bytes / 16) | 1) * 16; }
+
+template <int W> struct C3Cfg {
+    static constexpr int OWP = (W + 7) / 8 * 8;
+    static constexpr int R = (OWP == 8) ? 8 : 224 / OWP;      // output rows per chunk
+    static constexpr int KSTEPS = R * OWP / 16;
+    static constexpr int WP = OWP + 8;
+    static constexpr int XROWS = R + 2;
+    static constexpr int PPR = OWP / 8, XPR = WP / 8;         // 16-byte pieces per LDS row
+    static constexpr int PA = odd16(R * OWP * 2);             // bytes per co in LDS (odd multiple of 16)
+    static constexpr int PX = odd16(XROWS * WP * 2);          // bytes per ci in LDS
+    static constexpr int NPA = 64 * R * PPR, NPX = 64 * XROWS * XPR;
+    static constexpr int PA_T = (NPA + C3_THREADS - 1) / C3_THREADS;
+    static constexpr int PX_T = (NPX + C3_THREADS - 1) / C3_THREADS;
+    static constexpr int LDS = 64 * PA + 64 * PX;
+    static constexpr bool ALIGNED_A = (W % 8 == 0);
+    static_assert(OWP == 8 || OWP == 16 || OWP == 32 || OWP == 56, "supported row widths");
+    static_assert(R * OWP % 16 == 0, "whole MFMA K steps");
+};
+
+// What a workgroup does with finished accumulators (all of K of one example): squared norm of
+// its 64 x 64 x 9 block and the optional store in the framework's [Cout, Cin, 3, 3] order.
+__device__ __forceinline__ void c3_epilogue(const f32x16 (&acc)[9], const C3Args &a, int i, int unit, int co0, int ci0,
+                                            int wm, int wn, int lane, float *red)
+{
+    float ss = 0.0f;
+    const bool store = a.out_w != nullptr;
+    const int ci = ci0 + wn * 32 + (lane & 31);
+    float *out = a.out_w + (size_t)i * a.out_stride;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int co = co0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const bool ok = store && co < a.cout && ci < a.cin;
+        const size_t base = ((size_t)co * a.cin + ci) * 9;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const float v = acc[t][r];
+            ss += v * v;                              // channels beyond the layer are exact zeros
+            if (ok) out[base + t] = v;
+        }
+    }
+    const float tot = block_sum<4>(ss, red);
+    if (threadIdx.x == 0) a.partials[unit] = tot;
+}
+
+template <int W, bool SPLIT>
+__global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
+{
+    using C = C3Cfg<W>;
+    constexpr int XB = 6;                             // X pieces per thread in flight at once
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    __shared__ float red[4];
+    char *sX = lds, *sA = lds + 64 * C::PX;
+
+    // consecutive hardware workgroup ids rotate over the 8 XCDs; give each XCD a run of
+    // consecutive logical ids (the slices and tiles of the same examples share its L2)
+    const int tiles = a.tiles_co * a.tiles_ci;
+    const int total = a.n * tiles * a.ksplit;
+    const int per_xcd = (total + 7) >> 3;
+    const int wg = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (wg >= total) return;
+    const int split = wg % a.ksplit;
+    const int unit = wg / a.ksplit;                   // (example, tile)
+    const int i = unit / tiles, tile = unit - i * tiles;
+    const int tco = tile / a.tiles_ci, tci = tile - tco * a.tiles_ci;
+    const int co0 = tco * 64, ci0 = tci * 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int H = a.h;
+
+    // element offsets count from the start of the whole tensor (all n examples, below 2^31):
+    // whole-dword windows (10 elements from an even element index) may reach into the
+    // neighbouring example but never outside the tensor
+    const int x_ex = a.cin * H * W, dy_ex = a.cout * H * W;       // elements per example
+    const int x_base = i * x_ex, dy_base = i * dy_ex;
+    const int x_end = a.n * x_ex, dy_end = a.n * dy_ex;
+    const uint32_t *xw = reinterpret_cast<const uint32_t *>(a.x);
+    const uint32_t *dyw = reinterpret_cast<const uint32_t *>(a.dy);
+
+    f32x16 acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+    const int c_begin = split * a.chunks_per_split;
+    const int c_end = min(a.chunks, c_begin + a.chunks_per_split);
+
+    for (int chunk = c_begin; chunk < c_end; ++chunk) {
+        const int oh0 = chunk * C::R;
+        if (chunk != c_begin) __syncthreads();        // everyone is done reading the previous chunk
+
+        // ---- issue global loads, then shift / mask / write LDS.  The piece -> address decode is
+        // recomputed per chunk on purpose (the opaque copy of the thread id stops the compiler
+        // from keeping ~80 registers of loop-invariant addresses alive across the MFMA loop).
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        struct PieceA { int rel, lds_off, hi; bool valid, fast; };
+        auto piece_a = [&](int u) {
+            PieceA p;
+            const int id = tid + C3_THREADS * u;
+            const int co = id / (C::R * C::PPR), q = id - co * (C::R * C::PPR);
+            const int r = q / C::PPR, pc = q - r * C::PPR;
+            const int oh = oh0 + r;
+            p.valid = (id < C::NPA) && (co0 + co < a.cout) && (oh < H);
+            p.rel = dy_base + ((co0 + co) * H + oh) * W + pc * 8;
+            p.lds_off = co * C::PA + (r * C::OWP + pc * 8) * 2;
+            p.hi = W - pc * 8;                        // the row's end
+            p.fast = p.valid && (p.rel & ~1) + 10 <= dy_end;
+            return p;
+        };
+        struct PieceX { int rel, lds_off, lo, hi; bool valid, fast, write; };
+        auto piece_x = [&](int u) {
+            PieceX p;
+            const int id = tid + C3_THREADS * u;
+            const int ch = id / (C::XROWS * C::XPR), q = id - ch * (C::XROWS * C::XPR);
+            const int xr = q / C::XPR, pc = q - xr * C::XPR;
+            const int ih = oh0 - 1 + xr;
+            const int iw0 = pc * 8 - 1;
+            p.write = id < C::NPX;
+            p.lo = (pc == 0) ? 1 : 0;
+            p.hi = W - iw0;                           // may be <= 0: an all-zero piece
+            p.valid = p.write && (ci0 + ch < a.cin) && (ih >= 0) && (ih < H) && (p.hi > p.lo);
+            p.rel = x_base + ((ci0 + ch) * H + ih) * W + iw0;
+            p.lds_off = ch * C::PX + (xr * C::WP + pc * 8) * 2;
+            p.fast = p.valid && p.rel >= 0 && (p.rel & ~1) + 10 <= x_end;
+            return p;
+        };
+
+        // dY first, then X in batches of at most XB pieces per thread: the loads of a batch are all
+        // issued before the first is used, and a batch is small enough to sit in registers beside
+        // the 144 accumulators
+        {
+            uint4 ra4[C::ALIGNED_A ? C::PA_T : 1];
+            Raw<5> ra[C::ALIGNED_A ? 1 : C::PA_T];
+#pragma unroll
+            for (int u = 0; u < C::PA_T; ++u) {
+                const PieceA p = piece_a(u);
+                if constexpr (C::ALIGNED_A) ra4[u] = *reinterpret_cast<const uint4 *>(a.dy + (p.valid ? p.rel : 0));
+                else ra[u] = piece_load_words(dyw + ((p.fast ? p.rel : 0) >> 1));
+            }
+#pragma unroll
+            for (int u = 0; u < C::PA_T; ++u) {
+                const PieceA p = piece_a(u);
+                uint4 v;
+                if constexpr (C::ALIGNED_A) {
+                    v = p.valid ? ra4[u] : make_uint4(0u, 0u, 0u, 0u);
+                } else {
+                    uint32_t t[4];
+                    piece_finish<true, 1>(t, ra[u], (uint32_t)(p.rel & 1), 0, p.fast ? p.hi : 0);
+                    v = make_uint4(t[0], t[1], t[2], t[3]);
+                }
+                if (C::NPA % C3_THREADS == 0 || tid + C3_THREADS * u < C::NPA)
+                    *reinterpret_cast<uint4 *>(sA + p.lds_off) = v;
+            }
+        }
+#pragma unroll
+        for (int u0 = 0; u0 < C::PX_T; u0 += XB) {
+            Raw<5> rx[XB];
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                if (u0 + u < C::PX_T) {
+                    const PieceX p = piece_x(u0 + u);
+                    rx[u] = piece_load_words(xw + ((p.fast ? p.rel : 0) >> 1));
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                if (u0 + u >= C::PX_T) continue;
+                const PieceX p = piece_x(u0 + u);
+                uint32_t t[4];
+                piece_finish<true, 1>(t, rx[u], (uint32_t)(p.rel & 1), p.fast ? p.lo : 0, p.fast ? p.hi : 0);
+                const uint4 v = make_uint4(t[0], t[1], t[2], t[3]);
+                if (p.write) *reinterpret_cast<uint4 *>(sX + p.lds_off) = v;
+            }
+        }
+        // Pieces whose whole-dword window would have left the tensor (only the first rows of the
+        // first example and the last rows of the last one) were written as zeros above: fill them
+        // in element by element, touching nothing but the valid elements.
+        if (i == 0 || i == a.n - 1) {
+            if constexpr (!C::ALIGNED_A) {
+#pragma unroll 1
+                for (int u = 0; u < C::PA_T; ++u) {
+                    const PieceA p = piece_a(u);
+                    if (p.valid && !p.fast) {
+                        uint16_t *dst = reinterpret_cast<uint16_t *>(sA + p.lds_off);
+                        const int hi = min(8, p.hi);
+#pragma unroll 1
+                        for (int e = 0; e < hi; ++e) dst[e] = a.dy[p.rel + e];
+                    }
+                }
+            }
+#pragma unroll 1
+            for (int u = 0; u < C::PX_T; ++u) {
+                const PieceX p = piece_x(u);
+                if (p.valid && !p.fast) {
+                    uint16_t *dst = reinterpret_cast<uint16_t *>(sX + p.lds_off);
+                    const int hi = min(8, p.hi);
+#pragma unroll 1
+                    for (int e = p.lo; e < hi; ++e) dst[e] = a.x[p.rel + e];
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- MFMAs of the chunk
+        const char *pa = sA + (wm * 32 + (lane & 31)) * C::PA;
+        const char *px = sX + (wn * 32 + (lane & 31)) * C::PX;
+        const int half = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS; ++ks) {
+            const int kk = ks * 16 + half * 8;
+            const int r = kk / C::OWP, ow0 = kk - r * C::OWP;
+            const bf16x8 va = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + kk * 2));
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                const char *row = px + ((r + kh) * C::WP + ow0) * 2;
+                const uint4 d = *reinterpret_cast<const uint4 *>(row);
+                const uint32_t d4 = *reinterpret_cast<const uint32_t *>(row + 16);
+                const uint4 b0 = d;
+                const uint4 b1 = make_uint4(funnel(d.y, d.x, 16), funnel(d.z, d.y, 16), funnel(d.w, d.z, 16),
+                                            funnel(d4, d.w, 16));
+                const uint4 b2 = make_uint4(d.y, d.z, d.w, d4);
+                acc[kh * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, b0), acc[kh * 3 + 0], 0, 0, 0);
+                acc[kh * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, b1), acc[kh * 3 + 1], 0, 0, 0);
+                acc[kh * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, b2), acc[kh * 3 + 2], 0, 0, 0);
+            }
+        }
+    }
+
+    if constexpr (!SPLIT) {
+        c3_epilogue(acc, a, i, unit, co0, ci0, wm, wn, lane, red);
+    } else {
+        float *mine = a.ws_part + ((size_t)unit * a.ksplit + split) * (9 * 16 * C3_THREADS);
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mine[(t * 16 + r) * C3_THREADS + threadIdx.x] = acc[t][r];
+    }
+}
+
+// One workgroup per (example, tile): add the slices in order, then the common epilogue.
+__global__ void __launch_bounds__(C3_THREADS) conv3x3_fixup_kernel(const C3Args a)
+{
+    __shared__ float red[4];
+    const int tiles = a.tiles_co * a.tiles_ci;
+    const int unit = blockIdx.x;
+    const int i = unit / tiles, tile = unit - i * tiles;
+    const int tco = tile / a.tiles_ci, tci = tile - tco * a.tiles_ci;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    f32x16 acc[9];
+    const size_t slice = (size_t)9 * 16 * C3_THREADS;
+    const float *base = a.ws_part + (size_t)unit * a.ksplit * slice + threadIdx.x;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+        int s = 0;
+        for (; s + 2 <= a.ksplit; s += 2) {           // two slices' worth of loads in flight
+            float tmp[2][16];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmp[u][r] = base[(size_t)(s + u) * slice + (t * 16 + r) * C3_THREADS];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] += tmp[u][r];
+        }
+        for (; s < a.ksplit; ++s) {
+            float tmp[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tmp[r] = base[(size_t)s * slice + (t * 16 + r) * C3_THREADS];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] += tmp[r];
+        }
+    }
+    c3_epilogue(acc, a, i, unit, tco * 64, tci * 64, wave >> 1, wave & 1, lane, red);
+}
+
+// ------------------------------------------------------------------------------------ host
+
+struct C3Plan {
+    int rows;           // R of the width case
+    int tiles_co, tiles_ci, chunks, ksplit, chunks_per_split;
+};
+
+int rows_of_width(int w)
+{
+    const int owp = (w + 7) / 8 * 8;
+    return owp == 8 ? 8 : 224 / owp;
+}
+
+C3Plan c3_plan(const Geo &g)
+{
+    C3Plan p;
+    p.rows = rows_of_width(g.w);
+    p.tiles_co = (g.cout + 63) / 64;
+    p.tiles_ci = (g.cin + 63) / 64;
+    p.chunks = (g.h + p.rows - 1) / p.rows;
+    const long long units = (long long)g.n * p.tiles_co * p.tiles_ci;
+    p.ksplit = 1;
+    p.chunks_per_split = p.chunks;
+    if (units < 512 && p.chunks > 1) {
+        long long want = (512 + units - 1) / units;
+        if (want > p.chunks) want = p.chunks;
+        p.chunks_per_split = (int)((p.chunks + want - 1) / want);
+        p.ksplit = (p.chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+    }
+    return p;
+}
+
+size_t c3_align16(size_t b) { return (b + 15) & ~(size_t)15; }
+
+template <int W>
+dp_status c3_launch_w(const C3Args &a, unsigned blocks, hipStream_t s)
+{
+    using C = C3Cfg<W>;
+    static bool attr_done[2] = {false, false};
+    const int sp = a.ksplit > 1 ? 1 : 0;
+    const void *fn = sp ? reinterpret_cast<const void *>(&conv3x3_kernel<W, true>)
+                        : reinterpret_cast<const void *>(&conv3x3_kernel<W, false>);
+    if (!attr_done[sp]) {
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS) != hipSuccess)
+            return fail(DP_ERR_DEVICE, "conv3x3: cannot reserve %d bytes of LDS", C::LDS);
+        attr_done[sp] = true;
+    }
+    if (sp) hipLaunchKernelGGL((conv3x3_kernel<W, true>), dim3(blocks), dim3(C3_THREADS), C::LDS, s, a);
+    else hipLaunchKernelGGL((conv3x3_kernel<W, false>), dim3(blocks), dim3(C3_THREADS), C::LDS, s, a);
+    return check_launch("conv3x3");
+}
+
+}  // namespace
+
+bool conv3x3_applicable(const Geo &g, int mode)
+{
+    if (!g.bf16 || mode == MODE_WEIGHTED || g.has_bias) return false;
+    if (g.kh != 3 || g.kw != 3 || g.stride != 1 || g.pad != 1) return false;
+    if (g.cin < 64 || g.cout < 64) return false;
+    switch (g.w) {
+    case 7: case 8: case 14: case 16: case 28: case 32: case 56: break;
+    default: return false;
+    }
+    // 32-bit element offsets inside one example
+    return (long long)g.cin * g.h * g.w < (1ll << 30) && (long long)g.cout * g.h * g.w < (1ll << 30);
+}
+
+size_t conv3x3_ws_bytes(const Geo &g, int mode)
+{
+    (void)mode;
+    const C3Plan p = c3_plan(g);
+    const size_t units = (size_t)g.n * p.tiles_co * p.tiles_ci;
+    size_t b = c3_align16(units * sizeof(float));
+    if (p.ksplit > 1) b += units * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float);
+    return b;
+}
+
+const char *conv3x3_variant_name(const Geo &g, int mode)
+{
+    (void)mode;
+    static char names[8][48];
+    int slot;
+    switch (g.w) {
+    case 7: slot = 0; break; case 8: slot = 1; break; case 14: slot = 2; break; case 16: slot = 3; break;
+    case 28: slot = 4; break; case 32: slot = 5; break; default: slot = 6; break;
+    }
+    if (!names[slot][0]) snprintf(names[slot], sizeof names[slot], "conv3x3_rows<bf16,w%d,per_example>", g.w);
+    return names[slot];
+}
+
+dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
+                         float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s)
+{
+    (void)mode;
+    const C3Plan p = c3_plan(g);
+    C3Args a;
+    a.x = static_cast<const uint16_t *>(x);
+    a.dy = static_cast<const uint16_t *>(dy);
+    a.out_w = out_w;
+    a.out_stride = out_stride ? out_stride : g.pw;
+    a.group_sqnorm = group_sqnorm; a.clip_c = clip_c;
+    a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = g.h;
+    a.tiles_co = p.tiles_co; a.tiles_ci = p.tiles_ci;
+    a.chunks = p.chunks; a.ksplit = p.ksplit; a.chunks_per_split = p.chunks_per_split;
+    a.ex_per_split = 1;
+    const size_t units = (size_t)g.n * p.tiles_co * p.tiles_ci;
+    char *w = static_cast<char *>(ws);
+    a.partials = reinterpret_cast<float *>(w);
+    w += c3_align16(units * sizeof(float));
+    a.ws_part = p.ksplit > 1 ? reinterpret_cast<float *>(w) : nullptr;
+    const long long total = (long long)units * p.ksplit;
+    const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
+    dp_status st;
+    switch (g.w) {
+    case 7: st = c3_launch_w<7>(a, blocks, s); break;
+    case 8: st = c3_launch_w<8>(a, blocks, s); break;
+    case 14: st = c3_launch_w<14>(a, blocks, s); break;
+    case 16: st = c3_launch_w<16>(a, blocks, s); break;
+    case 28: st = c3_launch_w<28>(a, blocks, s); break;
+    case 32: st = c3_launch_w<32>(a, blocks, s); break;
+    default: st = c3_launch_w<56>(a, blocks, s); break;
+    }
+    if (st != DP_OK) return st;
+    if (p.ksplit > 1) {
+        hipLaunchKernelGGL(conv3x3_fixup_kernel, dim3((unsigned)units), dim3(C3_THREADS), 0, s, a);
+        st = check_launch("conv3x3_fixup");
+        if (st != DP_OK) return st;
+    }
+    if (sqnorm) st = launch_sum_partials(a.partials, g.n, p.tiles_co * p.tiles_ci, sqnorm, s);
+    return st;
+}
+
+}  // namespace dp

@@ -39,6 +39,14 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
                       hipStream_t s);
 
+// 3x3 stride-1 pad-1 bf16 convolutions staged from raw image rows (conv3x3.hip); launch_conv,
+// conv_ws_bytes and conv_variant_name route to these when conv3x3_applicable() says so.
+bool conv3x3_applicable(const Geo &g, int mode);
+size_t conv3x3_ws_bytes(const Geo &g, int mode);
+const char *conv3x3_variant_name(const Geo &g, int mode);
+dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
+                         float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s);
+
 size_t dense_ws_bytes(const Geo &g, int mode);
 dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                        size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,

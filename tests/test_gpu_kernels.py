@@ -103,6 +103,35 @@ def test_conv_per_example_grad_and_norm(name, layer, n, dtype):
     assert np.array_equal(sq, sq2)
 
 
+# 3x3 stride-1 pad-1 bf16 layers with >= 64 channels run in the raw-row kernel: every supported
+# row width, ragged channel counts, image heights that leave a partial last chunk, K sliced over
+# workgroups (few tiles) and unsliced (many).
+ROWS_CASES = [
+    ("w56 three chunks sliced", Layer("conv", 64, 64, 10, 56, 3, 3, 1, 1, False), 2, None),
+    ("w28 ragged channels", Layer("conv", 80, 72, 28, 28, 3, 3, 1, 1, False), 2, None),
+    ("w14 one chunk", Layer("conv", 130, 64, 14, 14, 3, 3, 1, 1, False), 3, None),
+    ("w16 short image", Layer("conv", 64, 96, 9, 16, 3, 3, 1, 1, False), 2, None),
+    ("w32 two chunks", Layer("conv", 64, 64, 12, 32, 3, 3, 1, 1, False), 2, None),
+    ("w8 one chunk", Layer("conv", 64, 64, 8, 8, 3, 3, 1, 1, False), 3, None),
+    ("w7 tall image", Layer("conv", 64, 70, 19, 7, 3, 3, 1, 1, False), 2, None),
+    ("w8 two chunks unsliced many examples", Layer("conv", 64, 64, 11, 8, 3, 3, 1, 1, False), 520, [0, 1, 259, 518, 519]),
+]
+
+
+@pytest.mark.parametrize("name,layer,n,sample", ROWS_CASES, ids=[c[0] for c in ROWS_CASES])
+def test_conv3x3_raw_row_kernel(name, layer, n, sample):
+    d = dp.make_desc(layer, n, "bf16")
+    assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD).startswith("conv3x3_rows")
+    x, dy = _inputs(layer, n, 211, "bf16")
+    gw, _, sq = _run_per_example(layer, x, dy, "bf16")
+    _, _, sq2 = _run_per_example(layer, x, dy, "bf16", materialise=False)
+    assert np.array_equal(sq, sq2)
+    for i in (sample if sample is not None else range(n)):
+        w, _ = oracle.example_grad(layer, x[i], dy[i])
+        assert_close(gw[i], w.reshape(-1), BF16_TOL, f"{name} dW[{i}]")
+        assert math.isclose(sq[i], oracle.sqnorm(w), rel_tol=BF16_TOL), (i, sq[i], oracle.sqnorm(w))
+
+
 def test_conv_strided_gradient_matrix_layout():
     layer = Layer("conv", 5, 9, 8, 8, 3, 3, 1, 1, True)
     x, dy = _inputs(layer, 3, 103, "f32")
