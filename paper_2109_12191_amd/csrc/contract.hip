@@ -574,8 +574,13 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
         for (int r = 0; r < 16; ++r) mine[(t * 16 + r) * THREADS + threadIdx.x] = acc[t][r];
 }
 
-// One workgroup per group of slices: add the partial tiles in slice order (same bits every
-// run), then the same epilogue as the unsliced case.
+// Slices of one tile meet here.  The sum over slices is elementwise, so it is spread over many
+// small workgroups: one per (tile, 32x32 accumulator block t, four of its sixteen registers).
+// Each thread adds its four values over the slices in slice order (same bits every run) with
+// eight slices of loads in flight, then does for them what the unsliced epilogue does.
+constexpr int FIX_R = 4;                       // accumulator registers per fixup thread
+constexpr int FIX_PARTS = 16 / FIX_R;
+
 template <int WAVES_M, int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS>
 __global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const ConvArgs a)
 {
@@ -583,44 +588,70 @@ __global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const ConvArgs a)
     constexpr int NACC = TM * TN + (BIAS ? TM : 0);
     __shared__ float red[4];
     const int tiles = a.tiles_m * a.tiles_n;
-    const int group = blockIdx.x;
+    const int part = blockIdx.x % FIX_PARTS;
+    const int t = (blockIdx.x / FIX_PARTS) % NACC;
+    const int group = blockIdx.x / (FIX_PARTS * NACC);
     const int i = WEIGHTED ? 0 : group / tiles;
     const int tile = WEIGHTED ? group : group - i * tiles;
     const int tile_m = tile / a.tiles_n, tile_n = tile - tile_m * a.tiles_n;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WAVES_N, wn = wave - wm * WAVES_N;
-    f32x16 acc[NACC];
-#pragma unroll
-    for (int t = 0; t < NACC; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-    // slice order is fixed; four slices' worth of loads are in flight per accumulator tile
+
     const size_t slice = (size_t)NACC * 16 * THREADS;
-    const float *base = a.ws_part + (size_t)group * a.ksplit * slice + threadIdx.x;
+    const float *base = a.ws_part + (size_t)group * a.ksplit * slice + (size_t)(t * 16 + part * FIX_R) * THREADS + threadIdx.x;
+    float v[FIX_R];
 #pragma unroll
-    for (int t = 0; t < NACC; ++t) {
-        int s = 0;
-        for (; s + 4 <= a.ksplit; s += 4) {
-            float tmp[4][16];
+    for (int r = 0; r < FIX_R; ++r) v[r] = 0.0f;
+    int s = 0;
+    for (; s + 8 <= a.ksplit; s += 8) {
+        float tmp[8][FIX_R];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) tmp[u][r] = base[(size_t)(s + u) * slice + (t * 16 + r) * THREADS];
+            for (int r = 0; r < FIX_R; ++r) tmp[u][r] = base[(size_t)(s + u) * slice + r * THREADS];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[t][r] += tmp[u][r];
-        }
-        for (; s < a.ksplit; ++s) {
-            float tmp[16];
+            for (int r = 0; r < FIX_R; ++r) v[r] += tmp[u][r];
+    }
+    for (; s < a.ksplit; ++s) {
+        float tmp[FIX_R];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) tmp[r] = base[(size_t)s * slice + (t * 16 + r) * THREADS];
+        for (int r = 0; r < FIX_R; ++r) tmp[r] = base[(size_t)s * slice + r * THREADS];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][r] += tmp[r];
+        for (int r = 0; r < FIX_R; ++r) v[r] += tmp[r];
+    }
+
+    const bool is_bias = BIAS && t >= TM * TN;
+    const int tm = is_bias ? t - TM * TN : t / TN, tn = is_bias ? 0 : t - tm * TN;
+    const int j = tile_n * NT + (wn * TN + tn) * 32 + (lane & 31);
+    const bool bias_lane = is_bias && tile_n == 0 && wn == 0 && (lane & 31) == 0;
+    float ss = 0.0f;
+#pragma unroll
+    for (int rr = 0; rr < FIX_R; ++rr) {
+        const int r = part * FIX_R + rr;
+        const int m = tile_m * MT + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (!is_bias) {
+            const bool ok = m < a.cout && j < a.J;
+            if constexpr (WEIGHTED) {
+                if (ok) a.out_w[(size_t)m * a.J + j] += v[rr];
+            } else {
+                ss += v[rr] * v[rr];
+                if (ok && a.out_w) a.out_w[(size_t)i * a.out_stride_w + (size_t)m * a.J + j] = v[rr];
+            }
+        } else if (bias_lane) {
+            if constexpr (WEIGHTED) {
+                if (m < a.cout) a.out_b[m] += v[rr];
+            } else {
+                ss += v[rr] * v[rr];
+                if (m < a.cout && a.out_w) a.out_b[(size_t)i * a.out_stride_b + m] = v[rr];
+            }
         }
     }
-    tile_epilogue<WAVES_N, TM, TN, WEIGHTED, BIAS>(acc, a, i, tile, tiles, tile_m * MT, tile_n * NT, wm, wn, lane,
-                                                  BIAS && tile_n == 0 && wn == 0, red);
+    if constexpr (!WEIGHTED) {
+        const float tot = block_sum<4>(ss, red);
+        if (threadIdx.x == 0) a.partials[blockIdx.x] = tot;
+    }
 }
 
 // ------------------------------------------------------------------------------------ host
@@ -694,6 +725,31 @@ static FullPlan full_plan(const Geo &g, int mode)
     return p;
 }
 
+// Clip-weighted contraction of a bf16 layer whose packed operands are small: rewrite the
+// operands first (pack.hip) and run the aligned one-long-row variant on `g2`, the geometry of
+// the packed tensors (example ranges as its "examples", im2col rows as its input channels).
+static bool packed_weighted(const Geo &g, int mode, PackPlan &pp, Geo &g2)
+{
+    if (mode != MODE_WEIGHTED || !g.bf16) return false;
+    const long long J = (long long)g.cin * g.kh * g.kw;
+    const int shape = (g.cout > 64 && J > 64) ? T128 : T64;
+    const long long tiles = (long long)((g.cout + kTileM[shape] - 1) / kTileM[shape]) * ((J + kTileN[shape] - 1) / kTileN[shape]);
+    long long groups = (256 + tiles - 1) / tiles;
+    if (groups > g.n) groups = g.n;
+    if (groups < 1) groups = 1;
+    pp = pack_plan(g, (int)groups);
+    if (pp.x_bytes + pp.dy_bytes > ((size_t)64 << 20)) return false;
+    if ((long long)J * pp.kg >= (1ll << 31) || (long long)g.cout * pp.kg >= (1ll << 31)) return false;
+    g2 = g;
+    g2.n = pp.groups;
+    g2.cin = (int)J;
+    g2.h = 1; g2.w = pp.kg; g2.oh = 1; g2.ow = pp.kg;
+    g2.kh = 1; g2.kw = 1; g2.stride = 1; g2.pad = 0;
+    g2.x_elems = (size_t)J * pp.kg;
+    g2.dy_elems = (size_t)g.cout * pp.kg;
+    return true;
+}
+
 ConvPlan conv_plan(const Geo &g, int mode)
 {
     const FullPlan f = full_plan(g, mode);
@@ -703,15 +759,29 @@ ConvPlan conv_plan(const Geo &g, int mode)
     return p;
 }
 
-// workspace: [norm partials n*tiles floats (per-example mode)] [partial tiles]
+// workspace: [partial squared norms (per-example mode)] [partial tiles]
 static size_t align16(size_t b) { return (b + 15) & ~(size_t)15; }
+
+// partial squared norms per example: one per tile, or one per fixup workgroup when K is sliced
+static size_t norm_partials_per_example(const FullPlan &f)
+{
+    const size_t tiles = (size_t)f.tiles_m * f.tiles_n;
+    return f.ksplit > 1 ? tiles * f.nacc * FIX_PARTS : tiles;
+}
+static size_t norm_partials(const Geo &g, const FullPlan &f) { return (size_t)g.n * norm_partials_per_example(f); }
 
 size_t conv_ws_bytes(const Geo &g, int mode)
 {
     if (conv3x3_applicable(g, mode)) return conv3x3_ws_bytes(g, mode);
+    PackPlan pp;
+    Geo g2;
+    if (packed_weighted(g, mode, pp, g2)) {
+        const FullPlan f = full_plan(g2, mode);
+        return align16(pp.x_bytes) + align16(pp.dy_bytes) + (f.ksplit > 1 ? f.part_floats * sizeof(float) : 0);
+    }
     const FullPlan f = full_plan(g, mode);
     size_t b = 0;
-    if (mode != MODE_WEIGHTED) b += align16((size_t)g.n * f.tiles_m * f.tiles_n * sizeof(float));
+    if (mode != MODE_WEIGHTED) b += align16(norm_partials(g, f) * sizeof(float));
     if (f.ksplit > 1) b += f.part_floats * sizeof(float);
     return b;
 }
@@ -766,12 +836,37 @@ static void launch_shape(const ConvArgs &a, int loader, bool weighted, bool bias
     else launch_shape2<BF16, WM, WN, TM, TN, 2>(a, weighted, bias, blocks, s);
 }
 
+static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
+                                  size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c,
+                                  void *ws, hipStream_t s);
+
 dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
                       hipStream_t s)
 {
     if (conv3x3_applicable(g, mode))
         return launch_conv3x3(g, mode, x, dy, out_w, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
+    PackPlan pp;
+    Geo g2;
+    if (packed_weighted(g, mode, pp, g2)) {
+        char *w = static_cast<char *>(ws);
+        void *xp = w;
+        w += align16(pp.x_bytes);
+        void *dyp = w;
+        w += align16(pp.dy_bytes);
+        const dp_status st = launch_pack_weighted(g, pp, x, dy, group_sqnorm, clip_c, xp, dyp, s);
+        if (st != DP_OK) return st;
+        // the factors are already in dYp: an infinite bound makes the kernel's own factor 1
+        return launch_conv_impl(g2, mode, xp, dyp, out_w, out_b, out_stride, nullptr, group_sqnorm,
+                                __builtin_inff(), w, s);
+    }
+    return launch_conv_impl(g, mode, x, dy, out_w, out_b, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
+}
+
+static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
+                                  size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c,
+                                  void *ws, hipStream_t s)
+{
     const FullPlan f = full_plan(g, mode);
     const bool weighted = mode == MODE_WEIGHTED;
     ConvArgs a;
@@ -793,7 +888,7 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
     a.partials = nullptr;
     if (!weighted) {
         a.partials = reinterpret_cast<float *>(w);
-        w += align16((size_t)g.n * tiles * sizeof(float));
+        w += align16(norm_partials(g, f) * sizeof(float));
     }
     a.ws_part = (f.ksplit > 1) ? reinterpret_cast<float *>(w) : nullptr;
     long long total;
@@ -817,13 +912,13 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
     if (st != DP_OK) return st;
     if (f.ksplit > 1) {
         switch (f.shape) {
-        case T64: launch_fixup<2, 2, 1, 1>(a, weighted, bias, f.groups, s); break;
-        default: launch_fixup<2, 2, 2, 2>(a, weighted, bias, f.groups, s); break;
+        case T64: launch_fixup<2, 2, 1, 1>(a, weighted, bias, f.groups * f.nacc * FIX_PARTS, s); break;
+        default: launch_fixup<2, 2, 2, 2>(a, weighted, bias, f.groups * f.nacc * FIX_PARTS, s); break;
         }
         st = check_launch("conv_fixup");
         if (st != DP_OK) return st;
     }
-    if (!weighted && sqnorm) st = launch_sum_partials(a.partials, g.n, tiles, sqnorm, s);
+    if (!weighted && sqnorm) st = launch_sum_partials(a.partials, g.n, (int)norm_partials_per_example(f), sqnorm, s);
     return st;
 }
 

@@ -288,43 +288,59 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
     }
 }
 
-// One workgroup per (example, tile): add the slices in order, then the common epilogue.
+// Slices of one (example, tile) meet here.  The sum is elementwise, so it is spread over many
+// small workgroups: one per (example, tile, tap t, four of the tap's sixteen accumulator
+// registers); each thread adds its four values in slice order with eight slices in flight, then
+// squares / stores them like the unsliced epilogue.
+constexpr int C3_FIX_R = 4, C3_FIX_PARTS = 16 / C3_FIX_R;
+
 __global__ void __launch_bounds__(C3_THREADS) conv3x3_fixup_kernel(const C3Args a)
 {
     __shared__ float red[4];
     const int tiles = a.tiles_co * a.tiles_ci;
-    const int unit = blockIdx.x;
+    const int part = blockIdx.x % C3_FIX_PARTS;
+    const int t = (blockIdx.x / C3_FIX_PARTS) % 9;
+    const int unit = blockIdx.x / (C3_FIX_PARTS * 9);
     const int i = unit / tiles, tile = unit - i * tiles;
     const int tco = tile / a.tiles_ci, tci = tile - tco * a.tiles_ci;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    f32x16 acc[9];
+    const int wm = wave >> 1, wn = wave & 1;
     const size_t slice = (size_t)9 * 16 * C3_THREADS;
-    const float *base = a.ws_part + (size_t)unit * a.ksplit * slice + threadIdx.x;
+    const float *base = a.ws_part + (size_t)unit * a.ksplit * slice + (size_t)(t * 16 + part * C3_FIX_R) * C3_THREADS + threadIdx.x;
+    float v[C3_FIX_R];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
+    for (int r = 0; r < C3_FIX_R; ++r) v[r] = 0.0f;
+    int s = 0;
+    for (; s + 8 <= a.ksplit; s += 8) {
+        float tmp[8][C3_FIX_R];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-        int s = 0;
-        for (; s + 2 <= a.ksplit; s += 2) {           // two slices' worth of loads in flight
-            float tmp[2][16];
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+            for (int r = 0; r < C3_FIX_R; ++r) tmp[u][r] = base[(size_t)(s + u) * slice + r * C3_THREADS];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) tmp[u][r] = base[(size_t)(s + u) * slice + (t * 16 + r) * C3_THREADS];
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[t][r] += tmp[u][r];
-        }
-        for (; s < a.ksplit; ++s) {
-            float tmp[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) tmp[r] = base[(size_t)s * slice + (t * 16 + r) * C3_THREADS];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][r] += tmp[r];
-        }
+            for (int r = 0; r < C3_FIX_R; ++r) v[r] += tmp[u][r];
     }
-    c3_epilogue(acc, a, i, unit, tco * 64, tci * 64, wave >> 1, wave & 1, lane, red);
+    for (; s < a.ksplit; ++s) {
+        float tmp[C3_FIX_R];
+#pragma unroll
+        for (int r = 0; r < C3_FIX_R; ++r) tmp[r] = base[(size_t)s * slice + r * C3_THREADS];
+#pragma unroll
+        for (int r = 0; r < C3_FIX_R; ++r) v[r] += tmp[r];
+    }
+    const int ci = tci * 64 + wn * 32 + (lane & 31);
+    float *out = a.out_w + (size_t)i * a.out_stride;
+    float ss = 0.0f;
+#pragma unroll
+    for (int rr = 0; rr < C3_FIX_R; ++rr) {
+        const int r = part * C3_FIX_R + rr;
+        const int co = tco * 64 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        ss += v[rr] * v[rr];
+        if (a.out_w && co < a.cout && ci < a.cin) out[((size_t)co * a.cin + ci) * 9 + t] = v[rr];
+    }
+    const float tot = block_sum<4>(ss, red);
+    if (threadIdx.x == 0) a.partials[blockIdx.x] = tot;
 }
 
 // ------------------------------------------------------------------------------------ host
@@ -360,6 +376,9 @@ C3Plan c3_plan(const Geo &g)
 }
 
 size_t c3_align16(size_t b) { return (b + 15) & ~(size_t)15; }
+
+// partial squared norms per (example, tile): one, or one per fixup workgroup when K is sliced
+size_t c3_partials_per_unit(const C3Plan &p) { return p.ksplit > 1 ? 9 * C3_FIX_PARTS : 1; }
 
 template <int W>
 dp_status c3_launch_w(const C3Args &a, unsigned blocks, hipStream_t s)
@@ -399,7 +418,7 @@ size_t conv3x3_ws_bytes(const Geo &g, int mode)
     (void)mode;
     const C3Plan p = c3_plan(g);
     const size_t units = (size_t)g.n * p.tiles_co * p.tiles_ci;
-    size_t b = c3_align16(units * sizeof(float));
+    size_t b = c3_align16(units * c3_partials_per_unit(p) * sizeof(float));
     if (p.ksplit > 1) b += units * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float);
     return b;
 }
@@ -435,7 +454,7 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     const size_t units = (size_t)g.n * p.tiles_co * p.tiles_ci;
     char *w = static_cast<char *>(ws);
     a.partials = reinterpret_cast<float *>(w);
-    w += c3_align16(units * sizeof(float));
+    w += c3_align16(units * c3_partials_per_unit(p) * sizeof(float));
     a.ws_part = p.ksplit > 1 ? reinterpret_cast<float *>(w) : nullptr;
     const long long total = (long long)units * p.ksplit;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
@@ -451,11 +470,11 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     }
     if (st != DP_OK) return st;
     if (p.ksplit > 1) {
-        hipLaunchKernelGGL(conv3x3_fixup_kernel, dim3((unsigned)units), dim3(C3_THREADS), 0, s, a);
+        hipLaunchKernelGGL(conv3x3_fixup_kernel, dim3((unsigned)(units * 9 * C3_FIX_PARTS)), dim3(C3_THREADS), 0, s, a);
         st = check_launch("conv3x3_fixup");
         if (st != DP_OK) return st;
     }
-    if (sqnorm) st = launch_sum_partials(a.partials, g.n, p.tiles_co * p.tiles_ci, sqnorm, s);
+    if (sqnorm) st = launch_sum_partials(a.partials, g.n, p.tiles_co * p.tiles_ci * (int)c3_partials_per_unit(p), sqnorm, s);
     return st;
 }
 

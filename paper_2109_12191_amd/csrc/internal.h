@@ -47,6 +47,16 @@ const char *conv3x3_variant_name(const Geo &g, int mode);
 dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
                          float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s);
 
+// Packed operands of the clip-weighted contraction (pack.hip): K-contiguous, aligned, dY
+// pre-scaled by the clip factors; `groups` example ranges of `eg` examples, rows of `kg` elements.
+struct PackPlan {
+    int S, SP, J, groups, eg, kg;
+    size_t x_bytes, dy_bytes;
+};
+PackPlan pack_plan(const Geo &g, int groups);
+dp_status launch_pack_weighted(const Geo &g, const PackPlan &p, const void *x, const void *dy,
+                               const float *group_sqnorm, float clip_c, void *xp, void *dyp, hipStream_t s);
+
 size_t dense_ws_bytes(const Geo &g, int mode);
 dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                        size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,

@@ -1,0 +1,119 @@
+// Operand packing for the clip-weighted contraction (the recomputation form of H4):
+//     acc[co, j] += sum_i f_i sum_k dY_i[co, k] * Xcol_i[j, k],   f_i = min(1, C / |g_i|)
+// is one GEMM whose K axis runs over (example, output position).  For layers with small
+// feature maps the operands are first rewritten K-contiguous and 16-byte aligned:
+//     dYp[grp][co][e * SP + k] = bf16(f_i * dY_i[co, k])            i = grp * EG + e
+//     Xp [grp][j ][e * SP + k] = Xpad_i[ci, oh*s + kh - p, ow*s + kw - p]   (im2col row j = (ci,kh,kw))
+// with SP = S rounded up to 8 and zeros in the padding, so that the contraction kernel streams
+// plain aligned pieces with no masks, gathers or per-example scaling, whatever the stride, kernel
+// size or parity of S.  The clip factor is applied here, in fp32, and rounded to bf16 once
+// (nearest even) -- the same arithmetic the in-kernel scaling performs.
+// `grp` splits the examples into ranges that different workgroups contract (the K slices).
+#include "internal.h"
+
+namespace dp {
+
+namespace {
+
+struct PackArgs {
+    const uint16_t *x, *dy;
+    uint16_t *xp, *dyp;
+    const float *group_sqnorm;
+    float clip_c;
+    int n, cin, cout, h, w, kh, kw, stride, pad, oh, ow;
+    int S, SP, J;
+    int groups, eg;                 // example ranges and examples per range
+    int kg8;                        // pieces per packed row: eg * SP / 8
+    long long x_pieces, dy_pieces;
+};
+
+__global__ void __launch_bounds__(256) pack_weighted_kernel(const PackArgs a)
+{
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    uint32_t out[4] = {0u, 0u, 0u, 0u};
+    if (q < a.x_pieces) {
+        const int kk8 = (int)(q % a.kg8);
+        const long long row = q / a.kg8;
+        const int j = (int)(row % a.J), grp = (int)(row / a.J);
+        const int kk = kk8 * 8;
+        const int e = kk / a.SP, k0 = kk - e * a.SP;
+        const int i = grp * a.eg + e;
+        if (i < a.n) {
+            const int taps = a.kh * a.kw;
+            const int ci = j / taps, t = j - ci * taps;
+            const int kh = t / a.kw, kw = t - kh * a.kw;
+            const uint16_t *src = a.x + ((size_t)i * a.cin + ci) * a.h * a.w;
+            int oh = k0 / a.ow, ow = k0 - oh * a.ow;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                uint32_t v = 0u;
+                if (k0 + u < a.S) {
+                    const int ih = oh * a.stride + kh - a.pad, iw = ow * a.stride + kw - a.pad;
+                    if (ih >= 0 && ih < a.h && iw >= 0 && iw < a.w) v = src[ih * a.w + iw];
+                }
+                out[u >> 1] |= v << ((u & 1) * 16);
+                if (++ow == a.ow) { ow = 0; ++oh; }
+            }
+        }
+        *reinterpret_cast<uint4 *>(a.xp + q * 8) = make_uint4(out[0], out[1], out[2], out[3]);
+        return;
+    }
+    const long long qd = q - a.x_pieces;
+    if (qd >= a.dy_pieces) return;
+    const int kk8 = (int)(qd % a.kg8);
+    const long long row = qd / a.kg8;
+    const int co = (int)(row % a.cout), grp = (int)(row / a.cout);
+    const int kk = kk8 * 8;
+    const int e = kk / a.SP, k0 = kk - e * a.SP;
+    const int i = grp * a.eg + e;
+    if (i < a.n) {
+        const float f = clip_factor(a.group_sqnorm[i], a.clip_c);
+        const uint16_t *src = a.dy + ((size_t)i * a.cout + co) * a.S;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            uint32_t v = 0u;
+            if (k0 + u < a.S) v = float_to_bf16_bits(bf16_bits_to_float(src[k0 + u]) * f);
+            out[u >> 1] |= v << ((u & 1) * 16);
+        }
+    }
+    *reinterpret_cast<uint4 *>(a.dyp + qd * 8) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+}  // namespace
+
+PackPlan pack_plan(const Geo &g, int groups)
+{
+    PackPlan p;
+    p.S = g.oh * g.ow;
+    p.SP = (p.S + 7) / 8 * 8;
+    p.J = g.cin * g.kh * g.kw;
+    p.groups = groups;
+    p.eg = (g.n + groups - 1) / groups;
+    p.groups = (g.n + p.eg - 1) / p.eg;          // no empty trailing range
+    p.kg = p.eg * p.SP;
+    p.x_bytes = (size_t)p.groups * p.J * p.kg * 2;
+    p.dy_bytes = (size_t)p.groups * g.cout * p.kg * 2;
+    return p;
+}
+
+dp_status launch_pack_weighted(const Geo &g, const PackPlan &p, const void *x, const void *dy,
+                               const float *group_sqnorm, float clip_c, void *xp, void *dyp, hipStream_t s)
+{
+    PackArgs a;
+    a.x = static_cast<const uint16_t *>(x);
+    a.dy = static_cast<const uint16_t *>(dy);
+    a.xp = static_cast<uint16_t *>(xp);
+    a.dyp = static_cast<uint16_t *>(dyp);
+    a.group_sqnorm = group_sqnorm; a.clip_c = clip_c;
+    a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = g.h; a.w = g.w; a.kh = g.kh; a.kw = g.kw;
+    a.stride = g.stride; a.pad = g.pad; a.oh = g.oh; a.ow = g.ow;
+    a.S = p.S; a.SP = p.SP; a.J = p.J; a.groups = p.groups; a.eg = p.eg; a.kg8 = p.kg / 8;
+    a.x_pieces = (long long)p.groups * p.J * a.kg8;
+    a.dy_pieces = (long long)p.groups * g.cout * a.kg8;
+    const long long blocks = (a.x_pieces + a.dy_pieces + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return fail(DP_ERR_UNSUPPORTED, "pack: layer too large");
+    hipLaunchKernelGGL(pack_weighted_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return check_launch("pack_weighted");
+}
+
+}  // namespace dp

@@ -93,6 +93,79 @@ __global__ void __launch_bounds__(256) dense_kernel(const DenseArgs a)
     }
 }
 
+// One token per example: the gradient is the rank-one product dy_i (x) x_i (plus db_i = dy_i), so
+// its squared Frobenius norm is |dy_i|^2 |x_i|^2 (+ |dy_i|^2) -- the same number H2 defines, from
+// two short reductions instead of Cout*Cin products.  One workgroup per example.
+template <bool BF16>
+__global__ void __launch_bounds__(256) dense_rank1_norm_kernel(const DenseArgs a, float *sqnorm)
+{
+    typedef typename In<BF16>::type E;
+    __shared__ float red[4];
+    const int i = blockIdx.x;
+    const E *xi = static_cast<const E *>(a.x) + (size_t)i * a.cin;
+    const E *dyi = static_cast<const E *>(a.dy) + (size_t)i * a.cout;
+    float sx = 0.0f, sd = 0.0f;
+    for (int k = threadIdx.x; k < a.cin; k += 256) { const float v = In<BF16>::ld(xi + k); sx += v * v; }
+    for (int o = threadIdx.x; o < a.cout; o += 256) { const float v = In<BF16>::ld(dyi + o); sd += v * v; }
+    sx = block_sum<4>(sx, red);
+    sd = block_sum<4>(sd, red);
+    if (threadIdx.x == 0) sqnorm[i] = sd * sx + (a.has_bias ? sd : 0.0f);
+}
+
+// One token per example, clip-weighted sum: acc[o, k] += sum_i (f_i dy_i[o]) x_i[k].  Same tile
+// as dense_kernel (DR rows x 256 columns, a thread owns a column); the examples are taken 32 at
+// a time: their scaled dy values go through LDS, a thread keeps eight x loads in flight, and
+// the sum over examples runs in example order.
+template <bool BF16>
+__global__ void __launch_bounds__(256) dense_rank1_weighted_kernel(const DenseArgs a)
+{
+    typedef typename In<BF16>::type E;
+    constexpr int EB = 32;
+    __shared__ float sd[EB][DR];
+    const int tile_k = blockIdx.x, tile_o = blockIdx.y;
+    const int k = tile_k * 256 + threadIdx.x;
+    const int o0 = tile_o * DR;
+    const bool k_ok = k < a.cin;
+    const E *xg = static_cast<const E *>(a.x), *dyg = static_cast<const E *>(a.dy);
+    const bool bias_thread = a.has_bias && tile_k == 0 && threadIdx.x < DR && o0 + threadIdx.x < a.cout;
+    float acc[DR];
+#pragma unroll
+    for (int r = 0; r < DR; ++r) acc[r] = 0.0f;
+    float accb = 0.0f;
+    for (int i0 = 0; i0 < a.n; i0 += EB) {
+        __syncthreads();
+        for (int q = threadIdx.x; q < EB * DR; q += 256) {
+            const int ii = q / DR, r = q - ii * DR;
+            const int i = i0 + ii, o = o0 + r;
+            float v = 0.0f;
+            if (i < a.n && o < a.cout)
+                v = In<BF16>::ld(dyg + (size_t)i * a.cout + o) * clip_factor(a.group_sqnorm[i], a.clip_c);
+            sd[ii][r] = v;
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int ib = 0; ib < EB; ib += 8) {          // eight x loads in flight at a time
+            float xv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                xv[u] = (k_ok && i0 + ib + u < a.n) ? In<BF16>::ld(xg + (size_t)(i0 + ib + u) * a.cin + k) : 0.0f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+#pragma unroll
+                for (int r = 0; r < DR; ++r) acc[r] += sd[ib + u][r] * xv[u];
+            }
+        }
+        if (bias_thread) {
+#pragma unroll
+            for (int ii = 0; ii < EB; ++ii) accb += sd[ii][threadIdx.x];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < DR; ++r)
+        if (k_ok && o0 + r < a.cout) a.out_w[(size_t)(o0 + r) * a.cin + k] += acc[r];
+    if (bias_thread) a.out_b[o0 + threadIdx.x] += accb;
+}
+
 size_t dense_ws_bytes(const Geo &g, int mode)
 {
     if (mode == MODE_WEIGHTED) return 0;
@@ -114,7 +187,18 @@ dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, fl
     a.tiles_k = (g.cin + 255) / 256;
     a.tiles_o = (g.cout + DR - 1) / DR;
     const bool weighted = mode == MODE_WEIGHTED;
+    if (!weighted && !out_w && a.tokens == 1) {
+        if (!sqnorm) return DP_OK;
+        if (g.bf16) hipLaunchKernelGGL((dense_rank1_norm_kernel<true>), dim3(g.n), dim3(256), 0, s, a, sqnorm);
+        else hipLaunchKernelGGL((dense_rank1_norm_kernel<false>), dim3(g.n), dim3(256), 0, s, a, sqnorm);
+        return check_launch("dense_rank1_norm");
+    }
     const dim3 grid(a.tiles_k, a.tiles_o, weighted ? 1 : g.n);
+    if (weighted && a.tokens == 1) {
+        if (g.bf16) hipLaunchKernelGGL((dense_rank1_weighted_kernel<true>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((dense_rank1_weighted_kernel<false>), grid, dim3(256), 0, s, a);
+        return check_launch("dense_rank1_weighted");
+    }
     if (g.bf16) {
         if (weighted) hipLaunchKernelGGL((dense_kernel<true, true>), grid, dim3(256), 0, s, a);
         else hipLaunchKernelGGL((dense_kernel<true, false>), grid, dim3(256), 0, s, a);

@@ -101,10 +101,15 @@ class PrivatiseStep:
             return mode
         if mode != "auto":
             raise ValueError(mode)
-        esize = 2 if self.wl.dtype == "bf16" else 4
+        # Cost model fitted to measured kernel times on MI355X (micro-batch n):
+        #   materialise: the [n, P] fp32 gradients are written by the contraction's epilogue and
+        #     read back by the streaming accumulate -- 8 n P bytes at ~3 TB/s effective;
+        #   recompute: a second (clip-weighted) contraction plus the packing / slice-sum kernels
+        #     around it -- ~40 us of fixed cost plus the layer's flops at ~100 TFLOP/s sustained.
+        # Layers with more than about a million parameters (late stages, the classifier) recompute.
         p = layer.pw + layer.pb
-        materialise = 8.0 * p / _HBM                       # write + read one fp32 gradient
-        recompute = max(layer.flops / (0.4 * _MFMA[self.wl.dtype]), layer.in_bytes(esize) / _HBM)
+        materialise = 8.0 * p * self.n / 3.0e12
+        recompute = 40.0e-6 + layer.flops * self.n / 100.0e12
         return "materialise" if materialise <= recompute else "recompute"
 
     # ---- views of one layer's tensors in the flat vectors

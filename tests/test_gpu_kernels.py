@@ -155,7 +155,12 @@ def test_dense_per_example_grad_and_norm(layer, dtype):
         assert_close(gb, ref_b, tol, "dense db")
     assert np.allclose(sq, ref_n2, rtol=tol)
     _, _, sq2 = _run_per_example(layer, x, dy, dtype, materialise=False)
-    assert np.array_equal(sq, sq2)
+    if layer.h == 1:
+        # one token per example: the norm-only call uses |dy|^2 |x|^2 (+ |dy|^2), the same number
+        # up to fp32 rounding order
+        assert np.allclose(sq2, ref_n2, rtol=F32_TOL), (sq2, ref_n2)
+    else:
+        assert np.array_equal(sq, sq2)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
