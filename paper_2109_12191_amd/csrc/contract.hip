@@ -308,41 +308,27 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
     constexpr int LS = (LOADER == 2) ? 2 : 1;
     constexpr int RA = (LOADER == 0) ? 4 : raw_n<BF16, 1>();
     constexpr int RB = (LOADER == 0) ? 4 : raw_n<BF16, LS>();
+    constexpr int EPD = BF16 ? 2 : 1;                  // elements per dword
     struct RawSet {
         Raw<RA> ra[PA];
         Raw<RB> rb[PB];
         uint32_t ma[PA], mb[PB];
         int i, c;                            // example and chunk (within the example) held by this set
+        int oh, ow0;                         // this thread's output position in that chunk (gather loaders)
     };
     RawSet set0, set1;
 
-    // Which chunks cannot use whole-dword reads: thresholds on the chunk index within an example,
-    // computed once (all wave-uniform).
-    const bool flat_tail = (LOADER == 0) && (a.S % EPP != 0);
-    const bool all_slow = (LOADER != 0 || flat_tail) && (a.force_slow || x_ex < 512 || dy_ex < 512);
-    int slow_a_from = 0x7FFFFFFF, slow_b_from = 0x7FFFFFFF, slow_b_until = -1;
-    if constexpr (LOADER == 0) {
-        if (flat_tail) slow_a_from = slow_b_from = (a.S - 1) / KC;       // the chunk that holds the row's tail
-    } else {
-        const int risk_a = (16 + a.ow - 1) / a.ow;      // trailing output rows within 32 bytes of a channel's end
-        const int risk_b = (16 + a.w - 1) / a.w;        // trailing input rows likewise
-        const int ta = (a.oh - risk_a) * a.kcolsp - KC + 1;              // first chunk reaching output row OH - risk_a
-        slow_a_from = ta <= 0 ? 0 : (ta + KC - 1) / KC;
-        const int need = a.h - risk_b - (a.kh - 1 - a.pad);             // input row reached by the lowest tap
-        const int ohb = need <= 0 ? 0 : (need + a.stride - 1) / a.stride;
-        if (ohb <= a.oh - 1) {
-            const int tb = ohb * a.kcolsp - KC + 1;
-            slow_b_from = tb <= 0 ? 0 : (tb + KC - 1) / KC;
-        }
-        slow_b_until = ((a.pad / a.stride + 1) * a.kcolsp - 1) / KC;    // chunks touching rows that reach the top padding
-    }
-    auto is_slow_a = [&](int i, int c) -> bool {
-        return all_slow || (i == a.n - 1 && tile_m == a.tiles_m - 1 && c >= slow_a_from);
-    };
-    auto is_slow_b = [&](int i, int c) -> bool {
-        return all_slow || (i == a.n - 1 && tile_n == a.tiles_n - 1 && c >= slow_b_from) ||
-               (i == 0 && tile_n == 0 && c <= slow_b_until);
-    };
+    // Whole-dword reads touch a few bytes around the elements they need.  That is harmless inside
+    // the tensor (a neighbouring row or example) but the window of a piece must not leave it:
+    //   LOADER 0: the partial last piece of a row is read from a window moved back to end with the
+    //     row, and rotated down in registers;
+    //   LOADER 1 / 2: a piece whose window would start before the first example or end after the
+    //     last one is staged as zeros and then filled in element by element (a handful of pieces
+    //     in the workgroups of the first and the last example).
+    // Tensors too small to have slack, and strides other than 1 and 2, stage every chunk element
+    // by element.
+    const bool all_slow = a.force_slow || x_ex < 512 || dy_ex < 512 || a.S < EPP;
+    constexpr uint32_t UNSAFE = 2u;          // bit 1 of a piece's meta word
 
     // Position of the next chunk to fetch: example, chunk within it, and this thread's (oh, ow0);
     // advanced incrementally (no division in the loop).
@@ -353,70 +339,104 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
     const int step_oh = (LOADER == 0) ? 0 : KC / a.kcolsp, step_ow = (LOADER == 0) ? KC : KC - step_oh * a.kcolsp;
     int f_oh = oh0, f_ow = ow00;
 
+    // dword pointer and element parity of example i's first element (tensors are 16-byte aligned)
+    auto ex_words = [&](const E *base, size_t ex_elems, int i, int &par) -> const uint32_t * {
+        const size_t eb = (size_t)i * ex_elems;
+        par = (int)(eb % EPD);
+        return reinterpret_cast<const uint32_t *>(base) + eb / EPD;
+    };
+
     // Issue every global load of the next chunk (no use of the data here, so no wait either).
     auto fetch = [&](RawSet &R) {
         const int i = f_i, c = f_c;
         R.i = i; R.c = c;
-        if constexpr (LOADER == 0) {
-            // one long row per channel; pieces are dword aligned (16-byte aligned when S % EPP == 0);
-            // only the last piece of a row can be partial, and only A is masked for it
-            const int kprime = f_ow;
-            const int hi = min(EPP, a.S - kprime);
-            if (!is_slow_a(i, c)) {
-                const E *pa_ = dyg + (size_t)i * dy_ex + kprime;
+        if (!all_slow) {
+            if constexpr (LOADER == 0) {
+                // one long row per channel; a piece is 16 bytes at a dword-aligned address.  Only the
+                // last piece of a row can be partial: its window is moved back by `back` elements
+                const int kprime = f_ow;
+                const int hi = min(EPP, a.S - kprime);
+                const int back = (hi > 0 && hi < EPP) ? EPP - hi : 0;
+                const uint32_t meta = (uint32_t)max(hi, 0) | ((uint32_t)back << 8);
+                const E *pa_ = dyg + (size_t)i * dy_ex + (kprime - back);
 #pragma unroll
                 for (int q = 0; q < PA; ++q) {
                     u32x4_a4 v = {0u, 0u, 0u, 0u};
                     if (hi > 0 && a_row_off[q] >= 0) v = *reinterpret_cast<const u32x4_a4 *>(pa_ + a_row_off[q]);
                     R.ra[q].d[0] = v.x; R.ra[q].d[1] = v.y; R.ra[q].d[2] = v.z; R.ra[q].d[3] = v.w;
-                    R.ma[q] = (uint32_t)max(hi, 0);
+                    R.ma[q] = meta;
                 }
-            }
-            if (!is_slow_b(i, c)) {
-                const E *pb_ = xg + (size_t)i * x_ex + kprime;
+                const E *pb_ = xg + (size_t)i * x_ex + (kprime - back);
 #pragma unroll
                 for (int q = 0; q < PB; ++q) {
                     u32x4_a4 v = {0u, 0u, 0u, 0u};
                     if (hi > 0 && b_off[q] >= 0) v = *reinterpret_cast<const u32x4_a4 *>(pb_ + b_off[q]);
                     R.rb[q].d[0] = v.x; R.rb[q].d[1] = v.y; R.rb[q].d[2] = v.z; R.rb[q].d[3] = v.w;
+                    R.mb[q] = meta;
                 }
-            }
-        } else {
-            const int oh = f_oh, ow0 = f_ow;
-            const bool k_ok = oh < a.oh;
-            if (!is_slow_a(i, c)) {
-                // A: dY_i[m, oh, ow0 .. ow0+EPP)
-                const E *ex_a = dyg + (size_t)i * dy_ex;
-                const int koff = k_ok ? oh * a.ow + ow0 : 0;
-                const int hi_a = k_ok ? min(a.ow - ow0, EPP) : 0;
+            } else {
+                const int oh = f_oh, ow0 = f_ow;
+                R.oh = oh; R.ow0 = ow0;
+                const bool k_ok = oh < a.oh;
+                const bool first = (i == 0), last = (i == a.n - 1);
+                {
+                    // A: dY_i[m, oh, ow0 .. ow0+EPP)
+                    int par;
+                    const uint32_t *wa = ex_words(dyg, dy_ex, i, par);
+                    const int koff = k_ok ? oh * a.ow + ow0 : 0;
+                    const int hi_a = k_ok ? min(a.ow - ow0, EPP) : 0;
 #pragma unroll
-                for (int q = 0; q < PA; ++q) {
-                    const bool ok = a_row_off[q] >= 0 && hi_a > 0;
-                    const E *src = ex_a + (ok ? a_row_off[q] + koff : 0);
-                    R.ra[q] = piece_load<BF16, 1>(src);
-                    R.ma[q] = ((uint32_t)(reinterpret_cast<uintptr_t>(src) >> 1) & 1u) | ((uint32_t)(ok ? hi_a : 0) << 16);
+                    for (int q = 0; q < PA; ++q) {
+                        const bool ok = a_row_off[q] >= 0 && hi_a > 0;
+                        const int e = (ok ? a_row_off[q] + koff : 0) + par;          // relative to wa, in elements
+                        const int ws = (e / EPD) * EPD - par, we = ws + RA * EPD;     // window, relative to the example
+                        const bool safe = (!first || ws >= 0) && (!last || we <= (int)dy_ex);
+                        const uint32_t *src = wa + (safe ? e / EPD : 0);
+                        if constexpr (BF16) {
+                            R.ra[q] = piece_load_words(src);
+                        } else {
+                            const u32x4_a4 v = *reinterpret_cast<const u32x4_a4 *>(src);
+                            R.ra[q].d[0] = v.x; R.ra[q].d[1] = v.y; R.ra[q].d[2] = v.z; R.ra[q].d[3] = v.w;
+                        }
+                        R.ma[q] = (uint32_t)(e & (EPD - 1)) | ((ok && !safe) ? UNSAFE : 0u) | ((uint32_t)(ok ? hi_a : 0) << 16);
+                    }
                 }
-            }
-            if (!is_slow_b(i, c)) {
-                // B: X_i[ci, oh*s + dh, (ow0 + e)*s + dw]; only the image edge is masked here,
-                // positions past OW meet the zeros of A
-                const E *ex_b = xg + (size_t)i * x_ex;
-                const int ihs = oh * a.stride, iws = ow0 * a.stride;
-                const int koff = ihs * a.w + iws;
+                {
+                    // B: X_i[ci, oh*s + dh, (ow0 + e)*s + dw]; only the image edge is masked here,
+                    // positions past OW meet the zeros of A
+                    int par;
+                    const uint32_t *wb = ex_words(xg, x_ex, i, par);
+                    const int ihs = oh * a.stride, iws = ow0 * a.stride;
+                    const int koff = ihs * a.w + iws;
 #pragma unroll
-                for (int q = 0; q < PB; ++q) {
-                    const int ih = ihs + (b_dhw[q] >> 16);
-                    const int first = iws + (int)(short)(b_dhw[q] & 0xFFFF);   // input column of e = 0
-                    int lo, hi;
-                    if constexpr (LOADER == 1) { lo = -first; hi = a.w - first; }
-                    else { lo = (1 - first) >> 1; hi = (a.w - first + 1) >> 1; }      // ceil(-first/2), ceil((W-first)/2)
-                    lo = min(max(lo, 0), EPP);
-                    hi = min(max(hi, lo), EPP);
-                    const bool ok = k_ok && (unsigned)ih < (unsigned)a.h && hi > lo;
-                    const E *src = ex_b + (ok ? b_off[q] + koff : 0);
-                    R.rb[q] = piece_load<BF16, LS>(src);
-                    R.mb[q] = ((uint32_t)(reinterpret_cast<uintptr_t>(src) >> 1) & 1u) | ((uint32_t)lo << 8) |
-                              ((uint32_t)(ok ? hi : lo) << 16);
+                    for (int q = 0; q < PB; ++q) {
+                        const int ih = ihs + (b_dhw[q] >> 16);
+                        const int first_col = iws + (int)(short)(b_dhw[q] & 0xFFFF);   // input column of e = 0
+                        int lo, hi;
+                        if constexpr (LOADER == 1) { lo = -first_col; hi = a.w - first_col; }
+                        else { lo = (1 - first_col) >> 1; hi = (a.w - first_col + 1) >> 1; }   // ceil(-first/2), ceil((W-first)/2)
+                        lo = min(max(lo, 0), EPP);
+                        hi = min(max(hi, lo), EPP);
+                        const bool ok = k_ok && (unsigned)ih < (unsigned)a.h && hi > lo;
+                        const int e = (ok ? b_off[q] + koff : 0) + par;
+                        // floor division: the first tap of the first row may start one element early
+                        const int ed = (e >= 0) ? e / EPD : -((-e + EPD - 1) / EPD);
+                        const int ws = ed * EPD - par, we = ws + RB * EPD;
+                        const bool safe = (!first || ws >= 0) && (!last || we <= (int)x_ex);
+                        const uint32_t *src = wb + (safe ? ed : 0);
+                        if constexpr (BF16 && LS == 1) {
+                            R.rb[q] = piece_load_words(src);
+                        } else {
+                            const u32x4_a4 v0 = *reinterpret_cast<const u32x4_a4 *>(src);
+                            R.rb[q].d[0] = v0.x; R.rb[q].d[1] = v0.y; R.rb[q].d[2] = v0.z; R.rb[q].d[3] = v0.w;
+                            if constexpr (LS == 2) {
+                                const u32x4_a4 v1 = *reinterpret_cast<const u32x4_a4 *>(src + 4);
+                                R.rb[q].d[4] = v1.x; R.rb[q].d[5] = v1.y; R.rb[q].d[6] = v1.z; R.rb[q].d[7] = v1.w;
+                            }
+                        }
+                        R.mb[q] = (uint32_t)(e & (EPD - 1)) | ((ok && !safe) ? UNSAFE : 0u) | ((uint32_t)lo << 8) |
+                                  ((uint32_t)(ok ? hi : lo) << 16);
+                    }
                 }
             }
         }
@@ -428,39 +448,90 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
         if (f_c == c_end) { f_c = c_begin; ++f_i; f_oh = oh0; f_ow = ow00; }
     };
 
-    // Finish the fetched pieces in registers and put the chunk into one LDS buffer (element by
-    // element for the chunks that may not use whole-dword reads).
+    // the partial last piece of a flat row was read `back` elements early: move it down (whole
+    // dwords: `back` is even for bf16) and zero what is shifted in
+    auto rotate_down = [&](uint32_t (&v)[4], int back) {
+        const int sh = back / EPD;
+        if (sh & 1) { v[0] = v[1]; v[1] = v[2]; v[2] = v[3]; v[3] = 0u; }
+        if (sh & 2) { v[0] = v[2]; v[1] = v[3]; v[2] = 0u; v[3] = 0u; }
+    };
+
+    // Finish the fetched pieces in registers and put the chunk into one LDS buffer.
     auto stage = [&](const RawSet &R, char *bufA, char *bufB) {
         const int i = R.i, c = R.c, k0 = c * KC;
         float f = 1.0f;
         if constexpr (WEIGHTED) f = clip_factor(a.group_sqnorm[i], a.clip_c);
-        if (is_slow_a(i, c)) {
+        if (all_slow) {
             slow_stage_a<BF16, MT, WEIGHTED>(bufA, dyg + (size_t)i * dy_ex, a.cout, a.S, a.oh, a.ow, a.kcolsp, m0, k0, f);
-        } else {
-#pragma unroll
-            for (int q = 0; q < PA; ++q) {
-                uint32_t v[4];
-                if constexpr (LOADER == 0) {
-                    v[0] = R.ra[q].d[0]; v[1] = R.ra[q].d[1]; v[2] = R.ra[q].d[2]; v[3] = R.ra[q].d[3];
-                    mask_piece<BF16>(v, 0, (int)R.ma[q]);
-                } else {
-                    piece_finish<BF16, 1>(v, R.ra[q], R.ma[q] & 1u, 0, (int)(R.ma[q] >> 16));
-                }
-                if constexpr (WEIGHTED) scale_regs<BF16, 4>(v, f);
-                *reinterpret_cast<uint4 *>(bufA + (row0 + 32 * q) * PITCH + (threadIdx.x & 7) * 16) =
-                    make_uint4(v[0], v[1], v[2], v[3]);
-            }
-        }
-        if (is_slow_b(i, c)) {
             slow_stage_b<BF16, NT>(bufB, xg + (size_t)i * x_ex, cols, a.h, a.w, a.oh, a.ow, a.stride, a.kcolsp, k0);
-        } else {
+            return;
+        }
+        const int lds_col = (threadIdx.x & 7) * 16;
 #pragma unroll
-            for (int q = 0; q < PB; ++q) {
-                uint32_t v[4];
-                if constexpr (LOADER == 0) { v[0] = R.rb[q].d[0]; v[1] = R.rb[q].d[1]; v[2] = R.rb[q].d[2]; v[3] = R.rb[q].d[3]; }
-                else piece_finish<BF16, LS>(v, R.rb[q], R.mb[q] & 1u, (int)((R.mb[q] >> 8) & 0xFFu), (int)(R.mb[q] >> 16));
-                *reinterpret_cast<uint4 *>(bufB + (row0 + 32 * q) * PITCH + (threadIdx.x & 7) * 16) =
-                    make_uint4(v[0], v[1], v[2], v[3]);
+        for (int q = 0; q < PA; ++q) {
+            uint32_t v[4];
+            if constexpr (LOADER == 0) {
+                v[0] = R.ra[q].d[0]; v[1] = R.ra[q].d[1]; v[2] = R.ra[q].d[2]; v[3] = R.ra[q].d[3];
+                rotate_down(v, (int)(R.ma[q] >> 8));
+                mask_piece<BF16>(v, 0, (int)(R.ma[q] & 0xFFu));
+            } else {
+                const int hi = (R.ma[q] & UNSAFE) ? 0 : (int)(R.ma[q] >> 16);
+                if constexpr (BF16) {
+                    piece_finish<BF16, 1>(v, R.ra[q], R.ma[q] & 1u, 0, hi);
+                } else {
+                    v[0] = R.ra[q].d[0]; v[1] = R.ra[q].d[1]; v[2] = R.ra[q].d[2]; v[3] = R.ra[q].d[3];
+                    mask_piece<BF16>(v, 0, hi);
+                }
+            }
+            if constexpr (WEIGHTED) scale_regs<BF16, 4>(v, f);
+            *reinterpret_cast<uint4 *>(bufA + (row0 + 32 * q) * PITCH + lds_col) = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            uint32_t v[4];
+            if constexpr (LOADER == 0) {
+                v[0] = R.rb[q].d[0]; v[1] = R.rb[q].d[1]; v[2] = R.rb[q].d[2]; v[3] = R.rb[q].d[3];
+                rotate_down(v, (int)(R.mb[q] >> 8));
+            } else {
+                const int lo = (int)((R.mb[q] >> 8) & 0xFFu);
+                const int hi = (R.mb[q] & UNSAFE) ? lo : (int)(R.mb[q] >> 16);
+                piece_finish<BF16, LS>(v, R.rb[q], R.mb[q] & 1u, lo, hi);
+            }
+            *reinterpret_cast<uint4 *>(bufB + (row0 + 32 * q) * PITCH + lds_col) = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+        if constexpr (LOADER != 0) {
+            // the few pieces staged as zeros because their window would have left the tensor
+            if (i == 0 || i == a.n - 1) {
+                const int oh = R.oh, ow0 = R.ow0;
+                const E *ex_a = dyg + (size_t)i * dy_ex;
+                const E *ex_b = xg + (size_t)i * x_ex;
+#pragma unroll
+                for (int q = 0; q < PA; ++q) {
+                    if (R.ma[q] & UNSAFE) {
+                        const E *src = ex_a + a_row_off[q] + oh * a.ow + ow0;
+                        E *dst = reinterpret_cast<E *>(bufA + (row0 + 32 * q) * PITCH + lds_col);
+                        const int hi = (int)(R.ma[q] >> 16);
+#pragma unroll 1
+                        for (int e = 0; e < hi; ++e) {
+                            E val = src[e];
+                            if constexpr (WEIGHTED) {
+                                if constexpr (BF16) val = float_to_bf16_bits(bf16_bits_to_float(val) * f);
+                                else val = val * f;
+                            }
+                            dst[e] = val;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < PB; ++q) {
+                    if (R.mb[q] & UNSAFE) {
+                        const E *src = ex_b + b_off[q] + oh * a.stride * a.w + ow0 * a.stride;
+                        E *dst = reinterpret_cast<E *>(bufB + (row0 + 32 * q) * PITCH + lds_col);
+                        const int lo = (int)((R.mb[q] >> 8) & 0xFFu), hi = (int)(R.mb[q] >> 16);
+#pragma unroll 1
+                        for (int e = lo; e < hi; ++e) dst[e] = src[e * LS];
+                    }
+                }
             }
         }
     };
