@@ -176,6 +176,15 @@ dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float si
 dp_status dp_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id,
                         dp_stream stream);
 
+/* Timing aid for benchmarks (not part of the method): the NEXT contraction kernel this thread
+ * launches through dp_per_example_grad or dp_clip_accumulate_recompute -- the kernel whose name
+ * dp_kernel_variant reports, not the small packing / slice-sum / partial-sum kernels around it --
+ * is bracketed by hipEventRecord(start, stream) and hipEventRecord(stop, stream) on the stream it
+ * is launched on.  start / stop are hipEvent_t handles passed as void*; the request is consumed
+ * by that launch; (NULL, NULL) cancels it.  Layers without a contraction (dense, GroupNorm)
+ * leave it pending.  Always DP_OK.                                                              */
+dp_status dp_profile_next_contraction(void *start, void *stop);
+
 /* Sentence describing the last error on this thread ("" if none).  Never NULL. */
 const char *dp_last_error(void);
 

@@ -60,6 +60,7 @@ def load_library():
         "dp_clip_accumulate_recompute": (it, [dpp, vp, vp, vp, fl, vp, vp, vp, sz, vp]),
         "dp_add_noise_finalize": (it, [vp, vp, sz, fl, fl, u64, u64, u64, u32, vp]),
         "dp_philox_raw": (it, [vp, sz, u64, u64, u32, vp]),
+        "dp_profile_next_contraction": (it, [vp, vp]),
         "dp_last_error": (C.c_char_p, []),
         "dp_version": (C.c_char_p, []),
     }
@@ -73,7 +74,7 @@ def load_library():
 
 EXPORTED = ("dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_recompute", "dp_add_noise_finalize",
-            "dp_philox_raw", "dp_last_error", "dp_version")
+            "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
 
 
 def make_desc(layer, n: int, dtype: str = "f32", layout: int = DP_NCHW) -> LayerDesc:
@@ -164,6 +165,14 @@ def dp_add_noise_finalize(acc, out, p: int, sigma: float, clip_total: float, tot
                           step: int, tensor_id: int, stream=None):
     _check(load_library().dp_add_noise_finalize(_ptr(acc), _ptr(out), p, sigma, clip_total, total_batch, seed,
                                                 step, tensor_id, _stream(stream)))
+
+
+def dp_profile_next_contraction(start_event, stop_event):
+    """Arm (or, with None, cancel) event bracketing of the next contraction kernel.  The arguments are
+    torch.cuda.Event objects that have been recorded once (that creates their HIP handles)."""
+    a = start_event.cuda_event if start_event is not None else None
+    b = stop_event.cuda_event if stop_event is not None else None
+    _check(load_library().dp_profile_next_contraction(a, b))
 
 
 def dp_philox_raw(raw, p: int, seed: int, step: int, tensor_id: int, stream=None):

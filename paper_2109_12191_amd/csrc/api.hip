@@ -10,6 +10,19 @@
 namespace dp {
 
 static thread_local char g_err[512] = "";
+static thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
+void profile_begin(hipStream_t s)
+{
+    if (g_prof_start) (void)hipEventRecord(g_prof_start, s);
+    g_prof_start = nullptr;
+}
+
+void profile_end(hipStream_t s)
+{
+    if (g_prof_stop) (void)hipEventRecord(g_prof_stop, s);
+    g_prof_stop = nullptr;
+}
 
 dp_status fail(dp_status code, const char *fmt, ...)
 {
@@ -130,6 +143,13 @@ using namespace dp;
 extern "C" {
 
 const char *dp_last_error(void) { return g_err; }
+
+dp_status dp_profile_next_contraction(void *start, void *stop)
+{
+    dp::g_prof_start = static_cast<hipEvent_t>(start);
+    dp::g_prof_stop = static_cast<hipEvent_t>(stop);
+    return DP_OK;
+}
 const char *dp_version(void) { return "0.1 gfx950"; }
 
 size_t dp_weight_count(const dp_layer_desc *desc)

@@ -970,6 +970,7 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
     const bool flat = (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0);
     const int loader = (flat && (!g.bf16 || a.S % 2 == 0)) ? 0 : (g.stride == 2 ? 2 : 1);
     a.force_slow = (g.stride > 2) ? 1 : 0;
+    profile_begin(s);
     if (g.bf16) {
         switch (f.shape) {
         case T64: launch_shape<true, 2, 2, 1, 1>(a, loader, weighted, bias, blocks, s); break;
@@ -979,6 +980,7 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
         if (f.shape == T64) launch_shape<false, 2, 2, 1, 1>(a, loader, weighted, bias, blocks, s);
         else launch_shape<false, 2, 2, 2, 2>(a, loader, weighted, bias, blocks, s);
     }
+    profile_end(s);
     dp_status st = check_launch("conv_contract");
     if (st != DP_OK) return st;
     if (f.ksplit > 1) {

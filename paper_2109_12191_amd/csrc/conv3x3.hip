@@ -48,6 +48,8 @@ struct C3Args {
 };
 
 constexpr int odd16(int bytes) { return ((bytes / 16) | 1) * 16; }
+constexpr int C3_RP = 292;                           // floats per row staged by the store epilogue: 288 + 4
+constexpr int C3_STORE_LDS = 4 * 8 * C3_RP * 4;      // bytes the store epilogue needs: 4 waves x 8 rows
 
 template <int W> struct C3Cfg {
     static constexpr int OWP = (W + 7) / 8 * 8;
@@ -61,7 +63,7 @@ template <int W> struct C3Cfg {
     static constexpr int NPA = 64 * R * PPR, NPX = 64 * XROWS * XPR;
     static constexpr int PA_T = (NPA + C3_THREADS - 1) / C3_THREADS;
     static constexpr int PX_T = (NPX + C3_THREADS - 1) / C3_THREADS;
-    static constexpr int LDS = 64 * PA + 64 * PX;
+    static constexpr int LDS = (64 * PA + 64 * PX > C3_STORE_LDS) ? 64 * PA + 64 * PX : C3_STORE_LDS;
     static constexpr bool ALIGNED_A = (W % 8 == 0);
     static_assert(OWP == 8 || OWP == 16 || OWP == 32 || OWP == 56, "supported row widths");
     static_assert(R * OWP % 16 == 0, "whole MFMA K steps");
@@ -69,23 +71,57 @@ template <int W> struct C3Cfg {
 
 // What a workgroup does with finished accumulators (all of K of one example): squared norm of
 // its 64 x 64 x 9 block and the optional store in the framework's [Cout, Cin, 3, 3] order.
+//
+// In the accumulator layout a lane holds, per tap, one input channel and sixteen output channels,
+// so a direct store writes 4 bytes every 36.  When the layer's channel counts allow it the block
+// goes through LDS instead (`lds`, free once the MFMAs are done): each wave lays down eight
+// output-channel rows of 32 ci x 9 taps = 288 consecutive floats of the gradient, and reads them
+// back as 16-byte pieces that leave as fully coalesced 1152-byte row segments.
 __device__ __forceinline__ void c3_epilogue(const f32x16 (&acc)[9], const C3Args &a, int i, int unit, int co0, int ci0,
-                                            int wm, int wn, int lane, float *red)
+                                            int wm, int wn, int lane, float *red, char *lds)
 {
     float ss = 0.0f;
     const bool store = a.out_w != nullptr;
-    const int ci = ci0 + wn * 32 + (lane & 31);
     float *out = a.out_w + (size_t)i * a.out_stride;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int co = co0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        const bool ok = store && co < a.cout && ci < a.cin;
-        const size_t base = ((size_t)co * a.cin + ci) * 9;
+    for (int t = 0; t < 9; ++t)
 #pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            const float v = acc[t][r];
-            ss += v * v;                              // channels beyond the layer are exact zeros
-            if (ok) out[base + t] = v;
+        for (int r = 0; r < 16; ++r) ss += acc[t][r] * acc[t][r];     // channels beyond the layer are exact zeros
+    // wave-uniform: whole 32-channel blocks, 16-byte aligned rows
+    const bool via_lds = store && lds != nullptr && (a.cin % 32 == 0) && (a.out_stride % 4 == 0) &&
+                         ((reinterpret_cast<uintptr_t>(a.out_w) & 15u) == 0);
+    if (via_lds) {
+        float *buf = reinterpret_cast<float *>(lds) + (threadIdx.x >> 6) * (8 * C3_RP);
+        const int cil = lane & 31, half = lane >> 5;
+        const int cib = ci0 + wn * 32;                                // first input channel of this wave
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            __syncthreads();                                          // previous pass read / MFMAs done with LDS
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                for (int t = 0; t < 9; ++t) buf[(half * 4 + rr) * C3_RP + cil * 9 + t] = acc[t][q * 4 + rr];
+            __syncthreads();
+#pragma unroll
+            for (int it = 0; it < 9; ++it) {
+                const int f4 = it * 64 + lane;                        // 8 rows x 72 pieces
+                const int row = f4 / 72, c4 = f4 - row * 72;
+                const int co = co0 + wm * 32 + q * 8 + row;
+                const float4 v = *reinterpret_cast<const float4 *>(buf + row * C3_RP + c4 * 4);
+                if (co < a.cout && cib < a.cin)
+                    *reinterpret_cast<float4 *>(out + ((size_t)co * a.cin + cib) * 9 + c4 * 4) = v;
+            }
+        }
+    } else if (store) {
+        const int ci = ci0 + wn * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int co = co0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            const bool ok = co < a.cout && ci < a.cin;
+            const size_t base = ((size_t)co * a.cin + ci) * 9;
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+                if (ok) out[base + t] = acc[t][r];
         }
     }
     const float tot = block_sum<4>(ss, red);
@@ -278,7 +314,7 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
     }
 
     if constexpr (!SPLIT) {
-        c3_epilogue(acc, a, i, unit, co0, ci0, wm, wn, lane, red);
+        c3_epilogue(acc, a, i, unit, co0, ci0, wm, wn, lane, red, lds);
     } else {
         float *mine = a.ws_part + ((size_t)unit * a.ksplit + split) * (9 * 16 * C3_THREADS);
 #pragma unroll
@@ -459,6 +495,7 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     const long long total = (long long)units * p.ksplit;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     dp_status st;
+    profile_begin(s);
     switch (g.w) {
     case 7: st = c3_launch_w<7>(a, blocks, s); break;
     case 8: st = c3_launch_w<8>(a, blocks, s); break;
@@ -468,6 +505,7 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     case 32: st = c3_launch_w<32>(a, blocks, s); break;
     default: st = c3_launch_w<56>(a, blocks, s); break;
     }
+    profile_end(s);
     if (st != DP_OK) return st;
     if (p.ksplit > 1) {
         hipLaunchKernelGGL(conv3x3_fixup_kernel, dim3((unsigned)(units * 9 * C3_FIX_PARTS)), dim3(C3_THREADS), 0, s, a);

@@ -13,6 +13,11 @@ namespace dp {
 dp_status fail(dp_status code, const char *fmt, ...);
 dp_status check_launch(const char *what);
 
+// ---- benchmark timing aid (api.hip): events armed by dp_profile_next_contraction.  A contraction
+// launcher calls profile_begin(s) right before and profile_end(s) right after its main kernel.
+void profile_begin(hipStream_t s);
+void profile_end(hipStream_t s);
+
 // ---- geometry of a validated descriptor ------------------------------------------------
 struct Geo {
     int kind, bf16, n;

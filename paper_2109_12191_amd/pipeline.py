@@ -83,18 +83,17 @@ class PrivatiseStep:
         self.side = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
         self.graph = None
         self.micro_steps_done = 0
-        # optional timing probe (bench.py): an object with bracket(variant, flops, bytes) that
-        # records an event on the current stream and returns the event to record afterwards
+        # optional timing probe (bench.py): an object with arm(variant, flops, bytes) that asks the
+        # library to bracket the next contraction kernel with a pair of events
         self.probe = None
         esize = 2 if wl.dtype == "bf16" else 4
         self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD), B.dp_kernel_variant(d, B.DP_WS_RECOMPUTE))
                         for d in self.descs]
         self.work = [(l.flops * wl.n, l.in_bytes(esize) * wl.n) for l in self.layers]
 
-    def _bracket(self, li: int, use: int):
-        if self.probe is None:
-            return None
-        return self.probe.bracket(self.variant[li][use], self.work[li][0], self.work[li][1])
+    def _arm(self, li: int, use: int):
+        if self.probe is not None and self.layers[li].kind == "conv":
+            self.probe.arm(self.variant[li][use], self.work[li][0], self.work[li][1])
 
     def _choose(self, layer, mode: str) -> str:
         if mode in ("materialise", "recompute"):
@@ -153,7 +152,7 @@ class PrivatiseStep:
             x, dy = inputs[li]
             st = self._stream_of(li)
             ws = self.ws_of[li]
-            stop = self._bracket(li, 0)
+            self._arm(li, 0)
             if self.form[li] == "materialise":
                 g_w = self.g[:, self.off_w[li]:]
                 g_b = self.g[:, self.off_b[li]:] if self.pb[li] else None
@@ -163,8 +162,6 @@ class PrivatiseStep:
             else:
                 B.dp_per_example_grad(self.descs[li], x, dy, None, None, self.layer_sqnorm[li], ws,
                                       ws_bytes=ws.numel(), stream=st)
-            if stop is not None:
-                stop.record()
         self._join()
         B.dp_norms(self.layer_sqnorm, self.group_of_layer_dev, L, self.n, self.n_groups, self.group_sqnorm)
         self._fork()
@@ -191,13 +188,11 @@ class PrivatiseStep:
             ws = self.ws_of[li]
             st = self.side[k % self.n_streams] if self.side else None
             k += 1
-            stop = self._bracket(li, 1)
+            self._arm(li, 1)
             B.dp_clip_accumulate_recompute(self.descs[li], x, dy, self.group_sqnorm[g], self.group_clip[g],
                                            self.acc_w(li).data_ptr(),
                                            self.acc_b(li).data_ptr() if self.pb[li] else None,
                                            ws, ws_bytes=ws.numel(), stream=st)
-            if stop is not None:
-                stop.record()
         self._join()
         self.micro_steps_done += 1
 

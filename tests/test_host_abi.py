@@ -131,3 +131,9 @@ def test_recompute_argument_errors(lib):
     nb = dp.make_desc(conv(8, 8, 3, 1, 8), 4)
     _raises(B.DP_ERR_INVALID_ARG, dp.dp_clip_accumulate_recompute, nb, FAKE, FAKE, FAKE, 1.0, FAKE, FAKE, FAKE,
             ws_bytes=1 << 20, stream=0)                    # acc_b for a layer without bias
+
+
+def test_profile_hook_accepts_null_events(lib):
+    """The benchmark timing aid can be armed / cancelled without a GPU (no HIP call is made until
+    a contraction is launched)."""
+    assert B.load_library().dp_profile_next_contraction(None, None) == 0
