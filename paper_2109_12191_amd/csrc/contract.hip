@@ -784,8 +784,10 @@ static FullPlan full_plan(const Geo &g, int mode)
             if (want < 1) want = 1;
             p.chunks_per_split = (int)((p.chunks_per_ex + want - 1) / want);
             p.ksplit = (p.chunks_per_ex + p.chunks_per_split - 1) / p.chunks_per_split;
-        } else if (units > 1536 && p.chunks_per_ex <= 4) {
-            long long e = units / 1024;
+        } else if (units > 768 && p.chunks_per_ex <= 4) {
+            // short K, many tiles: one round of ~512 workgroups that each stream several examples
+            // (loads run ahead across example boundaries) beats several rounds of short ones
+            long long e = (units + 511) / 512;
             if (e > 8) e = 8;
             if (e > g.n) e = g.n;
             p.ex_per_wg = (int)(e < 1 ? 1 : e);

@@ -403,7 +403,7 @@ C3Plan c3_plan(const Geo &g)
     p.ksplit = 1;
     p.chunks_per_split = p.chunks;
     if (units < 512 && p.chunks > 1) {
-        long long want = (512 + units - 1) / units;
+        long long want = (256 + units - 1) / units;
         if (want > p.chunks) want = p.chunks;
         p.chunks_per_split = (int)((p.chunks + want - 1) / want);
         p.ksplit = (p.chunks + p.chunks_per_split - 1) / p.chunks_per_split;

@@ -65,22 +65,31 @@ class PrivatiseStep:
         f32 = torch.float32
         self.acc = torch.zeros(self.p_total, dtype=f32, device=dev)
         self.out = torch.zeros(self.p_total, dtype=f32, device=dev)
-        self.g = torch.zeros((self.n, self.p_mat), dtype=f32, device=dev) if self.p_mat else None
-        self.layer_sqnorm = torch.zeros((L, self.n), dtype=f32, device=dev)
-        self.group_sqnorm = torch.zeros((self.n_groups, self.n), dtype=f32, device=dev)
-        self.group_of_layer_dev = torch.tensor(self.group_of_layer, dtype=torch.int32, device=dev)
-        # Workspaces.  With one stream all calls share one buffer (they run in order); with side
-        # streams the layers of a phase run concurrently, so each layer gets its own.
+        # Workspaces and per-micro-step buffers.  With one stream all calls run in order and share
+        # one workspace.  With side streams the layers of a phase run concurrently (a workspace per
+        # layer) and the two phases of consecutive micro-steps overlap: everything a micro-step
+        # writes before its clipped sum is done -- the gradient matrix, the norms, the workspaces --
+        # exists twice and micro-steps alternate between the copies.
         self.n_streams = max(1, int(streams))
+        self.copies = 2 if self.n_streams > 1 else 1
+        self._g = [torch.zeros((self.n, self.p_mat), dtype=f32, device=dev) if self.p_mat else None
+                   for _ in range(self.copies)]
+        self._layer_sqnorm = [torch.zeros((L, self.n), dtype=f32, device=dev) for _ in range(self.copies)]
+        self._group_sqnorm = [torch.zeros((self.n_groups, self.n), dtype=f32, device=dev) for _ in range(self.copies)]
+        self.group_of_layer_dev = torch.tensor(self.group_of_layer, dtype=torch.int32, device=dev)
         need = [max(16, B.dp_workspace_bytes(d, B.DP_WS_PER_EXAMPLE_GRAD),
                     B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE) if form == "recompute" else 0)
                 for d, form in zip(self.descs, self.form)]
         if self.n_streams == 1:
             shared = torch.empty(max(need), dtype=torch.uint8, device=dev)
-            self.ws_of = [shared] * L
+            self._ws = [[shared] * L]
         else:
-            self.ws_of = [torch.empty(b, dtype=torch.uint8, device=dev) for b in need]
+            self._ws = [[torch.empty(b, dtype=torch.uint8, device=dev) for b in need] for _ in range(self.copies)]
+        # side streams: `side` for the per-example phase, `side_b` for the clipped-sum phase
         self.side = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
+        self.side_b = [torch.cuda.Stream(device=dev) for _ in range(max(2, self.n_streams // 2))] if self.n_streams > 1 else []
+        self._b_done = [None] * self.copies      # per copy: events after which its buffers are free again
+        self._last = 0                           # copy used by the most recent micro-step
         self.graph = None
         self.micro_steps_done = 0
         # optional timing probe (bench.py): an object with arm(variant, flops, bytes) that asks the
@@ -124,80 +133,116 @@ class PrivatiseStep:
     def out_b(self, li: int) -> Optional[torch.Tensor]:
         return self.out[self.off_b[li]: self.off_b[li] + self.pb[li]] if self.pb[li] else None
 
+    @property
+    def group_sqnorm(self) -> torch.Tensor:
+        """[groups, n] squared norms of the most recent micro-step."""
+        return self._group_sqnorm[self._last]
+
+    @property
+    def layer_sqnorm(self) -> torch.Tensor:
+        return self._layer_sqnorm[self._last]
+
+    @property
+    def g(self) -> Optional[torch.Tensor]:
+        return self._g[self._last]
+
     def begin_step(self):
         self.acc.zero_()
         self.micro_steps_done = 0
+        self._b_done = [None] * self.copies
 
     def _stream_of(self, li: int):
         return self.side[li % self.n_streams] if self.side else None
 
-    def _fork(self):
-        main = torch.cuda.current_stream()
-        for st in self.side:
-            st.wait_stream(main)
-
-    def _join(self):
-        main = torch.cuda.current_stream()
-        for st in self.side:
-            main.wait_stream(st)
-
     def micro_step(self, inputs: Sequence):
         """inputs: per layer (x, dy) device tensors of the workload's dtype, n examples each.
-        Layers of one phase are independent; with side streams they are spread over them and the
-        phases are separated by joins on the current stream."""
+
+        Phase A (per-example gradients + norms of every layer) and phase B (clipped sum) of one
+        micro-step are separated by dp_norms.  Layers within a phase are independent; with side
+        streams they are spread over them, and phase A of the next micro-step does not wait for
+        phase B of this one (they work on different buffer copies).  The clipped sums reach the
+        accumulator in the same order on every run: each tensor is updated by one call per
+        micro-step, always issued on the same stream."""
         L = len(self.layers)
         gs = self.p_mat
-        self._fork()
+        c = self.micro_steps_done % self.copies
+        self._last = c
+        g_buf, lsq, gsq, wss = self._g[c], self._layer_sqnorm[c], self._group_sqnorm[c], self._ws[c]
+        main = torch.cuda.current_stream()
+        # ---- phase A
+        for st in self.side:
+            st.wait_stream(main)
+            if self._b_done[c] is not None:           # this copy's previous clipped sum has finished
+                for ev in self._b_done[c]:
+                    st.wait_event(ev)
         for li in range(L):
             x, dy = inputs[li]
             st = self._stream_of(li)
-            ws = self.ws_of[li]
+            ws = wss[li]
             self._arm(li, 0)
             if self.form[li] == "materialise":
-                g_w = self.g[:, self.off_w[li]:]
-                g_b = self.g[:, self.off_b[li]:] if self.pb[li] else None
+                g_w = g_buf[:, self.off_w[li]:]
+                g_b = g_buf[:, self.off_b[li]:] if self.pb[li] else None
                 B.dp_per_example_grad(self.descs[li], x, dy, g_w.data_ptr(),
                                       g_b.data_ptr() if g_b is not None else None,
-                                      self.layer_sqnorm[li], ws, g_stride=gs, ws_bytes=ws.numel(), stream=st)
+                                      lsq[li], ws, g_stride=gs, ws_bytes=ws.numel(), stream=st)
             else:
-                B.dp_per_example_grad(self.descs[li], x, dy, None, None, self.layer_sqnorm[li], ws,
+                B.dp_per_example_grad(self.descs[li], x, dy, None, None, lsq[li], ws,
                                       ws_bytes=ws.numel(), stream=st)
-        self._join()
-        B.dp_norms(self.layer_sqnorm, self.group_of_layer_dev, L, self.n, self.n_groups, self.group_sqnorm)
-        self._fork()
+        for st in self.side:
+            main.wait_stream(st)
+        B.dp_norms(lsq, self.group_of_layer_dev, L, self.n, self.n_groups, gsq)
+        # ---- phase B
+        for st in self.side_b:
+            st.wait_stream(main)
+        sb = self.side_b
         if self.p_mat:
+            st0 = sb[0] if sb else None
             if self.n_groups == 1:
                 # one clipping group: every materialised tensor shares the factors -> one pass
-                B.dp_clip_accumulate(self.g, self.group_sqnorm[0], self.group_clip[0], self.n, self.p_mat,
-                                     self.acc, g_stride=gs)
+                B.dp_clip_accumulate(g_buf, gsq[0], self.group_clip[0], self.n, self.p_mat,
+                                     self.acc, g_stride=gs, stream=st0)
             else:
                 for li in range(L):
                     if self.form[li] != "materialise":
                         continue
                     g = self.group_of_layer[li]
                     span = _pad4(self.pw[li]) + _pad4(self.pb[li])
-                    B.dp_clip_accumulate(self.g[:, self.off_w[li]:].data_ptr(), self.group_sqnorm[g],
+                    B.dp_clip_accumulate(g_buf[:, self.off_w[li]:].data_ptr(), gsq[g],
                                          self.group_clip[g], self.n, span,
-                                         self.acc[self.off_w[li]:].data_ptr(), g_stride=gs)
+                                         self.acc[self.off_w[li]:].data_ptr(), g_stride=gs, stream=st0)
         k = 0
         for li in range(L):
             if self.form[li] != "recompute":
                 continue
             x, dy = inputs[li]
             g = self.group_of_layer[li]
-            ws = self.ws_of[li]
-            st = self.side[k % self.n_streams] if self.side else None
+            ws = wss[li]
+            st = sb[(1 + k) % len(sb)] if sb else None
             k += 1
             self._arm(li, 1)
-            B.dp_clip_accumulate_recompute(self.descs[li], x, dy, self.group_sqnorm[g], self.group_clip[g],
+            B.dp_clip_accumulate_recompute(self.descs[li], x, dy, gsq[g], self.group_clip[g],
                                            self.acc_w(li).data_ptr(),
                                            self.acc_b(li).data_ptr() if self.pb[li] else None,
                                            ws, ws_bytes=ws.numel(), stream=st)
-        self._join()
+        if sb:
+            evs = []
+            for st in sb:
+                ev = torch.cuda.Event()
+                ev.record(st)
+                evs.append(ev)
+            self._b_done[c] = evs
         self.micro_steps_done += 1
+
+    def _drain(self):
+        """The current stream waits for every clipped sum issued so far."""
+        main = torch.cuda.current_stream()
+        for st in self.side_b:
+            main.wait_stream(st)
 
     def finalize(self):
         wl = self.wl
+        self._drain()
         for li in range(len(self.layers)):
             B.dp_add_noise_finalize(self.acc_w(li).data_ptr(), self.out_w(li).data_ptr(), self.pw[li], wl.sigma,
                                     wl.clip_total, wl.total_batch, wl.philox_seed, wl.step, 2 * li)
