@@ -27,9 +27,14 @@ if ROOT not in sys.path:
 MFMA_PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, flop/s
 HBM_PEAK = 8.0e12
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); filled in once measured, else null in the JSON line.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM bytes per launch of the dominant kernel (conv_contract<bf16,128x128,per_example>) from the two
+# rocprofv3 --pmc runs summarised in profiles/conv_contract_resnet50_hbm_traffic.txt: mean FETCH_SIZE and
+# WRITE_SIZE per dispatch in KiB, each scaled by what the same counter reads for clip_accumulate_kernel
+# (a plain streaming kernel of known size in the same runs).
+PMC_FETCH_KIB, PMC_FETCH_SCALE = 12987.0, 2.0
+PMC_WRITE_KIB, PMC_WRITE_SCALE = 30472.0, 1.0
+MEASURED_TRAFFIC_KERNEL = "conv_contract<bf16,128x128,per_example>"
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1024.0 * (PMC_FETCH_KIB * PMC_FETCH_SCALE + PMC_WRITE_KIB * PMC_WRITE_SCALE)
 
 
 class Probe:
@@ -103,7 +108,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-examples", type=int, default=16)
     ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
-    ap.add_argument("--streams", type=int, default=4, help="side streams for independent layers")
+    ap.add_argument("--streams", type=int, default=8, help="side streams for independent layers")
     ap.add_argument("--no-graph", action="store_true", help="issue every call from the host instead of a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -163,7 +168,11 @@ def main():
     achieved = dom["flops"] / (dom["total_ms"] * 1e-3)
     peak = MFMA_PEAK[wl.dtype]
     roofline = dict(bound="mfma", achieved=achieved / 1e12, peak=peak / 1e12, unit="TFLOP/s",
-                    frac=achieved / peak, traffic=MEASURED_TRAFFIC_BYTES_PER_LAUNCH, kernel=dom_name,
+                    frac=achieved / peak,
+                    traffic=MEASURED_TRAFFIC_BYTES_PER_LAUNCH if (dom_name == MEASURED_TRAFFIC_KERNEL and args.workload == "resnet50"
+                                                                 and args.mode == "auto" and args.n is None and args.hw is None) else None,
+                    traffic_unit="HBM bytes per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see profiles/)",
+                    kernel=dom_name,
                     launches=dom["launches"], avg_launch_us=dom["total_ms"] * 1e3 / dom["launches"],
                     algorithmic_flop_per_launch=dom["flops"] / dom["launches"],
                     share_of_contraction_time=dom["total_ms"] / sum(v["total_ms"] for v in contraction.values()),
