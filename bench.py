@@ -73,7 +73,7 @@ def cpu_baseline(wl, inputs0, budget_examples):
     import numpy as np
     import oracle
     cores = oracle.max_threads()
-    s = min(budget_examples, wl.n, max(cores, 1))
+    s = min(budget_examples, wl.n)
     host_inputs = [(x[:s].float().cpu().numpy(), dy[:s].float().cpu().numpy()) for x, dy in inputs0]
     acc_w, acc_b = oracle.new_accumulators(wl.layers)
     t0 = time.perf_counter()
@@ -106,7 +106,8 @@ def main():
     ap.add_argument("--accum", type=int, default=None)
     ap.add_argument("--hw", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-examples", type=int, default=16)
+    ap.add_argument("--cpu-examples", type=int, default=32,
+                    help="examples of micro-batch 0 the oracle is timed on (32 = about 10 s on 16 cores)")
     ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
     ap.add_argument("--streams", type=int, default=8, help="side streams for independent layers")
     ap.add_argument("--no-graph", action="store_true", help="issue every call from the host instead of a HIP graph")
@@ -165,16 +166,25 @@ def main():
     esize = wl.elem_bytes
     contraction = {k: v for k, v in summary.items() if k.startswith("conv")}
     dom_name, dom = max(contraction.items(), key=lambda kv: kv[1]["total_ms"])
-    achieved = dom["flops"] / (dom["total_ms"] * 1e-3)
+    # which roof binds this kernel: its arithmetic intensity against the ridge of the chip
+    secs = dom["total_ms"] * 1e-3
+    flop_rate, byte_rate = dom["flops"] / secs, dom["bytes"] / secs
     peak = MFMA_PEAK[wl.dtype]
-    roofline = dict(bound="mfma", achieved=achieved / 1e12, peak=peak / 1e12, unit="TFLOP/s",
-                    frac=achieved / peak,
+    intensity = dom["flops"] / dom["bytes"]
+    hbm_bound = intensity < peak / HBM_PEAK
+    roofline = dict(bound="hbm" if hbm_bound else "mfma",
+                    achieved=byte_rate / 1e9 if hbm_bound else flop_rate / 1e12,
+                    peak=HBM_PEAK / 1e9 if hbm_bound else peak / 1e12,
+                    unit="GB/s" if hbm_bound else "TFLOP/s",
+                    frac=byte_rate / HBM_PEAK if hbm_bound else flop_rate / peak,
                     traffic=MEASURED_TRAFFIC_BYTES_PER_LAUNCH if (dom_name == MEASURED_TRAFFIC_KERNEL and args.workload == "resnet50"
                                                                  and args.mode == "auto" and args.n is None and args.hw is None) else None,
                     traffic_unit="HBM bytes per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see profiles/)",
-                    kernel=dom_name,
-                    launches=dom["launches"], avg_launch_us=dom["total_ms"] * 1e3 / dom["launches"],
+                    kernel=dom_name, launches=dom["launches"], avg_launch_us=dom["total_ms"] * 1e3 / dom["launches"],
+                    algorithmic_bytes_per_launch=dom["bytes"] / dom["launches"],
                     algorithmic_flop_per_launch=dom["flops"] / dom["launches"],
+                    flop_per_byte=intensity, ridge_flop_per_byte=peak / HBM_PEAK,
+                    mfma_tflops=flop_rate / 1e12, mfma_frac=flop_rate / peak,
                     share_of_contraction_time=dom["total_ms"] / sum(v["total_ms"] for v in contraction.values()),
                     measured="HIP events recorded by the library around each launch of this kernel, on its stream, "
                              "in a call-by-call single-stream pass over the same steps right after the timed region")
@@ -183,7 +193,7 @@ def main():
             tf = v["flops"] / (v["total_ms"] * 1e-3) / 1e12 if v["total_ms"] else 0.0
             gb = v["bytes"] / (v["total_ms"] * 1e-3) / 1e9 if v["total_ms"] else 0.0
             print(f"{k:50s} launches {v['launches']:6d}  {v['total_ms'] / probe_steps:9.3f} ms/step  "
-                  f"{tf:8.1f} TFLOP/s  {gb:8.1f} GB/s(in)", file=sys.stderr)
+                  f"{tf:8.1f} TFLOP/s  {gb:8.1f} GB/s (algorithmic)  {v['flops'] / v['bytes']:6.1f} flop/B", file=sys.stderr)
         print("forms:", {f: ps.form.count(f) for f in set(ps.form)}, f"eager ms/step {probe_elapsed / probe_steps * 1e3:.2f}",
               file=sys.stderr)
 

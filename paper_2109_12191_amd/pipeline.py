@@ -98,11 +98,17 @@ class PrivatiseStep:
         esize = 2 if wl.dtype == "bf16" else 4
         self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD), B.dp_kernel_variant(d, B.DP_WS_RECOMPUTE))
                         for d in self.descs]
-        self.work = [(l.flops * wl.n, l.in_bytes(esize) * wl.n) for l in self.layers]
+        # algorithmic work of one call per layer: (flop, HBM bytes of the per-example call, HBM bytes of the
+        # recomputing clipped-sum call).  Bytes = the operands read once, plus the per-example gradients
+        # written when the layer materialises them, or the accumulator read and written by form (b).
+        self.work = [(l.flops * wl.n,
+                      l.in_bytes(esize) * wl.n + (4 * wl.n * (pw + pb) if form == "materialise" else 0),
+                      l.in_bytes(esize) * wl.n + 8 * (pw + pb))
+                     for l, pw, pb, form in zip(self.layers, self.pw, self.pb, self.form)]
 
     def _arm(self, li: int, use: int):
         if self.probe is not None and self.layers[li].kind == "conv":
-            self.probe.arm(self.variant[li][use], self.work[li][0], self.work[li][1])
+            self.probe.arm(self.variant[li][use], self.work[li][0], self.work[li][1 + use])
 
     def _choose(self, layer, mode: str) -> str:
         if mode in ("materialise", "recompute"):
