@@ -123,6 +123,22 @@ dp_status dp_per_example_grad(const dp_layer_desc *desc /*[host]*/, const void *
                               float *g_w, float *g_b, size_t g_stride, float *sqnorm,
                               void *ws, size_t ws_bytes, dp_stream stream);
 
+/* The same per-example call without the per-layer reduction: the partial squared norms of the layer
+ * stay in the workspace, ws[0 .. n * count) as a row-major [n, count] float matrix with
+ * count = dp_norm_partial_count(desc, g_w != NULL), until the workspace is used again.
+ * dp_norms_from_partials then reduces the partials of all layers in one launch, so a model of L
+ * layers needs L fewer small launches per micro-step than with dp_per_example_grad + dp_norms (H2,
+ * same sums in a fixed order).  Arguments as dp_per_example_grad.                                 */
+size_t dp_norm_partial_count(const dp_layer_desc *desc, int materialise);
+dp_status dp_per_example_grad_partials(const dp_layer_desc *desc, const void *x, const void *dy, float *g_w, float *g_b,
+                                       size_t g_stride, void *ws, size_t ws_bytes, dp_stream stream);
+
+/* group_sqnorm[g, i] = sum over the layers l of group g, in order, of sum_c partials[l][i * counts[l] + c].
+ * partials [host] array of n_layers device pointers (4-byte aligned); counts, group_of_layer [host]
+ * arrays of n_layers ints; group_sqnorm [device] [n_groups, n], overwritten.                       */
+dp_status dp_norms_from_partials(const float *const *partials, const int32_t *counts, const int32_t *group_of_layer,
+                                 int n_layers, int n, int n_groups, float *group_sqnorm, dp_stream stream);
+
 /* H2: per-example squared norms per clipping group (Section 2: one global norm;
  * Section 3.5: one norm per group):
  *   group_sqnorm[g, i] = sum over layers l with group_of_layer[l] == g of layer_sqnorm[l, i],

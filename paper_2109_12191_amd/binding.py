@@ -55,6 +55,9 @@ def load_library():
         "dp_kernel_variant": (C.c_char_p, [dpp, it]),
         "dp_per_example_grad": (it, [dpp, vp, vp, vp, vp, sz, vp, vp, sz, vp]),
         "dp_norms": (it, [vp, vp, it, it, it, vp, vp]),
+        "dp_norm_partial_count": (sz, [dpp, it]),
+        "dp_per_example_grad_partials": (it, [dpp, vp, vp, vp, vp, sz, vp, sz, vp]),
+        "dp_norms_from_partials": (it, [vp, vp, vp, it, it, it, vp, vp]),
         "dp_clip_factors": (it, [vp, fl, it, vp, vp]),
         "dp_clip_accumulate": (it, [vp, sz, vp, fl, it, sz, vp, vp]),
         "dp_clip_accumulate_recompute": (it, [dpp, vp, vp, vp, fl, vp, vp, vp, sz, vp]),
@@ -73,6 +76,7 @@ def load_library():
 
 
 EXPORTED = ("dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
+            "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_recompute", "dp_add_noise_finalize",
             "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
 
@@ -137,6 +141,35 @@ def dp_per_example_grad(desc, x, dy, g_w, g_b, sqnorm, ws, g_stride: int = 0, ws
     _check(load_library().dp_per_example_grad(C.byref(desc), _ptr(x), _ptr(dy), _ptr(g_w), _ptr(g_b), g_stride,
                                               _ptr(sqnorm), _ptr(ws),
                                               _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream)))
+
+
+def dp_norm_partial_count(desc, materialise: bool) -> int:
+    return int(load_library().dp_norm_partial_count(C.byref(desc), 1 if materialise else 0))
+
+
+def dp_per_example_grad_partials(desc, x, dy, g_w, g_b, ws, g_stride: int = 0, ws_bytes: Optional[int] = None,
+                                 stream=None):
+    _check(load_library().dp_per_example_grad_partials(C.byref(desc), _ptr(x), _ptr(dy), _ptr(g_w), _ptr(g_b),
+                                                       g_stride, _ptr(ws),
+                                                       _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream)))
+
+
+class PartialTable:
+    """Host arrays for dp_norms_from_partials, built once: device pointers of every layer's partial
+    sums (the start of its workspace), their per-example counts and the layer -> group map."""
+
+    def __init__(self, pointers, counts, groups):
+        n = len(pointers)
+        self.n_layers = n
+        self.ptrs = (C.c_void_p * n)(*[int(p) for p in pointers])
+        self.counts = (C.c_int32 * n)(*[int(c) for c in counts])
+        self.groups = (C.c_int32 * n)(*[int(g) for g in groups])
+
+
+def dp_norms_from_partials(table: "PartialTable", n: int, n_groups: int, group_sqnorm, stream=None):
+    _check(load_library().dp_norms_from_partials(C.cast(table.ptrs, C.c_void_p), C.cast(table.counts, C.c_void_p),
+                                                 C.cast(table.groups, C.c_void_p), table.n_layers, n, n_groups,
+                                                 _ptr(group_sqnorm), _stream(stream)))
 
 
 def dp_norms(layer_sqnorm, group_of_layer, n_layers: int, n: int, n_groups: int, group_sqnorm, stream=None):

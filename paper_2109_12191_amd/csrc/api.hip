@@ -211,6 +211,66 @@ dp_status dp_per_example_grad(const dp_layer_desc *desc, const void *x, const vo
     return launch_gn(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
 }
 
+static size_t norm_partial_count_for(const Geo &g, int mode)
+{
+    if (g.kind == DP_CONV2D) return conv_norm_partial_count(g, mode);
+    if (g.kind == DP_DENSE) return dense_norm_partial_count(g, mode);
+    return gn_norm_partial_count(g);
+}
+
+size_t dp_norm_partial_count(const dp_layer_desc *desc, int materialise)
+{
+    Geo g;
+    if (make_geo(desc, g) != DP_OK) return 0;
+    return norm_partial_count_for(g, materialise ? MODE_MATERIALISE : MODE_NORM);
+}
+
+dp_status dp_per_example_grad_partials(const dp_layer_desc *desc, const void *x, const void *dy, float *g_w, float *g_b,
+                                       size_t g_stride, void *ws, size_t ws_bytes, dp_stream stream)
+{
+    Geo g;
+    DP_TRY(make_geo(desc, g));
+    DP_TRY(check_ptr(x, "x", true));
+    DP_TRY(check_ptr(dy, "dy", true));
+    DP_TRY(check_ptr(g_w, "g_w", false));
+    DP_TRY(check_ptr(g_b, "g_b", false));
+    if (g_w && g.pb && !g_b) return fail(DP_ERR_INVALID_ARG, "g_w given but g_b is NULL for a layer with a bias");
+    if (!g_w && g_b) return fail(DP_ERR_INVALID_ARG, "g_b given without g_w");
+    if (g_stride) {
+        if (g_stride % 4) return fail(DP_ERR_INVALID_ARG, "g_stride must be a multiple of 4");
+        if (g_stride < g.pw || g_stride < g.pb) return fail(DP_ERR_INVALID_ARG, "g_stride smaller than the tensor");
+    }
+    DP_TRY(check_ws(g, MODE_NORM, ws, ws_bytes));
+    const int mode = g_w ? MODE_MATERIALISE : MODE_NORM;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    g_err[0] = 0;
+    // sqnorm == nullptr: the kernels leave their partial sums at the start of the workspace
+    if (g.kind == DP_CONV2D) return launch_conv(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
+    if (g.kind == DP_DENSE) return launch_dense(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
+    return launch_gn(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
+}
+
+dp_status dp_norms_from_partials(const float *const *partials, const int32_t *counts, const int32_t *group_of_layer,
+                                 int n_layers, int n, int n_groups, float *group_sqnorm, dp_stream stream)
+{
+    if (!partials || !counts || !group_of_layer)
+        return fail(DP_ERR_INVALID_ARG, "partials, counts and group_of_layer must be non-NULL host arrays");
+    DP_TRY(check_ptr(group_sqnorm, "group_sqnorm", true, 4));
+    if (n_layers < 1 || n < 1 || n_groups < 1)
+        return fail(DP_ERR_INVALID_ARG, "n_layers (%d), n (%d) and n_groups (%d) must be >= 1", n_layers, n, n_groups);
+    if (n_groups > 65535) return fail(DP_ERR_UNSUPPORTED, "more than 65535 clipping groups");
+    for (int l = 0; l < n_layers; ++l) {
+        if (!partials[l] || (reinterpret_cast<uintptr_t>(partials[l]) & 3u))
+            return fail(DP_ERR_INVALID_ARG, "partials[%d] is NULL or not 4-byte aligned", l);
+        if (counts[l] < 1) return fail(DP_ERR_INVALID_ARG, "counts[%d] = %d (need >= 1)", l, counts[l]);
+        if (group_of_layer[l] < 0 || group_of_layer[l] >= n_groups)
+            return fail(DP_ERR_INVALID_ARG, "group_of_layer[%d] = %d outside [0, %d)", l, group_of_layer[l], n_groups);
+    }
+    g_err[0] = 0;
+    return launch_norms_from_partials(partials, counts, group_of_layer, n_layers, n, n_groups, group_sqnorm,
+                                      static_cast<hipStream_t>(stream));
+}
+
 dp_status dp_norms(const float *layer_sqnorm, const int32_t *group_of_layer, int n_layers, int n, int n_groups,
                    float *group_sqnorm, dp_stream stream)
 {

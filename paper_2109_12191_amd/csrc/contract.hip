@@ -859,6 +859,12 @@ size_t conv_ws_bytes(const Geo &g, int mode)
     return b;
 }
 
+size_t conv_norm_partial_count(const Geo &g, int mode)
+{
+    if (conv3x3_applicable(g, mode)) return conv3x3_norm_partial_count(g);
+    return norm_partials_per_example(full_plan(g, mode));
+}
+
 const char *conv_variant_name(const Geo &g, int mode)
 {
     if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);

@@ -459,6 +459,12 @@ size_t conv3x3_ws_bytes(const Geo &g, int mode)
     return b;
 }
 
+size_t conv3x3_norm_partial_count(const Geo &g)
+{
+    const C3Plan p = c3_plan(g);
+    return (size_t)p.tiles_co * p.tiles_ci * c3_partials_per_unit(p);
+}
+
 const char *conv3x3_variant_name(const Geo &g, int mode)
 {
     (void)mode;

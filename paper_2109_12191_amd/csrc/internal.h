@@ -62,6 +62,13 @@ PackPlan pack_plan(const Geo &g, int groups);
 dp_status launch_pack_weighted(const Geo &g, const PackPlan &p, const void *x, const void *dy,
                                const float *group_sqnorm, float clip_c, void *xp, void *dyp, hipStream_t s);
 
+// Partial squared norms per example that a per-example call leaves at the start of its workspace
+// ([n, count] floats) when it is told not to reduce them (sqnorm == nullptr).
+size_t conv_norm_partial_count(const Geo &g, int mode);
+size_t conv3x3_norm_partial_count(const Geo &g);
+size_t dense_norm_partial_count(const Geo &g, int mode);
+size_t gn_norm_partial_count(const Geo &g);
+
 size_t dense_ws_bytes(const Geo &g, int mode);
 dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                        size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
@@ -76,6 +83,8 @@ dp_status launch_gn(const Geo &g, int mode, const void *x, const void *dy, float
 dp_status launch_sum_partials(const float *partials, int n, int per_example, float *sqnorm, hipStream_t s);
 dp_status launch_norms(const float *layer_sqnorm, const int32_t *group_of_layer, int n_layers, int n,
                        int n_groups, float *group_sqnorm, hipStream_t s);
+dp_status launch_norms_from_partials(const float *const *partials, const int32_t *counts, const int32_t *group_of_layer,
+                                     int n_layers, int n, int n_groups, float *group_sqnorm, hipStream_t s);
 dp_status launch_clip_factors(const float *sqnorm, float clip_c, int n, float *f, hipStream_t s);
 dp_status launch_clip_accumulate(const float *g, size_t stride, const float *sqnorm, float clip_c, int n,
                                  size_t p, float *acc, hipStream_t s);

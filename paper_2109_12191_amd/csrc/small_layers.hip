@@ -166,6 +166,14 @@ __global__ void __launch_bounds__(256) dense_rank1_weighted_kernel(const DenseAr
     if (bias_thread) a.out_b[o0 + threadIdx.x] += accb;
 }
 
+size_t dense_norm_partial_count(const Geo &g, int mode)
+{
+    if (mode == MODE_NORM && g.h == 1) return 1;      // rank-one closed form: one value per example
+    return (size_t)((g.cin + 255) / 256) * ((g.cout + DR - 1) / DR);
+}
+
+size_t gn_norm_partial_count(const Geo &g) { return (size_t)g.gn_groups; }
+
 size_t dense_ws_bytes(const Geo &g, int mode)
 {
     if (mode == MODE_WEIGHTED) return 0;
@@ -188,7 +196,7 @@ dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, fl
     a.tiles_o = (g.cout + DR - 1) / DR;
     const bool weighted = mode == MODE_WEIGHTED;
     if (!weighted && !out_w && a.tokens == 1) {
-        if (!sqnorm) return DP_OK;
+        if (!sqnorm) sqnorm = static_cast<float *>(ws);      // left as the single partial per example
         if (g.bf16) hipLaunchKernelGGL((dense_rank1_norm_kernel<true>), dim3(g.n), dim3(256), 0, s, a, sqnorm);
         else hipLaunchKernelGGL((dense_rank1_norm_kernel<false>), dim3(g.n), dim3(256), 0, s, a, sqnorm);
         return check_launch("dense_rank1_norm");

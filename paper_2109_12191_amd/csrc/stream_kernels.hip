@@ -52,6 +52,59 @@ dp_status launch_norms(const float *layer_sqnorm, const int32_t *group_of_layer,
     return check_launch("norms");
 }
 
+// Group norms straight from the per-layer partial sums the contraction kernels leave in their
+// workspaces (so that no per-layer reduction launch is needed): one wavefront per (group, example)
+// walks the layers of the group in order and, inside a layer, that example's partials 64 at a
+// time; fixed order, same bits on every run.
+constexpr int NP_MAX = 64;                 // layers per launch
+struct NormPartialArgs {
+    const float *ptr[NP_MAX];
+    int count[NP_MAX];
+    int group[NP_MAX];
+    int n_layers, n, accumulate;
+    float *group_sqnorm;
+};
+
+__global__ void __launch_bounds__(256) norms_from_partials_kernel(const NormPartialArgs a)
+{
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.y;
+    if (i >= a.n) return;
+    float s = 0.0f;
+    for (int l = 0; l < a.n_layers; ++l) {
+        if (a.group[l] != g) continue;
+        const int cnt = a.count[l];
+        const float *p = a.ptr[l] + (size_t)i * cnt;
+        for (int c = lane; c < cnt; c += 64) s += p[c];
+    }
+    s = wave_sum(s);
+    if (lane == 0) {
+        float *dst = a.group_sqnorm + (size_t)g * a.n + i;
+        *dst = a.accumulate ? *dst + s : s;
+    }
+}
+
+dp_status launch_norms_from_partials(const float *const *partials, const int32_t *counts, const int32_t *group_of_layer,
+                                     int n_layers, int n, int n_groups, float *group_sqnorm, hipStream_t s)
+{
+    for (int l0 = 0; l0 < n_layers; l0 += NP_MAX) {
+        NormPartialArgs a;
+        a.n_layers = n_layers - l0 < NP_MAX ? n_layers - l0 : NP_MAX;
+        for (int l = 0; l < NP_MAX; ++l) {
+            const bool live = l < a.n_layers;
+            a.ptr[l] = live ? partials[l0 + l] : nullptr;
+            a.count[l] = live ? counts[l0 + l] : 0;
+            a.group[l] = live ? group_of_layer[l0 + l] : -1;
+        }
+        a.n = n; a.accumulate = l0 > 0; a.group_sqnorm = group_sqnorm;
+        hipLaunchKernelGGL(norms_from_partials_kernel, dim3((n + 3) / 4, n_groups), dim3(256), 0, s, a);
+        const dp_status st = check_launch("norms_from_partials");
+        if (st != DP_OK) return st;
+    }
+    return DP_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 // H3
 __global__ void __launch_bounds__(256) clip_factors_kernel(const float *__restrict__ sqnorm, float clip_c, int n,

@@ -2,7 +2,7 @@
 
 This class owns device buffers (allocated through torch) and issues the library calls in
 order; it performs no arithmetic of its own.  Per micro-step:
-    dp_per_example_grad (every layer)  ->  dp_norms  ->  dp_clip_accumulate (materialised
+    dp_per_example_grad_partials (every layer)  ->  dp_norms_from_partials  ->  dp_clip_accumulate (materialised
     layers) and dp_clip_accumulate_recompute (the rest);
 once per optimiser step: dp_add_noise_finalize per parameter tensor.
 
@@ -74,17 +74,15 @@ class PrivatiseStep:
         self.copies = 2 if self.n_streams > 1 else 1
         self._g = [torch.zeros((self.n, self.p_mat), dtype=f32, device=dev) if self.p_mat else None
                    for _ in range(self.copies)]
-        self._layer_sqnorm = [torch.zeros((L, self.n), dtype=f32, device=dev) for _ in range(self.copies)]
         self._group_sqnorm = [torch.zeros((self.n_groups, self.n), dtype=f32, device=dev) for _ in range(self.copies)]
         self.group_of_layer_dev = torch.tensor(self.group_of_layer, dtype=torch.int32, device=dev)
         need = [max(16, B.dp_workspace_bytes(d, B.DP_WS_PER_EXAMPLE_GRAD),
                     B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE) if form == "recompute" else 0)
                 for d, form in zip(self.descs, self.form)]
-        if self.n_streams == 1:
-            shared = torch.empty(max(need), dtype=torch.uint8, device=dev)
-            self._ws = [[shared] * L]
-        else:
-            self._ws = [[torch.empty(b, dtype=torch.uint8, device=dev) for b in need] for _ in range(self.copies)]
+        # a workspace per layer: a layer's partial squared norms stay at its start until dp_norms_from_partials
+        self._ws = [[torch.empty(b, dtype=torch.uint8, device=dev) for b in need] for _ in range(self.copies)]
+        counts = [B.dp_norm_partial_count(d, form == "materialise") for d, form in zip(self.descs, self.form)]
+        self._partials = [B.PartialTable([w.data_ptr() for w in wss], counts, self.group_of_layer) for wss in self._ws]
         # side streams: `side` for the per-example phase, `side_b` for the clipped-sum phase
         self.side = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
         self.side_b = [torch.cuda.Stream(device=dev) for _ in range(max(2, self.n_streams // 2))] if self.n_streams > 1 else []
@@ -145,10 +143,6 @@ class PrivatiseStep:
         return self._group_sqnorm[self._last]
 
     @property
-    def layer_sqnorm(self) -> torch.Tensor:
-        return self._layer_sqnorm[self._last]
-
-    @property
     def g(self) -> Optional[torch.Tensor]:
         return self._g[self._last]
 
@@ -173,7 +167,7 @@ class PrivatiseStep:
         gs = self.p_mat
         c = self.micro_steps_done % self.copies
         self._last = c
-        g_buf, lsq, gsq, wss = self._g[c], self._layer_sqnorm[c], self._group_sqnorm[c], self._ws[c]
+        g_buf, gsq, wss = self._g[c], self._group_sqnorm[c], self._ws[c]
         main = torch.cuda.current_stream()
         # ---- phase A
         for st in self.side:
@@ -189,15 +183,15 @@ class PrivatiseStep:
             if self.form[li] == "materialise":
                 g_w = g_buf[:, self.off_w[li]:]
                 g_b = g_buf[:, self.off_b[li]:] if self.pb[li] else None
-                B.dp_per_example_grad(self.descs[li], x, dy, g_w.data_ptr(),
-                                      g_b.data_ptr() if g_b is not None else None,
-                                      lsq[li], ws, g_stride=gs, ws_bytes=ws.numel(), stream=st)
+                B.dp_per_example_grad_partials(self.descs[li], x, dy, g_w.data_ptr(),
+                                               g_b.data_ptr() if g_b is not None else None,
+                                               ws, g_stride=gs, ws_bytes=ws.numel(), stream=st)
             else:
-                B.dp_per_example_grad(self.descs[li], x, dy, None, None, lsq[li], ws,
-                                      ws_bytes=ws.numel(), stream=st)
+                B.dp_per_example_grad_partials(self.descs[li], x, dy, None, None, ws,
+                                               ws_bytes=ws.numel(), stream=st)
         for st in self.side:
             main.wait_stream(st)
-        B.dp_norms(lsq, self.group_of_layer_dev, L, self.n, self.n_groups, gsq)
+        B.dp_norms_from_partials(self._partials[c], self.n, self.n_groups, gsq)
         # ---- phase B
         for st in self.side_b:
             st.wait_stream(main)

@@ -295,3 +295,47 @@ def test_noise_moments_match_sigma_c_within_one_percent():
     assert abs(z.std() / (sigma * c) - 1.0) < 0.01
     assert abs(z.mean()) < 0.01 * sigma * c
     assert abs(np.mean(z ** 2) / (sigma * c) ** 2 - 1.0) < 0.01
+
+
+PARTIAL_CASES = [
+    ("generic conv, one tile row", conv(24, 40, 3, 1, 12, bias=True), 3, "f32"),
+    ("generic conv, K sliced", conv(24, 64, 3, 1, 56), 1, "bf16"),
+    ("1x1 flat", conv(150, 130, 1, 1, 14), 3, "bf16"),
+    ("raw-row 3x3 unsliced", Layer("conv", 130, 64, 14, 14, 3, 3, 1, 1, False), 3, "bf16"),
+    ("raw-row 3x3 sliced", Layer("conv", 64, 64, 10, 56, 3, 3, 1, 1, False), 2, "bf16"),
+    ("dense one token", dense(300, 37), 5, "bf16"),
+    ("dense three tokens", dense(300, 37, tokens=3), 4, "f32"),
+    ("groupnorm", gn_affine(24, 5, 3), 4, "f32"),
+]
+
+
+@pytest.mark.parametrize("materialise", [False, True], ids=["norm_only", "materialise"])
+@pytest.mark.parametrize("name,layer,n,dtype", PARTIAL_CASES, ids=[c[0] for c in PARTIAL_CASES])
+def test_partial_norm_path_matches_reduced_norms(name, layer, n, dtype, materialise):
+    """dp_per_example_grad_partials + dp_norms_from_partials give the norms dp_per_example_grad gives
+    (two layers share a group here, so the reduction over layers is exercised too)."""
+    x, dy = _inputs(layer, n, 307, dtype)
+    if layer.kind == "gn":
+        x = x * 1.5 + 0.25
+        if dtype == "bf16":
+            x = to_bf16_grid(x)
+    d = dp.make_desc(layer, n, dtype)
+    xd, dyd = dev(x, dtype), dev(dy, dtype)
+    nbytes = max(16, dp.dp_workspace_bytes(d))
+    sq = torch.zeros(n, device="cuda:0")
+    ws0 = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    gw = torch.empty((n, layer.pw), device="cuda:0") if materialise else None
+    gb = torch.empty((n, max(layer.pb, 1)), device="cuda:0") if materialise else None
+    dp.dp_per_example_grad(d, xd, dyd, gw, gb if (materialise and layer.pb) else None, sq, ws0)
+    wss = [torch.empty(nbytes, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+    gw2 = torch.empty((n, layer.pw), device="cuda:0") if materialise else None
+    for ws in wss:
+        dp.dp_per_example_grad_partials(d, xd, dyd, gw2, gb if (materialise and layer.pb) else None, ws)
+    count = dp.dp_norm_partial_count(d, materialise)
+    table = dp.PartialTable([w.data_ptr() for w in wss], [count, count], [0, 0])
+    out = torch.full((1, n), -1.0, device="cuda:0")
+    dp.dp_norms_from_partials(table, n, 1, out)
+    torch.cuda.synchronize()
+    assert np.allclose(host(out)[0], 2.0 * host(sq), rtol=1e-5, atol=0), (host(out)[0], host(sq))
+    if materialise:
+        assert torch.equal(gw, gw2)

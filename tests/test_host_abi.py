@@ -137,3 +137,31 @@ def test_profile_hook_accepts_null_events(lib):
     """The benchmark timing aid can be armed / cancelled without a GPU (no HIP call is made until
     a contraction is launched)."""
     assert B.load_library().dp_profile_next_contraction(None, None) == 0
+
+
+def test_norms_from_partials_rejects_bad_tables(lib):
+    import ctypes as C
+    ok_ptrs = (C.c_void_p * 2)(FAKE, FAKE)
+    ok_counts = (C.c_int32 * 2)(3, 1)
+    ok_groups = (C.c_int32 * 2)(0, 0)
+    f = lib.dp_norms_from_partials
+    cast = lambda a: C.cast(a, C.c_void_p)
+    assert f(None, cast(ok_counts), cast(ok_groups), 2, 4, 1, FAKE, None) == B.DP_ERR_INVALID_ARG
+    assert f(cast(ok_ptrs), cast(ok_counts), cast(ok_groups), 0, 4, 1, FAKE, None) == B.DP_ERR_INVALID_ARG
+    assert f(cast(ok_ptrs), cast(ok_counts), cast(ok_groups), 2, 4, 1, None, None) == B.DP_ERR_INVALID_ARG
+    assert f(cast((C.c_void_p * 2)(FAKE, 0)), cast(ok_counts), cast(ok_groups), 2, 4, 1, FAKE, None) == B.DP_ERR_INVALID_ARG
+    assert f(cast(ok_ptrs), cast((C.c_int32 * 2)(3, 0)), cast(ok_groups), 2, 4, 1, FAKE, None) == B.DP_ERR_INVALID_ARG
+    assert f(cast(ok_ptrs), cast(ok_counts), cast((C.c_int32 * 2)(0, 1)), 2, 4, 1, FAKE, None) == B.DP_ERR_INVALID_ARG
+    assert "group_of_layer" in dp.dp_last_error()
+
+
+def test_norm_partial_count_is_positive_and_needs_a_valid_descriptor(lib):
+    for layer in (conv(64, 64, 3, 1, 14), conv(3, 16, 3, 2, 9, bias=True), dense(20, 7), dense(20, 7, tokens=3), gn_affine(16, 8, 4)):
+        for dtype in ("f32", "bf16"):
+            d = dp.make_desc(layer, 5, dtype)
+            for mat in (False, True):
+                c = dp.dp_norm_partial_count(d, mat)
+                assert c >= 1
+                assert dp.dp_workspace_bytes(d, dp.DP_WS_PER_EXAMPLE_GRAD) >= 4 * 5 * c
+    bad = dp.make_desc(conv(4, 4, 3, 1, 8), 0, "f32")
+    assert dp.dp_norm_partial_count(bad, False) == 0
