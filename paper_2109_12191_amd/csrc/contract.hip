@@ -779,7 +779,8 @@ static FullPlan full_plan(const Geo &g, int mode)
     } else {
         const long long units = (long long)g.n * tiles;
         if (units < 512 && p.chunks_per_ex >= 8) {
-            long long want = (768 + units - 1) / units;
+            // few tiles, long K: slice K so that about 512 workgroups (one round: two per CU) run
+            long long want = 512 / units;
             if (want > p.chunks_per_ex / 4) want = p.chunks_per_ex / 4;
             if (want < 1) want = 1;
             p.chunks_per_split = (int)((p.chunks_per_ex + want - 1) / want);

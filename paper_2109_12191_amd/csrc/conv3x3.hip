@@ -128,9 +128,63 @@ __device__ __forceinline__ void c3_epilogue(const f32x16 (&acc)[9], const C3Args
     if (threadIdx.x == 0) a.partials[unit] = tot;
 }
 
-template <int W, bool SPLIT>
+// Weighted sum of one tile over all examples: acc[co, ci, tap] += block, through LDS in the same
+// coalesced row form as the store above when the shapes allow, else element by element.
+__device__ __forceinline__ void c3_add_to_accumulator(const f32x16 (&acc)[9], const C3Args &a, int co0, int ci0,
+                                                      int wm, int wn, int lane, char *lds)
+{
+    float *out = a.out_w;
+    const bool via_lds = (a.cin % 32 == 0) && ((reinterpret_cast<uintptr_t>(a.out_w) & 15u) == 0);
+    if (via_lds) {
+        float *buf = reinterpret_cast<float *>(lds) + (threadIdx.x >> 6) * (8 * C3_RP);
+        const int cil = lane & 31, half = lane >> 5;
+        const int cib = ci0 + wn * 32;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            __syncthreads();
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                for (int t = 0; t < 9; ++t) buf[(half * 4 + rr) * C3_RP + cil * 9 + t] = acc[t][q * 4 + rr];
+            __syncthreads();
+#pragma unroll
+            for (int it = 0; it < 9; ++it) {
+                const int f4 = it * 64 + lane;
+                const int row = f4 / 72, c4 = f4 - row * 72;
+                const int co = co0 + wm * 32 + q * 8 + row;
+                const float4 v = *reinterpret_cast<const float4 *>(buf + row * C3_RP + c4 * 4);
+                if (co < a.cout && cib < a.cin) {
+                    float4 *dst = reinterpret_cast<float4 *>(out + ((size_t)co * a.cin + cib) * 9 + c4 * 4);
+                    float4 o = *dst;
+                    o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+                    *dst = o;
+                }
+            }
+        }
+    } else {
+        const int ci = ci0 + wn * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int co = co0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            const bool ok = co < a.cout && ci < a.cin;
+            const size_t base = ((size_t)co * a.cin + ci) * 9;
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+                if (ok) out[base + t] += acc[t][r];
+        }
+    }
+}
+
+// MODE 0: one workgroup = all of K of one (example, tile); 1: a K slice of it (accumulators to the
+// workspace); 2: clip-weighted sum over a range of examples for one tile (dY scaled by f_i while it
+// is staged; added to the accumulator, or to the workspace when the examples are split into ranges).
+enum { C3_FULL = 0, C3_SLICED = 1, C3_WEIGHTED = 2 };
+
+template <int W, int MODE>
 __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
 {
+    constexpr bool SPLIT = MODE == C3_SLICED;
+    constexpr bool WEIGHTED = MODE == C3_WEIGHTED;
     using C = C3Cfg<W>;
     constexpr int XB = 6;                             // X pieces per thread in flight at once
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -140,13 +194,15 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
     // consecutive hardware workgroup ids rotate over the 8 XCDs; give each XCD a run of
     // consecutive logical ids (the slices and tiles of the same examples share its L2)
     const int tiles = a.tiles_co * a.tiles_ci;
-    const int total = a.n * tiles * a.ksplit;
+    const int total = (WEIGHTED ? 1 : a.n) * tiles * a.ksplit;
     const int per_xcd = (total + 7) >> 3;
     const int wg = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (wg >= total) return;
     const int split = wg % a.ksplit;
-    const int unit = wg / a.ksplit;                   // (example, tile)
-    const int i = unit / tiles, tile = unit - i * tiles;
+    const int unit = wg / a.ksplit;                   // (example, tile); weighted: tile
+    const int i_first = WEIGHTED ? split * a.ex_per_split : unit / tiles;
+    const int i_last = WEIGHTED ? min(a.n, i_first + a.ex_per_split) : i_first + 1;
+    const int tile = WEIGHTED ? unit : unit - i_first * tiles;
     const int tco = tile / a.tiles_ci, tci = tile - tco * a.tiles_ci;
     const int co0 = tco * 64, ci0 = tci * 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -157,7 +213,6 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
     // whole-dword windows (10 elements from an even element index) may reach into the
     // neighbouring example but never outside the tensor
     const int x_ex = a.cin * H * W, dy_ex = a.cout * H * W;       // elements per example
-    const int x_base = i * x_ex, dy_base = i * dy_ex;
     const int x_end = a.n * x_ex, dy_end = a.n * dy_ex;
     const uint32_t *xw = reinterpret_cast<const uint32_t *>(a.x);
     const uint32_t *dyw = reinterpret_cast<const uint32_t *>(a.dy);
@@ -168,12 +223,16 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
-    const int c_begin = split * a.chunks_per_split;
-    const int c_end = min(a.chunks, c_begin + a.chunks_per_split);
+    const int c_begin = WEIGHTED ? 0 : split * a.chunks_per_split;
+    const int c_end = WEIGHTED ? a.chunks : min(a.chunks, c_begin + a.chunks_per_split);
 
+    for (int i = i_first; i < i_last; ++i) {
+    const int x_base = i * x_ex, dy_base = i * dy_ex;
+    float f = 1.0f;
+    if constexpr (WEIGHTED) f = clip_factor(a.group_sqnorm[i], a.clip_c);
     for (int chunk = c_begin; chunk < c_end; ++chunk) {
         const int oh0 = chunk * C::R;
-        if (chunk != c_begin) __syncthreads();        // everyone is done reading the previous chunk
+        if (chunk != c_begin || i != i_first) __syncthreads();    // everyone is done reading the previous chunk
 
         // ---- issue global loads, then shift / mask / write LDS.  The piece -> address decode is
         // recomputed per chunk on purpose (the opaque copy of the thread id stops the compiler
@@ -235,6 +294,11 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
                     piece_finish<true, 1>(t, ra[u], (uint32_t)(p.rel & 1), 0, p.fast ? p.hi : 0);
                     v = make_uint4(t[0], t[1], t[2], t[3]);
                 }
+                if constexpr (WEIGHTED) {
+                    uint32_t t[4] = {v.x, v.y, v.z, v.w};
+                    scale_regs<true, 4>(t, f);
+                    v = make_uint4(t[0], t[1], t[2], t[3]);
+                }
                 if (C::NPA % C3_THREADS == 0 || tid + C3_THREADS * u < C::NPA)
                     *reinterpret_cast<uint4 *>(sA + p.lds_off) = v;
             }
@@ -271,7 +335,11 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
                         uint16_t *dst = reinterpret_cast<uint16_t *>(sA + p.lds_off);
                         const int hi = min(8, p.hi);
 #pragma unroll 1
-                        for (int e = 0; e < hi; ++e) dst[e] = a.dy[p.rel + e];
+                        for (int e = 0; e < hi; ++e) {
+                            uint16_t val = a.dy[p.rel + e];
+                            if constexpr (WEIGHTED) val = float_to_bf16_bits(bf16_bits_to_float(val) * f);
+                            dst[e] = val;
+                        }
                     }
                 }
             }
@@ -313,8 +381,12 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
         }
     }
 
-    if constexpr (!SPLIT) {
-        c3_epilogue(acc, a, i, unit, co0, ci0, wm, wn, lane, red, lds);
+    }   // examples
+
+    if constexpr (MODE == C3_FULL) {
+        c3_epilogue(acc, a, i_first, unit, co0, ci0, wm, wn, lane, red, lds);
+    } else if (WEIGHTED && a.ksplit == 1) {
+        c3_add_to_accumulator(acc, a, co0, ci0, wm, wn, lane, lds);
     } else {
         float *mine = a.ws_part + ((size_t)unit * a.ksplit + split) * (9 * 16 * C3_THREADS);
 #pragma unroll
@@ -330,14 +402,15 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
 // squares / stores them like the unsliced epilogue.
 constexpr int C3_FIX_R = 4, C3_FIX_PARTS = 16 / C3_FIX_R;
 
+template <bool WEIGHTED>
 __global__ void __launch_bounds__(C3_THREADS) conv3x3_fixup_kernel(const C3Args a)
 {
     __shared__ float red[4];
     const int tiles = a.tiles_co * a.tiles_ci;
     const int part = blockIdx.x % C3_FIX_PARTS;
     const int t = (blockIdx.x / C3_FIX_PARTS) % 9;
-    const int unit = blockIdx.x / (C3_FIX_PARTS * 9);
-    const int i = unit / tiles, tile = unit - i * tiles;
+    const int unit = blockIdx.x / (C3_FIX_PARTS * 9);             // (example, tile); weighted: tile
+    const int i = WEIGHTED ? 0 : unit / tiles, tile = unit - i * tiles;
     const int tco = tile / a.tiles_ci, tci = tile - tco * a.tiles_ci;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -366,24 +439,34 @@ __global__ void __launch_bounds__(C3_THREADS) conv3x3_fixup_kernel(const C3Args 
         for (int r = 0; r < C3_FIX_R; ++r) v[r] += tmp[r];
     }
     const int ci = tci * 64 + wn * 32 + (lane & 31);
-    float *out = a.out_w + (size_t)i * a.out_stride;
+    float *out = WEIGHTED ? a.out_w : a.out_w + (size_t)i * a.out_stride;
     float ss = 0.0f;
 #pragma unroll
     for (int rr = 0; rr < C3_FIX_R; ++rr) {
         const int r = part * C3_FIX_R + rr;
         const int co = tco * 64 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        ss += v[rr] * v[rr];
-        if (a.out_w && co < a.cout && ci < a.cin) out[((size_t)co * a.cin + ci) * 9 + t] = v[rr];
+        const bool ok = co < a.cout && ci < a.cin;
+        const size_t idx = ((size_t)co * a.cin + ci) * 9 + t;
+        if constexpr (WEIGHTED) {
+            if (ok) out[idx] += v[rr];
+        } else {
+            ss += v[rr] * v[rr];
+            if (a.out_w && ok) out[idx] = v[rr];
+        }
     }
-    const float tot = block_sum<4>(ss, red);
-    if (threadIdx.x == 0) a.partials[blockIdx.x] = tot;
+    if constexpr (!WEIGHTED) {
+        const float tot = block_sum<4>(ss, red);
+        if (threadIdx.x == 0) a.partials[blockIdx.x] = tot;
+    }
 }
 
 // ------------------------------------------------------------------------------------ host
 
 struct C3Plan {
     int rows;           // R of the width case
-    int tiles_co, tiles_ci, chunks, ksplit, chunks_per_split;
+    int tiles_co, tiles_ci, chunks;
+    int ksplit, chunks_per_split;      // per-example modes: K slices; weighted: example ranges
+    int ex_per_split;                  // weighted
 };
 
 int rows_of_width(int w)
@@ -392,16 +475,29 @@ int rows_of_width(int w)
     return owp == 8 ? 8 : 224 / owp;
 }
 
-C3Plan c3_plan(const Geo &g)
+C3Plan c3_plan(const Geo &g, int mode)
 {
     C3Plan p;
     p.rows = rows_of_width(g.w);
     p.tiles_co = (g.cout + 63) / 64;
     p.tiles_ci = (g.cin + 63) / 64;
     p.chunks = (g.h + p.rows - 1) / p.rows;
-    const long long units = (long long)g.n * p.tiles_co * p.tiles_ci;
     p.ksplit = 1;
     p.chunks_per_split = p.chunks;
+    p.ex_per_split = g.n;
+    const long long tiles = (long long)p.tiles_co * p.tiles_ci;
+    if (mode == MODE_WEIGHTED) {
+        // example ranges: about 256 workgroups, partial blocks in the workspace kept below ~100 MB
+        long long want = (256 + tiles - 1) / tiles;
+        const long long cap = (long long)(96.0e6 / (4.0 * 9 * 16 * C3_THREADS * (double)tiles));
+        if (want > cap) want = cap;
+        if (want > g.n) want = g.n;
+        if (want < 1) want = 1;
+        p.ex_per_split = (int)((g.n + want - 1) / want);
+        p.ksplit = (g.n + p.ex_per_split - 1) / p.ex_per_split;
+        return p;
+    }
+    const long long units = (long long)g.n * tiles;
     if (units < 512 && p.chunks > 1) {
         long long want = (256 + units - 1) / units;
         if (want > p.chunks) want = p.chunks;
@@ -416,44 +512,51 @@ size_t c3_align16(size_t b) { return (b + 15) & ~(size_t)15; }
 // partial squared norms per (example, tile): one, or one per fixup workgroup when K is sliced
 size_t c3_partials_per_unit(const C3Plan &p) { return p.ksplit > 1 ? 9 * C3_FIX_PARTS : 1; }
 
-template <int W>
-dp_status c3_launch_w(const C3Args &a, unsigned blocks, hipStream_t s)
+template <int W, int MODE>
+dp_status c3_launch_mode(const C3Args &a, unsigned blocks, hipStream_t s)
 {
     using C = C3Cfg<W>;
-    static bool attr_done[2] = {false, false};
-    const int sp = a.ksplit > 1 ? 1 : 0;
-    const void *fn = sp ? reinterpret_cast<const void *>(&conv3x3_kernel<W, true>)
-                        : reinterpret_cast<const void *>(&conv3x3_kernel<W, false>);
-    if (!attr_done[sp]) {
-        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS) != hipSuccess)
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&conv3x3_kernel<W, MODE>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS) != hipSuccess)
             return fail(DP_ERR_DEVICE, "conv3x3: cannot reserve %d bytes of LDS", C::LDS);
-        attr_done[sp] = true;
+        attr_done = true;
     }
-    if (sp) hipLaunchKernelGGL((conv3x3_kernel<W, true>), dim3(blocks), dim3(C3_THREADS), C::LDS, s, a);
-    else hipLaunchKernelGGL((conv3x3_kernel<W, false>), dim3(blocks), dim3(C3_THREADS), C::LDS, s, a);
+    hipLaunchKernelGGL((conv3x3_kernel<W, MODE>), dim3(blocks), dim3(C3_THREADS), C::LDS, s, a);
     return check_launch("conv3x3");
+}
+
+template <int W>
+dp_status c3_launch_w(const C3Args &a, bool weighted, unsigned blocks, hipStream_t s)
+{
+    if (weighted) return c3_launch_mode<W, C3_WEIGHTED>(a, blocks, s);
+    if (a.ksplit > 1) return c3_launch_mode<W, C3_SLICED>(a, blocks, s);
+    return c3_launch_mode<W, C3_FULL>(a, blocks, s);
 }
 
 }  // namespace
 
 bool conv3x3_applicable(const Geo &g, int mode)
 {
-    if (!g.bf16 || mode == MODE_WEIGHTED || g.has_bias) return false;
+    (void)mode;
+    if (!g.bf16 || g.has_bias) return false;
     if (g.kh != 3 || g.kw != 3 || g.stride != 1 || g.pad != 1) return false;
     if (g.cin < 64 || g.cout < 64) return false;
     switch (g.w) {
     case 7: case 8: case 14: case 16: case 28: case 32: case 56: break;
     default: return false;
     }
-    // 32-bit element offsets inside one example
-    return (long long)g.cin * g.h * g.w < (1ll << 30) && (long long)g.cout * g.h * g.w < (1ll << 30);
+    // 32-bit element offsets inside the whole tensor
+    return (long long)g.n * g.cin * g.h * g.w < (1ll << 31) && (long long)g.n * g.cout * g.h * g.w < (1ll << 31);
 }
 
 size_t conv3x3_ws_bytes(const Geo &g, int mode)
 {
-    (void)mode;
-    const C3Plan p = c3_plan(g);
-    const size_t units = (size_t)g.n * p.tiles_co * p.tiles_ci;
+    const C3Plan p = c3_plan(g, mode);
+    const size_t tiles = (size_t)p.tiles_co * p.tiles_ci;
+    if (mode == MODE_WEIGHTED) return p.ksplit > 1 ? tiles * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float) : 0;
+    const size_t units = (size_t)g.n * tiles;
     size_t b = c3_align16(units * c3_partials_per_unit(p) * sizeof(float));
     if (p.ksplit > 1) b += units * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float);
     return b;
@@ -461,28 +564,29 @@ size_t conv3x3_ws_bytes(const Geo &g, int mode)
 
 size_t conv3x3_norm_partial_count(const Geo &g)
 {
-    const C3Plan p = c3_plan(g);
+    const C3Plan p = c3_plan(g, MODE_NORM);
     return (size_t)p.tiles_co * p.tiles_ci * c3_partials_per_unit(p);
 }
 
 const char *conv3x3_variant_name(const Geo &g, int mode)
 {
-    (void)mode;
-    static char names[8][48];
+    static char names[2][8][48];
     int slot;
     switch (g.w) {
     case 7: slot = 0; break; case 8: slot = 1; break; case 14: slot = 2; break; case 16: slot = 3; break;
     case 28: slot = 4; break; case 32: slot = 5; break; default: slot = 6; break;
     }
-    if (!names[slot][0]) snprintf(names[slot], sizeof names[slot], "conv3x3_rows<bf16,w%d,per_example>", g.w);
-    return names[slot];
+    const int wt = mode == MODE_WEIGHTED ? 1 : 0;
+    if (!names[wt][slot][0])
+        snprintf(names[wt][slot], sizeof names[wt][slot], "conv3x3_rows<bf16,w%d,%s>", g.w, wt ? "weighted" : "per_example");
+    return names[wt][slot];
 }
 
 dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
                          float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s)
 {
-    (void)mode;
-    const C3Plan p = c3_plan(g);
+    const bool weighted = mode == MODE_WEIGHTED;
+    const C3Plan p = c3_plan(g, mode);
     C3Args a;
     a.x = static_cast<const uint16_t *>(x);
     a.dy = static_cast<const uint16_t *>(dy);
@@ -492,33 +596,40 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = g.h;
     a.tiles_co = p.tiles_co; a.tiles_ci = p.tiles_ci;
     a.chunks = p.chunks; a.ksplit = p.ksplit; a.chunks_per_split = p.chunks_per_split;
-    a.ex_per_split = 1;
-    const size_t units = (size_t)g.n * p.tiles_co * p.tiles_ci;
+    a.ex_per_split = p.ex_per_split;
+    const size_t tiles = (size_t)p.tiles_co * p.tiles_ci;
+    const size_t units = weighted ? tiles : (size_t)g.n * tiles;
     char *w = static_cast<char *>(ws);
-    a.partials = reinterpret_cast<float *>(w);
-    w += c3_align16(units * c3_partials_per_unit(p) * sizeof(float));
+    a.partials = nullptr;
+    if (!weighted) {
+        a.partials = reinterpret_cast<float *>(w);
+        w += c3_align16(units * c3_partials_per_unit(p) * sizeof(float));
+    }
     a.ws_part = p.ksplit > 1 ? reinterpret_cast<float *>(w) : nullptr;
     const long long total = (long long)units * p.ksplit;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     dp_status st;
     profile_begin(s);
     switch (g.w) {
-    case 7: st = c3_launch_w<7>(a, blocks, s); break;
-    case 8: st = c3_launch_w<8>(a, blocks, s); break;
-    case 14: st = c3_launch_w<14>(a, blocks, s); break;
-    case 16: st = c3_launch_w<16>(a, blocks, s); break;
-    case 28: st = c3_launch_w<28>(a, blocks, s); break;
-    case 32: st = c3_launch_w<32>(a, blocks, s); break;
-    default: st = c3_launch_w<56>(a, blocks, s); break;
+    case 7: st = c3_launch_w<7>(a, weighted, blocks, s); break;
+    case 8: st = c3_launch_w<8>(a, weighted, blocks, s); break;
+    case 14: st = c3_launch_w<14>(a, weighted, blocks, s); break;
+    case 16: st = c3_launch_w<16>(a, weighted, blocks, s); break;
+    case 28: st = c3_launch_w<28>(a, weighted, blocks, s); break;
+    case 32: st = c3_launch_w<32>(a, weighted, blocks, s); break;
+    default: st = c3_launch_w<56>(a, weighted, blocks, s); break;
     }
     profile_end(s);
     if (st != DP_OK) return st;
     if (p.ksplit > 1) {
-        hipLaunchKernelGGL(conv3x3_fixup_kernel, dim3((unsigned)(units * 9 * C3_FIX_PARTS)), dim3(C3_THREADS), 0, s, a);
+        const unsigned fix_blocks = (unsigned)(units * 9 * C3_FIX_PARTS);
+        if (weighted) hipLaunchKernelGGL(conv3x3_fixup_kernel<true>, dim3(fix_blocks), dim3(C3_THREADS), 0, s, a);
+        else hipLaunchKernelGGL(conv3x3_fixup_kernel<false>, dim3(fix_blocks), dim3(C3_THREADS), 0, s, a);
         st = check_launch("conv3x3_fixup");
         if (st != DP_OK) return st;
     }
-    if (sqnorm) st = launch_sum_partials(a.partials, g.n, p.tiles_co * p.tiles_ci * (int)c3_partials_per_unit(p), sqnorm, s);
+    if (!weighted && sqnorm)
+        st = launch_sum_partials(a.partials, g.n, p.tiles_co * p.tiles_ci * (int)c3_partials_per_unit(p), sqnorm, s);
     return st;
 }
 

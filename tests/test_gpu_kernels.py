@@ -257,6 +257,39 @@ def test_clip_accumulate_recompute(name, layer, n, dtype):
         assert_close(host(ab)[:layer.pb] - acc0_b[:layer.pb], ref_b - acc0_b[:layer.pb], tol, f"{name} acc_b increment")
 
 
+ROWS_WEIGHTED_CASES = [
+    # name, layer, n  (raw-row kernel in its clip-weighted mode: example ranges through the workspace, or one range)
+    ("w7 ranges", Layer("conv", 128, 128, 7, 7, 3, 3, 1, 1, False), 9),
+    ("w14 ragged channels ranges", Layer("conv", 80, 72, 14, 14, 3, 3, 1, 1, False), 5),
+    ("w28 two chunks", Layer("conv", 64, 64, 10, 28, 3, 3, 1, 1, False), 3),
+    ("w56 short image", Layer("conv", 64, 64, 6, 56, 3, 3, 1, 1, False), 2),
+    ("w8 many tiles one range", Layer("conv", 1024, 1024, 8, 8, 3, 3, 1, 1, False), 2),
+]
+
+
+@pytest.mark.parametrize("name,layer,n", ROWS_WEIGHTED_CASES, ids=[c[0] for c in ROWS_WEIGHTED_CASES])
+def test_conv3x3_raw_row_kernel_weighted(name, layer, n):
+    d = dp.make_desc(layer, n, "bf16")
+    assert dp.dp_kernel_variant(d, dp.DP_WS_RECOMPUTE).startswith("conv3x3_rows")
+    x, dy = _inputs(layer, n, 223, "bf16")
+    rng = np.random.default_rng(19)
+    n2 = (rng.uniform(0.3, 2.5, n) ** 2).astype(np.float32)
+    n2[1] = 0.0
+    f = np.array([oracle.clip_factor(float(v), 1.0) for v in n2])
+    acc0 = rng.standard_normal(layer.pw).astype(np.float32) * 0.01
+    idx = np.arange(layer.pw) if layer.pw <= 200_000 else rng.choice(layer.pw, size=20_000, replace=False)
+    ref = oracle.weighted_sum_elems(layer, x, dy, f, idx)
+    ws = torch.empty(max(16, dp.dp_workspace_bytes(d, dp.DP_WS_RECOMPUTE)), dtype=torch.uint8, device="cuda:0")
+    aw = dev(acc0)
+    dp.dp_clip_accumulate_recompute(d, dev(x, "bf16"), dev(dy, "bf16"), dev(n2), 1.0, aw, None, ws)
+    got = host(aw)
+    assert_close(got[idx] - acc0[idx], ref, BF16_TOL, f"{name} increment")
+    # same call again from the same start: same bits
+    aw2 = dev(acc0)
+    dp.dp_clip_accumulate_recompute(d, dev(x, "bf16"), dev(dy, "bf16"), dev(n2), 1.0, aw2, None, ws)
+    assert torch.equal(aw, aw2)
+
+
 def test_philox_integer_stream_is_bit_exact():
     for seed, step, tid, p in [(0, 0, 0, 1), (0, 0, 0, 3), (0, 0, 1, 1027), (0x123456789ABCDEF, 0x100000005, 77, 4096),
                                (2**64 - 1, 2**40 + 3, 2**32 - 1, 65537), (42, 7, 3, 1_000_001)]:
