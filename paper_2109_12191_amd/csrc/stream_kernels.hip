@@ -147,16 +147,15 @@ __global__ void __launch_bounds__(256) clip_accumulate_kernel(const float *__res
             const float *row = g + (size_t)base * stride + e;
             int j = 0;
             if constexpr (VEC == 4) {
-                for (; j + 4 <= cnt; j += 4) {
-                    const float4 a = *reinterpret_cast<const float4 *>(row + (size_t)(j + 0) * stride);
-                    const float4 b = *reinterpret_cast<const float4 *>(row + (size_t)(j + 1) * stride);
-                    const float4 c = *reinterpret_cast<const float4 *>(row + (size_t)(j + 2) * stride);
-                    const float4 d = *reinterpret_cast<const float4 *>(row + (size_t)(j + 3) * stride);
-                    const float f0 = fs[j], f1 = fs[j + 1], f2 = fs[j + 2], f3 = fs[j + 3];
-                    s[0] += f0 * a.x; s[1] += f0 * a.y; s[2] += f0 * a.z; s[3] += f0 * a.w;
-                    s[0] += f1 * b.x; s[1] += f1 * b.y; s[2] += f1 * b.z; s[3] += f1 * b.w;
-                    s[0] += f2 * c.x; s[1] += f2 * c.y; s[2] += f2 * c.z; s[3] += f2 * c.w;
-                    s[0] += f3 * d.x; s[1] += f3 * d.y; s[2] += f3 * d.z; s[3] += f3 * d.w;
+                for (; j + 8 <= cnt; j += 8) {        // eight rows' loads in flight per thread
+                    float4 v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4 *>(row + (size_t)(j + u) * stride);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {    // example order: same bits on every run
+                        const float fu = fs[j + u];
+                        s[0] += fu * v[u].x; s[1] += fu * v[u].y; s[2] += fu * v[u].z; s[3] += fu * v[u].w;
+                    }
                 }
                 for (; j < cnt; ++j) {
                     const float4 a = *reinterpret_cast<const float4 *>(row + (size_t)j * stride);
