@@ -241,15 +241,24 @@ class PrivatiseStep:
             main.wait_stream(st)
 
     def finalize(self):
+        """H5 on every parameter tensor; the per-tensor calls are independent and go round the side streams."""
         wl = self.wl
         self._drain()
+        main = torch.cuda.current_stream()
+        for st in self.side:
+            st.wait_stream(main)
+        k = 0
         for li in range(len(self.layers)):
+            st = self.side[k % len(self.side)] if self.side else None
+            k += 1
             B.dp_add_noise_finalize(self.acc_w(li).data_ptr(), self.out_w(li).data_ptr(), self.pw[li], wl.sigma,
-                                    wl.clip_total, wl.total_batch, wl.philox_seed, wl.step, 2 * li)
+                                    wl.clip_total, wl.total_batch, wl.philox_seed, wl.step, 2 * li, stream=st)
             if self.pb[li]:
                 B.dp_add_noise_finalize(self.acc_b(li).data_ptr(), self.out_b(li).data_ptr(), self.pb[li],
                                         wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step,
-                                        2 * li + 1)
+                                        2 * li + 1, stream=st)
+        for st in self.side:
+            main.wait_stream(st)
 
     def run(self, inputs_per_micro_step: Sequence[Sequence]):
         self.begin_step()
