@@ -824,6 +824,21 @@ static bool packed_weighted(const Geo &g, int mode, PackPlan &pp, Geo &g2)
     return true;
 }
 
+// Per-example calls of strided 1x1 bf16 convolutions (projection shortcuts): contract on a compact
+// copy of the sampled positions of X (pack.hip) with the stride-1 loaders.
+static bool subsampled(const Geo &g, int mode, Geo &g2)
+{
+    if (mode == MODE_WEIGHTED || !g.bf16) return false;
+    if (g.kh != 1 || g.kw != 1 || g.stride < 2 || g.pad != 0) return false;
+    const size_t s = (size_t)g.oh * g.ow;
+    if ((size_t)g.n * g.cin * s * 2 > ((size_t)96 << 20) || g.cin * s < 512) return false;
+    if (s % 2) return false;                   // odd rows would go through the gather loader anyway: no gain
+    g2 = g;
+    g2.h = g.oh; g2.w = g.ow; g2.stride = 1;
+    g2.x_elems = (size_t)g.cin * s;
+    return true;
+}
+
 ConvPlan conv_plan(const Geo &g, int mode)
 {
     const FullPlan f = full_plan(g, mode);
@@ -853,6 +868,7 @@ size_t conv_ws_bytes(const Geo &g, int mode)
         const FullPlan f = full_plan(g2, mode);
         return align16(pp.x_bytes) + align16(pp.dy_bytes) + (f.ksplit > 1 ? f.part_floats * sizeof(float) : 0);
     }
+    if (subsampled(g, mode, g2)) return conv_ws_bytes(g2, mode) + align16(g2.x_elems * g.n * 2);
     const FullPlan f = full_plan(g, mode);
     size_t b = 0;
     if (mode != MODE_WEIGHTED) b += align16(norm_partials(g, f) * sizeof(float));
@@ -863,6 +879,8 @@ size_t conv_ws_bytes(const Geo &g, int mode)
 size_t conv_norm_partial_count(const Geo &g, int mode)
 {
     if (conv3x3_applicable(g, mode)) return conv3x3_norm_partial_count(g);
+    Geo g2;
+    if (subsampled(g, mode, g2)) return norm_partials_per_example(full_plan(g2, mode));
     return norm_partials_per_example(full_plan(g, mode));
 }
 
@@ -939,6 +957,13 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
         // the factors are already in dYp: an infinite bound makes the kernel's own factor 1
         return launch_conv_impl(g2, mode, xp, dyp, out_w, out_b, out_stride, nullptr, group_sqnorm,
                                 __builtin_inff(), w, s);
+    }
+    if (subsampled(g, mode, g2)) {
+        // the sub-problem's own workspace comes first (its partial norms stay at the start), the copy of X after it
+        void *xs = static_cast<char *>(ws) + conv_ws_bytes(g2, mode);
+        const dp_status st = launch_subsample(g, x, xs, s);
+        if (st != DP_OK) return st;
+        return launch_conv_impl(g2, mode, xs, dy, out_w, out_b, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
     }
     return launch_conv_impl(g, mode, x, dy, out_w, out_b, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
 }

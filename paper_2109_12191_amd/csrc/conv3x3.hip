@@ -183,7 +183,6 @@ enum { C3_FULL = 0, C3_SLICED = 1, C3_WEIGHTED = 2 };
 template <int W, int MODE>
 __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
 {
-    constexpr bool SPLIT = MODE == C3_SLICED;
     constexpr bool WEIGHTED = MODE == C3_WEIGHTED;
     using C = C3Cfg<W>;
     constexpr int XB = 6;                             // X pieces per thread in flight at once

@@ -69,6 +69,9 @@ size_t conv3x3_norm_partial_count(const Geo &g);
 size_t dense_norm_partial_count(const Geo &g, int mode);
 size_t gn_norm_partial_count(const Geo &g);
 
+// compact copy of the rows / columns a strided 1x1 convolution reads: out[n*cin][OH*OW] (pack.hip)
+dp_status launch_subsample(const Geo &g, const void *x, void *out, hipStream_t s);
+
 size_t dense_ws_bytes(const Geo &g, int mode);
 dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                        size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,

@@ -79,6 +79,45 @@ __global__ void __launch_bounds__(256) pack_weighted_kernel(const PackArgs a)
     *reinterpret_cast<uint4 *>(a.dyp + qd * 8) = make_uint4(out[0], out[1], out[2], out[3]);
 }
 
+// Strided 1x1 convolutions only look at every stride-th row and column of X: this copies those
+// into a compact [n*cin][OH*OW] tensor so that the contraction runs its plain aligned loader on
+// half (a quarter, with both strides) of the bytes.  One thread per pair of output elements.
+__global__ void __launch_bounds__(256) subsample_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ out,
+                                                        long long rows, int h, int w, int oh, int ow, int stride)
+{
+    const int S = oh * ow, pairs = (S + 1) / 2;
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= rows * pairs) return;
+    const long long row = t / pairs;
+    const int k = (int)(t - row * pairs) * 2;
+    const uint16_t *src = x + (size_t)row * h * w;
+    const int r0 = k / ow, c0 = k - r0 * ow;
+    const uint32_t lo = src[(size_t)r0 * stride * w + c0 * stride];
+    uint16_t *dst = out + (size_t)row * S + k;
+    if (k + 1 < S) {
+        const int k1 = k + 1, r1 = k1 / ow, c1 = k1 - r1 * ow;
+        const uint32_t hi = src[(size_t)r1 * stride * w + c1 * stride];
+        if (((size_t)row * S) % 2 == 0) *reinterpret_cast<uint32_t *>(dst) = lo | (hi << 16);
+        else { dst[0] = (uint16_t)lo; dst[1] = (uint16_t)hi; }
+    } else {
+        dst[0] = (uint16_t)lo;
+    }
+}
+
+}  // namespace
+
+dp_status launch_subsample(const Geo &g, const void *x, void *out, hipStream_t s)
+{
+    const long long rows = (long long)g.n * g.cin;
+    const long long threads = rows * ((g.oh * g.ow + 1) / 2);
+    const long long blocks = (threads + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return fail(DP_ERR_UNSUPPORTED, "subsample: layer too large");
+    hipLaunchKernelGGL(subsample_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint16_t *>(x),
+                       static_cast<uint16_t *>(out), rows, g.h, g.w, g.oh, g.ow, g.stride);
+    return check_launch("subsample");
+}
+
+namespace {
 }  // namespace
 
 PackPlan pack_plan(const Geo &g, int groups)
