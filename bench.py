@@ -110,6 +110,8 @@ def main():
                     help="examples of micro-batch 0 the oracle is timed on (32 = about 10 s on 16 cores)")
     ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
     ap.add_argument("--streams", type=int, default=8, help="side streams for independent layers")
+    ap.add_argument("--fused-update", action="store_true",
+                    help="finalize applies the SGD-with-momentum step in the same kernel (extra work inside the step)")
     ap.add_argument("--no-graph", action="store_true", help="issue every call from the host instead of a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -127,6 +129,8 @@ def main():
     wl = get_workload(args.workload, n=args.n, accum=args.accum, hw=args.hw)
     ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=args.streams)
     inputs = make_device_inputs(wl, wl.accum, device)
+    if args.fused_update:
+        ps.enable_update(lr=0.1, momentum=0.9, keep_gradient=False)
     torch.cuda.synchronize()
 
     # The timed step: the whole path (8 micro-steps + finalize).  By default it is recorded once
@@ -215,6 +219,7 @@ def main():
                                f"C={wl.clip_c}, sigma={wl.sigma}, {wl.dtype} inputs, fp32 accumulators",
                    "clipped_sum_forms": {f: ps.form.count(f) for f in sorted(set(ps.form))},
                    "issue": "host calls" if args.no_graph else f"HIP graph, {args.streams} side streams",
+                   "finalize": "noise + SGD-momentum update fused" if args.fused_update else "noise + divide by |B|",
                    "flop_per_example": wl.flops_per_example, "input_bytes_per_example": wl.in_bytes_per_example},
         "roofline": roofline,
     }

@@ -187,6 +187,20 @@ dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float si
                                 uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
                                 dp_stream stream);
 
+/* H5 fused with the SGD step that consumes it (the step right after the path: "SGD ... with a
+ * stepped learning rate decay policy", Algorithm section; "vanilla SGD with momentum (0.9)",
+ * Sections 4.2-4.3): with g[e] = (acc[e] + sigma * clip_total * z_e) / total_batch as above,
+ *     velocity[e] = momentum * velocity[e] + g[e];   theta[e] -= lr * velocity[e]
+ * or, with velocity == NULL (momentum must be 0),  theta[e] -= lr * g[e].
+ * g is written to `out` only if out != NULL.  lr is this step's learning rate (decay and scaling
+ * policies are the caller's).  acc, theta, velocity, out [device] [p] fp32, 16-byte aligned;
+ * theta and velocity are updated in place.  Same stream contract and errors as
+ * dp_add_noise_finalize; lr or momentum not finite, momentum < 0, momentum != 0 without a
+ * velocity buffer -> DP_ERR_INVALID_ARG.                                                         */
+dp_status dp_add_noise_finalize_update(const float *acc, float *theta, float *velocity, float *out, size_t p, float sigma,
+                                       float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
+                                       uint32_t tensor_id, float lr, float momentum, dp_stream stream);
+
 /* The raw 32-bit Philox word behind each element of the stream above (diagnostic; lets a
  * test compare the integer stream bit for bit).  raw [device] [p] uint32.                      */
 dp_status dp_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id,

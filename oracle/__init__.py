@@ -70,6 +70,8 @@ def _load():
     lib.orc_noise_finalize.restype = None
     lib.orc_noise_finalize.argtypes = [dp, dp, C.c_size_t, C.c_double, C.c_double, C.c_uint64, C.c_uint64,
                                        C.c_uint64, C.c_uint32]
+    lib.orc_sgd_update.restype = None
+    lib.orc_sgd_update.argtypes = [dp, dp, dp, C.c_size_t, C.c_double, C.c_double]
     lib.orc_max_threads.restype = C.c_int
     for name in ("orc_x_elems", "orc_dy_elems", "orc_w_elems", "orc_b_elems"):
         getattr(lib, name).restype = C.c_size_t
@@ -201,6 +203,15 @@ def noise_finalize(acc, sigma: float, clip_total: float, total_batch: int, seed:
     _load().orc_noise_finalize(_dp(acc), _dp(out), acc.size, sigma, clip_total, total_batch, seed, step,
                                tensor_id)
     return out.reshape(acc.shape)
+
+
+def sgd_update(g, theta, v, lr: float, momentum: float):
+    """One SGD step on a finalized gradient: returns (theta', v').  v None = no momentum buffer."""
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    theta = np.array(theta, dtype=np.float64).reshape(-1).copy()
+    vv = None if v is None else np.array(v, dtype=np.float64).reshape(-1).copy()
+    _load().orc_sgd_update(_dp(g.reshape(-1)), _dp(theta), _dp(vv) if vv is not None else None, theta.size, lr, momentum)
+    return theta, vv
 
 
 def privatise(wl, inputs_per_micro_step, threads: int = 0):

@@ -192,6 +192,22 @@ double orc_clip_factor(double n2, double clip_c)
     return r < 1.0 ? r : 1.0;
 }
 
+/* SGD step on the privatised gradient (Algorithm section: "SGD ... with a stepped learning rate
+ * decay policy"; Sections 4.2-4.3: "vanilla SGD with momentum (0.9)").  g is the finalized
+ * gradient of one tensor; the buffer v is the plain heavy-ball momentum: v <- mu v + g,
+ * theta <- theta - lr v.  mu == 0 (or v == NULL) is SGD without momentum.                    */
+void orc_sgd_update(const double *g, double *theta, double *v, size_t p, double lr, double momentum)
+{
+    for (size_t e = 0; e < p; ++e) {
+        double step = g[e];
+        if (v) {
+            v[e] = momentum * v[e] + g[e];
+            step = v[e];
+        }
+        theta[e] -= lr * step;
+    }
+}
+
 int orc_max_threads(void)
 {
 #ifdef _OPENMP

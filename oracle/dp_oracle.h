@@ -104,6 +104,9 @@ void orc_noise_normal(uint64_t seed, uint64_t step, uint32_t tensor_id, size_t f
 void orc_noise_finalize(const double *acc, double *out, size_t p, double sigma, double clip_total,
                         uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id);
 
+/* theta <- theta - lr * v with v <- momentum * v + g (v may be NULL: theta <- theta - lr * g). */
+void orc_sgd_update(const double *g, double *theta, double *v, size_t p, double lr, double momentum);
+
 int orc_max_threads(void);
 
 #ifdef __cplusplus

@@ -347,6 +347,27 @@ dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float si
                                  static_cast<hipStream_t>(stream));
 }
 
+dp_status dp_add_noise_finalize_update(const float *acc, float *theta, float *velocity, float *out, size_t p, float sigma,
+                                       float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
+                                       uint32_t tensor_id, float lr, float momentum, dp_stream stream)
+{
+    DP_TRY(check_ptr(acc, "acc", true));
+    DP_TRY(check_ptr(theta, "theta", true));
+    DP_TRY(check_ptr(velocity, "velocity", false));
+    DP_TRY(check_ptr(out, "out", false));
+    if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0 parameters");
+    if (std::isnan(sigma) || sigma < 0.0f || std::isinf(sigma)) return fail(DP_ERR_INVALID_ARG, "sigma must be finite and >= 0");
+    if (!(clip_total > 0.0f) || !std::isfinite(clip_total)) return fail(DP_ERR_INVALID_ARG, "clip_total must be finite and > 0");
+    if (total_batch < 1) return fail(DP_ERR_INVALID_ARG, "total_batch = 0");
+    if (!std::isfinite(lr)) return fail(DP_ERR_INVALID_ARG, "lr must be finite");
+    if (!std::isfinite(momentum) || momentum < 0.0f) return fail(DP_ERR_INVALID_ARG, "momentum must be finite and >= 0");
+    if (momentum != 0.0f && !velocity) return fail(DP_ERR_INVALID_ARG, "momentum != 0 needs a velocity buffer");
+    if (p >= ((size_t)1 << 40)) return fail(DP_ERR_UNSUPPORTED, "p too large");
+    g_err[0] = 0;
+    return launch_noise_finalize_update(acc, theta, velocity, out, p, sigma, clip_total, total_batch, seed, step,
+                                        tensor_id, lr, momentum, static_cast<hipStream_t>(stream));
+}
+
 dp_status dp_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id, dp_stream stream)
 {
     DP_TRY(check_ptr(raw, "raw", true, 4));

@@ -295,6 +295,77 @@ dp_status launch_noise_finalize(const float *acc, float *out, size_t p, float si
     return check_launch("noise_finalize");
 }
 
+// H5 fused with the optimiser step that follows it: g = (acc + scale z) / |B| is formed in registers
+// and applied at once -- v <- mu v + g, theta <- theta - lr v (v == nullptr: theta <- theta - lr g);
+// g is written only if the caller asks for it.  20 bytes per parameter instead of 8 + 20.
+template <bool NOISE>
+__global__ void __launch_bounds__(256) noise_finalize_update_kernel(const float *__restrict__ acc, float *__restrict__ theta,
+                                                                     float *__restrict__ vbuf, float *__restrict__ out,
+                                                                     size_t p, float scale, float inv_batch, float lr,
+                                                                     float momentum, uint32_t k0, uint32_t k1,
+                                                                     uint32_t step_lo, uint32_t tensor_id)
+{
+    const uint64_t q = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t e = (size_t)q * 4;
+    if (e >= p) return;
+    float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if constexpr (NOISE) {
+        const Philox4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), tensor_id, step_lo, k0, k1);
+        box_muller(r.x, r.y, z[0], z[1]);
+        box_muller(r.z, r.w, z[2], z[3]);
+    }
+    const bool full = e + 4 <= p;
+    float a[4], t[4], v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (full) {
+        const float4 av = *reinterpret_cast<const float4 *>(acc + e), tv = *reinterpret_cast<const float4 *>(theta + e);
+        a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
+        t[0] = tv.x; t[1] = tv.y; t[2] = tv.z; t[3] = tv.w;
+        if (vbuf) { const float4 vv = *reinterpret_cast<const float4 *>(vbuf + e); v[0] = vv.x; v[1] = vv.y; v[2] = vv.z; v[3] = vv.w; }
+    } else {
+        for (int j = 0; j < 4; ++j) {
+            const bool ok = e + j < p;
+            a[j] = ok ? acc[e + j] : 0.0f;
+            t[j] = ok ? theta[e + j] : 0.0f;
+            v[j] = (ok && vbuf) ? vbuf[e + j] : 0.0f;
+        }
+    }
+    float g[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        g[j] = (a[j] + scale * z[j]) * inv_batch;
+        if (vbuf) { v[j] = momentum * v[j] + g[j]; t[j] -= lr * v[j]; }
+        else t[j] -= lr * g[j];
+    }
+    if (full) {
+        *reinterpret_cast<float4 *>(theta + e) = make_float4(t[0], t[1], t[2], t[3]);
+        if (vbuf) *reinterpret_cast<float4 *>(vbuf + e) = make_float4(v[0], v[1], v[2], v[3]);
+        if (out) *reinterpret_cast<float4 *>(out + e) = make_float4(g[0], g[1], g[2], g[3]);
+    } else {
+        for (int j = 0; e + j < p; ++j) {
+            theta[e + j] = t[j];
+            if (vbuf) vbuf[e + j] = v[j];
+            if (out) out[e + j] = g[j];
+        }
+    }
+}
+
+dp_status launch_noise_finalize_update(const float *acc, float *theta, float *vbuf, float *out, size_t p, float sigma,
+                                       float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
+                                       uint32_t tensor_id, float lr, float momentum, hipStream_t s)
+{
+    const size_t calls = (p + 3) / 4;
+    const unsigned blocks = (unsigned)((calls + 255) / 256);
+    const float inv_batch = 1.0f / (float)total_batch;
+    if (sigma > 0.0f)
+        hipLaunchKernelGGL(noise_finalize_update_kernel<true>, dim3(blocks), dim3(256), 0, s, acc, theta, vbuf, out, p,
+                           sigma * clip_total, inv_batch, lr, momentum, (uint32_t)seed, (uint32_t)(seed >> 32),
+                           (uint32_t)step, tensor_id);
+    else
+        hipLaunchKernelGGL(noise_finalize_update_kernel<false>, dim3(blocks), dim3(256), 0, s, acc, theta, vbuf, out, p,
+                           0.0f, inv_batch, lr, momentum, 0u, 0u, 0u, 0u);
+    return check_launch("noise_finalize_update");
+}
+
 __global__ void __launch_bounds__(256) philox_raw_kernel(uint32_t *__restrict__ raw, size_t p, uint32_t k0,
                                                           uint32_t k1, uint32_t step_lo, uint32_t tensor_id)
 {

@@ -86,6 +86,10 @@ class PrivatiseStep:
         # side streams: `side` for the per-example phase, `side_b` for the clipped-sum phase
         self.side = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
         self.side_b = [torch.cuda.Stream(device=dev) for _ in range(max(2, self.n_streams // 2))] if self.n_streams > 1 else []
+        # optional fused optimiser step (enable_update): parameters and momentum buffer, laid out like acc
+        self.theta = None
+        self.velocity = None
+        self._update = None                      # (lr, momentum, keep_gradient)
         self._b_done = [None] * self.copies      # per copy: events after which its buffers are free again
         self._last = 0                           # copy used by the most recent micro-step
         self.graph = None
@@ -145,6 +149,23 @@ class PrivatiseStep:
     @property
     def g(self) -> Optional[torch.Tensor]:
         return self._g[self._last]
+
+    def enable_update(self, lr: float, momentum: float = 0.0, theta: Optional[torch.Tensor] = None,
+                      keep_gradient: bool = True):
+        """Make finalize() apply the SGD step in the same kernel (dp_add_noise_finalize_update): theta and the
+        momentum buffer are flat vectors laid out like the accumulator.  `lr` can be changed per step with set_lr."""
+        self.theta = torch.zeros_like(self.acc) if theta is None else theta
+        self.velocity = torch.zeros_like(self.acc) if momentum != 0.0 else None
+        self._update = [float(lr), float(momentum), bool(keep_gradient)]
+
+    def set_lr(self, lr: float):
+        self._update[0] = float(lr)
+
+    def theta_w(self, li: int) -> torch.Tensor:
+        return self.theta[self.off_w[li]: self.off_w[li] + self.pw[li]]
+
+    def theta_b(self, li: int) -> Optional[torch.Tensor]:
+        return self.theta[self.off_b[li]: self.off_b[li] + self.pb[li]] if self.pb[li] else None
 
     def begin_step(self):
         self.acc.zero_()
@@ -251,14 +272,24 @@ class PrivatiseStep:
         for li in range(len(self.layers)):
             st = self.side[k % len(self.side)] if self.side else None
             k += 1
-            B.dp_add_noise_finalize(self.acc_w(li).data_ptr(), self.out_w(li).data_ptr(), self.pw[li], wl.sigma,
-                                    wl.clip_total, wl.total_batch, wl.philox_seed, wl.step, 2 * li, stream=st)
+            self._finalize_tensor(self.off_w[li], self.pw[li], 2 * li, st)
             if self.pb[li]:
-                B.dp_add_noise_finalize(self.acc_b(li).data_ptr(), self.out_b(li).data_ptr(), self.pb[li],
-                                        wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step,
-                                        2 * li + 1, stream=st)
+                self._finalize_tensor(self.off_b[li], self.pb[li], 2 * li + 1, st)
         for st in self.side:
             main.wait_stream(st)
+
+    def _finalize_tensor(self, off: int, p: int, tensor_id: int, st):
+        wl = self.wl
+        acc, out = self.acc[off:].data_ptr(), self.out[off:].data_ptr()
+        if self._update is None:
+            B.dp_add_noise_finalize(acc, out, p, wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step,
+                                    tensor_id, stream=st)
+        else:
+            lr, momentum, keep = self._update
+            B.dp_add_noise_finalize_update(acc, self.theta[off:].data_ptr(),
+                                           self.velocity[off:].data_ptr() if self.velocity is not None else None,
+                                           out if keep else None, p, wl.sigma, wl.clip_total, wl.total_batch,
+                                           wl.philox_seed, wl.step, tensor_id, lr, momentum, stream=st)
 
     def run(self, inputs_per_micro_step: Sequence[Sequence]):
         self.begin_step()

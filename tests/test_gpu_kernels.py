@@ -372,3 +372,31 @@ def test_partial_norm_path_matches_reduced_norms(name, layer, n, dtype, material
     assert np.allclose(host(out)[0], 2.0 * host(sq), rtol=1e-5, atol=0), (host(out)[0], host(sq))
     if materialise:
         assert torch.equal(gw, gw2)
+
+
+@pytest.mark.parametrize("p,sigma,momentum,with_out", [(4099, 1.1, 0.9, True), (6, 0.0, 0.0, False), (203_530, 0.7, 0.5, False),
+                                                       (1024, 1.0, 0.0, True)])
+def test_fused_noise_finalize_and_sgd_update(p, sigma, momentum, with_out):
+    """dp_add_noise_finalize_update against the oracle: finalize in fp64, then its SGD step; two steps in a
+    row so the momentum buffer is carried."""
+    rng = np.random.default_rng(p)
+    theta = rng.standard_normal(p).astype(np.float32)
+    vel = (rng.standard_normal(p) * 0.1).astype(np.float32)
+    use_v = momentum != 0.0 or p == 1024          # a buffer with momentum 0 is legal too
+    th_d, v_d = dev(theta), dev(vel) if use_v else None
+    th_ref, v_ref = theta.astype(np.float64), (vel.astype(np.float64) if use_v else None)
+    for step in range(2):
+        acc = (rng.standard_normal(p) * 3.0).astype(np.float32)
+        out_d = torch.zeros(p, device="cuda:0") if with_out else None
+        lr = 0.1 / (step + 1)
+        dp.dp_add_noise_finalize_update(dev(acc), th_d, v_d, out_d, p, sigma, 1.5, 64, 42, step, 9, lr, momentum)
+        g_ref = oracle.noise_finalize(acc, sigma, 1.5, 64, 42, step, 9)
+        th_ref, v_ref = oracle.sgd_update(g_ref, th_ref, v_ref, lr, momentum)
+        if with_out:
+            assert_close(host(out_d), g_ref, F32_TOL, f"g step {step}")
+            sep = torch.zeros(p, device="cuda:0")
+            dp.dp_add_noise_finalize(dev(acc), sep, p, sigma, 1.5, 64, 42, step, 9)
+            assert torch.equal(out_d, sep)             # the fused call forms the same gradient bits
+        assert_close(host(th_d), th_ref, F32_TOL, f"theta step {step}")
+        if use_v:
+            assert_close(host(v_d), v_ref, F32_TOL, f"velocity step {step}")

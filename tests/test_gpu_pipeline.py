@@ -122,3 +122,28 @@ def test_graph_replay_with_side_streams_matches_eager_every_time():
     # multi-stream without a graph as well
     ms = dp.PrivatiseStep(wl, streams=3)
     assert torch.equal(ms.run(steps), want)
+
+
+def test_fused_optimiser_update_over_two_steps():
+    """finalize with the SGD step fused in: theta after two optimiser steps (momentum carried) against the
+    oracle's finalize + update."""
+    wl = get_workload("conv3x3", n=4, accum=2, hw=14)
+    steps = [[(dev(x), dev(dy)) for x, dy in make_inputs(wl, m)] for m in range(wl.accum)]
+    ref = oracle.privatise(wl, [make_inputs(wl, m) for m in range(wl.accum)])
+    ps = dp.PrivatiseStep(wl, streams=2)
+    rng = np.random.default_rng(23)
+    theta0 = rng.standard_normal(ps.p_total).astype(np.float32)
+    ps.enable_update(lr=0.05, momentum=0.9, theta=dev(theta0))
+    ps.run(steps)
+    ps.set_lr(0.025)
+    ps.run(steps)                                    # same data and Philox step: same gradient again
+    torch.cuda.synchronize()
+    for li, l in enumerate(wl.layers):
+        for off, cnt, g in ((ps.off_w[li], ps.pw[li], ref["out_w"][li]), (ps.off_b[li], ps.pb[li], ref["out_b"][li])):
+            if not cnt:
+                continue
+            th, v = theta0[off: off + cnt].astype(np.float64), np.zeros(cnt)
+            th, v = oracle.sgd_update(g.reshape(-1), th, v, 0.05, 0.9)
+            th, v = oracle.sgd_update(g.reshape(-1), th, v, 0.025, 0.9)
+            assert_close(host(ps.theta[off: off + cnt]), th, F32_TOL, f"theta layer {li}")
+            assert_close(host(ps.out[off: off + cnt]), g.reshape(-1), F32_TOL, f"gradient layer {li}")

@@ -165,3 +165,25 @@ def test_norm_partial_count_is_positive_and_needs_a_valid_descriptor(lib):
                 assert dp.dp_workspace_bytes(d, dp.DP_WS_PER_EXAMPLE_GRAD) >= 4 * 5 * c
     bad = dp.make_desc(conv(4, 4, 3, 1, 8), 0, "f32")
     assert dp.dp_norm_partial_count(bad, False) == 0
+
+
+def test_fused_update_rejects_bad_arguments(lib):
+    f = lib.dp_add_noise_finalize_update
+    ok = dict(acc=FAKE, theta=FAKE, velocity=FAKE, out=None, p=16, sigma=1.0, clip=1.0, batch=8, seed=0, step=0, tid=0,
+              lr=0.1, mom=0.9)
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["acc"], a["theta"], a["velocity"], a["out"], a["p"], a["sigma"], a["clip"], a["batch"], a["seed"],
+                 a["step"], a["tid"], a["lr"], a["mom"], None)
+    assert call(acc=None) == B.DP_ERR_INVALID_ARG
+    assert call(theta=None) == B.DP_ERR_INVALID_ARG
+    assert call(theta=FAKE + 4) == B.DP_ERR_INVALID_ARG
+    assert call(p=0) == B.DP_ERR_INVALID_ARG
+    assert call(sigma=-1.0) == B.DP_ERR_INVALID_ARG
+    assert call(clip=0.0) == B.DP_ERR_INVALID_ARG
+    assert call(batch=0) == B.DP_ERR_INVALID_ARG
+    assert call(lr=float("nan")) == B.DP_ERR_INVALID_ARG
+    assert call(mom=-0.1) == B.DP_ERR_INVALID_ARG
+    assert call(mom=float("inf")) == B.DP_ERR_INVALID_ARG
+    assert call(velocity=None, mom=0.9) == B.DP_ERR_INVALID_ARG
+    assert "velocity" in dp.dp_last_error()
