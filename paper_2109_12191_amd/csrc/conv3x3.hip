@@ -40,7 +40,8 @@ struct C3Args {
     float *ws_part;                   // sliced K / example ranges: accumulators in register layout
     const float *group_sqnorm;        // weighted: [n]
     float clip_c;
-    int n, cin, cout, h;
+    int n, cin, cout, h;              // h: OUTPUT height (= input height for stride 1)
+    int hin;                          // input height
     int tiles_co, tiles_ci;
     int chunks;                       // ceil(H / R)
     int ksplit, chunks_per_split;     // per-example mode: K slices
@@ -51,12 +52,18 @@ constexpr int odd16(int bytes) { return ((bytes / 16) | 1) * 16; }
 constexpr int C3_RP = 292;                           // floats per row staged by the store epilogue: 288 + 4
 constexpr int C3_STORE_LDS = 4 * 8 * C3_RP * 4;      // bytes the store epilogue needs: 4 waves x 8 rows
 
-template <int W> struct C3Cfg {
+// W is the OUTPUT row width.  Stride 1 reads X itself (input width W).  Stride 2 reads a copy of X
+// whose rows have been split by column parity (deinterleave2_kernel below): each row is
+//     O'[c] = X[2c - 1], c = 0 .. OWP+7   (zero for 2c-1 outside the row)   then   E[c] = X[2c], c = 0 .. OWP-1,
+// so that tap kw = 0 is O'[ow], kw = 1 is E[ow], kw = 2 is O'[ow + 1]: contiguous runs again.
+template <int W, int STRIDE> struct C3Cfg {
     static constexpr int OWP = (W + 7) / 8 * 8;
-    static constexpr int R = (OWP == 8) ? 8 : 224 / OWP;      // output rows per chunk
+    static constexpr int R = (STRIDE == 1) ? ((OWP == 8) ? 8 : 224 / OWP)            // output rows per chunk
+                                           : ((OWP == 16) ? 5 : 8);
     static constexpr int KSTEPS = R * OWP / 16;
-    static constexpr int WP = OWP + 8;
-    static constexpr int XROWS = R + 2;
+    static constexpr int WP = (STRIDE == 1) ? OWP + 8 : 2 * OWP + 8;                  // elements per staged X row
+    static constexpr int E_OFF = OWP + 8;                                           // stride 2: where E starts in a row
+    static constexpr int XROWS = (STRIDE == 1) ? R + 2 : 2 * R + 1;
     static constexpr int PPR = OWP / 8, XPR = WP / 8;         // 16-byte pieces per LDS row
     static constexpr int PA = odd16(R * OWP * 2);             // bytes per co in LDS (odd multiple of 16)
     static constexpr int PX = odd16(XROWS * WP * 2);          // bytes per ci in LDS
@@ -67,6 +74,7 @@ template <int W> struct C3Cfg {
     static constexpr bool ALIGNED_A = (W % 8 == 0);
     static_assert(OWP == 8 || OWP == 16 || OWP == 32 || OWP == 56, "supported row widths");
     static_assert(R * OWP % 16 == 0, "whole MFMA K steps");
+    static_assert(LDS <= 80 * 1024, "two workgroups per CU");
 };
 
 // What a workgroup does with finished accumulators (all of K of one example): squared norm of
@@ -180,11 +188,11 @@ __device__ __forceinline__ void c3_add_to_accumulator(const f32x16 (&acc)[9], co
 // is staged; added to the accumulator, or to the workspace when the examples are split into ranges).
 enum { C3_FULL = 0, C3_SLICED = 1, C3_WEIGHTED = 2 };
 
-template <int W, int MODE>
+template <int W, int MODE, int STRIDE>
 __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
 {
     constexpr bool WEIGHTED = MODE == C3_WEIGHTED;
-    using C = C3Cfg<W>;
+    using C = C3Cfg<W, STRIDE>;
     constexpr int XB = 6;                             // X pieces per thread in flight at once
     extern __shared__ __attribute__((aligned(16))) char lds[];
     __shared__ float red[4];
@@ -211,7 +219,8 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
     // element offsets count from the start of the whole tensor (all n examples, below 2^31):
     // whole-dword windows (10 elements from an even element index) may reach into the
     // neighbouring example but never outside the tensor
-    const int x_ex = a.cin * H * W, dy_ex = a.cout * H * W;       // elements per example
+    constexpr int XROW = (STRIDE == 1) ? W : C::WP;               // elements per row of the X tensor read here
+    const int x_ex = a.cin * a.hin * XROW, dy_ex = a.cout * H * W;    // elements per example
     const int x_end = a.n * x_ex, dy_end = a.n * dy_ex;
     const uint32_t *xw = reinterpret_cast<const uint32_t *>(a.x);
     const uint32_t *dyw = reinterpret_cast<const uint32_t *>(a.dy);
@@ -258,15 +267,24 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
             const int id = tid + C3_THREADS * u;
             const int ch = id / (C::XROWS * C::XPR), q = id - ch * (C::XROWS * C::XPR);
             const int xr = q / C::XPR, pc = q - xr * C::XPR;
-            const int ih = oh0 - 1 + xr;
-            const int iw0 = pc * 8 - 1;
             p.write = id < C::NPX;
-            p.lo = (pc == 0) ? 1 : 0;
-            p.hi = W - iw0;                           // may be <= 0: an all-zero piece
-            p.valid = p.write && (ci0 + ch < a.cin) && (ih >= 0) && (ih < H) && (p.hi > p.lo);
-            p.rel = x_base + ((ci0 + ch) * H + ih) * W + iw0;
             p.lds_off = ch * C::PX + (xr * C::WP + pc * 8) * 2;
-            p.fast = p.valid && p.rel >= 0 && (p.rel & ~1) + 10 <= x_end;
+            if constexpr (STRIDE == 1) {
+                const int ih = oh0 - 1 + xr;
+                const int iw0 = pc * 8 - 1;
+                p.lo = (pc == 0) ? 1 : 0;
+                p.hi = W - iw0;                           // may be <= 0: an all-zero piece
+                p.valid = p.write && (ci0 + ch < a.cin) && (ih >= 0) && (ih < H) && (p.hi > p.lo);
+                p.rel = x_base + ((ci0 + ch) * H + ih) * W + iw0;
+                p.fast = p.valid && p.rel >= 0 && (p.rel & ~1) + 10 <= x_end;
+            } else {
+                // rows of the parity-split copy: whole aligned pieces, zeros already in place
+                const int ih = 2 * oh0 - 1 + xr;
+                p.lo = 0; p.hi = 8;
+                p.valid = p.write && (ci0 + ch < a.cin) && (ih >= 0) && (ih < a.hin);
+                p.rel = x_base + ((ci0 + ch) * a.hin + ih) * C::WP + pc * 8;
+                p.fast = p.valid;
+            }
             return p;
         };
 
@@ -302,24 +320,45 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
                     *reinterpret_cast<uint4 *>(sA + p.lds_off) = v;
             }
         }
+        if constexpr (STRIDE == 1) {
 #pragma unroll
-        for (int u0 = 0; u0 < C::PX_T; u0 += XB) {
-            Raw<5> rx[XB];
+            for (int u0 = 0; u0 < C::PX_T; u0 += XB) {
+                Raw<5> rx[XB];
 #pragma unroll
-            for (int u = 0; u < XB; ++u) {
-                if (u0 + u < C::PX_T) {
+                for (int u = 0; u < XB; ++u) {
+                    if (u0 + u < C::PX_T) {
+                        const PieceX p = piece_x(u0 + u);
+                        rx[u] = piece_load_words(xw + ((p.fast ? p.rel : 0) >> 1));
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < XB; ++u) {
+                    if (u0 + u >= C::PX_T) continue;
                     const PieceX p = piece_x(u0 + u);
-                    rx[u] = piece_load_words(xw + ((p.fast ? p.rel : 0) >> 1));
+                    uint32_t t[4];
+                    piece_finish<true, 1>(t, rx[u], (uint32_t)(p.rel & 1), p.fast ? p.lo : 0, p.fast ? p.hi : 0);
+                    const uint4 v = make_uint4(t[0], t[1], t[2], t[3]);
+                    if (p.write) *reinterpret_cast<uint4 *>(sX + p.lds_off) = v;
                 }
             }
+        } else {
+            constexpr int XB2 = 8;                    // aligned 16-byte copies: four registers per piece
 #pragma unroll
-            for (int u = 0; u < XB; ++u) {
-                if (u0 + u >= C::PX_T) continue;
-                const PieceX p = piece_x(u0 + u);
-                uint32_t t[4];
-                piece_finish<true, 1>(t, rx[u], (uint32_t)(p.rel & 1), p.fast ? p.lo : 0, p.fast ? p.hi : 0);
-                const uint4 v = make_uint4(t[0], t[1], t[2], t[3]);
-                if (p.write) *reinterpret_cast<uint4 *>(sX + p.lds_off) = v;
+            for (int u0 = 0; u0 < C::PX_T; u0 += XB2) {
+                uint4 rx[XB2];
+#pragma unroll
+                for (int u = 0; u < XB2; ++u) {
+                    if (u0 + u < C::PX_T) {
+                        const PieceX p = piece_x(u0 + u);
+                        rx[u] = *reinterpret_cast<const uint4 *>(a.x + (p.valid ? p.rel : 0));
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < XB2; ++u) {
+                    if (u0 + u >= C::PX_T) continue;
+                    const PieceX p = piece_x(u0 + u);
+                    if (p.write) *reinterpret_cast<uint4 *>(sX + p.lds_off) = p.valid ? rx[u] : make_uint4(0u, 0u, 0u, 0u);
+                }
             }
         }
         // Pieces whose whole-dword window would have left the tensor (only the first rows of the
@@ -343,7 +382,7 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
                 }
             }
 #pragma unroll 1
-            for (int u = 0; u < C::PX_T; ++u) {
+            for (int u = 0; u < (STRIDE == 1 ? C::PX_T : 0); ++u) {
                 const PieceX p = piece_x(u);
                 if (p.valid && !p.fast) {
                     uint16_t *dst = reinterpret_cast<uint16_t *>(sX + p.lds_off);
@@ -366,20 +405,25 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
             const bf16x8 va = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + kk * 2));
 #pragma unroll
             for (int kh = 0; kh < 3; ++kh) {
-                const char *row = px + ((r + kh) * C::WP + ow0) * 2;
+                const char *row = px + ((STRIDE * r + kh) * C::WP + ow0) * 2;
                 const uint4 d = *reinterpret_cast<const uint4 *>(row);
                 const uint32_t d4 = *reinterpret_cast<const uint32_t *>(row + 16);
-                const uint4 b0 = d;
-                const uint4 b1 = make_uint4(funnel(d.y, d.x, 16), funnel(d.z, d.y, 16), funnel(d.w, d.z, 16),
-                                            funnel(d4, d.w, 16));
-                const uint4 b2 = make_uint4(d.y, d.z, d.w, d4);
+                const uint4 sh = make_uint4(funnel(d.y, d.x, 16), funnel(d.z, d.y, 16), funnel(d.w, d.z, 16),
+                                            funnel(d4, d.w, 16));                 // the same run one element on
+                uint4 b0, b1, b2;
+                if constexpr (STRIDE == 1) {
+                    b0 = d; b1 = sh; b2 = make_uint4(d.y, d.z, d.w, d4);
+                } else {
+                    b0 = d;                                                          // O'[ow]     = X[2 ow - 1]
+                    b1 = *reinterpret_cast<const uint4 *>(row + C::E_OFF * 2);       // E[ow]      = X[2 ow]
+                    b2 = sh;                                                         // O'[ow + 1] = X[2 ow + 1]
+                }
                 acc[kh * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, b0), acc[kh * 3 + 0], 0, 0, 0);
                 acc[kh * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, b1), acc[kh * 3 + 1], 0, 0, 0);
                 acc[kh * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, b2), acc[kh * 3 + 2], 0, 0, 0);
             }
         }
     }
-
     }   // examples
 
     if constexpr (MODE == C3_FULL) {
@@ -393,6 +437,33 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mine[(t * 16 + r) * C3_THREADS + threadIdx.x] = acc[t][r];
     }
+}
+
+// Parity split of the rows of X for the stride-2 kernel: out[row][0 .. OWP+8) = O'[c] = X[row][2c - 1],
+// out[row][OWP+8 .. 2 OWP+8) = E[c] = X[row][2c]; zero where the column is outside the row.  `rows` =
+// n * cin * hin rows of `win` (even) elements; one thread per 16-byte output piece, which needs
+// the high (O') or low (E) halves of eight consecutive dwords of the input row.
+__global__ void __launch_bounds__(256) deinterleave2_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ out,
+                                                            long long rows, int win, int owp)
+{
+    const int xpr = (2 * owp + 8) / 8, opr = (owp + 8) / 8;
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= rows * xpr) return;
+    const long long row = q / xpr;
+    const int pc = (int)(q - row * xpr);
+    const bool odd_plane = pc < opr;
+    const int first = odd_plane ? 8 * pc - 1 : 8 * (pc - opr);      // dword of element 0 of the piece
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(x + (size_t)row * win);
+    const int nd = win / 2;
+    uint32_t h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int d = first + e;
+        const uint32_t w = (d >= 0 && d < nd) ? src[d] : 0u;
+        h[e] = odd_plane ? (w >> 16) : (w & 0xFFFFu);
+    }
+    *reinterpret_cast<uint4 *>(out + q * 8) =
+        make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
 }
 
 // Slices of one (example, tile) meet here.  The sum is elementwise, so it is spread over many
@@ -468,19 +539,28 @@ struct C3Plan {
     int ex_per_split;                  // weighted
 };
 
-int rows_of_width(int w)
+int rows_of_width(int ow, int stride)
 {
-    const int owp = (w + 7) / 8 * 8;
+    const int owp = (ow + 7) / 8 * 8;
+    if (stride == 2) return owp == 16 ? 5 : 8;
     return owp == 8 ? 8 : 224 / owp;
+}
+
+// bytes of the parity-split copy of X the stride-2 kernel reads (0 for stride 1)
+size_t c3_split_bytes(const Geo &g)
+{
+    if (g.stride != 2) return 0;
+    const int owp = (g.ow + 7) / 8 * 8;
+    return (size_t)g.n * g.cin * g.h * (2 * owp + 8) * sizeof(uint16_t);
 }
 
 C3Plan c3_plan(const Geo &g, int mode)
 {
     C3Plan p;
-    p.rows = rows_of_width(g.w);
+    p.rows = rows_of_width(g.ow, g.stride);
     p.tiles_co = (g.cout + 63) / 64;
     p.tiles_ci = (g.cin + 63) / 64;
-    p.chunks = (g.h + p.rows - 1) / p.rows;
+    p.chunks = (g.oh + p.rows - 1) / p.rows;
     p.ksplit = 1;
     p.chunks_per_split = p.chunks;
     p.ex_per_split = g.n;
@@ -511,40 +591,52 @@ size_t c3_align16(size_t b) { return (b + 15) & ~(size_t)15; }
 // partial squared norms per (example, tile): one, or one per fixup workgroup when K is sliced
 size_t c3_partials_per_unit(const C3Plan &p) { return p.ksplit > 1 ? 9 * C3_FIX_PARTS : 1; }
 
-template <int W, int MODE>
+template <int W, int MODE, int STRIDE>
 dp_status c3_launch_mode(const C3Args &a, unsigned blocks, hipStream_t s)
 {
-    using C = C3Cfg<W>;
+    using C = C3Cfg<W, STRIDE>;
     static bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&conv3x3_kernel<W, MODE>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&conv3x3_kernel<W, MODE, STRIDE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS) != hipSuccess)
             return fail(DP_ERR_DEVICE, "conv3x3: cannot reserve %d bytes of LDS", C::LDS);
         attr_done = true;
     }
-    hipLaunchKernelGGL((conv3x3_kernel<W, MODE>), dim3(blocks), dim3(C3_THREADS), C::LDS, s, a);
+    hipLaunchKernelGGL((conv3x3_kernel<W, MODE, STRIDE>), dim3(blocks), dim3(C3_THREADS), C::LDS, s, a);
     return check_launch("conv3x3");
 }
 
-template <int W>
+template <int W, int STRIDE>
 dp_status c3_launch_w(const C3Args &a, bool weighted, unsigned blocks, hipStream_t s)
 {
-    if (weighted) return c3_launch_mode<W, C3_WEIGHTED>(a, blocks, s);
-    if (a.ksplit > 1) return c3_launch_mode<W, C3_SLICED>(a, blocks, s);
-    return c3_launch_mode<W, C3_FULL>(a, blocks, s);
+    if constexpr (STRIDE == 1) {
+        if (weighted) return c3_launch_mode<W, C3_WEIGHTED, STRIDE>(a, blocks, s);
+    }
+    if (a.ksplit > 1) return c3_launch_mode<W, C3_SLICED, STRIDE>(a, blocks, s);
+    return c3_launch_mode<W, C3_FULL, STRIDE>(a, blocks, s);
 }
 
 }  // namespace
 
 bool conv3x3_applicable(const Geo &g, int mode)
 {
-    (void)mode;
     if (!g.bf16 || g.has_bias) return false;
-    if (g.kh != 3 || g.kw != 3 || g.stride != 1 || g.pad != 1) return false;
+    if (g.kh != 3 || g.kw != 3 || g.pad != 1) return false;
     if (g.cin < 64 || g.cout < 64) return false;
-    switch (g.w) {
-    case 7: case 8: case 14: case 16: case 28: case 32: case 56: break;
-    default: return false;
+    if (g.stride == 1) {
+        switch (g.w) {
+        case 7: case 8: case 14: case 16: case 28: case 32: case 56: break;
+        default: return false;
+        }
+    } else if (g.stride == 2) {
+        // even images only (rows split by column parity, output exactly half the size)
+        if (g.h % 2 || g.w % 2 || g.oh * 2 != g.h || g.ow * 2 != g.w) return false;
+        // measured: worthwhile for the per-example calls on 14- and 7-wide outputs; wider outputs (short chunks,
+        // K slicing) and the clip-weighted form do better in the general kernel / on packed operands
+        if (mode == MODE_WEIGHTED || (g.ow != 7 && g.ow != 14)) return false;
+        if ((long long)g.n * g.cin * g.h * (2 * ((g.ow + 7) / 8 * 8) + 8) >= (1ll << 31)) return false;
+    } else {
+        return false;
     }
     // 32-bit element offsets inside the whole tensor
     return (long long)g.n * g.cin * g.h * g.w < (1ll << 31) && (long long)g.n * g.cout * g.h * g.w < (1ll << 31);
@@ -554,11 +646,12 @@ size_t conv3x3_ws_bytes(const Geo &g, int mode)
 {
     const C3Plan p = c3_plan(g, mode);
     const size_t tiles = (size_t)p.tiles_co * p.tiles_ci;
-    if (mode == MODE_WEIGHTED) return p.ksplit > 1 ? tiles * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float) : 0;
+    const size_t split = c3_align16(c3_split_bytes(g));
+    if (mode == MODE_WEIGHTED) return split + (p.ksplit > 1 ? tiles * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float) : 0);
     const size_t units = (size_t)g.n * tiles;
     size_t b = c3_align16(units * c3_partials_per_unit(p) * sizeof(float));
     if (p.ksplit > 1) b += units * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float);
-    return b;
+    return b + split;
 }
 
 size_t conv3x3_norm_partial_count(const Geo &g)
@@ -569,16 +662,17 @@ size_t conv3x3_norm_partial_count(const Geo &g)
 
 const char *conv3x3_variant_name(const Geo &g, int mode)
 {
-    static char names[2][8][48];
+    static char names[2][2][8][56];
     int slot;
-    switch (g.w) {
+    switch (g.ow) {
     case 7: slot = 0; break; case 8: slot = 1; break; case 14: slot = 2; break; case 16: slot = 3; break;
     case 28: slot = 4; break; case 32: slot = 5; break; default: slot = 6; break;
     }
-    const int wt = mode == MODE_WEIGHTED ? 1 : 0;
-    if (!names[wt][slot][0])
-        snprintf(names[wt][slot], sizeof names[wt][slot], "conv3x3_rows<bf16,w%d,%s>", g.w, wt ? "weighted" : "per_example");
-    return names[wt][slot];
+    const int wt = mode == MODE_WEIGHTED ? 1 : 0, st = g.stride == 2 ? 1 : 0;
+    if (!names[st][wt][slot][0])
+        snprintf(names[st][wt][slot], sizeof names[st][wt][slot], "conv3x3_rows<bf16,w%d%s,%s>", g.ow, st ? ",s2" : "",
+                 wt ? "weighted" : "per_example");
+    return names[st][wt][slot];
 }
 
 dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
@@ -592,7 +686,7 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     a.out_w = out_w;
     a.out_stride = out_stride ? out_stride : g.pw;
     a.group_sqnorm = group_sqnorm; a.clip_c = clip_c;
-    a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = g.h;
+    a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = g.oh; a.hin = g.h;
     a.tiles_co = p.tiles_co; a.tiles_ci = p.tiles_ci;
     a.chunks = p.chunks; a.ksplit = p.ksplit; a.chunks_per_split = p.chunks_per_split;
     a.ex_per_split = p.ex_per_split;
@@ -605,18 +699,35 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
         w += c3_align16(units * c3_partials_per_unit(p) * sizeof(float));
     }
     a.ws_part = p.ksplit > 1 ? reinterpret_cast<float *>(w) : nullptr;
+    if (p.ksplit > 1) w += units * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float);
     const long long total = (long long)units * p.ksplit;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     dp_status st;
+    if (g.stride == 2) {
+        // rows of X split by column parity, after everything else in the workspace
+        const int owp = (g.ow + 7) / 8 * 8;
+        const long long rows = (long long)g.n * g.cin * g.h;
+        const long long pieces = rows * ((2 * owp + 8) / 8);
+        hipLaunchKernelGGL(deinterleave2_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, a.x,
+                           reinterpret_cast<uint16_t *>(w), rows, g.w, owp);
+        st = check_launch("deinterleave2");
+        if (st != DP_OK) return st;
+        a.x = reinterpret_cast<const uint16_t *>(w);
+    }
     profile_begin(s);
-    switch (g.w) {
-    case 7: st = c3_launch_w<7>(a, weighted, blocks, s); break;
-    case 8: st = c3_launch_w<8>(a, weighted, blocks, s); break;
-    case 14: st = c3_launch_w<14>(a, weighted, blocks, s); break;
-    case 16: st = c3_launch_w<16>(a, weighted, blocks, s); break;
-    case 28: st = c3_launch_w<28>(a, weighted, blocks, s); break;
-    case 32: st = c3_launch_w<32>(a, weighted, blocks, s); break;
-    default: st = c3_launch_w<56>(a, weighted, blocks, s); break;
+    if (g.stride == 2) {
+        if (g.ow == 7) st = c3_launch_w<7, 2>(a, weighted, blocks, s);
+        else st = c3_launch_w<14, 2>(a, weighted, blocks, s);
+    } else {
+        switch (g.w) {
+        case 7: st = c3_launch_w<7, 1>(a, weighted, blocks, s); break;
+        case 8: st = c3_launch_w<8, 1>(a, weighted, blocks, s); break;
+        case 14: st = c3_launch_w<14, 1>(a, weighted, blocks, s); break;
+        case 16: st = c3_launch_w<16, 1>(a, weighted, blocks, s); break;
+        case 28: st = c3_launch_w<28, 1>(a, weighted, blocks, s); break;
+        case 32: st = c3_launch_w<32, 1>(a, weighted, blocks, s); break;
+        default: st = c3_launch_w<56, 1>(a, weighted, blocks, s); break;
+        }
     }
     profile_end(s);
     if (st != DP_OK) return st;
