@@ -110,6 +110,8 @@ def main():
                     help="examples of micro-batch 0 the oracle is timed on (32 = about 10 s on 16 cores)")
     ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
     ap.add_argument("--streams", type=int, default=8, help="side streams for independent layers")
+    ap.add_argument("--noise", default="once", choices=["once", "per_example"],
+                    help="once: N(0, sigma^2 C^2) in finalize; per_example: every clipped example brings N(0, sigma^2 C^2/|B|)")
     ap.add_argument("--fused-update", action="store_true",
                     help="finalize applies the SGD-with-momentum step in the same kernel (extra work inside the step)")
     ap.add_argument("--no-graph", action="store_true", help="issue every call from the host instead of a HIP graph")
@@ -127,7 +129,7 @@ def main():
     dp.load_library()
     device = torch.device("cuda:0")
     wl = get_workload(args.workload, n=args.n, accum=args.accum, hw=args.hw)
-    ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=args.streams)
+    ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=args.streams, noise=args.noise)
     inputs = make_device_inputs(wl, wl.accum, device)
     if args.fused_update:
         ps.enable_update(lr=0.1, momentum=0.9, keep_gradient=False)
@@ -152,7 +154,7 @@ def main():
 
     # Roofline of the dominant kernel: the same steps issued call by call on ONE stream right
     # after the timed region, every contraction kernel bracketed by events on that stream.
-    pe = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=1)
+    pe = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=1, noise=args.noise)
     probe = Probe()
     pe.probe = probe
     pe.run(inputs)
@@ -220,6 +222,7 @@ def main():
                    "clipped_sum_forms": {f: ps.form.count(f) for f in sorted(set(ps.form))},
                    "issue": "host calls" if args.no_graph else f"HIP graph, {args.streams} side streams",
                    "finalize": "noise + SGD-momentum update fused" if args.fused_update else "noise + divide by |B|",
+                   "noise_form": args.noise,
                    "flop_per_example": wl.flops_per_example, "input_bytes_per_example": wl.in_bytes_per_example},
         "roofline": roofline,
     }

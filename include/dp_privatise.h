@@ -187,6 +187,21 @@ dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float si
                                 uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
                                 dp_stream stream);
 
+/* The per-example form of the noise (second equation of the Algorithm section, the form the paper's
+ * implementation uses): every clipped example carries its own N(0, sigma^2 clip_total^2 / total_batch)
+ * draw, so that after all total_batch examples the accumulated noise has the variance of the
+ * once-per-step form.  Called once per micro-step and tensor, after the clipped sum:
+ *     acc[e] += sigma * clip_total / sqrt(total_batch) * sum_{j = first_example}^{first_example + n_examples - 1} z(j, e)
+ * with z(j, .) from Philox4x32-10 as above but counter (q, j, tensor_id, step mod 2^32) and key
+ * (seed mod 2^32, (seed div 2^32) xor 0x50455245): j is the example's index within the optimiser step.
+ * The step is then finished with dp_add_noise_finalize(sigma = 0).  Same distribution as the
+ * once-per-step form, different bits, n_examples Philox calls per four parameters.
+ * acc [device] [p] fp32, 16-byte aligned.  first_example + n_examples > total_batch, n_examples < 1,
+ * bad sigma / clip_total -> DP_ERR_INVALID_ARG.                                                  */
+dp_status dp_add_example_noise(float *acc, size_t p, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
+                               uint64_t step, uint32_t tensor_id, uint64_t first_example, int n_examples,
+                               dp_stream stream);
+
 /* H5 fused with the SGD step that consumes it (the step right after the path: "SGD ... with a
  * stepped learning rate decay policy", Algorithm section; "vanilla SGD with momentum (0.9)",
  * Sections 4.2-4.3): with g[e] = (acc[e] + sigma * clip_total * z_e) / total_batch as above,

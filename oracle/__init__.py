@@ -70,6 +70,9 @@ def _load():
     lib.orc_noise_finalize.restype = None
     lib.orc_noise_finalize.argtypes = [dp, dp, C.c_size_t, C.c_double, C.c_double, C.c_uint64, C.c_uint64,
                                        C.c_uint64, C.c_uint32]
+    lib.orc_add_example_noise.restype = None
+    lib.orc_add_example_noise.argtypes = [dp, C.c_size_t, C.c_double, C.c_double, C.c_uint64, C.c_uint64, C.c_uint64,
+                                          C.c_uint32, C.c_uint64, C.c_int]
     lib.orc_sgd_update.restype = None
     lib.orc_sgd_update.argtypes = [dp, dp, dp, C.c_size_t, C.c_double, C.c_double]
     lib.orc_max_threads.restype = C.c_int
@@ -205,6 +208,15 @@ def noise_finalize(acc, sigma: float, clip_total: float, total_batch: int, seed:
     return out.reshape(acc.shape)
 
 
+def add_example_noise(acc, sigma: float, clip_total: float, total_batch: int, seed: int, step: int, tensor_id: int,
+                      first_example: int, count: int) -> np.ndarray:
+    """acc + the per-example noise draws of `count` examples (per-example form of the noise)."""
+    out = np.array(acc, dtype=np.float64).reshape(-1).copy()
+    _load().orc_add_example_noise(_dp(out), out.size, sigma, clip_total, total_batch, seed, step, tensor_id,
+                                  first_example, count)
+    return out.reshape(np.shape(acc))
+
+
 def sgd_update(g, theta, v, lr: float, momentum: float):
     """One SGD step on a finalized gradient: returns (theta', v').  v None = no momentum buffer."""
     g = np.ascontiguousarray(g, dtype=np.float64)
@@ -214,21 +226,30 @@ def sgd_update(g, theta, v, lr: float, momentum: float):
     return theta, vv
 
 
-def privatise(wl, inputs_per_micro_step, threads: int = 0):
+def privatise(wl, inputs_per_micro_step, threads: int = 0, noise_form: str = "once"):
     """Whole optimiser step of a workload: clip-accumulate over its micro-steps, then noise and
     divide.  Tensor ids: 2*layer for the weight, 2*layer+1 for the bias.
     Returns dict(acc_w, acc_b, out_w, out_b, n2, f) (lists over layers; n2, f over micro-steps)."""
     layers = list(wl.layers)
     acc_w, acc_b = new_accumulators(layers)
     n2s, fs = [], []
-    for inputs in inputs_per_micro_step:
+    for m, inputs in enumerate(inputs_per_micro_step):
         n2, f = clip_accumulate(layers, inputs, wl.group_of_layer, wl.group_clip, acc_w, acc_b, threads)
         n2s.append(n2)
         fs.append(f)
+        if noise_form == "per_example":
+            # every clipped example brings its own N(0, sigma^2 C^2 / |B|) draw
+            for li in range(len(layers)):
+                acc_w[li][...] = add_example_noise(acc_w[li], wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed,
+                                                   wl.step, 2 * li, m * wl.n, wl.n)
+                if acc_b[li] is not None:
+                    acc_b[li][...] = add_example_noise(acc_b[li], wl.sigma, wl.clip_total, wl.total_batch,
+                                                       wl.philox_seed, wl.step, 2 * li + 1, m * wl.n, wl.n)
+    sigma_end = 0.0 if noise_form == "per_example" else wl.sigma
     out_w, out_b = [], []
     for li, l in enumerate(layers):
-        out_w.append(noise_finalize(acc_w[li], wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed,
+        out_w.append(noise_finalize(acc_w[li], sigma_end, wl.clip_total, wl.total_batch, wl.philox_seed,
                                     wl.step, 2 * li))
-        out_b.append(noise_finalize(acc_b[li], wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed,
+        out_b.append(noise_finalize(acc_b[li], sigma_end, wl.clip_total, wl.total_batch, wl.philox_seed,
                                     wl.step, 2 * li + 1) if acc_b[li] is not None else None)
     return dict(acc_w=acc_w, acc_b=acc_b, out_w=out_w, out_b=out_b, n2=n2s, f=fs)

@@ -192,6 +192,38 @@ double orc_clip_factor(double n2, double clip_c)
     return r < 1.0 ? r : 1.0;
 }
 
+static double uniform_open(uint32_t r);     /* defined with the noise stream below */
+
+/* Per-example form of the noise (second equation of the Algorithm section): every clipped example
+ * carries its own N(0, sigma^2 C^2 / |B|) draw, so the sum over the |B| examples of a step has the
+ * variance sigma^2 C^2 of the once-per-step form.  The draws of example j (its index within the
+ * optimiser step) come from the same Philox4x32-10 / Box-Muller construction with the example index
+ * in the second counter word and a flipped key word, so the two forms never share a draw:
+ *   counter (q, j, tensor_id, step lo), key (seed lo, seed hi ^ 0x50455245), elements 4q..4q+3.
+ * acc[e] += sigma * clip_total / sqrt(total_batch) * sum_{j = first .. first+count-1} z(j, e).     */
+void orc_add_example_noise(double *acc, size_t p, double sigma, double clip_total, uint64_t total_batch,
+                           uint64_t seed, uint64_t step, uint32_t tensor_id, uint64_t first_example, int count)
+{
+    const double two_pi = 6.283185307179586476925286766559;
+    const double scale = sigma * clip_total / sqrt((double)total_batch);
+    if (sigma == 0.0) return;
+    for (size_t e = 0; e < p; ++e) {
+        double sum = 0.0;
+        for (int jj = 0; jj < count; ++jj) {
+            const uint64_t j = first_example + (uint64_t)jj;
+            const uint32_t ctr[4] = { (uint32_t)(e / 4), (uint32_t)j, tensor_id, (uint32_t)step };
+            const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) ^ 0x50455245u };
+            uint32_t r[4];
+            orc_philox4x32_10(ctr, key, r);
+            const int pair = (int)((e % 4) / 2);
+            const double ua = uniform_open(r[2 * pair]), ub = uniform_open(r[2 * pair + 1]);
+            const double radius = sqrt(-2.0 * log(ua));
+            sum += (e % 2 == 0) ? radius * cos(two_pi * ub) : radius * sin(two_pi * ub);
+        }
+        acc[e] += scale * sum;
+    }
+}
+
 /* SGD step on the privatised gradient (Algorithm section: "SGD ... with a stepped learning rate
  * decay policy"; Sections 4.2-4.3: "vanilla SGD with momentum (0.9)").  g is the finalized
  * gradient of one tensor; the buffer v is the plain heavy-ball momentum: v <- mu v + g,

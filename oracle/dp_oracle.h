@@ -104,6 +104,11 @@ void orc_noise_normal(uint64_t seed, uint64_t step, uint32_t tensor_id, size_t f
 void orc_noise_finalize(const double *acc, double *out, size_t p, double sigma, double clip_total,
                         uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id);
 
+/* acc[e] += sigma * clip_total / sqrt(total_batch) * (sum of the per-example draws of `count` examples
+ * starting at example index first_example); see the .c file for the stream. */
+void orc_add_example_noise(double *acc, size_t p, double sigma, double clip_total, uint64_t total_batch,
+                           uint64_t seed, uint64_t step, uint32_t tensor_id, uint64_t first_example, int count);
+
 /* theta <- theta - lr * v with v <- momentum * v + g (v may be NULL: theta <- theta - lr * g). */
 void orc_sgd_update(const double *g, double *theta, double *v, size_t p, double lr, double momentum);
 

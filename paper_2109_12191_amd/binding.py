@@ -62,6 +62,7 @@ def load_library():
         "dp_clip_accumulate": (it, [vp, sz, vp, fl, it, sz, vp, vp]),
         "dp_clip_accumulate_recompute": (it, [dpp, vp, vp, vp, fl, vp, vp, vp, sz, vp]),
         "dp_add_noise_finalize": (it, [vp, vp, sz, fl, fl, u64, u64, u64, u32, vp]),
+        "dp_add_example_noise": (it, [vp, sz, fl, fl, u64, u64, u64, u32, u64, it, vp]),
         "dp_add_noise_finalize_update": (it, [vp, vp, vp, vp, sz, fl, fl, u64, u64, u64, u32, fl, fl, vp]),
         "dp_philox_raw": (it, [vp, sz, u64, u64, u32, vp]),
         "dp_profile_next_contraction": (it, [vp, vp]),
@@ -78,7 +79,7 @@ def load_library():
 
 EXPORTED = ("dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
-            "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update",
+            "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
             "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
 
 
@@ -199,6 +200,12 @@ def dp_add_noise_finalize(acc, out, p: int, sigma: float, clip_total: float, tot
                           step: int, tensor_id: int, stream=None):
     _check(load_library().dp_add_noise_finalize(_ptr(acc), _ptr(out), p, sigma, clip_total, total_batch, seed,
                                                 step, tensor_id, _stream(stream)))
+
+
+def dp_add_example_noise(acc, p: int, sigma: float, clip_total: float, total_batch: int, seed: int, step: int,
+                         tensor_id: int, first_example: int, n_examples: int, stream=None):
+    _check(load_library().dp_add_example_noise(_ptr(acc), p, sigma, clip_total, total_batch, seed, step, tensor_id,
+                                               first_example, n_examples, _stream(stream)))
 
 
 def dp_add_noise_finalize_update(acc, theta, velocity, out, p: int, sigma: float, clip_total: float, total_batch: int,

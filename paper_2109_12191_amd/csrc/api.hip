@@ -347,6 +347,27 @@ dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float si
                                  static_cast<hipStream_t>(stream));
 }
 
+dp_status dp_add_example_noise(float *acc, size_t p, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
+                               uint64_t step, uint32_t tensor_id, uint64_t first_example, int n_examples,
+                               dp_stream stream)
+{
+    DP_TRY(check_ptr(acc, "acc", true));
+    if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0 parameters");
+    if (std::isnan(sigma) || sigma < 0.0f || std::isinf(sigma)) return fail(DP_ERR_INVALID_ARG, "sigma must be finite and >= 0");
+    if (!(clip_total > 0.0f) || !std::isfinite(clip_total)) return fail(DP_ERR_INVALID_ARG, "clip_total must be finite and > 0");
+    if (total_batch < 1) return fail(DP_ERR_INVALID_ARG, "total_batch = 0");
+    if (n_examples < 1) return fail(DP_ERR_INVALID_ARG, "n_examples = %d (need >= 1)", n_examples);
+    if (first_example + (uint64_t)n_examples > total_batch)
+        return fail(DP_ERR_INVALID_ARG, "examples %llu..%llu are outside the step's %llu examples",
+                    (unsigned long long)first_example, (unsigned long long)(first_example + n_examples - 1),
+                    (unsigned long long)total_batch);
+    if (total_batch > 0xFFFFFFFFull) return fail(DP_ERR_UNSUPPORTED, "more than 2^32 examples per step");
+    if (p > ((size_t)1 << 34)) return fail(DP_ERR_UNSUPPORTED, "p too large for the per-example stream");
+    g_err[0] = 0;
+    return launch_example_noise(acc, p, sigma, clip_total, total_batch, seed, step, tensor_id, first_example, n_examples,
+                                static_cast<hipStream_t>(stream));
+}
+
 dp_status dp_add_noise_finalize_update(const float *acc, float *theta, float *velocity, float *out, size_t p, float sigma,
                                        float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
                                        uint32_t tensor_id, float lr, float momentum, dp_stream stream)

@@ -96,6 +96,8 @@ dp_status launch_add_partial_sums(const float *parts, int n_parts, size_t slice,
 dp_status launch_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,
                                 uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
                                 hipStream_t s);
+dp_status launch_example_noise(float *acc, size_t p, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
+                               uint64_t step, uint32_t tensor_id, uint64_t first_example, int count, hipStream_t s);
 dp_status launch_noise_finalize_update(const float *acc, float *theta, float *vbuf, float *out, size_t p, float sigma,
                                        float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
                                        uint32_t tensor_id, float lr, float momentum, hipStream_t s);

@@ -295,6 +295,46 @@ dp_status launch_noise_finalize(const float *acc, float *out, size_t p, float si
     return check_launch("noise_finalize");
 }
 
+// Per-example form of the noise (second equation of the Algorithm section): acc[e] += scale * sum_j z(j, e)
+// over `count` examples starting at `first`; example j's draws use the counter (q, j, tensor_id, step) and the
+// key (seed lo, seed hi ^ 0x50455245).  One thread per four parameters; the examples are summed in order.
+__global__ void __launch_bounds__(256) example_noise_kernel(float *__restrict__ acc, size_t p, float scale, uint32_t k0,
+                                                             uint32_t k1, uint32_t step_lo, uint32_t tensor_id,
+                                                             uint32_t first, int count)
+{
+    const uint64_t q = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t e = (size_t)q * 4;
+    if (e >= p) return;
+    float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int j = 0; j < count; ++j) {
+        const Philox4 r = philox4x32_10((uint32_t)q, first + (uint32_t)j, tensor_id, step_lo, k0, k1);
+        float z[4];
+        box_muller(r.x, r.y, z[0], z[1]);
+        box_muller(r.z, r.w, z[2], z[3]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sum[u] += z[u];
+    }
+    if (e + 4 <= p) {
+        float4 a = *reinterpret_cast<float4 *>(acc + e);
+        a.x += scale * sum[0]; a.y += scale * sum[1]; a.z += scale * sum[2]; a.w += scale * sum[3];
+        *reinterpret_cast<float4 *>(acc + e) = a;
+    } else {
+        for (int u = 0; e + u < p; ++u) acc[e + u] += scale * sum[u];
+    }
+}
+
+dp_status launch_example_noise(float *acc, size_t p, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
+                               uint64_t step, uint32_t tensor_id, uint64_t first_example, int count, hipStream_t s)
+{
+    if (sigma == 0.0f) return DP_OK;
+    const size_t calls = (p + 3) / 4;
+    const float scale = sigma * clip_total / sqrtf((float)total_batch);
+    hipLaunchKernelGGL(example_noise_kernel, dim3((unsigned)((calls + 255) / 256)), dim3(256), 0, s, acc, p, scale,
+                       (uint32_t)seed, (uint32_t)(seed >> 32) ^ 0x50455245u, (uint32_t)step, tensor_id,
+                       (uint32_t)first_example, count);
+    return check_launch("example_noise");
+}
+
 // H5 fused with the optimiser step that follows it: g = (acc + scale z) / |B| is formed in registers
 // and applied at once -- v <- mu v + g, theta <- theta - lr v (v == nullptr: theta <- theta - lr g);
 // g is written only if the caller asks for it.  20 bytes per parameter instead of 8 + 20.

@@ -30,9 +30,14 @@ def _pad4(v: int) -> int:
 
 
 class PrivatiseStep:
-    def __init__(self, wl, device: str = "cuda:0", mode: str = "auto", streams: int = 1):
+    def __init__(self, wl, device: str = "cuda:0", mode: str = "auto", streams: int = 1, noise: str = "once"):
         B.load_library()
         self.wl = wl
+        if noise not in ("once", "per_example"):
+            raise ValueError(noise)
+        # "once": N(0, sigma^2 C^2) added in finalize (first equation of the Algorithm section);
+        # "per_example": every clipped example brings N(0, sigma^2 C^2 / |B|) (second equation)
+        self.noise = noise
         self.device = torch.device(device)
         self.layers = list(wl.layers)
         self.n = wl.n
@@ -232,6 +237,10 @@ class PrivatiseStep:
                     B.dp_clip_accumulate(g_buf[:, self.off_w[li]:].data_ptr(), gsq[g],
                                          self.group_clip[g], self.n, span,
                                          self.acc[self.off_w[li]:].data_ptr(), g_stride=gs, stream=st0)
+        if self.noise == "per_example":
+            for li in range(L):
+                if self.form[li] == "materialise":
+                    self._example_noise(li, sb[0] if sb else None)
         k = 0
         for li in range(L):
             if self.form[li] != "recompute":
@@ -246,6 +255,8 @@ class PrivatiseStep:
                                            self.acc_w(li).data_ptr(),
                                            self.acc_b(li).data_ptr() if self.pb[li] else None,
                                            ws, ws_bytes=ws.numel(), stream=st)
+            if self.noise == "per_example":
+                self._example_noise(li, st)
         if sb:
             evs = []
             for st in sb:
@@ -254,6 +265,17 @@ class PrivatiseStep:
                 evs.append(ev)
             self._b_done[c] = evs
         self.micro_steps_done += 1
+
+    def _example_noise(self, li: int, st):
+        """Per-example noise of this micro-step's examples for the tensors of layer li, on the stream that
+        updates those tensors."""
+        wl = self.wl
+        first = self.micro_steps_done * self.n
+        B.dp_add_example_noise(self.acc_w(li).data_ptr(), self.pw[li], wl.sigma, wl.clip_total, wl.total_batch,
+                               wl.philox_seed, wl.step, 2 * li, first, self.n, stream=st)
+        if self.pb[li]:
+            B.dp_add_example_noise(self.acc_b(li).data_ptr(), self.pb[li], wl.sigma, wl.clip_total, wl.total_batch,
+                                   wl.philox_seed, wl.step, 2 * li + 1, first, self.n, stream=st)
 
     def _drain(self):
         """The current stream waits for every clipped sum issued so far."""
@@ -281,14 +303,15 @@ class PrivatiseStep:
     def _finalize_tensor(self, off: int, p: int, tensor_id: int, st):
         wl = self.wl
         acc, out = self.acc[off:].data_ptr(), self.out[off:].data_ptr()
+        sigma = wl.sigma if self.noise == "once" else 0.0        # per-example form: the noise is already in acc
         if self._update is None:
-            B.dp_add_noise_finalize(acc, out, p, wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step,
+            B.dp_add_noise_finalize(acc, out, p, sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step,
                                     tensor_id, stream=st)
         else:
             lr, momentum, keep = self._update
             B.dp_add_noise_finalize_update(acc, self.theta[off:].data_ptr(),
                                            self.velocity[off:].data_ptr() if self.velocity is not None else None,
-                                           out if keep else None, p, wl.sigma, wl.clip_total, wl.total_batch,
+                                           out if keep else None, p, sigma, wl.clip_total, wl.total_batch,
                                            wl.philox_seed, wl.step, tensor_id, lr, momentum, stream=st)
 
     def run(self, inputs_per_micro_step: Sequence[Sequence]):

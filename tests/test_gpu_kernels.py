@@ -405,3 +405,23 @@ def test_fused_noise_finalize_and_sgd_update(p, sigma, momentum, with_out):
         assert_close(host(th_d), th_ref, F32_TOL, f"theta step {step}")
         if use_v:
             assert_close(host(v_d), v_ref, F32_TOL, f"velocity step {step}")
+
+
+@pytest.mark.parametrize("p,first,count,batch", [(4099, 0, 8, 8), (6, 3, 2, 16), (203_530, 32, 32, 256)])
+def test_per_example_noise_form(p, first, count, batch):
+    """dp_add_example_noise against the oracle: the sum of the per-example draws lands on the accumulator."""
+    rng = np.random.default_rng(p)
+    acc0 = (rng.standard_normal(p) * 0.5).astype(np.float32)
+    acc = dev(acc0)
+    dp.dp_add_example_noise(acc, p, 1.1, 0.9, batch, 0xABCDEF0123, 3, 5, first, count)
+    ref = oracle.add_example_noise(acc0, 1.1, 0.9, batch, 0xABCDEF0123, 3, 5, first, count)
+    assert_close(host(acc) - acc0, ref - acc0, F32_TOL, "per-example noise increment")
+    # moments of what was added (count examples of variance sigma^2 C^2 / batch each)
+    if p > 100_000:
+        inc = host(acc) - acc0
+        target = 1.1 * 0.9 * math.sqrt(count / batch)
+        assert abs(inc.mean()) < 0.01 * target and abs(inc.std() / target - 1.0) < 0.01
+    # sigma = 0 leaves the accumulator alone
+    acc2 = dev(acc0)
+    dp.dp_add_example_noise(acc2, p, 0.0, 0.9, batch, 1, 1, 1, first, count)
+    assert torch.equal(acc2, dev(acc0))

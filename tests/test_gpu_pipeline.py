@@ -147,3 +147,19 @@ def test_fused_optimiser_update_over_two_steps():
             th, v = oracle.sgd_update(g.reshape(-1), th, v, 0.025, 0.9)
             assert_close(host(ps.theta[off: off + cnt]), th, F32_TOL, f"theta layer {li}")
             assert_close(host(ps.out[off: off + cnt]), g.reshape(-1), F32_TOL, f"gradient layer {li}")
+
+
+@pytest.mark.parametrize("streams", [1, 3])
+def test_per_example_noise_form_whole_path(streams):
+    """The paper's as-built form: noise per clipped example, nothing added in finalize."""
+    wl = get_workload("resnet50", n=4, accum=2, hw=64)
+    host_steps = [make_inputs(wl, m) for m in range(wl.accum)]
+    ref = oracle.privatise(wl, host_steps, noise_form="per_example")
+    steps = [[(dev(x, wl.dtype), dev(dy, wl.dtype)) for x, dy in inputs] for inputs in host_steps]
+    ps = dp.PrivatiseStep(wl, streams=streams, noise="per_example")
+    ps.run(steps)
+    torch.cuda.synchronize()
+    for li, l in enumerate(wl.layers):
+        assert_close(host(ps.out_w(li)), ref["out_w"][li], BF16_TOL, f"out_w[{li}] {l.name}")
+        if l.pb:
+            assert_close(host(ps.out_b(li)), ref["out_b"][li], BF16_TOL, f"out_b[{li}]")

@@ -187,3 +187,17 @@ def test_fused_update_rejects_bad_arguments(lib):
     assert call(mom=float("inf")) == B.DP_ERR_INVALID_ARG
     assert call(velocity=None, mom=0.9) == B.DP_ERR_INVALID_ARG
     assert "velocity" in dp.dp_last_error()
+
+
+def test_example_noise_rejects_bad_arguments(lib):
+    f = lib.dp_add_example_noise
+    def call(acc=FAKE, p=16, sigma=1.0, clip=1.0, batch=8, first=0, cnt=4):
+        return f(acc, p, sigma, clip, batch, 0, 0, 0, first, cnt, None)
+    assert call(acc=None) == B.DP_ERR_INVALID_ARG
+    assert call(p=0) == B.DP_ERR_INVALID_ARG
+    assert call(sigma=float("nan")) == B.DP_ERR_INVALID_ARG
+    assert call(clip=-1.0) == B.DP_ERR_INVALID_ARG
+    assert call(batch=0) == B.DP_ERR_INVALID_ARG
+    assert call(cnt=0) == B.DP_ERR_INVALID_ARG
+    assert call(first=6, cnt=4) == B.DP_ERR_INVALID_ARG          # examples beyond the step
+    assert "outside" in dp.dp_last_error()
