@@ -234,7 +234,7 @@ struct GnArgs {
 };
 
 template <bool BF16>
-__global__ void __launch_bounds__(256) gn_affine_kernel(const GnArgs a)
+__global__ void __launch_bounds__(256) gn_affine_3pass_kernel(const GnArgs a)
 {
     typedef typename In<BF16>::type E;
     __shared__ float red[4];
@@ -281,6 +281,69 @@ __global__ void __launch_bounds__(256) gn_affine_kernel(const GnArgs a)
     if (threadIdx.x == 0) a.partials[(size_t)i * a.groups + grp] = tot;
 }
 
+// One sweep over x and dy (groups of at most GN_CMAX channels): with k = the group's first element as
+// a shift (so that the variance does not cancel), every wave takes channels in turn and accumulates
+//     sum (x-k), sum (x-k)^2 for the group statistics,   sum dy (x-k), sum dy for the channel;
+// then dgamma_c = rstd (sum dy (x-k) - (mean-k) sum dy), dbeta_c = sum dy.  Four independent loads per
+// lane and stream are in flight.
+constexpr int GN_CMAX = 256;
+
+template <bool BF16>
+__global__ void __launch_bounds__(256) gn_affine_kernel(const GnArgs a)
+{
+    typedef typename In<BF16>::type E;
+    __shared__ float red[4];
+    __shared__ float s_dx[GN_CMAX], s_d[GN_CMAX];
+    const int grp = blockIdx.x, i = blockIdx.y;
+    const int cg = a.c / a.groups;
+    const size_t first = ((size_t)i * a.c + (size_t)grp * cg) * a.hw;
+    const int cnt = cg * a.hw;
+    const E *xg = static_cast<const E *>(a.x) + first;
+    const E *dyg = static_cast<const E *>(a.dy) + first;
+    const float k = In<BF16>::ld(xg);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    float sx = 0.0f, sxx = 0.0f;
+    for (int cl = wave; cl < cg; cl += 4) {
+        const E *xc = xg + (size_t)cl * a.hw, *dc = dyg + (size_t)cl * a.hw;
+        float dx[4] = {0.0f, 0.0f, 0.0f, 0.0f}, d1[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        float x1[4] = {0.0f, 0.0f, 0.0f, 0.0f}, x2[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        int p = lane;
+        for (; p + 192 < a.hw; p += 256) {
+            float xv[4], dv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { xv[u] = In<BF16>::ld(xc + p + 64 * u) - k; dv[u] = In<BF16>::ld(dc + p + 64 * u); }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { dx[u] += dv[u] * xv[u]; d1[u] += dv[u]; x1[u] += xv[u]; x2[u] += xv[u] * xv[u]; }
+        }
+        for (; p < a.hw; p += 64) {
+            const float xv = In<BF16>::ld(xc + p) - k, dv = In<BF16>::ld(dc + p);
+            dx[0] += dv * xv; d1[0] += dv; x1[0] += xv; x2[0] += xv * xv;
+        }
+        const float sdx = wave_sum((dx[0] + dx[1]) + (dx[2] + dx[3]));
+        const float sd = wave_sum((d1[0] + d1[1]) + (d1[2] + d1[3]));
+        sx += (x1[0] + x1[1]) + (x1[2] + x1[3]);
+        sxx += (x2[0] + x2[1]) + (x2[2] + x2[3]);
+        if (lane == 0) { s_dx[cl] = sdx; s_d[cl] = sd; }
+    }
+    const float m1 = block_sum<4>(sx, red) / (float)cnt;               // mean - k
+    const float m2 = block_sum<4>(sxx, red) / (float)cnt;
+    const float var = fmaxf(m2 - m1 * m1, 0.0f);
+    const float rstd = 1.0f / sqrtf(var + a.eps);
+    float ss = 0.0f;
+    for (int cl = threadIdx.x; cl < cg; cl += 256) {                   // block_sum's barriers made s_dx / s_d visible
+        const float sg = rstd * (s_dx[cl] - m1 * s_d[cl]), sb = s_d[cl];
+        const int c = grp * cg + cl;
+        ss += sg * sg + sb * sb;
+        if (a.out_w) {
+            a.out_w[(size_t)i * a.out_stride_w + c] = sg;
+            a.out_b[(size_t)i * a.out_stride_b + c] = sb;
+        }
+    }
+    const float tot = block_sum<4>(ss, red);
+    if (threadIdx.x == 0) a.partials[(size_t)i * a.groups + grp] = tot;
+}
+
 size_t gn_ws_bytes(const Geo &g, int mode)
 {
     size_t b = (size_t)g.n * g.gn_groups * sizeof(float);
@@ -310,8 +373,14 @@ dp_status launch_gn(const Geo &g, int mode, const void *x, const void *dy, float
     }
     a.out_w = gw; a.out_b = gb;
     const dim3 grid(g.gn_groups, g.n);
-    if (g.bf16) hipLaunchKernelGGL(gn_affine_kernel<true>, grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(gn_affine_kernel<false>, grid, dim3(256), 0, s, a);
+    const bool one_sweep = g.cin / g.gn_groups <= GN_CMAX;
+    if (g.bf16) {
+        if (one_sweep) hipLaunchKernelGGL(gn_affine_kernel<true>, grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(gn_affine_3pass_kernel<true>, grid, dim3(256), 0, s, a);
+    } else {
+        if (one_sweep) hipLaunchKernelGGL(gn_affine_kernel<false>, grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(gn_affine_3pass_kernel<false>, grid, dim3(256), 0, s, a);
+    }
     dp_status st = check_launch("gn_affine");
     if (st != DP_OK) return st;
     if (weighted) {

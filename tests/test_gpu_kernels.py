@@ -169,7 +169,7 @@ def test_dense_per_example_grad_and_norm(layer, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("c,hw,groups", [(16, 32, 8), (64, 8, 8), (24, 5, 3), (32, 7, 32)])
+@pytest.mark.parametrize("c,hw,groups", [(16, 32, 8), (64, 8, 8), (24, 5, 3), (32, 7, 32), (64, 56, 32), (600, 3, 2)])
 def test_groupnorm_affine_grad_and_norm(c, hw, groups, dtype):
     tol = F32_TOL if dtype == "f32" else BF16_TOL
     layer = gn_affine(c, hw, groups)
@@ -425,3 +425,15 @@ def test_per_example_noise_form(p, first, count, batch):
     acc2 = dev(acc0)
     dp.dp_add_example_noise(acc2, p, 0.0, 0.9, batch, 1, 1, 1, first, count)
     assert torch.equal(acc2, dev(acc0))
+
+
+def test_groupnorm_affine_with_a_large_mean_and_small_spread():
+    """Statistics are taken about a shift, so a group whose values sit far from zero keeps its variance."""
+    layer = gn_affine(16, 12, 4)
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((3,) + tuple(layer.x_shape)) * 0.05 + 40.0).astype(np.float32)
+    dy = (rng.standard_normal((3,) + tuple(layer.dy_shape)) * 0.05).astype(np.float32)
+    ref_w, ref_b, ref_n2 = _oracle_grads(layer, x, dy)
+    gw, gb, sq = _run_per_example(layer, x, dy, "f32")
+    assert_close(gw, ref_w, 2e-3, "dgamma")          # x - mean itself is only known to ~1e-4 relative in fp32 here
+    assert_close(gb, ref_b, F32_TOL, "dbeta")

@@ -163,3 +163,12 @@ def test_per_example_noise_form_whole_path(streams):
         assert_close(host(ps.out_w(li)), ref["out_w"][li], BF16_TOL, f"out_w[{li}] {l.name}")
         if l.pb:
             assert_close(host(ps.out_b(li)), ref["out_b"][li], BF16_TOL, f"out_b[{li}]")
+
+
+@pytest.mark.parametrize("name,n,accum,hw", [("resnet18_gn", 3, 2, 16), ("resnet50_gn", 2, 1, 64), ("resnet101_gn", 2, 1, 32)])
+def test_further_layer_sets_with_groupnorm(name, n, accum, hw):
+    """The paper's other networks (ResNet-18-GN, ResNet-101-GN32) and ResNet-50 with its GroupNorm gradients:
+    same kernels, more shapes; whole path against the oracle on small maps."""
+    wl = get_workload(name, n=n, accum=accum, hw=hw)
+    assert any(l.kind == "gn" for l in wl.layers)
+    _check(wl, "auto")

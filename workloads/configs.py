@@ -17,9 +17,12 @@ from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
-from .layers import Layer, conv, resnet20_layers, resnet50_layers, tiny_mlp_layers
+from .layers import (GN, Layer, conv, resnet18_layers, resnet20_layers, resnet50_layers, resnet_bottleneck_layers,
+                     tiny_mlp_layers)
 
-WORKLOAD_NAMES = ("mlp", "conv3x3", "resnet20", "resnet50", "resnet50_nano")
+WORKLOAD_NAMES = ("mlp", "conv3x3", "resnet20", "resnet50", "resnet50_nano",
+                  # further layer sets for the same kernels (the paper's other networks)
+                  "resnet50_gn", "resnet101_gn", "resnet18_gn")
 
 
 @dataclass(frozen=True)
@@ -102,6 +105,17 @@ def get_workload(name: str, *, n: Optional[int] = None, accum: Optional[int] = N
         layers = tuple(resnet50_layers(hw or 224))
         wl = Workload(name, layers, 1, 1024, "bf16", "per_layer", 1.0, 0.8,
                       tuple("absnormal" for _ in layers), 0.01, 1005)
+    elif name in ("resnet50_gn", "resnet101_gn"):
+        # bottleneck ResNets with GroupNorm(32) scale/shift gradients in the set (Table 3: ResNet-101-GN32)
+        blocks = (3, 4, 6, 3) if name == "resnet50_gn" else (3, 4, 23, 3)
+        layers = tuple(resnet_bottleneck_layers(blocks, hw or 224, 1000, 32))
+        wl = Workload(name, layers, 32, 8, "bf16", "global", 1.0, 1.0,
+                      tuple("normal" if l.kind == GN else "absnormal" for l in layers), 0.01, 1006)
+    elif name == "resnet18_gn":
+        # the CIFAR-10 / chest-CT network of Sections 4.2 and 5: ResNet-18 with GroupNorm, batch 32 x accumulation
+        layers = tuple(resnet18_layers(hw or 32, 10, 32))
+        wl = Workload(name, layers, 32, 8, "bf16", "global", 1.0, 1.0,
+                      tuple("normal" if l.kind == GN else "absnormal" for l in layers), 0.01, 1007)
     else:
         raise KeyError(f"unknown workload {name!r}; choose from {WORKLOAD_NAMES}")
     if n is not None:

@@ -138,28 +138,67 @@ def resnet20_layers(with_gn: bool = True, hw: int = 32) -> List[Layer]:
     return out
 
 
-def resnet50_layers(hw: int = 224, num_classes: int = 1000) -> List[Layer]:
-    """ResNet-50 with the stride on the 3x3 conv of each stage's first bottleneck:
-    53 bias-free convs plus one dense layer with bias.  `hw` scales the input
-    resolution (224 is the real one; smaller values give the same channel
-    structure on smaller feature maps for tests)."""
+def resnet_bottleneck_layers(blocks=(3, 4, 6, 3), hw: int = 224, num_classes: int = 1000,
+                             gn_groups: int = 0) -> List[Layer]:
+    """Bottleneck ResNet (50: blocks 3,4,6,3; 101: 3,4,23,3) with the stride on the 3x3 conv of each
+    stage's first bottleneck: bias-free convs plus one dense layer with bias.  With gn_groups > 0 every
+    conv is followed by a GroupNorm whose scale/shift gradients are part of the set (its input is the
+    conv's output).  `hw` scales the input resolution (224 is the real one)."""
     out: List[Layer] = []
-    c1 = conv(3, 64, 7, 2, hw, name="conv1")
-    out.append(c1)
+
+    def add(layer: Layer):
+        out.append(layer)
+        if gn_groups:
+            out.append(gn_affine(layer.cout, layer.oh, gn_groups, name=layer.name + ".gn"))
+        return layer
+
+    c1 = add(conv(3, 64, 7, 2, hw, name="conv1"))
     res = (c1.oh + 2 - 3) // 2 + 1          # 3x3 stride-2 max-pool, pad 1
     cin = 64
-    for si, (width, blocks) in enumerate([(64, 3), (128, 4), (256, 6), (512, 3)]):
+    for si, (width, nb) in enumerate(zip((64, 128, 256, 512), blocks)):
         cout = 4 * width
-        for b in range(blocks):
+        for b in range(nb):
             stride = 2 if (si > 0 and b == 0) else 1
             tag = f"s{si + 1}b{b + 1}"
-            out.append(conv(cin, width, 1, 1, res, name=tag + ".c1"))
-            c2 = conv(width, width, 3, stride, res, name=tag + ".c2")
-            out.append(c2)
-            out.append(conv(width, cout, 1, 1, c2.oh, name=tag + ".c3"))
+            add(conv(cin, width, 1, 1, res, name=tag + ".c1"))
+            c2 = add(conv(width, width, 3, stride, res, name=tag + ".c2"))
+            add(conv(width, cout, 1, 1, c2.oh, name=tag + ".c3"))
             if b == 0:
-                out.append(conv(cin, cout, 1, stride, res, name=tag + ".down"))
+                add(conv(cin, cout, 1, stride, res, name=tag + ".down"))
             res = c2.oh
             cin = cout
     out.append(dense(2048, num_classes, name="fc"))
+    return out
+
+
+def resnet50_layers(hw: int = 224, num_classes: int = 1000) -> List[Layer]:
+    """ResNet-50: 53 bias-free convs plus one dense layer with bias (no GroupNorm gradients)."""
+    return resnet_bottleneck_layers((3, 4, 6, 3), hw, num_classes, 0)
+
+
+def resnet18_layers(hw: int = 32, num_classes: int = 10, gn_groups: int = 32) -> List[Layer]:
+    """CIFAR-style ResNet-18 with GroupNorm: a 3x3 stem, four stages of two basic blocks (two 3x3
+    convs each), 1x1 stride-2 projection shortcuts at the start of stages 2-4, a GroupNorm affine
+    after every conv, dense 512 -> classes with bias."""
+    out: List[Layer] = []
+
+    def add(layer: Layer):
+        out.append(layer)
+        if gn_groups:
+            out.append(gn_affine(layer.cout, layer.oh, gn_groups, name=layer.name + ".gn"))
+        return layer
+
+    res = add(conv(3, 64, 3, 1, hw, name="conv1")).oh
+    cin = 64
+    for si, width in enumerate((64, 128, 256, 512)):
+        for b in range(2):
+            stride = 2 if (si > 0 and b == 0) else 1
+            tag = f"s{si + 1}b{b + 1}"
+            c1 = add(conv(cin, width, 3, stride, res, name=tag + ".c1"))
+            add(conv(width, width, 3, 1, c1.oh, name=tag + ".c2"))
+            if stride == 2:
+                add(conv(cin, width, 1, 2, res, name=tag + ".down"))
+            res = c1.oh
+            cin = width
+    out.append(dense(512, num_classes, name="fc"))
     return out
