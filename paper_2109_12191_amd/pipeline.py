@@ -234,13 +234,17 @@ class PrivatiseStep:
                         continue
                     g = self.group_of_layer[li]
                     span = _pad4(self.pw[li]) + _pad4(self.pb[li])
+                    # one call per layer, each always on the same stream (any stream will do: the calls
+                    # touch disjoint parts of the accumulator)
                     B.dp_clip_accumulate(g_buf[:, self.off_w[li]:].data_ptr(), gsq[g],
                                          self.group_clip[g], self.n, span,
-                                         self.acc[self.off_w[li]:].data_ptr(), g_stride=gs, stream=st0)
+                                         self.acc[self.off_w[li]:].data_ptr(), g_stride=gs,
+                                         stream=sb[li % len(sb)] if sb else None)
         if self.noise == "per_example":
             for li in range(L):
                 if self.form[li] == "materialise":
-                    self._example_noise(li, sb[0] if sb else None)
+                    one_pass = self.n_groups == 1
+                    self._example_noise(li, (sb[0] if one_pass else sb[li % len(sb)]) if sb else None)
         k = 0
         for li in range(L):
             if self.form[li] != "recompute":
