@@ -31,8 +31,8 @@ HBM_PEAK = 8.0e12
 # rocprofv3 --pmc runs summarised in profiles/conv_contract_resnet50_hbm_traffic.txt: mean FETCH_SIZE and
 # WRITE_SIZE per dispatch in KiB, each scaled by what the same counter reads for clip_accumulate_kernel
 # (a plain streaming kernel of known size in the same runs).
-PMC_FETCH_KIB, PMC_FETCH_SCALE = 12987.0, 2.0
-PMC_WRITE_KIB, PMC_WRITE_SCALE = 30472.0, 1.0
+PMC_FETCH_KIB, PMC_FETCH_SCALE = 11953.0, 2.0
+PMC_WRITE_KIB, PMC_WRITE_SCALE = 26196.0, 1.0
 MEASURED_TRAFFIC_KERNEL = "conv_contract<bf16,128x128,per_example>"
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1024.0 * (PMC_FETCH_KIB * PMC_FETCH_SCALE + PMC_WRITE_KIB * PMC_WRITE_SCALE)
 
