@@ -805,6 +805,9 @@ static FullPlan full_plan(const Geo &g, int mode)
 static bool packed_weighted(const Geo &g, int mode, PackPlan &pp, Geo &g2)
 {
     if (mode != MODE_WEIGHTED || !g.bf16) return false;
+    // a 1x1 stride-1 layer with even S is already K-contiguous and dword aligned: the aligned loader reads it
+    // in place and scales dY while staging, which beats packing it first (measured)
+    if (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0 && (g.oh * g.ow) % 2 == 0) return false;
     const long long J = (long long)g.cin * g.kh * g.kw;
     const int shape = (g.cout > 64 && J > 64) ? T128 : T64;
     const long long tiles = (long long)((g.cout + kTileM[shape] - 1) / kTileM[shape]) * ((J + kTileN[shape] - 1) / kTileN[shape]);
