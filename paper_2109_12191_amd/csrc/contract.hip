@@ -755,6 +755,12 @@ static FullPlan full_plan(const Geo &g, int mode)
     p.chunks_per_ex = (int)(((long long)p.oh * p.kcolsp + kc - 1) / kc);
 
     p.shape = (g.cout > 64 && J > 64) ? T128 : T64;
+    if (p.shape == T128 && mode != MODE_WEIGHTED && p.chunks_per_ex >= 8) {
+        // long K and few 128x128 tiles: 64x64 tiles give four times the (example, tile) units, so K
+        // needs no (or less) slicing and far fewer partial tiles travel through the workspace
+        const long long t128 = (long long)((g.cout + 127) / 128) * ((J + 127) / 128);
+        if ((long long)g.n * t128 < 512) p.shape = T64;
+    }
     p.tiles_m = (g.cout + kTileM[p.shape] - 1) / kTileM[p.shape];
     p.tiles_n = (J + kTileN[p.shape] - 1) / kTileN[p.shape];
     const int tiles = p.tiles_m * p.tiles_n;
@@ -779,8 +785,9 @@ static FullPlan full_plan(const Geo &g, int mode)
     } else {
         const long long units = (long long)g.n * tiles;
         if (units < 512 && p.chunks_per_ex >= 8) {
-            // few tiles, long K: slice K so that about 512 workgroups (one round: two per CU) run
-            long long want = 512 / units;
+            // few tiles, long K: slice K so that about 256 workgroups run (one per CU: measured best when several
+            // layers share the chip; more slices mean more partial tiles through the workspace)
+            long long want = 256 / units;
             if (want > p.chunks_per_ex / 4) want = p.chunks_per_ex / 4;
             if (want < 1) want = 1;
             p.chunks_per_split = (int)((p.chunks_per_ex + want - 1) / want);

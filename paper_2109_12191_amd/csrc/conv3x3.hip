@@ -577,8 +577,8 @@ C3Plan c3_plan(const Geo &g, int mode)
         return p;
     }
     const long long units = (long long)g.n * tiles;
-    if (units < 512 && p.chunks > 1) {
-        long long want = (256 + units - 1) / units;
+    if (units < 128 && p.chunks > 1) {
+        long long want = (128 + units - 1) / units;
         if (want > p.chunks) want = p.chunks;
         p.chunks_per_split = (int)((p.chunks + want - 1) / want);
         p.ksplit = (p.chunks + p.chunks_per_split - 1) / p.chunks_per_split;
