@@ -27,14 +27,22 @@ if ROOT not in sys.path:
 MFMA_PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, flop/s
 HBM_PEAK = 8.0e12
 
-# HBM bytes per launch of the dominant kernel (conv_contract<bf16,128x128,per_example>) from the two
-# rocprofv3 --pmc runs summarised in profiles/conv_contract_resnet50_hbm_traffic.txt: mean FETCH_SIZE and
-# WRITE_SIZE per dispatch in KiB, each scaled by what the same counter reads for clip_accumulate_kernel
-# (a plain streaming kernel of known size in the same runs).
-PMC_FETCH_KIB, PMC_FETCH_SCALE = 11953.0, 2.0
-PMC_WRITE_KIB, PMC_WRITE_SCALE = 26196.0, 1.0
-MEASURED_TRAFFIC_KERNEL = "conv_contract<bf16,128x128,per_example>"
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1024.0 * (PMC_FETCH_KIB * PMC_FETCH_SCALE + PMC_WRITE_KIB * PMC_WRITE_SCALE)
+# HBM bytes per launch of the contraction variants from the two rocprofv3 --pmc runs summarised in
+# profiles/conv_contract_resnet50_hbm_traffic.txt: mean FETCH_SIZE and WRITE_SIZE per dispatch in KiB, each
+# scaled by what the same counter reads for clip_accumulate_kernel (a plain streaming kernel of known size in
+# the same runs: FETCH_SIZE reads half of its bytes, WRITE_SIZE all of them).
+PMC_FETCH_SCALE, PMC_WRITE_SCALE = 2.0, 1.0
+PMC_KIB_PER_LAUNCH = {          # variant -> (FETCH_SIZE, WRITE_SIZE)
+    "conv_contract<bf16,64x64,per_example>": (23199.0, 9217.0),
+    "conv_contract<bf16,128x128,per_example>": (7775.0, 26197.0),
+}
+
+
+def measured_traffic(variant):
+    if variant not in PMC_KIB_PER_LAUNCH:
+        return None
+    f, w = PMC_KIB_PER_LAUNCH[variant]
+    return 1024.0 * (f * PMC_FETCH_SCALE + w * PMC_WRITE_SCALE)
 
 
 class Probe:
@@ -183,8 +191,8 @@ def main():
                     peak=HBM_PEAK / 1e9 if hbm_bound else peak / 1e12,
                     unit="GB/s" if hbm_bound else "TFLOP/s",
                     frac=byte_rate / HBM_PEAK if hbm_bound else flop_rate / peak,
-                    traffic=MEASURED_TRAFFIC_BYTES_PER_LAUNCH if (dom_name == MEASURED_TRAFFIC_KERNEL and args.workload == "resnet50"
-                                                                 and args.mode == "auto" and args.n is None and args.hw is None) else None,
+                    traffic=measured_traffic(dom_name) if (args.workload == "resnet50" and args.mode == "auto" and args.n is None
+                                                           and args.hw is None and args.accum is None) else None,
                     traffic_unit="HBM bytes per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see profiles/)",
                     kernel=dom_name, launches=dom["launches"], avg_launch_us=dom["total_ms"] * 1e3 / dom["launches"],
                     algorithmic_bytes_per_launch=dom["bytes"] / dom["launches"],

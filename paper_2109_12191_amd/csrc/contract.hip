@@ -788,6 +788,8 @@ static FullPlan full_plan(const Geo &g, int mode)
             // few tiles, long K: slice K so that about 256 workgroups run (one per CU: measured best when several
             // layers share the chip; more slices mean more partial tiles through the workspace)
             long long want = 256 / units;
+            const long long by_length = (p.chunks_per_ex + 23) / 24;      // and no workgroup walks more than ~24 chunks
+            if (want < by_length) want = by_length;
             if (want > p.chunks_per_ex / 4) want = p.chunks_per_ex / 4;
             if (want < 1) want = 1;
             p.chunks_per_split = (int)((p.chunks_per_ex + want - 1) / want);
