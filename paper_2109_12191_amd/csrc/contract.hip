@@ -25,8 +25,8 @@
 //     shuffles to one partial per (example, tile) -- the gradient is never re-read for the
 //     norm -- and, if asked, the tile is stored (materialised per-example gradient).  A
 //     workgroup may take several examples in a row (short K) so loads stream across example
-//     boundaries, or a slice of one example's K (long K, few tiles); slices meet in a
-//     workspace and the last one to arrive adds them in fixed order and runs the epilogue.
+//     boundaries, or a slice of one example's K (long K, few tiles); slices store their tiles
+//     in a workspace and a second kernel adds them in slice order and runs the epilogue.
 //   * weighted mode: K runs over (example, position) with dY_i scaled by the clip factor f_i
 //     while it is staged, so the tile is sum_i f_i dW_i; example ranges meet the same way and
 //     the sum is added to the accumulator.
