@@ -179,29 +179,33 @@ def main():
     summary = probe.summary()
     esize = wl.elem_bytes
     contraction = {k: v for k, v in summary.items() if k.startswith("conv")}
-    dom_name, dom = max(contraction.items(), key=lambda kv: kv[1]["total_ms"])
-    # which roof binds this kernel: its arithmetic intensity against the ridge of the chip
-    secs = dom["total_ms"] * 1e-3
-    flop_rate, byte_rate = dom["flops"] / secs, dom["bytes"] / secs
-    peak = MFMA_PEAK[wl.dtype]
-    intensity = dom["flops"] / dom["bytes"]
-    hbm_bound = intensity < peak / HBM_PEAK
-    roofline = dict(bound="hbm" if hbm_bound else "mfma",
-                    achieved=byte_rate / 1e9 if hbm_bound else flop_rate / 1e12,
-                    peak=HBM_PEAK / 1e9 if hbm_bound else peak / 1e12,
-                    unit="GB/s" if hbm_bound else "TFLOP/s",
-                    frac=byte_rate / HBM_PEAK if hbm_bound else flop_rate / peak,
-                    traffic=measured_traffic(dom_name) if (args.workload == "resnet50" and args.mode == "auto" and args.n is None
-                                                           and args.hw is None and args.accum is None) else None,
-                    traffic_unit="HBM bytes per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see profiles/)",
-                    kernel=dom_name, launches=dom["launches"], avg_launch_us=dom["total_ms"] * 1e3 / dom["launches"],
-                    algorithmic_bytes_per_launch=dom["bytes"] / dom["launches"],
-                    algorithmic_flop_per_launch=dom["flops"] / dom["launches"],
-                    flop_per_byte=intensity, ridge_flop_per_byte=peak / HBM_PEAK,
-                    mfma_tflops=flop_rate / 1e12, mfma_frac=flop_rate / peak,
-                    share_of_contraction_time=dom["total_ms"] / sum(v["total_ms"] for v in contraction.values()),
-                    measured="HIP events recorded by the library around each launch of this kernel, on its stream, "
-                             "in a call-by-call single-stream pass over the same steps right after the timed region")
+    if not contraction:
+        # a workload without convolutions (the two-layer MLP): no contraction kernel to report on
+        roofline = None
+    else:
+        dom_name, dom = max(contraction.items(), key=lambda kv: kv[1]["total_ms"])
+        # which roof binds this kernel: its arithmetic intensity against the ridge of the chip
+        secs = dom["total_ms"] * 1e-3
+        flop_rate, byte_rate = dom["flops"] / secs, dom["bytes"] / secs
+        peak = MFMA_PEAK[wl.dtype]
+        intensity = dom["flops"] / dom["bytes"]
+        hbm_bound = intensity < peak / HBM_PEAK
+        roofline = dict(bound="hbm" if hbm_bound else "mfma",
+                        achieved=byte_rate / 1e9 if hbm_bound else flop_rate / 1e12,
+                        peak=HBM_PEAK / 1e9 if hbm_bound else peak / 1e12,
+                        unit="GB/s" if hbm_bound else "TFLOP/s",
+                        frac=byte_rate / HBM_PEAK if hbm_bound else flop_rate / peak,
+                        traffic=measured_traffic(dom_name) if (args.workload == "resnet50" and args.mode == "auto" and args.n is None
+                                                               and args.hw is None and args.accum is None) else None,
+                        traffic_unit="HBM bytes per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see profiles/)",
+                        kernel=dom_name, launches=dom["launches"], avg_launch_us=dom["total_ms"] * 1e3 / dom["launches"],
+                        algorithmic_bytes_per_launch=dom["bytes"] / dom["launches"],
+                        algorithmic_flop_per_launch=dom["flops"] / dom["launches"],
+                        flop_per_byte=intensity, ridge_flop_per_byte=peak / HBM_PEAK,
+                        mfma_tflops=flop_rate / 1e12, mfma_frac=flop_rate / peak,
+                        share_of_contraction_time=dom["total_ms"] / sum(v["total_ms"] for v in contraction.values()),
+                        measured="HIP events recorded by the library around each launch of this kernel, on its stream, "
+                                 "in a call-by-call single-stream pass over the same steps right after the timed region")
     if args.table:
         for k, v in sorted(summary.items(), key=lambda kv: -kv[1]["total_ms"]):
             tf = v["flops"] / (v["total_ms"] * 1e-3) / 1e12 if v["total_ms"] else 0.0
