@@ -182,7 +182,8 @@ dp_status dp_clip_accumulate_recompute(const dp_layer_desc *desc /*[host]*/, con
  * z1 = R sin(2 pi u1), R = sqrt(-2 ln u0); (u2,u3) -> z2, z3.  The result does not depend on
  * the launch geometry.  sigma == 0 evaluates no random numbers.  out may alias acc.
  * clip_total = sqrt(sum_g C_g^2), the bound on the whole clipped gradient.
- * acc, out  [device] [p] fp32.  sigma >= 0, clip_total > 0 and finite, total_batch >= 1.       */
+ * acc, out  [device] [p] fp32.  sigma >= 0, clip_total > 0 (finite unless sigma == 0: an infinite
+ * bound draws no noise), total_batch >= 1.                                                    */
 dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,
                                 uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
                                 dp_stream stream);

@@ -339,7 +339,8 @@ dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float si
     DP_TRY(check_ptr(out, "out", true));
     if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0 parameters");
     if (std::isnan(sigma) || sigma < 0.0f || std::isinf(sigma)) return fail(DP_ERR_INVALID_ARG, "sigma must be finite and >= 0");
-    if (!(clip_total > 0.0f) || !std::isfinite(clip_total)) return fail(DP_ERR_INVALID_ARG, "clip_total must be finite and > 0");
+    if (!(clip_total > 0.0f) || (sigma > 0.0f && !std::isfinite(clip_total)))
+        return fail(DP_ERR_INVALID_ARG, "clip_total must be > 0, and finite unless sigma is 0");
     if (total_batch < 1) return fail(DP_ERR_INVALID_ARG, "total_batch = 0");
     if (p >= ((size_t)1 << 40)) return fail(DP_ERR_UNSUPPORTED, "p too large");
     g_err[0] = 0;
@@ -354,7 +355,8 @@ dp_status dp_add_example_noise(float *acc, size_t p, float sigma, float clip_tot
     DP_TRY(check_ptr(acc, "acc", true));
     if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0 parameters");
     if (std::isnan(sigma) || sigma < 0.0f || std::isinf(sigma)) return fail(DP_ERR_INVALID_ARG, "sigma must be finite and >= 0");
-    if (!(clip_total > 0.0f) || !std::isfinite(clip_total)) return fail(DP_ERR_INVALID_ARG, "clip_total must be finite and > 0");
+    if (!(clip_total > 0.0f) || (sigma > 0.0f && !std::isfinite(clip_total)))
+        return fail(DP_ERR_INVALID_ARG, "clip_total must be > 0, and finite unless sigma is 0");
     if (total_batch < 1) return fail(DP_ERR_INVALID_ARG, "total_batch = 0");
     if (n_examples < 1) return fail(DP_ERR_INVALID_ARG, "n_examples = %d (need >= 1)", n_examples);
     if (first_example + (uint64_t)n_examples > total_batch)
@@ -378,7 +380,8 @@ dp_status dp_add_noise_finalize_update(const float *acc, float *theta, float *ve
     DP_TRY(check_ptr(out, "out", false));
     if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0 parameters");
     if (std::isnan(sigma) || sigma < 0.0f || std::isinf(sigma)) return fail(DP_ERR_INVALID_ARG, "sigma must be finite and >= 0");
-    if (!(clip_total > 0.0f) || !std::isfinite(clip_total)) return fail(DP_ERR_INVALID_ARG, "clip_total must be finite and > 0");
+    if (!(clip_total > 0.0f) || (sigma > 0.0f && !std::isfinite(clip_total)))
+        return fail(DP_ERR_INVALID_ARG, "clip_total must be > 0, and finite unless sigma is 0");
     if (total_batch < 1) return fail(DP_ERR_INVALID_ARG, "total_batch = 0");
     if (!std::isfinite(lr)) return fail(DP_ERR_INVALID_ARG, "lr must be finite");
     if (!std::isfinite(momentum) || momentum < 0.0f) return fail(DP_ERR_INVALID_ARG, "momentum must be finite and >= 0");

@@ -172,3 +172,34 @@ def test_further_layer_sets_with_groupnorm(name, n, accum, hw):
     wl = get_workload(name, n=n, accum=accum, hw=hw)
     assert any(l.kind == "gn" for l in wl.layers)
     _check(wl, "auto")
+
+
+def test_both_clip_branches_zero_example_and_infinite_bound():
+    """The five workloads clip every example; here the bound is the median norm (half the examples keep their
+    gradient), one example is all zeros (factor 1, contributes nothing), and a second run has C = inf, sigma = 0
+    (the result is the plain mean gradient)."""
+    import math
+    from dataclasses import replace
+    base = get_workload("resnet50", n=6, accum=2, hw=64)
+    host_steps = [make_inputs(base, m) for m in range(base.accum)]
+    for li in range(len(base.layers)):                     # example 3 of micro-step 0: all-zero gradient
+        host_steps[0][li][1][3] = 0.0
+    probe = oracle.privatise(base, host_steps)
+    med = float(np.sqrt(np.median(np.concatenate([n2[:, 0] for n2 in probe["n2"]]))))
+    for wl in (replace(base, clip_c=med), replace(base, clip_c=math.inf, sigma=0.0)):
+        ref = oracle.privatise(wl, host_steps)
+        f_all = np.concatenate([f[:, 0] for f in ref["f"]])
+        if math.isfinite(wl.clip_c):
+            assert (f_all < 1).sum() >= 4 and (f_all == 1).sum() >= 4          # both branches are taken
+        steps = [[(dev(x, wl.dtype), dev(dy, wl.dtype)) for x, dy in inputs] for inputs in host_steps]
+        for mode in ("auto", "recompute"):
+            ps = dp.PrivatiseStep(wl, mode=mode, streams=2)
+            ps.begin_step()
+            ps.micro_step(steps[0])
+            torch.cuda.synchronize()
+            assert host(ps.group_sqnorm)[0, 3] == 0.0                           # the zero example
+            ps.micro_step(steps[1])
+            ps.finalize()
+            torch.cuda.synchronize()
+            for li, l in enumerate(wl.layers):
+                assert_close(host(ps.out_w(li)), ref["out_w"][li], BF16_TOL, f"{mode} C={wl.clip_c} out_w[{li}] {l.name}")

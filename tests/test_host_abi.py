@@ -201,3 +201,10 @@ def test_example_noise_rejects_bad_arguments(lib):
     assert call(cnt=0) == B.DP_ERR_INVALID_ARG
     assert call(first=6, cnt=4) == B.DP_ERR_INVALID_ARG          # examples beyond the step
     assert "outside" in dp.dp_last_error()
+
+
+def test_infinite_bound_is_legal_only_without_noise(lib):
+    """C = inf with sigma = 0 (plain mean gradient) is a legal finalize; with noise it has no meaning."""
+    f = lib.dp_add_noise_finalize
+    assert f(FAKE, FAKE, 16, 1.0, float("inf"), 8, 0, 0, 0, None) == B.DP_ERR_INVALID_ARG
+    assert "clip_total" in dp.dp_last_error()
