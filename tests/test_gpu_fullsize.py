@@ -38,7 +38,7 @@ def test_resnet50_full_size_micro_step_every_element():
     wl = get_workload("resnet50", accum=1)            # config 4 shapes, one micro-step of 32 examples
     print(f"\n[fullsize] {wl.name}: n={wl.n}, {wl.n_params} parameters, drawing inputs", flush=True)
     steps = make_device_inputs(wl, 1, torch.device("cuda:0"))
-    ps = dp.PrivatiseStep(wl, mode="auto", streams=4)
+    ps = dp.PrivatiseStep(wl, mode="auto", streams=8)
     ps.capture(steps)
     ps.replay()
     torch.cuda.synchronize()
@@ -62,7 +62,7 @@ def test_resnet50_full_size_micro_step_every_element():
 def test_resnet50_nano_full_size_two_micro_steps_every_element():
     wl = get_workload("resnet50_nano", accum=2)       # config 5 shapes: micro-batch 1, 54 clipping groups
     steps = make_device_inputs(wl, 2, torch.device("cuda:0"))
-    ps = dp.PrivatiseStep(wl, mode="auto", streams=4)
+    ps = dp.PrivatiseStep(wl, mode="auto", streams=8)
     ps.capture(steps)
     ps.replay()
     torch.cuda.synchronize()
