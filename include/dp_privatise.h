@@ -86,11 +86,15 @@ size_t dp_weight_count(const dp_layer_desc *desc /*[host]*/);
 size_t dp_bias_count(const dp_layer_desc *desc /*[host]*/);
 
 /* Bytes of device workspace the given call needs for this descriptor (pure host; 0 on a
- * bad descriptor).  DP_WS_PER_EXAMPLE_GRAD: one float per (example, output tile).
- * DP_WS_RECOMPUTE: up to a few copies of the layer's parameter tensor when the examples are
- * cut into ranges to fill the chip, plus n*2*cin floats for GroupNorm layers.  The workspace
- * carries partial sums so that reductions run in a fixed order: the same inputs give the
- * same bits on every call.                                                                   */
+ * bad descriptor).  What it holds, depending on the layer: partial squared norms (one float
+ * per example and output tile, or per slice-sum workgroup), the partial tiles of contractions
+ * whose K (or example range) is cut into slices, and rewritten copies of the operands where a
+ * kernel reads them in another layout (sampled positions of a strided 1x1 conv, parity-split
+ * rows of a strided 3x3 conv, K-contiguous pre-scaled operands of the clip-weighted form);
+ * DP_WS_RECOMPUTE of a GroupNorm layer: n*2*cin floats.  From a few KB to a few tens of MB.
+ * Partial sums go through the workspace so that reductions run in a fixed order: the same
+ * inputs give the same bits on every call.  The contents are scratch: nothing has to be
+ * preserved between calls (except as dp_per_example_grad_partials documents).               */
 size_t dp_workspace_bytes(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_use*/);
 
 /* Name of the kernel variant that dp_per_example_grad (use = DP_WS_PER_EXAMPLE_GRAD) or
