@@ -1,0 +1,56 @@
+"""CPU-only checks of the host-side planning: which kernel variant every layer of the benchmark's
+ResNet-50 set is sent to, and that the workspace queries are consistent with each other."""
+import pytest
+
+import paper_2109_12191_amd as dp
+from workloads import get_workload
+
+
+@pytest.fixture(scope="module")
+def wl():
+    dp.load_library()
+    return get_workload("resnet50")
+
+
+def test_resnet50_layers_go_to_the_expected_kernels(wl):
+    per_example, weighted = {}, {}
+    for l in wl.layers:
+        d = dp.make_desc(l, wl.n, wl.dtype)
+        per_example[l.name] = dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD)
+        weighted[l.name] = dp.dp_kernel_variant(d, dp.DP_WS_RECOMPUTE)
+    # every 3x3 stride-1 conv runs in the raw-row kernel, named for its row width
+    for name, width in (("s1b1.c2", 56), ("s2b2.c2", 28), ("s3b2.c2", 14), ("s4b2.c2", 7)):
+        assert per_example[name] == f"conv3x3_rows<bf16,w{width},per_example>"
+        assert weighted[name] == f"conv3x3_rows<bf16,w{width},weighted>"
+    # the strided 3x3 convs onto 14- and 7-wide outputs too; the one onto 28 stays in the general kernel
+    assert per_example["s3b1.c2"] == "conv3x3_rows<bf16,w14,s2,per_example>"
+    assert per_example["s4b1.c2"] == "conv3x3_rows<bf16,w7,s2,per_example>"
+    assert per_example["s2b1.c2"].startswith("conv_contract<bf16,")
+    assert weighted["s4b1.c2"].startswith("conv_contract<bf16,")
+    # 1x1 convs: general kernel; the classifier: the dense kernels
+    assert per_example["s3b2.c3"] == "conv_contract<bf16,128x128,per_example>"
+    assert per_example["s1b1.c1"] == "conv_contract<bf16,64x64,per_example>"
+    assert per_example["fc"] == "dense<bf16>"
+    assert sum(v.startswith("conv3x3_rows") for v in per_example.values()) == 15
+
+
+def test_workspace_queries_are_consistent(wl):
+    total = 0
+    for l in wl.layers:
+        d = dp.make_desc(l, wl.n, wl.dtype)
+        for use in (dp.DP_WS_PER_EXAMPLE_GRAD, dp.DP_WS_RECOMPUTE):
+            b = dp.dp_workspace_bytes(d, use)
+            assert 0 <= b < 256 << 20, (l.name, use, b)
+            assert b % 4 == 0
+        for mat in (False, True):
+            c = dp.dp_norm_partial_count(d, mat)
+            assert 1 <= c <= 4096
+            # the partial norms [n, count] sit at the start of the per-example workspace
+            assert dp.dp_workspace_bytes(d, dp.DP_WS_PER_EXAMPLE_GRAD) >= 4 * wl.n * c, l.name
+        total += dp.dp_workspace_bytes(d, dp.DP_WS_PER_EXAMPLE_GRAD)
+    assert total < 2 << 30           # all 54 per-layer workspaces together stay small next to 288 GB
+
+
+def test_descriptor_counts_match_the_layer_set(wl):
+    assert sum(dp.dp_weight_count(dp.make_desc(l, wl.n, wl.dtype)) + dp.dp_bias_count(dp.make_desc(l, wl.n, wl.dtype))
+               for l in wl.layers) == 25_503_912
