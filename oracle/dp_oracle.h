@@ -19,7 +19,9 @@
  *
  * Pins (see tests/): Philox known-answer vectors of the published algorithm, finite
  * differences, library GEMM / autograd special cases, closed-form norms, the clip
- * invariant, and noise moments.  No function here is "parity unpinned".
+ * invariant, noise moments; for the per-example noise form its moments, the independence of
+ * the examples' draws and the documented counter / key words; for the SGD step the closed-form
+ * momentum series and a library optimiser.  No function here is "parity unpinned".
  */
 #ifndef DP_ORACLE_H
 #define DP_ORACLE_H
