@@ -844,10 +844,12 @@ static bool subsampled(const Geo &g, int mode, Geo &g2)
     if (g.kh != 1 || g.kw != 1 || g.stride < 2 || g.pad != 0) return false;
     const size_t s = (size_t)g.oh * g.ow;
     if ((size_t)g.n * g.cin * s * 2 > ((size_t)96 << 20) || g.cin * s < 512) return false;
-    if (s % 2) return false;                   // odd rows would go through the gather loader anyway: no gain
     g2 = g;
     g2.h = g.oh; g2.w = g.ow; g2.stride = 1;
     g2.x_elems = (size_t)g.cin * s;
+    // odd rows would go through the gather loader anyway (no gain) unless the norm-only call can then take
+    // the Gram route
+    if (s % 2 && !gram_norm_applicable(g2, mode)) return false;
     return true;
 }
 
@@ -871,16 +873,28 @@ static size_t norm_partials_per_example(const FullPlan &f)
 }
 static size_t norm_partials(const Geo &g, const FullPlan &f) { return (size_t)g.n * norm_partials_per_example(f); }
 
+// Exact workspace need of the kernels that (g, mode) is dispatched to.
+static size_t conv_ws_bytes_mode(const Geo &g, int mode);
+
+// One per-example workspace serves norm-only and materialising calls (they may take different routes).
 size_t conv_ws_bytes(const Geo &g, int mode)
 {
+    if (mode == MODE_WEIGHTED) return conv_ws_bytes_mode(g, mode);
+    const size_t a = conv_ws_bytes_mode(g, MODE_NORM), b = conv_ws_bytes_mode(g, MODE_MATERIALISE);
+    return a > b ? a : b;
+}
+
+static size_t conv_ws_bytes_mode(const Geo &g, int mode)
+{
     if (conv3x3_applicable(g, mode)) return conv3x3_ws_bytes(g, mode);
+    if (gram_norm_applicable(g, mode)) return gram_ws_bytes(g);
     PackPlan pp;
     Geo g2;
     if (packed_weighted(g, mode, pp, g2)) {
         const FullPlan f = full_plan(g2, mode);
         return align16(pp.x_bytes) + align16(pp.dy_bytes) + (f.ksplit > 1 ? f.part_floats * sizeof(float) : 0);
     }
-    if (subsampled(g, mode, g2)) return conv_ws_bytes(g2, mode) + align16(g2.x_elems * g.n * 2);
+    if (subsampled(g, mode, g2)) return conv_ws_bytes_mode(g2, mode) + align16(g2.x_elems * g.n * 2);
     const FullPlan f = full_plan(g, mode);
     size_t b = 0;
     if (mode != MODE_WEIGHTED) b += align16(norm_partials(g, f) * sizeof(float));
@@ -891,14 +905,16 @@ size_t conv_ws_bytes(const Geo &g, int mode)
 size_t conv_norm_partial_count(const Geo &g, int mode)
 {
     if (conv3x3_applicable(g, mode)) return conv3x3_norm_partial_count(g);
+    if (gram_norm_applicable(g, mode)) return gram_norm_partial_count();
     Geo g2;
-    if (subsampled(g, mode, g2)) return norm_partials_per_example(full_plan(g2, mode));
+    if (subsampled(g, mode, g2)) return conv_norm_partial_count(g2, mode);
     return norm_partials_per_example(full_plan(g, mode));
 }
 
 const char *conv_variant_name(const Geo &g, int mode)
 {
     if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);
+    if (gram_norm_applicable(g, mode)) return "conv_gram_norm<bf16>";
     static char names[2][4][2][2][64];
     static bool init = false;
     if (!init) {
@@ -956,6 +972,7 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
 {
     if (conv3x3_applicable(g, mode))
         return launch_conv3x3(g, mode, x, dy, out_w, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
+    if (gram_norm_applicable(g, mode)) return launch_gram_norm(g, x, dy, sqnorm, ws, s);
     PackPlan pp;
     Geo g2;
     if (packed_weighted(g, mode, pp, g2)) {
@@ -972,9 +989,10 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
     }
     if (subsampled(g, mode, g2)) {
         // the sub-problem's own workspace comes first (its partial norms stay at the start), the copy of X after it
-        void *xs = static_cast<char *>(ws) + conv_ws_bytes(g2, mode);
+        void *xs = static_cast<char *>(ws) + conv_ws_bytes_mode(g2, mode);
         const dp_status st = launch_subsample(g, x, xs, s);
         if (st != DP_OK) return st;
+        if (gram_norm_applicable(g2, mode)) return launch_gram_norm(g2, xs, dy, sqnorm, ws, s);
         return launch_conv_impl(g2, mode, xs, dy, out_w, out_b, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
     }
     return launch_conv_impl(g, mode, x, dy, out_w, out_b, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);

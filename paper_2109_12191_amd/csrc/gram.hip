@@ -1,0 +1,186 @@
+// Squared norms of per-example 1x1-convolution gradients on small feature maps, without forming
+// the gradients (H2 for the layers whose gradients are recomputed later, never stored).
+//
+// For a 1x1 stride-1 convolution dW_i = A_i B_i^T with A_i = dY_i [Cout x S], B_i = X_i [Cin x S], so
+//     ||dW_i||_F^2 = sum_{k,k'} (A_i^T A_i)[k,k'] * (B_i^T B_i)[k,k']
+// -- the same number as the sum of squares of dW_i's entries, from two S x S Gram matrices instead
+// of a Cout x Cin x S contraction.  With S <= 64 (7x7 maps: S = 49) that is ~8x fewer flops and no
+// large tile to square.  Both Grams are contractions over CHANNELS, so each operand is transposed
+// on its way into LDS (T[k][c], channels contiguous) and then feeds v_mfma_f32_32x32x16_bf16 like
+// any K-contiguous operand.
+//
+// Kernel 1: a workgroup takes one example and a slice of the channels of both operands and leaves
+// its two partial 64x64 Grams (accumulator register layout) in the workspace.  Kernel 2: one
+// workgroup per example adds the slices in order, multiplies the Grams element by element and
+// reduces.  Fixed order everywhere: same bits on every run.
+#include "internal.h"
+#include "pieces.h"
+
+namespace dp {
+
+namespace {
+
+constexpr int GR_THREADS = 256;
+constexpr int GR_CB = 256;                         // channels staged at a time
+constexpr int GR_PT = GR_CB * 2 + 16;              // bytes per LDS row k (odd multiple of 16)
+
+struct GramArgs {
+    const uint16_t *a, *b;                         // dY [n][ca][S], X [n][cb][S]
+    float *part;                                   // [n][splits][2][4096]
+    float *out;                                    // [n][GR_PARTS] partial squared norms
+    int n, ca, cb, S, splits;
+    int total_a, total_b;                          // elements in each tensor
+};
+
+// Gram of channels [c0, c1) of one example's matrix src[c][S] (element offset `base` from the
+// tensor start): acc += T^T T restricted to this wave's 32x32 block (kb, kb2).
+__device__ __forceinline__ void gram_part(f32x16 &acc, const uint16_t *tensor, int base, int total, int c0, int c1, int S,
+                                          char *lds, int kb, int kb2, int lane)
+{
+    const uint32_t *words = reinterpret_cast<const uint32_t *>(tensor);
+    for (int cblk = c0; cblk < c1; cblk += GR_CB) {
+        __syncthreads();                           // the previous block has been consumed
+        // ---- stage T[k][c]: thread -> (channel c = id % 256, piece pc = id / 256 of 8 positions)
+        constexpr int NP = 8;                      // pieces per channel (64 positions)
+        Raw<5> raw[NP];
+#pragma unroll
+        for (int pc = 0; pc < NP; ++pc) {
+            const int c = cblk + (int)threadIdx.x;
+            const int e0 = base + c * S + pc * 8;  // element index in the tensor
+            const bool need = c < c1 && pc * 8 < S;
+            const bool safe = need && (e0 & ~1) + 10 <= total;
+            raw[pc] = piece_load_words(words + ((safe ? e0 : base) >> 1));
+        }
+#pragma unroll
+        for (int pc = 0; pc < NP; ++pc) {
+            const int c = cblk + (int)threadIdx.x;
+            const int e0 = base + c * S + pc * 8;
+            const bool need = c < c1 && pc * 8 < S;
+            const bool safe = need && (e0 & ~1) + 10 <= total;
+            const int hi = need ? min(8, S - pc * 8) : 0;
+            uint32_t v[4];
+            piece_finish<true, 1>(v, raw[pc], (uint32_t)(e0 & 1), 0, safe ? hi : 0);
+            if (need && !safe) {                   // the last rows of the tensor: element by element
+                v[0] = v[1] = v[2] = v[3] = 0u;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (e < hi) v[e >> 1] |= (uint32_t)tensor[e0 + e] << ((e & 1) * 16);
+            }
+            uint16_t *col = reinterpret_cast<uint16_t *>(lds + (pc * 8) * GR_PT) + threadIdx.x;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(col) + e * GR_PT) =
+                    (uint16_t)(v[e >> 1] >> ((e & 1) * 16));
+        }
+        __syncthreads();
+        // ---- MFMAs over the channels of this block
+        const int nks = (min(GR_CB, c1 - cblk) + 15) / 16;
+        const char *pa = lds + (kb * 32 + (lane & 31)) * GR_PT + (lane >> 5) * 16;
+        const char *pb = lds + (kb2 * 32 + (lane & 31)) * GR_PT + (lane >> 5) * 16;
+        for (int ks = 0; ks < nks; ++ks) {
+            const bf16x8 va = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + ks * 32));
+            const bf16x8 vb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pb + ks * 32));
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, vb, acc, 0, 0, 0);
+        }
+    }
+}
+
+__global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const GramArgs a)
+{
+    __shared__ __attribute__((aligned(16))) char lds[64 * GR_PT];
+    const int i = blockIdx.x / a.splits, s = blockIdx.x - i * a.splits;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kb = wave >> 1, kb2 = wave & 1;
+    const int ca_per = (a.ca + a.splits - 1) / a.splits, cb_per = (a.cb + a.splits - 1) / a.splits;
+    f32x16 ga, gb;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { ga[r] = 0.0f; gb[r] = 0.0f; }
+    gram_part(ga, a.a, i * a.ca * a.S, a.total_a, min(a.ca, s * ca_per), min(a.ca, (s + 1) * ca_per), a.S, lds, kb, kb2, lane);
+    gram_part(gb, a.b, i * a.cb * a.S, a.total_b, min(a.cb, s * cb_per), min(a.cb, (s + 1) * cb_per), a.S, lds, kb, kb2, lane);
+    float *mine = a.part + (size_t)blockIdx.x * 2 * 4096;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        mine[r * GR_THREADS + threadIdx.x] = ga[r];
+        mine[4096 + r * GR_THREADS + threadIdx.x] = gb[r];
+    }
+}
+
+// One workgroup per (example, accumulator register r): 256 Gram entries each; the slices are added in
+// order, the two Grams multiplied entry by entry and the products reduced to one partial norm.
+constexpr int GR_PARTS = 16;
+
+__global__ void __launch_bounds__(GR_THREADS) gram_combine_kernel(const GramArgs a)
+{
+    __shared__ float red[4];
+    const int i = blockIdx.x / GR_PARTS, r = blockIdx.x - i * GR_PARTS;
+    const float *base = a.part + (size_t)i * a.splits * 2 * 4096 + r * GR_THREADS + threadIdx.x;
+    float va[16], vb[16];                          // at most 16 slices, all loads in flight together
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+        const bool live = s < a.splits;
+        va[s] = live ? base[(size_t)s * 2 * 4096] : 0.0f;
+        vb[s] = live ? base[(size_t)s * 2 * 4096 + 4096] : 0.0f;
+    }
+    float ga = 0.0f, gb = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) { ga += va[s]; gb += vb[s]; }
+    const float tot = block_sum<4>(ga * gb, red);
+    if (threadIdx.x == 0) a.out[blockIdx.x] = tot;
+}
+
+int gram_splits(const Geo &g)
+{
+    // about 256 workgroups, each with at least 64 channels of the smaller operand
+    int s = 256 / g.n;
+    const int cmin = g.cin < g.cout ? g.cin : g.cout;
+    if (s > cmin / 64) s = cmin / 64;
+    if (s > 16) s = 16;
+    return s < 1 ? 1 : s;
+}
+
+size_t gram_align16(size_t b) { return (b + 15) & ~(size_t)15; }
+
+}  // namespace
+
+bool gram_norm_applicable(const Geo &g, int mode)
+{
+    if (mode != MODE_NORM || !g.bf16 || g.has_bias) return false;
+    if (g.kh != 1 || g.kw != 1 || g.stride != 1 || g.pad != 0) return false;
+    const long long S = (long long)g.oh * g.ow;
+    if (S > 64 || S < 8) return false;
+    if (g.cin < 128 || g.cout < 128) return false;
+    // the Gram route wins when S is small against the channel counts (S^2 (Cin+Cout) << S Cin Cout)
+    if (S * (g.cin + g.cout) * 4 > (long long)g.cin * g.cout) return false;
+    return (long long)g.n * g.cin * S < (1ll << 31) && (long long)g.n * g.cout * S < (1ll << 31);
+}
+
+size_t gram_ws_bytes(const Geo &g)
+{
+    return gram_align16((size_t)g.n * GR_PARTS * sizeof(float)) + (size_t)g.n * gram_splits(g) * 2 * 4096 * sizeof(float);
+}
+
+dp_status launch_gram_norm(const Geo &g, const void *x, const void *dy, float *sqnorm, void *ws, hipStream_t s)
+{
+    GramArgs a;
+    a.a = static_cast<const uint16_t *>(dy);
+    a.b = static_cast<const uint16_t *>(x);
+    a.n = g.n; a.ca = g.cout; a.cb = g.cin; a.S = g.oh * g.ow; a.splits = gram_splits(g);
+    a.total_a = g.n * g.cout * a.S;
+    a.total_b = g.n * g.cin * a.S;
+    // the partial norms [n][16] sit at the start of the workspace, the partial Grams after them
+    a.out = static_cast<float *>(ws);
+    a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + gram_align16((size_t)g.n * GR_PARTS * sizeof(float)));
+    profile_begin(s);
+    hipLaunchKernelGGL(gram_partial_kernel, dim3((unsigned)(g.n * a.splits)), dim3(GR_THREADS), 0, s, a);
+    profile_end(s);
+    dp_status st = check_launch("gram_partial");
+    if (st != DP_OK) return st;
+    hipLaunchKernelGGL(gram_combine_kernel, dim3((unsigned)(g.n * GR_PARTS)), dim3(GR_THREADS), 0, s, a);
+    st = check_launch("gram_combine");
+    if (st != DP_OK || !sqnorm) return st;
+    return launch_sum_partials(a.out, g.n, GR_PARTS, sqnorm, s);
+}
+
+size_t gram_norm_partial_count(void) { return GR_PARTS; }
+
+}  // namespace dp

@@ -72,6 +72,12 @@ size_t gn_norm_partial_count(const Geo &g);
 // compact copy of the rows / columns a strided 1x1 convolution reads: out[n*cin][OH*OW] (pack.hip)
 dp_status launch_subsample(const Geo &g, const void *x, void *out, hipStream_t s);
 
+// Norm-only calls of 1x1 convolutions on small feature maps through two Gram matrices (gram.hip).
+bool gram_norm_applicable(const Geo &g, int mode);
+size_t gram_ws_bytes(const Geo &g);
+size_t gram_norm_partial_count(void);
+dp_status launch_gram_norm(const Geo &g, const void *x, const void *dy, float *sqnorm, void *ws, hipStream_t s);
+
 size_t dense_ws_bytes(const Geo &g, int mode);
 dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                        size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,

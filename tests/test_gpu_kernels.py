@@ -437,3 +437,34 @@ def test_groupnorm_affine_with_a_large_mean_and_small_spread():
     gw, gb, sq = _run_per_example(layer, x, dy, "f32")
     assert_close(gw, ref_w, 2e-3, "dgamma")          # x - mean itself is only known to ~1e-4 relative in fp32 here
     assert_close(gb, ref_b, F32_TOL, "dbeta")
+
+
+GRAM_CASES = [
+    ("512->2048 7x7", conv(512, 2048, 1, 1, 7), 5),
+    ("2048->512 7x7", conv(2048, 512, 1, 1, 7), 3),
+    ("384->640 7x7 ragged channel blocks", conv(384, 640, 1, 1, 7), 4),
+    ("512->1024 8x8 (S = 64)", conv(512, 1024, 1, 1, 8), 2),
+    ("512->512 4x4", conv(512, 512, 1, 1, 4), 33),
+]
+
+
+@pytest.mark.parametrize("name,layer,n", GRAM_CASES, ids=[c[0] for c in GRAM_CASES])
+def test_gram_route_norms(name, layer, n):
+    """Norm-only calls of 1x1 convs on small maps go through two Gram matrices: same norms as the oracle's
+    sum of squares and as the materialising call's."""
+    d = dp.make_desc(layer, n, "bf16")
+    assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD) == "conv_gram_norm<bf16>"
+    count = dp.dp_norm_partial_count(d, False)
+    x, dy = _inputs(layer, n, 401, "bf16", x_abs=True)
+    _, _, sq_mat = _run_per_example(layer, x, dy, "bf16")
+    _, _, sq = _run_per_example(layer, x, dy, "bf16", materialise=False)
+    assert np.allclose(sq, sq_mat, rtol=2e-5, atol=0), (sq, sq_mat)
+    for i in (0, n - 1):
+        w, _ = oracle.example_grad(layer, x[i], dy[i])
+        assert math.isclose(sq[i], oracle.sqnorm(w), rel_tol=1e-4), (i, sq[i], oracle.sqnorm(w))
+    # the partial-norm entry point leaves the same numbers at the start of the workspace
+    ws = torch.empty(dp.dp_workspace_bytes(d), dtype=torch.uint8, device="cuda:0")
+    dp.dp_per_example_grad_partials(d, dev(x, "bf16"), dev(dy, "bf16"), None, None, ws)
+    torch.cuda.synchronize()
+    parts = host(ws[: 4 * n * count].view(torch.float32)).reshape(n, count)
+    assert np.allclose(parts.sum(axis=1), sq, rtol=1e-5)

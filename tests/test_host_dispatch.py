@@ -29,6 +29,9 @@ def test_resnet50_layers_go_to_the_expected_kernels(wl):
     assert weighted["s4b1.c2"].startswith("conv_contract<bf16,")
     # 1x1 convs: general kernel; the classifier: the dense kernels
     assert per_example["s3b2.c3"] == "conv_contract<bf16,128x128,per_example>"
+    # norm-only calls of the 1x1 convs on 7x7 maps take the Gram route
+    for name in ("s4b1.c3", "s4b2.c1", "s4b2.c3", "s4b3.c1", "s4b3.c3"):
+        assert per_example[name] == "conv_gram_norm<bf16>", name
     assert per_example["s1b1.c1"] == "conv_contract<bf16,64x64,per_example>"
     assert per_example["fc"] == "dense<bf16>"
     assert sum(v.startswith("conv3x3_rows") for v in per_example.values()) == 15
