@@ -170,6 +170,18 @@ dp_status dp_clip_factors(const float *sqnorm, float clip_c, int n, float *f, dp
 dp_status dp_clip_accumulate(const float *g, size_t g_stride, const float *sqnorm, float clip_c, int n,
                              size_t p, float *acc, dp_stream stream);
 
+/* H4, materialised form, for several clipping groups in one launch (Section 3.5: one bound per group
+ * of tensors): the columns [0, p) of g are cut into n_seg segments; segment k covers columns
+ * seg_begin[k] .. seg_begin[k+1] (the last one ends at p), belongs to clipping group seg_group[k] and is
+ * clipped to seg_clip[k]:
+ *     acc[e] += sum_{i<n} min(1, seg_clip[k] / sqrt(group_sqnorm[seg_group[k], i])) * g[i, e],  e in segment k.
+ * Same sums, same order as one dp_clip_accumulate call per segment.
+ * g, acc as above; group_sqnorm [device] [n_groups, n]; seg_begin, seg_group, seg_clip [host] arrays of
+ * n_seg entries, boundaries increasing multiples of 4 starting at 0; p a multiple of 4.               */
+dp_status dp_clip_accumulate_segments(const float *g, size_t g_stride, const float *group_sqnorm, int n_groups,
+                                      const size_t *seg_begin, const int32_t *seg_group, const float *seg_clip, int n_seg,
+                                      int n, size_t p, float *acc, dp_stream stream);
+
 /* H4, recomputing form: the same sum without per-example gradients in memory,
  *   acc_w += sum_i f_i * dW_i,  acc_b += sum_i f_i * db_i,
  * evaluated as one contraction over (example, position) with dY_i scaled by f_i as it is

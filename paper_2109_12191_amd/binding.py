@@ -60,6 +60,7 @@ def load_library():
         "dp_norms_from_partials": (it, [vp, vp, vp, it, it, it, vp, vp]),
         "dp_clip_factors": (it, [vp, fl, it, vp, vp]),
         "dp_clip_accumulate": (it, [vp, sz, vp, fl, it, sz, vp, vp]),
+        "dp_clip_accumulate_segments": (it, [vp, sz, vp, it, vp, vp, vp, it, it, sz, vp, vp]),
         "dp_clip_accumulate_recompute": (it, [dpp, vp, vp, vp, fl, vp, vp, vp, sz, vp]),
         "dp_add_noise_finalize": (it, [vp, vp, sz, fl, fl, u64, u64, u64, u32, vp]),
         "dp_add_example_noise": (it, [vp, sz, fl, fl, u64, u64, u64, u32, u64, it, vp]),
@@ -79,7 +80,7 @@ def load_library():
 
 EXPORTED = ("dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
-            "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
+            "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_segments", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
             "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
 
 
@@ -186,6 +187,25 @@ def dp_clip_factors(sqnorm, clip_c: float, n: int, f, stream=None):
 def dp_clip_accumulate(g, sqnorm, clip_c: float, n: int, p: int, acc, g_stride: int = 0, stream=None):
     _check(load_library().dp_clip_accumulate(_ptr(g), g_stride, _ptr(sqnorm), clip_c, n, p, _ptr(acc),
                                              _stream(stream)))
+
+
+class SegmentTable:
+    """Host arrays for dp_clip_accumulate_segments: column where each segment starts, its clipping group and bound."""
+
+    def __init__(self, begins, groups, clips):
+        k = len(begins)
+        self.n_seg = k
+        self.begin = (C.c_size_t * k)(*[int(b) for b in begins])
+        self.group = (C.c_int32 * k)(*[int(g) for g in groups])
+        self.clip = (C.c_float * k)(*[float(c) for c in clips])
+
+
+def dp_clip_accumulate_segments(g, group_sqnorm, n_groups: int, table: "SegmentTable", n: int, p: int, acc,
+                                g_stride: int = 0, stream=None):
+    _check(load_library().dp_clip_accumulate_segments(_ptr(g), g_stride, _ptr(group_sqnorm), n_groups,
+                                                      C.cast(table.begin, C.c_void_p), C.cast(table.group, C.c_void_p),
+                                                      C.cast(table.clip, C.c_void_p), table.n_seg, n, p, _ptr(acc),
+                                                      _stream(stream)))
 
 
 def dp_clip_accumulate_recompute(desc, x, dy, sqnorm, clip_c: float, acc_w, acc_b, ws,

@@ -310,6 +310,31 @@ dp_status dp_clip_accumulate(const float *g, size_t g_stride, const float *sqnor
     return launch_clip_accumulate(g, g_stride, sqnorm, clip_c, n, p, acc, static_cast<hipStream_t>(stream));
 }
 
+dp_status dp_clip_accumulate_segments(const float *g, size_t g_stride, const float *group_sqnorm, int n_groups,
+                                      const size_t *seg_begin, const int32_t *seg_group, const float *seg_clip, int n_seg,
+                                      int n, size_t p, float *acc, dp_stream stream)
+{
+    DP_TRY(check_ptr(g, "g", true));
+    DP_TRY(check_ptr(group_sqnorm, "group_sqnorm", true, 4));
+    DP_TRY(check_ptr(acc, "acc", true));
+    if (!seg_begin || !seg_group || !seg_clip) return fail(DP_ERR_INVALID_ARG, "segment tables must be non-NULL host arrays");
+    if (n < 1 || n_groups < 1 || n_seg < 1) return fail(DP_ERR_INVALID_ARG, "n, n_groups and n_seg must be >= 1");
+    if (p < 4 || p % 4) return fail(DP_ERR_INVALID_ARG, "p must be a positive multiple of 4");
+    if (g_stride == 0) g_stride = p;
+    if (g_stride < p || g_stride % 4) return fail(DP_ERR_INVALID_ARG, "g_stride must be a multiple of 4 and at least p");
+    if (p >= ((size_t)1 << 40)) return fail(DP_ERR_UNSUPPORTED, "p too large");
+    if (seg_begin[0] != 0) return fail(DP_ERR_INVALID_ARG, "the first segment must start at column 0");
+    for (int k = 0; k < n_seg; ++k) {
+        const size_t end = k + 1 < n_seg ? seg_begin[k + 1] : p;
+        if (seg_begin[k] % 4 || seg_begin[k] >= end) return fail(DP_ERR_INVALID_ARG, "segment %d: boundaries must be increasing multiples of 4 below p", k);
+        if (seg_group[k] < 0 || seg_group[k] >= n_groups) return fail(DP_ERR_INVALID_ARG, "segment %d: group %d outside [0, %d)", k, seg_group[k], n_groups);
+        DP_TRY(check_clip(seg_clip[k]));
+    }
+    g_err[0] = 0;
+    return launch_clip_accumulate_segments(g, g_stride, group_sqnorm, seg_begin, seg_group, seg_clip, n_seg, n, p, acc,
+                                           static_cast<hipStream_t>(stream));
+}
+
 dp_status dp_clip_accumulate_recompute(const dp_layer_desc *desc, const void *x, const void *dy, const float *sqnorm,
                                        float clip_c, float *acc_w, float *acc_b, void *ws, size_t ws_bytes,
                                        dp_stream stream)

@@ -97,6 +97,9 @@ dp_status launch_norms_from_partials(const float *const *partials, const int32_t
 dp_status launch_clip_factors(const float *sqnorm, float clip_c, int n, float *f, hipStream_t s);
 dp_status launch_clip_accumulate(const float *g, size_t stride, const float *sqnorm, float clip_c, int n,
                                  size_t p, float *acc, hipStream_t s);
+dp_status launch_clip_accumulate_segments(const float *g, size_t stride, const float *group_sqnorm, const size_t *seg_begin,
+                                          const int32_t *seg_group, const float *seg_clip, int n_seg, int n, size_t p,
+                                          float *acc, hipStream_t s);
 dp_status launch_add_partial_sums(const float *parts, int n_parts, size_t slice, size_t pw, float *acc_w,
                                   float *acc_b, hipStream_t s);
 dp_status launch_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,

@@ -177,6 +177,69 @@ __global__ void __launch_bounds__(256) clip_accumulate_kernel(const float *__res
     }
 }
 
+// The same sum for several clipping groups in one launch: the columns [0, p) of the gradient matrix are cut
+// into segments (one per tensor or per group), each with its own bound and its own row of squared norms.
+// A thread finds the segment of its four columns by bisection of the (at most SEG_MAX + 1) boundaries it
+// gets as kernel arguments; boundaries are multiples of 4, so a thread never straddles two segments.
+constexpr int SEG_MAX = 64;
+struct SegArgs {
+    unsigned long long begin[SEG_MAX + 1];         // column where each segment starts; begin[n_seg] = p
+    float clip[SEG_MAX];
+    int group[SEG_MAX];
+    int n_seg;
+};
+
+__global__ void __launch_bounds__(256) clip_accumulate_segments_kernel(const float *__restrict__ g, size_t stride,
+                                                                       const float *__restrict__ group_sqnorm,
+                                                                       const SegArgs sa, int n, size_t p,
+                                                                       float *__restrict__ acc)
+{
+    const size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= p) return;
+    int lo = 0, hi = sa.n_seg - 1;                 // last segment with begin <= e
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (sa.begin[mid] <= e) lo = mid; else hi = mid - 1;
+    }
+    const float *sq = group_sqnorm + (size_t)sa.group[lo] * n;
+    const float c = sa.clip[lo];
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    const float *row = g + e;
+#pragma unroll 8
+    for (int i = 0; i < n; ++i) {                  // example order: same bits on every run
+        const float f = clip_factor(sq[i], c);
+        const float4 v = *reinterpret_cast<const float4 *>(row + (size_t)i * stride);
+        s0 += f * v.x; s1 += f * v.y; s2 += f * v.z; s3 += f * v.w;
+    }
+    float4 a = *reinterpret_cast<float4 *>(acc + e);
+    a.x += s0; a.y += s1; a.z += s2; a.w += s3;
+    *reinterpret_cast<float4 *>(acc + e) = a;
+}
+
+dp_status launch_clip_accumulate_segments(const float *g, size_t stride, const float *group_sqnorm, const size_t *seg_begin,
+                                          const int32_t *seg_group, const float *seg_clip, int n_seg, int n, size_t p,
+                                          float *acc, hipStream_t s)
+{
+    for (int s0 = 0; s0 < n_seg; s0 += SEG_MAX) {
+        SegArgs sa;
+        sa.n_seg = n_seg - s0 < SEG_MAX ? n_seg - s0 : SEG_MAX;
+        const size_t first = seg_begin[s0], last = (s0 + sa.n_seg == n_seg) ? p : seg_begin[s0 + sa.n_seg];
+        for (int k = 0; k < SEG_MAX; ++k) {
+            const bool live = k < sa.n_seg;
+            sa.begin[k] = live ? seg_begin[s0 + k] - first : last - first;
+            sa.clip[k] = live ? seg_clip[s0 + k] : 1.0f;
+            sa.group[k] = live ? seg_group[s0 + k] : 0;
+        }
+        sa.begin[SEG_MAX] = last - first;
+        const size_t span = last - first;
+        hipLaunchKernelGGL(clip_accumulate_segments_kernel, dim3((unsigned)((span / 4 + 255) / 256)), dim3(256), 0, s,
+                           g + first, stride, group_sqnorm, sa, n, span, acc + first);
+        const dp_status st = check_launch("clip_accumulate_segments");
+        if (st != DP_OK) return st;
+    }
+    return DP_OK;
+}
+
 dp_status launch_clip_accumulate(const float *g, size_t stride, const float *sqnorm, float clip_c, int n, size_t p,
                                  float *acc, hipStream_t s)
 {

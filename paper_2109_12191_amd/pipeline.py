@@ -66,6 +66,9 @@ class PrivatiseStep:
             if self.form[i] == "materialise":
                 self.p_mat = pos
         self.p_total = max(pos, 4)
+        mat = [i for i in order if self.form[i] == "materialise"]
+        self._segments = B.SegmentTable([self.off_w[i] for i in mat], [self.group_of_layer[i] for i in mat],
+                                        [self.group_clip[self.group_of_layer[i]] for i in mat]) if mat else None
         dev = self.device
         f32 = torch.float32
         self.acc = torch.zeros(self.p_total, dtype=f32, device=dev)
@@ -229,22 +232,13 @@ class PrivatiseStep:
                 B.dp_clip_accumulate(g_buf, gsq[0], self.group_clip[0], self.n, self.p_mat,
                                      self.acc, g_stride=gs, stream=st0)
             else:
-                for li in range(L):
-                    if self.form[li] != "materialise":
-                        continue
-                    g = self.group_of_layer[li]
-                    span = _pad4(self.pw[li]) + _pad4(self.pb[li])
-                    # one call per layer, each always on the same stream (any stream will do: the calls
-                    # touch disjoint parts of the accumulator)
-                    B.dp_clip_accumulate(g_buf[:, self.off_w[li]:].data_ptr(), gsq[g],
-                                         self.group_clip[g], self.n, span,
-                                         self.acc[self.off_w[li]:].data_ptr(), g_stride=gs,
-                                         stream=sb[li % len(sb)] if sb else None)
+                # several clipping groups: one launch over all materialised tensors, a segment per layer
+                B.dp_clip_accumulate_segments(g_buf, gsq, self.n_groups, self._segments, self.n, self.p_mat,
+                                              self.acc, g_stride=gs, stream=st0)
         if self.noise == "per_example":
             for li in range(L):
                 if self.form[li] == "materialise":
-                    one_pass = self.n_groups == 1
-                    self._example_noise(li, (sb[0] if one_pass else sb[li % len(sb)]) if sb else None)
+                    self._example_noise(li, sb[0] if sb else None)
         k = 0
         for li in range(L):
             if self.form[li] != "recompute":

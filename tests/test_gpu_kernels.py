@@ -468,3 +468,30 @@ def test_gram_route_norms(name, layer, n):
     torch.cuda.synchronize()
     parts = host(ws[: 4 * n * count].view(torch.float32)).reshape(n, count)
     assert np.allclose(parts.sum(axis=1), sq, rtol=1e-5)
+
+
+def test_clip_accumulate_segments_matches_one_call_per_segment():
+    """Several clipping groups in one launch: same bits as a dp_clip_accumulate call per segment, and the oracle's sum."""
+    rng = np.random.default_rng(31)
+    n, sizes, groups = 7, [36, 4, 1028, 260, 8, 4096], [0, 0, 1, 2, 2, 1]
+    begins = np.concatenate([[0], np.cumsum(sizes)[:-1]])
+    p = int(sum(sizes))
+    stride = p + 8
+    g = rng.standard_normal((n, stride)).astype(np.float32)
+    n2 = (rng.uniform(0.3, 2.5, (3, n)) ** 2).astype(np.float32)
+    n2[1, 2] = 0.0
+    clips = [0.7, 0.7, 1.3, 2.0, 2.0, 1.3]
+    acc0 = rng.standard_normal(p).astype(np.float32)
+    acc = dev(acc0)
+    table = dp.SegmentTable(begins, groups, clips)
+    dp.dp_clip_accumulate_segments(dev(g), dev(n2), 3, table, n, p, acc, g_stride=stride)
+    ref_dev = dev(acc0)
+    gd, n2d = dev(g), dev(n2)
+    ref = acc0.astype(np.float64)
+    for b, sz, grp, c in zip(begins, sizes, groups, clips):
+        dp.dp_clip_accumulate(gd[:, b:].data_ptr(), n2d[grp], c, n, sz, ref_dev[b:].data_ptr(), g_stride=stride)
+        f = np.array([oracle.clip_factor(float(v), c) for v in n2[grp]])
+        ref[b: b + sz] += (f[:, None] * g[:, b: b + sz].astype(np.float64)).sum(axis=0)
+    torch.cuda.synchronize()
+    assert torch.equal(acc, ref_dev)
+    assert_close(host(acc) - acc0, ref - acc0, F32_TOL, "segments increment")

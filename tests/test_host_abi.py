@@ -208,3 +208,20 @@ def test_infinite_bound_is_legal_only_without_noise(lib):
     f = lib.dp_add_noise_finalize
     assert f(FAKE, FAKE, 16, 1.0, float("inf"), 8, 0, 0, 0, None) == B.DP_ERR_INVALID_ARG
     assert "clip_total" in dp.dp_last_error()
+
+
+def test_clip_accumulate_segments_rejects_bad_tables(lib):
+    import ctypes as C
+    f = lib.dp_clip_accumulate_segments
+    def call(begins=(0, 8), groups=(0, 1), clips=(1.0, 1.0), n_groups=2, n=4, p=16, g=FAKE, acc=FAKE, sq=FAKE):
+        k = len(begins)
+        return f(g, 0, sq, n_groups, C.cast((C.c_size_t * k)(*begins), C.c_void_p), C.cast((C.c_int32 * k)(*groups), C.c_void_p),
+                 C.cast((C.c_float * k)(*clips), C.c_void_p), k, n, p, acc, None)
+    assert call(g=None) == B.DP_ERR_INVALID_ARG
+    assert call(p=18) == B.DP_ERR_INVALID_ARG                    # not a multiple of 4
+    assert call(begins=(4, 8)) == B.DP_ERR_INVALID_ARG           # must start at 0
+    assert call(begins=(0, 6)) == B.DP_ERR_INVALID_ARG           # not a multiple of 4
+    assert call(begins=(0, 16)) == B.DP_ERR_INVALID_ARG          # empty last segment
+    assert call(groups=(0, 2)) == B.DP_ERR_INVALID_ARG           # group out of range
+    assert call(clips=(1.0, 0.0)) == B.DP_ERR_INVALID_ARG
+    assert call(n=0) == B.DP_ERR_INVALID_ARG
