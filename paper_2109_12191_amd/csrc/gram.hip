@@ -9,8 +9,8 @@
 // on its way into LDS (T[k][c], channels contiguous) and then feeds v_mfma_f32_32x32x16_bf16 like
 // any K-contiguous operand.
 //
-// Kernel 1: a workgroup takes one example and a slice of the channels of both operands and leaves
-// its two partial 64x64 Grams (accumulator register layout) in the workspace.  Kernel 2: one
+// Kernel 1: a workgroup takes one example and a slice of at most 256 channels of one operand and leaves
+// its partial 64x64 Gram (accumulator register layout) in the workspace.  Kernel 2: one
 // workgroup per example adds the slices in order, multiplies the Grams element by element and
 // reduces.  Fixed order everywhere: same bits on every run.
 #include "internal.h"
@@ -26,9 +26,10 @@ constexpr int GR_PT = GR_CB * 2 + 16;              // bytes per LDS row k (odd m
 
 struct GramArgs {
     const uint16_t *a, *b;                         // dY [n][ca][S], X [n][cb][S]
-    float *part;                                   // [n][splits][2][4096]
+    float *part;                                   // [n][sa + sb][4096]: slices of the dY Gram, then of the X Gram
     float *out;                                    // [n][GR_PARTS] partial squared norms
-    int n, ca, cb, S, splits;
+    int n, ca, cb, S;
+    int sa, sb;                                    // channel slices (of at most 256 channels) of dY and of X
     int total_a, total_b;                          // elements in each tensor
 };
 
@@ -88,21 +89,22 @@ __device__ __forceinline__ void gram_part(f32x16 &acc, const uint16_t *tensor, i
 __global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const GramArgs a)
 {
     __shared__ __attribute__((aligned(16))) char lds[64 * GR_PT];
-    const int i = blockIdx.x / a.splits, s = blockIdx.x - i * a.splits;
+    const int slots = a.sa + a.sb;
+    const int i = blockIdx.x / slots, s = blockIdx.x - i * slots;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kb = wave >> 1, kb2 = wave & 1;
-    const int ca_per = (a.ca + a.splits - 1) / a.splits, cb_per = (a.cb + a.splits - 1) / a.splits;
-    f32x16 ga, gb;
+    f32x16 gm;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { ga[r] = 0.0f; gb[r] = 0.0f; }
-    gram_part(ga, a.a, i * a.ca * a.S, a.total_a, min(a.ca, s * ca_per), min(a.ca, (s + 1) * ca_per), a.S, lds, kb, kb2, lane);
-    gram_part(gb, a.b, i * a.cb * a.S, a.total_b, min(a.cb, s * cb_per), min(a.cb, (s + 1) * cb_per), a.S, lds, kb, kb2, lane);
-    float *mine = a.part + (size_t)blockIdx.x * 2 * 4096;
+    for (int r = 0; r < 16; ++r) gm[r] = 0.0f;
+    // one slice of one operand per workgroup: a single block of channels, one memory round trip
+    if (s < a.sa)
+        gram_part(gm, a.a, i * a.ca * a.S, a.total_a, s * GR_CB, min(a.ca, (s + 1) * GR_CB), a.S, lds, kb, kb2, lane);
+    else
+        gram_part(gm, a.b, i * a.cb * a.S, a.total_b, (s - a.sa) * GR_CB, min(a.cb, (s - a.sa + 1) * GR_CB), a.S, lds, kb, kb2,
+                  lane);
+    float *mine = a.part + (size_t)blockIdx.x * 4096;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        mine[r * GR_THREADS + threadIdx.x] = ga[r];
-        mine[4096 + r * GR_THREADS + threadIdx.x] = gb[r];
-    }
+    for (int r = 0; r < 16; ++r) mine[r * GR_THREADS + threadIdx.x] = gm[r];
 }
 
 // One workgroup per (example, accumulator register r): 256 Gram entries each; the slices are added in
@@ -113,13 +115,12 @@ __global__ void __launch_bounds__(GR_THREADS) gram_combine_kernel(const GramArgs
 {
     __shared__ float red[4];
     const int i = blockIdx.x / GR_PARTS, r = blockIdx.x - i * GR_PARTS;
-    const float *base = a.part + (size_t)i * a.splits * 2 * 4096 + r * GR_THREADS + threadIdx.x;
-    float va[16], vb[16];                          // at most 16 slices, all loads in flight together
+    const float *base = a.part + (size_t)i * (a.sa + a.sb) * 4096 + r * GR_THREADS + threadIdx.x;
+    float va[16], vb[16];                          // at most 16 slices per operand, all loads in flight together
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
-        const bool live = s < a.splits;
-        va[s] = live ? base[(size_t)s * 2 * 4096] : 0.0f;
-        vb[s] = live ? base[(size_t)s * 2 * 4096 + 4096] : 0.0f;
+        va[s] = s < a.sa ? base[(size_t)s * 4096] : 0.0f;
+        vb[s] = s < a.sb ? base[(size_t)(a.sa + s) * 4096] : 0.0f;
     }
     float ga = 0.0f, gb = 0.0f;
 #pragma unroll
@@ -128,15 +129,7 @@ __global__ void __launch_bounds__(GR_THREADS) gram_combine_kernel(const GramArgs
     if (threadIdx.x == 0) a.out[blockIdx.x] = tot;
 }
 
-int gram_splits(const Geo &g)
-{
-    // about 256 workgroups, each with at least 64 channels of the smaller operand
-    int s = 256 / g.n;
-    const int cmin = g.cin < g.cout ? g.cin : g.cout;
-    if (s > cmin / 64) s = cmin / 64;
-    if (s > 16) s = 16;
-    return s < 1 ? 1 : s;
-}
+int gram_slots(const Geo &g) { return (g.cout + GR_CB - 1) / GR_CB + (g.cin + GR_CB - 1) / GR_CB; }
 
 size_t gram_align16(size_t b) { return (b + 15) & ~(size_t)15; }
 
@@ -148,7 +141,7 @@ bool gram_norm_applicable(const Geo &g, int mode)
     if (g.kh != 1 || g.kw != 1 || g.stride != 1 || g.pad != 0) return false;
     const long long S = (long long)g.oh * g.ow;
     if (S > 64 || S < 8) return false;
-    if (g.cin < 128 || g.cout < 128) return false;
+    if (g.cin < 128 || g.cout < 128 || g.cin > 16 * GR_CB || g.cout > 16 * GR_CB) return false;
     // the Gram route wins when S is small against the channel counts (S^2 (Cin+Cout) << S Cin Cout)
     if (S * (g.cin + g.cout) * 4 > (long long)g.cin * g.cout) return false;
     return (long long)g.n * g.cin * S < (1ll << 31) && (long long)g.n * g.cout * S < (1ll << 31);
@@ -156,7 +149,7 @@ bool gram_norm_applicable(const Geo &g, int mode)
 
 size_t gram_ws_bytes(const Geo &g)
 {
-    return gram_align16((size_t)g.n * GR_PARTS * sizeof(float)) + (size_t)g.n * gram_splits(g) * 2 * 4096 * sizeof(float);
+    return gram_align16((size_t)g.n * GR_PARTS * sizeof(float)) + (size_t)g.n * gram_slots(g) * 4096 * sizeof(float);
 }
 
 dp_status launch_gram_norm(const Geo &g, const void *x, const void *dy, float *sqnorm, void *ws, hipStream_t s)
@@ -164,14 +157,15 @@ dp_status launch_gram_norm(const Geo &g, const void *x, const void *dy, float *s
     GramArgs a;
     a.a = static_cast<const uint16_t *>(dy);
     a.b = static_cast<const uint16_t *>(x);
-    a.n = g.n; a.ca = g.cout; a.cb = g.cin; a.S = g.oh * g.ow; a.splits = gram_splits(g);
+    a.n = g.n; a.ca = g.cout; a.cb = g.cin; a.S = g.oh * g.ow;
+    a.sa = (g.cout + GR_CB - 1) / GR_CB; a.sb = (g.cin + GR_CB - 1) / GR_CB;
     a.total_a = g.n * g.cout * a.S;
     a.total_b = g.n * g.cin * a.S;
     // the partial norms [n][16] sit at the start of the workspace, the partial Grams after them
     a.out = static_cast<float *>(ws);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + gram_align16((size_t)g.n * GR_PARTS * sizeof(float)));
     profile_begin(s);
-    hipLaunchKernelGGL(gram_partial_kernel, dim3((unsigned)(g.n * a.splits)), dim3(GR_THREADS), 0, s, a);
+    hipLaunchKernelGGL(gram_partial_kernel, dim3((unsigned)(g.n * (a.sa + a.sb))), dim3(GR_THREADS), 0, s, a);
     profile_end(s);
     dp_status st = check_launch("gram_partial");
     if (st != DP_OK) return st;
