@@ -886,8 +886,8 @@ size_t conv_ws_bytes(const Geo &g, int mode)
 
 static size_t conv_ws_bytes_mode(const Geo &g, int mode)
 {
-    if (conv3x3_applicable(g, mode)) return conv3x3_ws_bytes(g, mode);
     if (gram_norm_applicable(g, mode)) return gram_ws_bytes(g);
+    if (conv3x3_applicable(g, mode)) return conv3x3_ws_bytes(g, mode);
     PackPlan pp;
     Geo g2;
     if (packed_weighted(g, mode, pp, g2)) {
@@ -904,8 +904,8 @@ static size_t conv_ws_bytes_mode(const Geo &g, int mode)
 
 size_t conv_norm_partial_count(const Geo &g, int mode)
 {
-    if (conv3x3_applicable(g, mode)) return conv3x3_norm_partial_count(g);
     if (gram_norm_applicable(g, mode)) return gram_norm_partial_count();
+    if (conv3x3_applicable(g, mode)) return conv3x3_norm_partial_count(g);
     Geo g2;
     if (subsampled(g, mode, g2)) return conv_norm_partial_count(g2, mode);
     return norm_partials_per_example(full_plan(g, mode));
@@ -913,8 +913,8 @@ size_t conv_norm_partial_count(const Geo &g, int mode)
 
 const char *conv_variant_name(const Geo &g, int mode)
 {
-    if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);
     if (gram_norm_applicable(g, mode)) return "conv_gram_norm<bf16>";
+    if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);
     static char names[2][4][2][2][64];
     static bool init = false;
     if (!init) {
@@ -970,9 +970,9 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
                       hipStream_t s)
 {
+    if (gram_norm_applicable(g, mode)) return launch_gram_norm(g, x, dy, sqnorm, ws, s);
     if (conv3x3_applicable(g, mode))
         return launch_conv3x3(g, mode, x, dy, out_w, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
-    if (gram_norm_applicable(g, mode)) return launch_gram_norm(g, x, dy, sqnorm, ws, s);
     PackPlan pp;
     Geo g2;
     if (packed_weighted(g, mode, pp, g2)) {

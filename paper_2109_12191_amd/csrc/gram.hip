@@ -1,5 +1,6 @@
-// Squared norms of per-example 1x1-convolution gradients on small feature maps, without forming
-// the gradients (H2 for the layers whose gradients are recomputed later, never stored).
+// Squared norms of per-example convolution gradients on small feature maps (1x1 stride 1; 3x3 pad 1 with
+// stride 1 or 2), without forming the gradients (H2 for the layers whose gradients are recomputed later,
+// never stored).
 //
 // For a 1x1 stride-1 convolution dW_i = A_i B_i^T with A_i = dY_i [Cout x S], B_i = X_i [Cin x S], so
 //     ||dW_i||_F^2 = sum_{k,k'} (A_i^T A_i)[k,k'] * (B_i^T B_i)[k,k']
@@ -7,7 +8,8 @@
 // of a Cout x Cin x S contraction.  With S <= 64 (7x7 maps: S = 49) that is ~8x fewer flops and no
 // large tile to square.  Both Grams are contractions over CHANNELS, so each operand is transposed
 // on its way into LDS (T[k][c], channels contiguous) and then feeds v_mfma_f32_32x32x16_bf16 like
-// any K-contiguous operand.
+// any K-contiguous operand.  For a 3x3 convolution B_i is the im2col matrix (rows (ci, kh, kw)), gathered
+// from the image while it is transposed.
 //
 // Kernel 1: a workgroup takes one example and a slice of at most 256 channels of one operand and leaves
 // its partial 64x64 Gram (accumulator register layout) in the workspace.  Kernel 2: one
@@ -31,6 +33,9 @@ struct GramArgs {
     int n, ca, cb, S;
     int sa, sb;                                    // channel slices (of at most 256 channels) of dY and of X
     int total_a, total_b;                          // elements in each tensor
+    // 3x3 pad-1 convolutions: the rows of the second operand are im2col rows (ci, kh, kw) gathered from the
+    // image X [n][cin][h][w]; cb = cin * 9 then.  taps == 1: X is the operand itself.
+    int taps, cin, h, w, ow, stride;
 };
 
 // Gram of channels [c0, c1) of one example's matrix src[c][S] (element offset `base` from the
@@ -86,6 +91,43 @@ __device__ __forceinline__ void gram_part(f32x16 &acc, const uint16_t *tensor, i
     }
 }
 
+// The same for im2col rows [c0, c1) of a 3x3 pad-1 convolution (row j = (ci, kh, kw), column k = (oh, ow)):
+//     T[k][j] = Xpad[ci][oh * stride + kh - 1][ow * stride + kw - 1],
+// gathered element by element (the nine taps of a channel re-read the same few bytes, from L1).
+__device__ __forceinline__ void gram_part_im2col(f32x16 &acc, const GramArgs &a, int i, int c0, int c1, char *lds, int kb,
+                                                 int kb2, int lane)
+{
+    for (int cblk = c0; cblk < c1; cblk += GR_CB) {
+        __syncthreads();
+        const int j = cblk + (int)threadIdx.x;
+        const bool live = j < c1;
+        const int ci = j / 9, tap = j - ci * 9;
+        const int dh = tap / 3 - 1, dw = tap - (tap / 3) * 3 - 1;
+        const uint16_t *img = a.b + ((size_t)i * a.cin + (live ? ci : 0)) * a.h * a.w;
+        uint16_t vals[64];
+        int oh = 0, owc = 0;
+#pragma unroll
+        for (int k = 0; k < 64; ++k) {
+            const int ih = oh * a.stride + dh, iw = owc * a.stride + dw;
+            const bool ok = live && k < a.S && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
+            vals[k] = ok ? img[ih * a.w + iw] : (uint16_t)0;
+            if (++owc == a.ow) { owc = 0; ++oh; }
+        }
+        uint16_t *col = reinterpret_cast<uint16_t *>(lds) + threadIdx.x;
+#pragma unroll
+        for (int k = 0; k < 64; ++k) *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(col) + k * GR_PT) = vals[k];
+        __syncthreads();
+        const int nks = (min(GR_CB, c1 - cblk) + 15) / 16;
+        const char *pa = lds + (kb * 32 + (lane & 31)) * GR_PT + (lane >> 5) * 16;
+        const char *pb = lds + (kb2 * 32 + (lane & 31)) * GR_PT + (lane >> 5) * 16;
+        for (int ks = 0; ks < nks; ++ks) {
+            const bf16x8 va = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + ks * 32));
+            const bf16x8 vb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pb + ks * 32));
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, vb, acc, 0, 0, 0);
+        }
+    }
+}
+
 __global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const GramArgs a)
 {
     __shared__ __attribute__((aligned(16))) char lds[64 * GR_PT];
@@ -99,9 +141,11 @@ __global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const GramArgs
     // one slice of one operand per workgroup: a single block of channels, one memory round trip
     if (s < a.sa)
         gram_part(gm, a.a, i * a.ca * a.S, a.total_a, s * GR_CB, min(a.ca, (s + 1) * GR_CB), a.S, lds, kb, kb2, lane);
-    else
+    else if (a.taps == 1)
         gram_part(gm, a.b, i * a.cb * a.S, a.total_b, (s - a.sa) * GR_CB, min(a.cb, (s - a.sa + 1) * GR_CB), a.S, lds, kb, kb2,
                   lane);
+    else
+        gram_part_im2col(gm, a, i, (s - a.sa) * GR_CB, min(a.cb, (s - a.sa + 1) * GR_CB), lds, kb, kb2, lane);
     float *mine = a.part + (size_t)blockIdx.x * 4096;
 #pragma unroll
     for (int r = 0; r < 16; ++r) mine[r * GR_THREADS + threadIdx.x] = gm[r];
@@ -110,26 +154,29 @@ __global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const GramArgs
 // One workgroup per (example, accumulator register r): 256 Gram entries each; the slices are added in
 // order, the two Grams multiplied entry by entry and the products reduced to one partial norm.
 constexpr int GR_PARTS = 16;
+constexpr int GR_SA_MAX = 16, GR_SB_MAX = 40;      // slices of 256 rows: Cout <= 4096, Cin*k*k <= 10240
 
 __global__ void __launch_bounds__(GR_THREADS) gram_combine_kernel(const GramArgs a)
 {
     __shared__ float red[4];
     const int i = blockIdx.x / GR_PARTS, r = blockIdx.x - i * GR_PARTS;
     const float *base = a.part + (size_t)i * (a.sa + a.sb) * 4096 + r * GR_THREADS + threadIdx.x;
-    float va[16], vb[16];                          // at most 16 slices per operand, all loads in flight together
+    float va[GR_SA_MAX], vb[GR_SB_MAX];            // all loads in flight together
 #pragma unroll
-    for (int s = 0; s < 16; ++s) {
-        va[s] = s < a.sa ? base[(size_t)s * 4096] : 0.0f;
-        vb[s] = s < a.sb ? base[(size_t)(a.sa + s) * 4096] : 0.0f;
-    }
+    for (int s = 0; s < GR_SA_MAX; ++s) va[s] = s < a.sa ? base[(size_t)s * 4096] : 0.0f;
+#pragma unroll
+    for (int s = 0; s < GR_SB_MAX; ++s) vb[s] = s < a.sb ? base[(size_t)(a.sa + s) * 4096] : 0.0f;
     float ga = 0.0f, gb = 0.0f;
 #pragma unroll
-    for (int s = 0; s < 16; ++s) { ga += va[s]; gb += vb[s]; }
+    for (int s = 0; s < GR_SA_MAX; ++s) ga += va[s];
+#pragma unroll
+    for (int s = 0; s < GR_SB_MAX; ++s) gb += vb[s];
     const float tot = block_sum<4>(ga * gb, red);
     if (threadIdx.x == 0) a.out[blockIdx.x] = tot;
 }
 
-int gram_slots(const Geo &g) { return (g.cout + GR_CB - 1) / GR_CB + (g.cin + GR_CB - 1) / GR_CB; }
+int gram_rows_b(const Geo &g) { return g.cin * g.kh * g.kw; }
+int gram_slots(const Geo &g) { return (g.cout + GR_CB - 1) / GR_CB + (gram_rows_b(g) + GR_CB - 1) / GR_CB; }
 
 size_t gram_align16(size_t b) { return (b + 15) & ~(size_t)15; }
 
@@ -138,13 +185,15 @@ size_t gram_align16(size_t b) { return (b + 15) & ~(size_t)15; }
 bool gram_norm_applicable(const Geo &g, int mode)
 {
     if (mode != MODE_NORM || !g.bf16 || g.has_bias) return false;
-    if (g.kh != 1 || g.kw != 1 || g.stride != 1 || g.pad != 0) return false;
-    const long long S = (long long)g.oh * g.ow;
+    const bool one = g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0;
+    const bool three = g.kh == 3 && g.kw == 3 && g.pad == 1 && (g.stride == 1 || g.stride == 2);
+    if (!one && !three) return false;
+    const long long S = (long long)g.oh * g.ow, J = (long long)g.cin * g.kh * g.kw;
     if (S > 64 || S < 8) return false;
-    if (g.cin < 128 || g.cout < 128 || g.cin > 16 * GR_CB || g.cout > 16 * GR_CB) return false;
-    // the Gram route wins when S is small against the channel counts (S^2 (Cin+Cout) << S Cin Cout)
-    if (S * (g.cin + g.cout) * 4 > (long long)g.cin * g.cout) return false;
-    return (long long)g.n * g.cin * S < (1ll << 31) && (long long)g.n * g.cout * S < (1ll << 31);
+    if (g.cin < 128 || g.cout < 128 || g.cout > GR_SA_MAX * GR_CB || J > GR_SB_MAX * GR_CB) return false;
+    // the Gram route wins when S is small against the channel counts (S^2 (J+Cout) << S J Cout)
+    if (S * (J + g.cout) * 4 > J * g.cout) return false;
+    return (long long)g.n * g.cin * g.h * g.w < (1ll << 31) && (long long)g.n * g.cout * S < (1ll << 31);
 }
 
 size_t gram_ws_bytes(const Geo &g)
@@ -157,10 +206,11 @@ dp_status launch_gram_norm(const Geo &g, const void *x, const void *dy, float *s
     GramArgs a;
     a.a = static_cast<const uint16_t *>(dy);
     a.b = static_cast<const uint16_t *>(x);
-    a.n = g.n; a.ca = g.cout; a.cb = g.cin; a.S = g.oh * g.ow;
-    a.sa = (g.cout + GR_CB - 1) / GR_CB; a.sb = (g.cin + GR_CB - 1) / GR_CB;
+    a.n = g.n; a.ca = g.cout; a.cb = gram_rows_b(g); a.S = g.oh * g.ow;
+    a.sa = (g.cout + GR_CB - 1) / GR_CB; a.sb = (a.cb + GR_CB - 1) / GR_CB;
+    a.taps = g.kh * g.kw; a.cin = g.cin; a.h = g.h; a.w = g.w; a.ow = g.ow; a.stride = g.stride;
     a.total_a = g.n * g.cout * a.S;
-    a.total_b = g.n * g.cin * a.S;
+    a.total_b = g.n * g.cin * g.h * g.w;
     // the partial norms [n][16] sit at the start of the workspace, the partial Grams after them
     a.out = static_cast<float *>(ws);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + gram_align16((size_t)g.n * GR_PARTS * sizeof(float)));

@@ -445,6 +445,9 @@ GRAM_CASES = [
     ("384->640 7x7 ragged channel blocks", conv(384, 640, 1, 1, 7), 4),
     ("512->1024 8x8 (S = 64)", conv(512, 1024, 1, 1, 8), 2),
     ("512->512 4x4", conv(512, 512, 1, 1, 4), 33),
+    ("3x3 512->512 7x7", conv(512, 512, 3, 1, 7), 3),
+    ("3x3 stride 2 14->7 ragged", conv(320, 264, 3, 2, 14), 4),
+    ("3x3 6x8 rectangular", Layer("conv", 128, 256, 6, 8, 3, 3, 1, 1, False), 3),
 ]
 
 

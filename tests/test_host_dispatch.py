@@ -19,12 +19,14 @@ def test_resnet50_layers_go_to_the_expected_kernels(wl):
         per_example[l.name] = dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD)
         weighted[l.name] = dp.dp_kernel_variant(d, dp.DP_WS_RECOMPUTE)
     # every 3x3 stride-1 conv runs in the raw-row kernel, named for its row width
-    for name, width in (("s1b1.c2", 56), ("s2b2.c2", 28), ("s3b2.c2", 14), ("s4b2.c2", 7)):
+    for name, width in (("s1b1.c2", 56), ("s2b2.c2", 28), ("s3b2.c2", 14)):
         assert per_example[name] == f"conv3x3_rows<bf16,w{width},per_example>"
         assert weighted[name] == f"conv3x3_rows<bf16,w{width},weighted>"
+    assert weighted["s4b2.c2"] == "conv3x3_rows<bf16,w7,weighted>"
     # the strided 3x3 convs onto 14- and 7-wide outputs too; the one onto 28 stays in the general kernel
     assert per_example["s3b1.c2"] == "conv3x3_rows<bf16,w14,s2,per_example>"
-    assert per_example["s4b1.c2"] == "conv3x3_rows<bf16,w7,s2,per_example>"
+    # norm-only calls on 7x7 maps take the Gram route (3x3 convs included); their materialising calls do not
+    assert per_example["s4b1.c2"] == "conv_gram_norm<bf16>" and per_example["s4b2.c2"] == "conv_gram_norm<bf16>"
     assert per_example["s2b1.c2"].startswith("conv_contract<bf16,")
     assert weighted["s4b1.c2"].startswith("conv_contract<bf16,")
     # 1x1 convs: general kernel; the classifier: the dense kernels
@@ -34,7 +36,7 @@ def test_resnet50_layers_go_to_the_expected_kernels(wl):
         assert per_example[name] == "conv_gram_norm<bf16>", name
     assert per_example["s1b1.c1"] == "conv_contract<bf16,64x64,per_example>"
     assert per_example["fc"] == "dense<bf16>"
-    assert sum(v.startswith("conv3x3_rows") for v in per_example.values()) == 15
+    assert sum(v.startswith("conv3x3_rows") for v in per_example.values()) == 12
 
 
 def test_workspace_queries_are_consistent(wl):
