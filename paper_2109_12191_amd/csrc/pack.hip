@@ -43,6 +43,16 @@ __global__ void __launch_bounds__(256) pack_weighted_kernel(const PackArgs a)
             const int ci = j / taps, t = j - ci * taps;
             const int kh = t / a.kw, kw = t - kh * a.kw;
             const uint16_t *src = a.x + ((size_t)i * a.cin + ci) * a.h * a.w;
+            if (taps == 1 && a.stride == 1 && a.pad == 0) {
+                // 1x1 stride 1: the im2col row is the channel itself
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t v = (k0 + u < a.S) ? src[k0 + u] : 0u;
+                    out[u >> 1] |= v << ((u & 1) * 16);
+                }
+                *reinterpret_cast<uint4 *>(a.xp + q * 8) = make_uint4(out[0], out[1], out[2], out[3]);
+                return;
+            }
             int oh = k0 / a.ow, ow = k0 - oh * a.ow;
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
