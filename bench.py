@@ -85,13 +85,13 @@ def cpu_baseline(wl, inputs0, budget_examples):
     host_inputs = [(x[:s].float().cpu().numpy(), dy[:s].float().cpu().numpy()) for x, dy in inputs0]
     acc_w, acc_b = oracle.new_accumulators(wl.layers)
     t0 = time.perf_counter()
-    oracle.clip_accumulate(wl.layers, host_inputs, wl.group_of_layer, wl.group_clip, acc_w, acc_b, threads=cores)
+    oracle.clip_accumulate(wl.layers, host_inputs, wl.group_of_layer, oracle.group_bounds(wl.clip_c, wl.n_groups)[0], acc_w, acc_b, threads=cores)
     # noise + finalize on every parameter, once (amortised over the whole batch in `value`)
     t1 = time.perf_counter()
     p_sample = 0
     for li, l in enumerate(wl.layers):
         if li % 8 == 0:      # a bounded sample of tensors, scaled to all parameters below
-            oracle.noise_finalize(acc_w[li], wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step, 2 * li)
+            oracle.noise_finalize(acc_w[li], wl.sigma, oracle.group_bounds(wl.clip_c, wl.n_groups)[1], wl.total_batch, wl.philox_seed, wl.step, 2 * li)
             p_sample += l.pw
     t2 = time.perf_counter()
     per_example = (t1 - t0) / s

@@ -78,6 +78,14 @@ typedef struct dp_layer_desc {
 
 typedef void *dp_stream;   /* a hipStream_t */
 
+/* Bounds for M = n_groups clipping groups (Section 3.5: every group is clipped to C / sqrt(M), so the
+ * squared group norms add up to at most C^2; M = 1 is the single global bound of Section 2):
+ *   group_clip[g] = clip_c / sqrt(n_groups),   *clip_total = sqrt(sum_g group_clip[g]^2)
+ * clip_total, the bound on the whole clipped gradient, is what the noise of H5 is scaled by.
+ * group_clip [host] n_groups floats, clip_total [host] one float, both written.  Pure host.
+ * clip_c <= 0 or NaN, n_groups < 1, NULL outputs -> DP_ERR_INVALID_ARG.                        */
+dp_status dp_group_clip_bounds(float clip_c, int n_groups, float *group_clip, float *clip_total);
+
 /* Which call a workspace is sized for. */
 typedef enum { DP_WS_PER_EXAMPLE_GRAD = 0, DP_WS_RECOMPUTE = 1 } dp_ws_use;
 
@@ -213,15 +221,16 @@ dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float si
  * (seed mod 2^32, (seed div 2^32) xor 0x50455245): j is the example's index within the optimiser step.
  * The step is then finished with dp_add_noise_finalize(sigma = 0).  Same distribution as the
  * once-per-step form, different bits, n_examples Philox calls per four parameters.
- * acc [device] [p] fp32, 16-byte aligned.  first_example + n_examples > total_batch, n_examples < 1,
- * bad sigma / clip_total -> DP_ERR_INVALID_ARG.                                                  */
+ * acc [device] [p] fp32, 16-byte aligned.  step_dev [device]: NULL, or one uint64 the kernel reads the
+ * step from instead of `step` (see dp_add_noise_finalize_flat).  first_example + n_examples >
+ * total_batch, n_examples < 1, bad sigma / clip_total -> DP_ERR_INVALID_ARG.                       */
 dp_status dp_add_example_noise(float *acc, size_t p, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
                                uint64_t step, uint32_t tensor_id, uint64_t first_example, int n_examples,
-                               dp_stream stream);
+                               const uint64_t *step_dev, dp_stream stream);
 
-/* H5 fused with the SGD step that consumes it (the step right after the path: "SGD ... with a
- * stepped learning rate decay policy", Algorithm section; "vanilla SGD with momentum (0.9)",
- * Sections 4.2-4.3): with g[e] = (acc[e] + sigma * clip_total * z_e) / total_batch as above,
+/* H5 fused with the SGD step that consumes it (the step right after the path: Section 2 names SGD
+ * with a stepped learning-rate decay as the optimiser, Sections 3.2 and 3.3 run it with momentum
+ * 0.9): with g[e] = (acc[e] + sigma * clip_total * z_e) / total_batch as above,
  *     velocity[e] = momentum * velocity[e] + g[e];   theta[e] -= lr * velocity[e]
  * or, with velocity == NULL (momentum must be 0),  theta[e] -= lr * g[e].
  * g is written to `out` only if out != NULL.  lr is this step's learning rate (decay and scaling
@@ -232,6 +241,25 @@ dp_status dp_add_example_noise(float *acc, size_t p, float sigma, float clip_tot
 dp_status dp_add_noise_finalize_update(const float *acc, float *theta, float *velocity, float *out, size_t p, float sigma,
                                        float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
                                        uint32_t tensor_id, float lr, float momentum, dp_stream stream);
+
+/* H5 (optionally with the fused SGD step) for every tensor of a flat parameter vector in ONE launch.
+ * The vector acc (and out, theta, velocity, laid out alike) holds n_seg tensors; tensor k occupies the
+ * elements seg_begin[k] .. seg_begin[k] + seg_size[k] and draws its noise exactly as
+ * dp_add_noise_finalize(acc + seg_begin[k], ..., p = seg_size[k], tensor_id = seg_tensor_id[k]) would:
+ * same counters, same bits.  Elements between tensors (padding) are neither read nor written.
+ * seg_begin, seg_size, seg_tensor_id  [host] n_seg entries; every seg_begin a multiple of 4, tensors in
+ *            increasing order without overlap, every seg_size in [1, 2^32).
+ * step_dev   [device] NULL, or one uint64: then the kernel takes the step from this word instead of
+ *            `step` -- a caller that replays a captured graph advances the word between replays, so
+ *            that no two optimiser steps ever share a noise draw.
+ * theta      [device] NULL = finalize only (out required).  Otherwise the SGD step of
+ *            dp_add_noise_finalize_update is applied to theta / velocity with lr and momentum, and out
+ *            may be NULL.
+ * Errors as dp_add_noise_finalize / dp_add_noise_finalize_update.                                   */
+dp_status dp_add_noise_finalize_flat(const float *acc, float *out, float *theta, float *velocity,
+                                     const uint64_t *seg_begin, const uint64_t *seg_size, const uint32_t *seg_tensor_id,
+                                     int n_seg, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
+                                     uint64_t step, const uint64_t *step_dev, float lr, float momentum, dp_stream stream);
 
 /* The raw 32-bit Philox word behind each element of the stream above (diagnostic; lets a
  * test compare the integer stream bit for bit).  raw [device] [p] uint32.                      */

@@ -54,6 +54,8 @@ def _load():
     lib.orc_sqnorm.argtypes = [dp, C.c_size_t]
     lib.orc_clip_factor.restype = C.c_double
     lib.orc_clip_factor.argtypes = [C.c_double, C.c_double]
+    lib.orc_group_bounds.restype = None
+    lib.orc_group_bounds.argtypes = [C.c_double, C.c_int, dp, dp]
     lib.orc_clip_accumulate.restype = C.c_int
     lib.orc_clip_accumulate.argtypes = [lp, C.c_int, C.POINTER(fp), C.POINTER(fp), C.c_int, C.c_int, dp,
                                         C.POINTER(dp), C.POINTER(dp), dp, dp, C.c_int]
@@ -132,6 +134,14 @@ def sqnorm(g) -> float:
 
 def clip_factor(n2: float, clip_c: float) -> float:
     return float(_load().orc_clip_factor(float(n2), float(clip_c)))
+
+
+def group_bounds(clip_c: float, n_groups: int):
+    """(per-group bounds C / sqrt(M), bound on the whole clipped gradient) for M clipping groups (Section 3.5)."""
+    gc = np.empty(n_groups, dtype=np.float64)
+    tot = np.empty(1, dtype=np.float64)
+    _load().orc_group_bounds(float(clip_c), int(n_groups), _dp(gc), _dp(tot))
+    return [float(c) for c in gc], float(tot[0])
 
 
 def new_accumulators(layers):
@@ -231,25 +241,26 @@ def privatise(wl, inputs_per_micro_step, threads: int = 0, noise_form: str = "on
     divide.  Tensor ids: 2*layer for the weight, 2*layer+1 for the bias.
     Returns dict(acc_w, acc_b, out_w, out_b, n2, f) (lists over layers; n2, f over micro-steps)."""
     layers = list(wl.layers)
+    group_clip, clip_total = group_bounds(wl.clip_c, wl.n_groups)
     acc_w, acc_b = new_accumulators(layers)
     n2s, fs = [], []
     for m, inputs in enumerate(inputs_per_micro_step):
-        n2, f = clip_accumulate(layers, inputs, wl.group_of_layer, wl.group_clip, acc_w, acc_b, threads)
+        n2, f = clip_accumulate(layers, inputs, wl.group_of_layer, group_clip, acc_w, acc_b, threads)
         n2s.append(n2)
         fs.append(f)
         if noise_form == "per_example":
             # every clipped example brings its own N(0, sigma^2 C^2 / |B|) draw
             for li in range(len(layers)):
-                acc_w[li][...] = add_example_noise(acc_w[li], wl.sigma, wl.clip_total, wl.total_batch, wl.philox_seed,
+                acc_w[li][...] = add_example_noise(acc_w[li], wl.sigma, clip_total, wl.total_batch, wl.philox_seed,
                                                    wl.step, 2 * li, m * wl.n, wl.n)
                 if acc_b[li] is not None:
-                    acc_b[li][...] = add_example_noise(acc_b[li], wl.sigma, wl.clip_total, wl.total_batch,
+                    acc_b[li][...] = add_example_noise(acc_b[li], wl.sigma, clip_total, wl.total_batch,
                                                        wl.philox_seed, wl.step, 2 * li + 1, m * wl.n, wl.n)
     sigma_end = 0.0 if noise_form == "per_example" else wl.sigma
     out_w, out_b = [], []
     for li, l in enumerate(layers):
-        out_w.append(noise_finalize(acc_w[li], sigma_end, wl.clip_total, wl.total_batch, wl.philox_seed,
+        out_w.append(noise_finalize(acc_w[li], sigma_end, clip_total, wl.total_batch, wl.philox_seed,
                                     wl.step, 2 * li))
-        out_b.append(noise_finalize(acc_b[li], sigma_end, wl.clip_total, wl.total_batch, wl.philox_seed,
+        out_b.append(noise_finalize(acc_b[li], sigma_end, clip_total, wl.total_batch, wl.philox_seed,
                                     wl.step, 2 * li + 1) if acc_b[li] is not None else None)
     return dict(acc_w=acc_w, acc_b=acc_b, out_w=out_w, out_b=out_b, n2=n2s, f=fs)

@@ -192,6 +192,19 @@ double orc_clip_factor(double n2, double clip_c)
     return r < 1.0 ? r : 1.0;
 }
 
+/* Per-group bounds (Section 3.5): with M clipping groups every group is clipped to C / sqrt(M), so that
+ * the squared group norms add up to at most C^2; the noise is scaled by the bound on the whole clipped
+ * gradient, sqrt(sum_g C_g^2).  With M = 1 this is the single global bound of Section 2.            */
+void orc_group_bounds(double clip_c, int n_groups, double *group_clip, double *clip_total)
+{
+    double sum = 0.0;
+    for (int g = 0; g < n_groups; ++g) {
+        group_clip[g] = clip_c / sqrt((double)n_groups);
+        sum += group_clip[g] * group_clip[g];
+    }
+    *clip_total = sqrt(sum);
+}
+
 static double uniform_open(uint32_t r);     /* defined with the noise stream below */
 
 /* Per-example form of the noise (second equation of the Algorithm section): every clipped example
@@ -224,8 +237,8 @@ void orc_add_example_noise(double *acc, size_t p, double sigma, double clip_tota
     }
 }
 
-/* SGD step on the privatised gradient (Algorithm section: "SGD ... with a stepped learning rate
- * decay policy"; Sections 4.2-4.3: "vanilla SGD with momentum (0.9)").  g is the finalized
+/* SGD step on the privatised gradient (Section 2 names SGD with a stepped learning-rate decay as the
+ * optimiser; Sections 3.2 and 3.3 run it with momentum 0.9).  g is the finalized
  * gradient of one tensor; the buffer v is the plain heavy-ball momentum: v <- mu v + g,
  * theta <- theta - lr v.  mu == 0 (or v == NULL) is SGD without momentum.                    */
 void orc_sgd_update(const double *g, double *theta, double *v, size_t p, double lr, double momentum)

@@ -70,6 +70,10 @@ double orc_sqnorm(const double *g, size_t n);
 /* min(1, C / sqrt(n2)); 1 when n2 == 0 or C is +inf.                                      */
 double orc_clip_factor(double n2, double clip_c);
 
+/* Bounds for M = n_groups clipping groups (Section 3.5): group_clip[g] = clip_c / sqrt(M) for every g,
+ * *clip_total = sqrt(sum_g group_clip[g]^2), the bound on the whole clipped gradient (scales the noise). */
+void orc_group_bounds(double clip_c, int n_groups, double *group_clip, double *clip_total);
+
 /* One micro-step of clip-and-accumulate over n examples:
  *   for each example i: per-layer gradients, per-group squared norms n2[i*n_groups + g],
  *   factors f[i*n_groups + g], then acc_w[l] += f * gw, acc_b[l] += f * gb.

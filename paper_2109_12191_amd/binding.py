@@ -49,6 +49,7 @@ def load_library():
     vp, sz, u64, u32, fl, it = C.c_void_p, C.c_size_t, C.c_uint64, C.c_uint32, C.c_float, C.c_int
     dpp = C.POINTER(LayerDesc)
     sigs = {
+        "dp_group_clip_bounds": (it, [fl, it, vp, vp]),
         "dp_weight_count": (sz, [dpp]),
         "dp_bias_count": (sz, [dpp]),
         "dp_workspace_bytes": (sz, [dpp, it]),
@@ -63,8 +64,9 @@ def load_library():
         "dp_clip_accumulate_segments": (it, [vp, sz, vp, it, vp, vp, vp, it, it, sz, vp, vp]),
         "dp_clip_accumulate_recompute": (it, [dpp, vp, vp, vp, fl, vp, vp, vp, sz, vp]),
         "dp_add_noise_finalize": (it, [vp, vp, sz, fl, fl, u64, u64, u64, u32, vp]),
-        "dp_add_example_noise": (it, [vp, sz, fl, fl, u64, u64, u64, u32, u64, it, vp]),
+        "dp_add_example_noise": (it, [vp, sz, fl, fl, u64, u64, u64, u32, u64, it, vp, vp]),
         "dp_add_noise_finalize_update": (it, [vp, vp, vp, vp, sz, fl, fl, u64, u64, u64, u32, fl, fl, vp]),
+        "dp_add_noise_finalize_flat": (it, [vp, vp, vp, vp, vp, vp, vp, it, fl, fl, u64, u64, u64, vp, fl, fl, vp]),
         "dp_philox_raw": (it, [vp, sz, u64, u64, u32, vp]),
         "dp_profile_next_contraction": (it, [vp, vp]),
         "dp_last_error": (C.c_char_p, []),
@@ -78,10 +80,10 @@ def load_library():
     return lib
 
 
-EXPORTED = ("dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
+EXPORTED = ("dp_group_clip_bounds", "dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_segments", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
-            "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
+            "dp_add_noise_finalize_flat", "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
 
 
 def make_desc(layer, n: int, dtype: str = "f32", layout: int = DP_NCHW) -> LayerDesc:
@@ -121,6 +123,14 @@ def dp_last_error() -> str:
 
 def dp_version() -> str:
     return load_library().dp_version().decode()
+
+
+def dp_group_clip_bounds(clip_c: float, n_groups: int):
+    """(list of per-group bounds, bound on the whole clipped gradient), both computed by the library."""
+    gc = (C.c_float * max(n_groups, 1))()
+    tot = C.c_float()
+    _check(load_library().dp_group_clip_bounds(clip_c, n_groups, C.cast(gc, C.c_void_p), C.cast(C.byref(tot), C.c_void_p)))
+    return [float(v) for v in gc], float(tot.value)
 
 
 def dp_weight_count(desc: LayerDesc) -> int:
@@ -223,9 +233,9 @@ def dp_add_noise_finalize(acc, out, p: int, sigma: float, clip_total: float, tot
 
 
 def dp_add_example_noise(acc, p: int, sigma: float, clip_total: float, total_batch: int, seed: int, step: int,
-                         tensor_id: int, first_example: int, n_examples: int, stream=None):
+                         tensor_id: int, first_example: int, n_examples: int, step_dev=None, stream=None):
     _check(load_library().dp_add_example_noise(_ptr(acc), p, sigma, clip_total, total_batch, seed, step, tensor_id,
-                                               first_example, n_examples, _stream(stream)))
+                                               first_example, n_examples, _ptr(step_dev), _stream(stream)))
 
 
 def dp_add_noise_finalize_update(acc, theta, velocity, out, p: int, sigma: float, clip_total: float, total_batch: int,
@@ -233,6 +243,28 @@ def dp_add_noise_finalize_update(acc, theta, velocity, out, p: int, sigma: float
     _check(load_library().dp_add_noise_finalize_update(_ptr(acc), _ptr(theta), _ptr(velocity), _ptr(out), p, sigma,
                                                        clip_total, total_batch, seed, step, tensor_id, lr, momentum,
                                                        _stream(stream)))
+
+
+class TensorTable:
+    """Host arrays for dp_add_noise_finalize_flat: where each tensor starts in the flat parameter vector,
+    its size and its Philox tensor id."""
+
+    def __init__(self, begins, sizes, tensor_ids):
+        k = len(begins)
+        self.n_seg = k
+        self.begin = (C.c_uint64 * k)(*[int(b) for b in begins])
+        self.size = (C.c_uint64 * k)(*[int(v) for v in sizes])
+        self.tensor_id = (C.c_uint32 * k)(*[int(t) for t in tensor_ids])
+
+
+def dp_add_noise_finalize_flat(acc, out, table: "TensorTable", sigma: float, clip_total: float, total_batch: int,
+                               seed: int, step: int = 0, step_dev=None, theta=None, velocity=None, lr: float = 0.0,
+                               momentum: float = 0.0, stream=None):
+    _check(load_library().dp_add_noise_finalize_flat(_ptr(acc), _ptr(out), _ptr(theta), _ptr(velocity),
+                                                     C.cast(table.begin, C.c_void_p), C.cast(table.size, C.c_void_p),
+                                                     C.cast(table.tensor_id, C.c_void_p), table.n_seg, sigma, clip_total,
+                                                     total_batch, seed, step, _ptr(step_dev), lr, momentum,
+                                                     _stream(stream)))
 
 
 def dp_profile_next_contraction(start_event, stop_event):

@@ -152,6 +152,22 @@ dp_status dp_profile_next_contraction(void *start, void *stop)
 }
 const char *dp_version(void) { return "0.1 gfx950"; }
 
+dp_status dp_group_clip_bounds(float clip_c, int n_groups, float *group_clip, float *clip_total)
+{
+    DP_TRY(check_clip(clip_c));
+    if (n_groups < 1) return fail(DP_ERR_INVALID_ARG, "n_groups = %d (need >= 1)", n_groups);
+    if (!group_clip || !clip_total) return fail(DP_ERR_INVALID_ARG, "group_clip and clip_total must be non-NULL");
+    const double each = (double)clip_c / std::sqrt((double)n_groups);
+    double sum = 0.0;
+    for (int g = 0; g < n_groups; ++g) {
+        group_clip[g] = (float)each;
+        sum += (double)group_clip[g] * (double)group_clip[g];
+    }
+    *clip_total = (float)std::sqrt(sum);
+    g_err[0] = 0;
+    return DP_OK;
+}
+
 size_t dp_weight_count(const dp_layer_desc *desc)
 {
     Geo g;
@@ -375,9 +391,10 @@ dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float si
 
 dp_status dp_add_example_noise(float *acc, size_t p, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
                                uint64_t step, uint32_t tensor_id, uint64_t first_example, int n_examples,
-                               dp_stream stream)
+                               const uint64_t *step_dev, dp_stream stream)
 {
     DP_TRY(check_ptr(acc, "acc", true));
+    DP_TRY(check_ptr(step_dev, "step_dev", false, 8));
     if (p < 1) return fail(DP_ERR_INVALID_ARG, "p = 0 parameters");
     if (std::isnan(sigma) || sigma < 0.0f || std::isinf(sigma)) return fail(DP_ERR_INVALID_ARG, "sigma must be finite and >= 0");
     if (!(clip_total > 0.0f) || (sigma > 0.0f && !std::isfinite(clip_total)))
@@ -392,7 +409,7 @@ dp_status dp_add_example_noise(float *acc, size_t p, float sigma, float clip_tot
     if (p > ((size_t)1 << 34)) return fail(DP_ERR_UNSUPPORTED, "p too large for the per-example stream");
     g_err[0] = 0;
     return launch_example_noise(acc, p, sigma, clip_total, total_batch, seed, step, tensor_id, first_example, n_examples,
-                                static_cast<hipStream_t>(stream));
+                                step_dev, static_cast<hipStream_t>(stream));
 }
 
 dp_status dp_add_noise_finalize_update(const float *acc, float *theta, float *velocity, float *out, size_t p, float sigma,
@@ -415,6 +432,42 @@ dp_status dp_add_noise_finalize_update(const float *acc, float *theta, float *ve
     g_err[0] = 0;
     return launch_noise_finalize_update(acc, theta, velocity, out, p, sigma, clip_total, total_batch, seed, step,
                                         tensor_id, lr, momentum, static_cast<hipStream_t>(stream));
+}
+
+dp_status dp_add_noise_finalize_flat(const float *acc, float *out, float *theta, float *velocity,
+                                     const uint64_t *seg_begin, const uint64_t *seg_size, const uint32_t *seg_tensor_id,
+                                     int n_seg, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
+                                     uint64_t step, const uint64_t *step_dev, float lr, float momentum, dp_stream stream)
+{
+    DP_TRY(check_ptr(acc, "acc", true));
+    DP_TRY(check_ptr(out, "out", theta == nullptr));
+    DP_TRY(check_ptr(theta, "theta", false));
+    DP_TRY(check_ptr(velocity, "velocity", false));
+    DP_TRY(check_ptr(step_dev, "step_dev", false, 8));
+    if (!seg_begin || !seg_size || !seg_tensor_id) return fail(DP_ERR_INVALID_ARG, "segment tables must be non-NULL host arrays");
+    if (n_seg < 1) return fail(DP_ERR_INVALID_ARG, "n_seg = %d (need >= 1)", n_seg);
+    if (std::isnan(sigma) || sigma < 0.0f || std::isinf(sigma)) return fail(DP_ERR_INVALID_ARG, "sigma must be finite and >= 0");
+    if (!(clip_total > 0.0f) || (sigma > 0.0f && !std::isfinite(clip_total)))
+        return fail(DP_ERR_INVALID_ARG, "clip_total must be > 0, and finite unless sigma is 0");
+    if (total_batch < 1) return fail(DP_ERR_INVALID_ARG, "total_batch = 0");
+    if (velocity && !theta) return fail(DP_ERR_INVALID_ARG, "velocity given without theta");
+    if (theta) {
+        if (!std::isfinite(lr)) return fail(DP_ERR_INVALID_ARG, "lr must be finite");
+        if (!std::isfinite(momentum) || momentum < 0.0f) return fail(DP_ERR_INVALID_ARG, "momentum must be finite and >= 0");
+        if (momentum != 0.0f && !velocity) return fail(DP_ERR_INVALID_ARG, "momentum != 0 needs a velocity buffer");
+    }
+    uint64_t end = 0;
+    for (int k = 0; k < n_seg; ++k) {
+        if (seg_begin[k] % 4) return fail(DP_ERR_INVALID_ARG, "tensor %d: seg_begin must be a multiple of 4", k);
+        if (seg_begin[k] < end) return fail(DP_ERR_INVALID_ARG, "tensor %d overlaps the one before it (or the order is not increasing)", k);
+        if (seg_size[k] < 1) return fail(DP_ERR_INVALID_ARG, "tensor %d: seg_size = 0", k);
+        if (seg_size[k] >= ((uint64_t)1 << 32)) return fail(DP_ERR_UNSUPPORTED, "tensor %d: 2^32 elements or more", k);
+        end = seg_begin[k] + seg_size[k];
+    }
+    if (end >= ((uint64_t)1 << 40)) return fail(DP_ERR_UNSUPPORTED, "parameter vector too large");
+    g_err[0] = 0;
+    return launch_noise_finalize_flat(acc, out, theta, velocity, seg_begin, seg_size, seg_tensor_id, n_seg, sigma, clip_total,
+                                      total_batch, seed, step, step_dev, lr, momentum, static_cast<hipStream_t>(stream));
 }
 
 dp_status dp_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id, dp_stream stream)

@@ -727,10 +727,10 @@ __global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const ConvArgs a)
 
 // ------------------------------------------------------------------------------------ host
 
-enum TileShape { T64 = 0, T128 = 1, T256x64 = 2, T64x256 = 3 };
-static const int kTileM[4] = {64, 128, 256, 64};
-static const int kTileN[4] = {64, 128, 64, 256};
-static const char *kTileName[4] = {"64x64", "128x128", "256x64", "64x256"};
+enum TileShape { T64 = 0, T128 = 1 };
+static const int kTileM[2] = {64, 128};
+static const int kTileN[2] = {64, 128};
+static const char *kTileName[2] = {"64x64", "128x128"};
 
 struct FullPlan {
     int shape, tiles_m, tiles_n;
@@ -772,8 +772,6 @@ static FullPlan full_plan(const Geo &g, int mode)
     if (mode == MODE_WEIGHTED) {
         // example ranges: enough workgroups to fill the chip, with the partial tiles that are
         // written and read back (cache-resident in practice) kept below ~100 MB
-        const double in_bytes = (double)g.n * (double)(g.x_elems + g.dy_elems) * (g.bf16 ? 2 : 4);
-        (void)in_bytes;
         long long want = (512 + tiles - 1) / tiles;
         const long long cap = (long long)(96.0e6 / (4.0 * (double)tiles * (double)tile_floats));
         if (want > cap) want = cap;
@@ -853,15 +851,6 @@ static bool subsampled(const Geo &g, int mode, Geo &g2)
     return true;
 }
 
-ConvPlan conv_plan(const Geo &g, int mode)
-{
-    const FullPlan f = full_plan(g, mode);
-    ConvPlan p;
-    p.big = f.shape;
-    p.tiles_m = f.tiles_m; p.tiles_n = f.tiles_n; p.splits = f.ksplit;
-    return p;
-}
-
 // workspace: [partial squared norms (per-example mode)] [partial tiles]
 static size_t align16(size_t b) { return (b + 15) & ~(size_t)15; }
 
@@ -915,19 +904,21 @@ const char *conv_variant_name(const Geo &g, int mode)
 {
     if (gram_norm_applicable(g, mode)) return "conv_gram_norm<bf16>";
     if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);
-    static char names[2][4][2][2][64];
-    static bool init = false;
-    if (!init) {
-        for (int b = 0; b < 2; ++b)
-            for (int s = 0; s < 4; ++s)
-                for (int w = 0; w < 2; ++w)
-                    for (int bi = 0; bi < 2; ++bi)
-                        snprintf(names[b][s][w][bi], 64, "conv_contract<%s,%s,%s%s>", b ? "bf16" : "f32", kTileName[s],
-                                 w ? "weighted" : "per_example", bi ? ",bias" : "");
-        init = true;
-    }
+    struct Names {
+        char v[2][2][2][2][64];
+        Names()
+        {
+            for (int b = 0; b < 2; ++b)
+                for (int s = 0; s < 2; ++s)
+                    for (int w = 0; w < 2; ++w)
+                        for (int bi = 0; bi < 2; ++bi)
+                            snprintf(v[b][s][w][bi], 64, "conv_contract<%s,%s,%s%s>", b ? "bf16" : "f32", kTileName[s],
+                                     w ? "weighted" : "per_example", bi ? ",bias" : "");
+        }
+    };
+    static const Names names;               // initialised once, thread-safe
     const FullPlan f = full_plan(g, mode);
-    return names[g.bf16 ? 1 : 0][f.shape][mode == MODE_WEIGHTED ? 1 : 0][g.has_bias ? 1 : 0];
+    return names.v[g.bf16 ? 1 : 0][f.shape][mode == MODE_WEIGHTED ? 1 : 0][g.has_bias ? 1 : 0];
 }
 
 template <int WM, int WN, int TM, int TN>

@@ -662,17 +662,23 @@ size_t conv3x3_norm_partial_count(const Geo &g)
 
 const char *conv3x3_variant_name(const Geo &g, int mode)
 {
-    static char names[2][2][8][56];
-    int slot;
-    switch (g.ow) {
-    case 7: slot = 0; break; case 8: slot = 1; break; case 14: slot = 2; break; case 16: slot = 3; break;
-    case 28: slot = 4; break; case 32: slot = 5; break; default: slot = 6; break;
-    }
-    const int wt = mode == MODE_WEIGHTED ? 1 : 0, st = g.stride == 2 ? 1 : 0;
-    if (!names[st][wt][slot][0])
-        snprintf(names[st][wt][slot], sizeof names[st][wt][slot], "conv3x3_rows<bf16,w%d%s,%s>", g.ow, st ? ",s2" : "",
-                 wt ? "weighted" : "per_example");
-    return names[st][wt][slot];
+    static const int widths[7] = {7, 8, 14, 16, 28, 32, 56};
+    struct Names {
+        char v[2][2][7][56];
+        Names()
+        {
+            for (int st = 0; st < 2; ++st)
+                for (int wt = 0; wt < 2; ++wt)
+                    for (int k = 0; k < 7; ++k)
+                        snprintf(v[st][wt][k], 56, "conv3x3_rows<bf16,w%d%s,%s>", widths[k], st ? ",s2" : "",
+                                 wt ? "weighted" : "per_example");
+        }
+    };
+    static const Names names;               // initialised once, thread-safe
+    int slot = 6;
+    for (int k = 0; k < 7; ++k)
+        if (widths[k] == g.ow) slot = k;
+    return names.v[g.stride == 2 ? 1 : 0][mode == MODE_WEIGHTED ? 1 : 0][slot];
 }
 
 dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,

@@ -31,13 +31,6 @@ struct Geo {
 // Contraction modes of the conv / dense kernels.
 enum Mode { MODE_NORM = 0, MODE_MATERIALISE = 1, MODE_WEIGHTED = 2 };
 
-// Tiling plan of the conv contraction for one descriptor (host side, contract.hip).
-struct ConvPlan {
-    int big;            // 1: 128x128 workgroup tile, 0: 64x64
-    int tiles_m, tiles_n;
-    int splits;         // MODE_WEIGHTED: number of example ranges reduced through the workspace
-};
-ConvPlan conv_plan(const Geo &g, int mode);
 size_t conv_ws_bytes(const Geo &g, int mode);
 const char *conv_variant_name(const Geo &g, int mode);
 dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
@@ -100,28 +93,32 @@ dp_status launch_clip_accumulate(const float *g, size_t stride, const float *sqn
 dp_status launch_clip_accumulate_segments(const float *g, size_t stride, const float *group_sqnorm, const size_t *seg_begin,
                                           const int32_t *seg_group, const float *seg_clip, int n_seg, int n, size_t p,
                                           float *acc, hipStream_t s);
-dp_status launch_add_partial_sums(const float *parts, int n_parts, size_t slice, size_t pw, float *acc_w,
-                                  float *acc_b, hipStream_t s);
 dp_status launch_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,
                                 uint64_t total_batch, uint64_t seed, uint64_t step, uint32_t tensor_id,
                                 hipStream_t s);
 dp_status launch_example_noise(float *acc, size_t p, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
-                               uint64_t step, uint32_t tensor_id, uint64_t first_example, int count, hipStream_t s);
+                               uint64_t step, uint32_t tensor_id, uint64_t first_example, int count,
+                               const uint64_t *step_dev, hipStream_t s);
 dp_status launch_noise_finalize_update(const float *acc, float *theta, float *vbuf, float *out, size_t p, float sigma,
                                        float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
                                        uint32_t tensor_id, float lr, float momentum, hipStream_t s);
+dp_status launch_noise_finalize_flat(const float *acc, float *out, float *theta, float *vbuf, const uint64_t *seg_begin,
+                                     const uint64_t *seg_size, const uint32_t *seg_tensor_id, int n_seg, float sigma,
+                                     float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
+                                     const uint64_t *step_dev, float lr, float momentum, hipStream_t s);
 dp_status launch_philox_raw(uint32_t *raw, size_t p, uint64_t seed, uint64_t step, uint32_t tensor_id,
                             hipStream_t s);
 
 // ---- device helpers --------------------------------------------------------------------
 #if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC__)
 
-// min(1, C / sqrt(n2)); 1 for a zero gradient or an infinite bound.
+// min(1, C / sqrt(n2)); 1 for a zero gradient or an infinite bound; 0 for a squared norm that is
+// NaN or negative (a broken example contributes nothing instead of passing unclipped).
 __device__ __forceinline__ float clip_factor(float n2, float clip_c)
 {
-    if (!(n2 > 0.0f)) return 1.0f;
+    if (n2 == 0.0f) return 1.0f;
     const float r = clip_c / sqrtf(n2);     // +inf / x = +inf -> 1
-    return r < 1.0f ? r : 1.0f;
+    return r < 1.0f ? r : (r >= 1.0f ? 1.0f : 0.0f);
 }
 
 __device__ __forceinline__ float wave_sum(float v)

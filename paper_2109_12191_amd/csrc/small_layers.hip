@@ -220,8 +220,9 @@ dp_status launch_dense(const Geo &g, int mode, const void *x, const void *dy, fl
 }
 
 // ------------------------------------------------------------------------------------------
-// GroupNorm affine: one workgroup per (example, group).  Mean and biased variance of the
-// group's (C/G)*H*W elements in two passes (the group is L2-resident after the first), then
+// GroupNorm affine, groups of more than GN_CMAX channels: one workgroup per (example, group).  Mean
+// and biased variance of the group's (C/G)*H*W elements in two passes (the group is L2-resident
+// after the first), then
 // each wave takes channels of the group in turn and reduces sum dy*xhat and sum dy with
 // shuffles.
 struct GnArgs {
@@ -245,12 +246,14 @@ __global__ void __launch_bounds__(256) gn_affine_3pass_kernel(const GnArgs a)
     const E *xg = static_cast<const E *>(a.x) + first;
     const E *dyg = static_cast<const E *>(a.dy) + first;
 
+    // the mean is taken about the group's first element, so that a group far from zero keeps its spread
+    const float k = In<BF16>::ld(xg);
     float s = 0.0f;
-    for (int p = threadIdx.x; p < cnt; p += 256) s += In<BF16>::ld(xg + p);
-    const float mean = block_sum<4>(s, red) / (float)cnt;
+    for (int p = threadIdx.x; p < cnt; p += 256) s += In<BF16>::ld(xg + p) - k;
+    const float m1 = block_sum<4>(s, red) / (float)cnt;              // mean - k
     float v = 0.0f;
     for (int p = threadIdx.x; p < cnt; p += 256) {
-        const float d = In<BF16>::ld(xg + p) - mean;
+        const float d = (In<BF16>::ld(xg + p) - k) - m1;
         v += d * d;
     }
     const float var = block_sum<4>(v, red) / (float)cnt;
@@ -263,7 +266,7 @@ __global__ void __launch_bounds__(256) gn_affine_3pass_kernel(const GnArgs a)
         float sg = 0.0f, sb = 0.0f;
         for (int p = lane; p < a.hw; p += 64) {
             const float d = In<BF16>::ld(dc + p);
-            sg += d * ((In<BF16>::ld(xc + p) - mean) * rstd);
+            sg += d * (((In<BF16>::ld(xc + p) - k) - m1) * rstd);
             sb += d;
         }
         sg = wave_sum(sg);

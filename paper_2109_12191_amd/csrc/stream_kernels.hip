@@ -255,28 +255,6 @@ dp_status launch_clip_accumulate(const float *g, size_t stride, const float *sqn
     return check_launch("clip_accumulate");
 }
 
-// Combine the example ranges of the recomputing form: each of n_parts workspace slices holds
-// [weights (pw) | bias (slice - pw)]; acc_w[e] += sum_k parts[k, e], k increasing; likewise acc_b.
-__global__ void __launch_bounds__(256) add_partial_sums_kernel(const float *__restrict__ parts, int n_parts,
-                                                                size_t slice, size_t pw, float *__restrict__ acc_w,
-                                                                float *__restrict__ acc_b)
-{
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= slice) return;
-    float s = 0.0f;
-    for (int k = 0; k < n_parts; ++k) s += parts[(size_t)k * slice + e];
-    if (e < pw) acc_w[e] += s;
-    else acc_b[e - pw] += s;
-}
-
-dp_status launch_add_partial_sums(const float *parts, int n_parts, size_t slice, size_t pw, float *acc_w,
-                                  float *acc_b, hipStream_t s)
-{
-    hipLaunchKernelGGL(add_partial_sums_kernel, dim3((unsigned)((slice + 255) / 256)), dim3(256), 0, s, parts,
-                       n_parts, slice, pw, acc_w, acc_b);
-    return check_launch("add_partial_sums");
-}
-
 // ------------------------------------------------------------------------------------------
 // H5: Philox4x32-10 (Salmon et al., SC'11) + Box-Muller + finalize.
 struct Philox4 { uint32_t x, y, z, w; };
@@ -362,12 +340,14 @@ dp_status launch_noise_finalize(const float *acc, float *out, size_t p, float si
 // over `count` examples starting at `first`; example j's draws use the counter (q, j, tensor_id, step) and the
 // key (seed lo, seed hi ^ 0x50455245).  One thread per four parameters; the examples are summed in order.
 __global__ void __launch_bounds__(256) example_noise_kernel(float *__restrict__ acc, size_t p, float scale, uint32_t k0,
-                                                             uint32_t k1, uint32_t step_lo, uint32_t tensor_id,
-                                                             uint32_t first, int count)
+                                                             uint32_t k1, uint32_t step_arg, uint32_t tensor_id,
+                                                             uint32_t first, int count,
+                                                             const unsigned long long *__restrict__ step_dev)
 {
     const uint64_t q = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     const size_t e = (size_t)q * 4;
     if (e >= p) return;
+    const uint32_t step_lo = step_dev ? (uint32_t)*step_dev : step_arg;
     float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int j = 0; j < count; ++j) {
         const Philox4 r = philox4x32_10((uint32_t)q, first + (uint32_t)j, tensor_id, step_lo, k0, k1);
@@ -387,14 +367,15 @@ __global__ void __launch_bounds__(256) example_noise_kernel(float *__restrict__ 
 }
 
 dp_status launch_example_noise(float *acc, size_t p, float sigma, float clip_total, uint64_t total_batch, uint64_t seed,
-                               uint64_t step, uint32_t tensor_id, uint64_t first_example, int count, hipStream_t s)
+                               uint64_t step, uint32_t tensor_id, uint64_t first_example, int count,
+                               const uint64_t *step_dev, hipStream_t s)
 {
     if (sigma == 0.0f) return DP_OK;
     const size_t calls = (p + 3) / 4;
     const float scale = sigma * clip_total / sqrtf((float)total_batch);
     hipLaunchKernelGGL(example_noise_kernel, dim3((unsigned)((calls + 255) / 256)), dim3(256), 0, s, acc, p, scale,
                        (uint32_t)seed, (uint32_t)(seed >> 32) ^ 0x50455245u, (uint32_t)step, tensor_id,
-                       (uint32_t)first_example, count);
+                       (uint32_t)first_example, count, reinterpret_cast<const unsigned long long *>(step_dev));
     return check_launch("example_noise");
 }
 
@@ -467,6 +448,123 @@ dp_status launch_noise_finalize_update(const float *acc, float *theta, float *vb
         hipLaunchKernelGGL(noise_finalize_update_kernel<false>, dim3(blocks), dim3(256), 0, s, acc, theta, vbuf, out, p,
                            0.0f, inv_batch, lr, momentum, 0u, 0u, 0u, 0u);
     return check_launch("noise_finalize_update");
+}
+
+// H5 over a whole flat parameter vector in one launch.  The vector holds several tensors (each starting
+// at a multiple of 4 floats, padding after a tensor is left untouched); every tensor keeps its own
+// Philox counters (tensor id, element index within the tensor), so the bits are those of one
+// dp_add_noise_finalize call per tensor.  A workgroup covers FLAT_BLOCK consecutive elements of ONE
+// tensor: it finds its tensor by bisection over the tensors' first-workgroup numbers (uniform, scalar
+// loads), so no thread straddles two tensors.  The step may come from a device word, which lets a
+// captured graph draw fresh noise on every replay.
+constexpr int FLAT_SEG_MAX = 128;
+constexpr int FLAT_BLOCK = 1024;                // elements per workgroup: 256 threads x 4
+struct FlatArgs {
+    unsigned long long begin[FLAT_SEG_MAX];     // first element of tensor k in the flat vector
+    unsigned int size[FLAT_SEG_MAX];            // elements of tensor k
+    unsigned int first_block[FLAT_SEG_MAX + 1]; // workgroup where tensor k starts; [n_seg] = grid size
+    unsigned int tensor_id[FLAT_SEG_MAX];
+    int n_seg;
+};
+
+template <bool NOISE, bool UPDATE>
+__global__ void __launch_bounds__(256) noise_finalize_flat_kernel(const float *__restrict__ acc, float *__restrict__ out,
+                                                                   float *__restrict__ theta, float *__restrict__ vbuf,
+                                                                   const FlatArgs fa, float scale, float inv_batch, float lr,
+                                                                   float momentum, uint32_t k0, uint32_t k1, uint32_t step_lo,
+                                                                   const unsigned long long *__restrict__ step_dev)
+{
+    int lo = 0, hi = fa.n_seg - 1;              // last tensor whose first workgroup is <= blockIdx.x
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (fa.first_block[mid] <= blockIdx.x) lo = mid; else hi = mid - 1;
+    }
+    const uint32_t size = fa.size[lo];
+    const uint32_t q = (blockIdx.x - fa.first_block[lo]) * 256u + threadIdx.x;       // Philox call within the tensor
+    const uint32_t e = q * 4u;
+    if (e >= size) return;
+    const size_t at = (size_t)fa.begin[lo] + e;
+    const bool full = e + 4u <= size;
+    // the loads go out first; the integer and transcendental work below hides their latency
+    float a[4] = {0.0f, 0.0f, 0.0f, 0.0f}, t[4] = {0.0f, 0.0f, 0.0f, 0.0f}, v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (full) {
+        const float4 av = *reinterpret_cast<const float4 *>(acc + at);
+        a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
+        if constexpr (UPDATE) {
+            const float4 tv = *reinterpret_cast<const float4 *>(theta + at);
+            t[0] = tv.x; t[1] = tv.y; t[2] = tv.z; t[3] = tv.w;
+            if (vbuf) { const float4 vv = *reinterpret_cast<const float4 *>(vbuf + at); v[0] = vv.x; v[1] = vv.y; v[2] = vv.z; v[3] = vv.w; }
+        }
+    } else {
+        for (int j = 0; e + j < size; ++j) {
+            a[j] = acc[at + j];
+            if constexpr (UPDATE) { t[j] = theta[at + j]; if (vbuf) v[j] = vbuf[at + j]; }
+        }
+    }
+    float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if constexpr (NOISE) {
+        const uint32_t step_word = step_dev ? (uint32_t)*step_dev : step_lo;
+        const Philox4 r = philox4x32_10(q, 0u, fa.tensor_id[lo], step_word, k0, k1);
+        box_muller(r.x, r.y, z[0], z[1]);
+        box_muller(r.z, r.w, z[2], z[3]);
+    }
+    float g[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        g[j] = (a[j] + scale * z[j]) * inv_batch;
+        if constexpr (UPDATE) {
+            if (vbuf) { v[j] = momentum * v[j] + g[j]; t[j] -= lr * v[j]; }
+            else t[j] -= lr * g[j];
+        }
+    }
+    if (full) {
+        if (out) *reinterpret_cast<float4 *>(out + at) = make_float4(g[0], g[1], g[2], g[3]);
+        if constexpr (UPDATE) {
+            *reinterpret_cast<float4 *>(theta + at) = make_float4(t[0], t[1], t[2], t[3]);
+            if (vbuf) *reinterpret_cast<float4 *>(vbuf + at) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    } else {
+        for (int j = 0; e + j < size; ++j) {
+            if (out) out[at + j] = g[j];
+            if constexpr (UPDATE) { theta[at + j] = t[j]; if (vbuf) vbuf[at + j] = v[j]; }
+        }
+    }
+}
+
+dp_status launch_noise_finalize_flat(const float *acc, float *out, float *theta, float *vbuf, const uint64_t *seg_begin,
+                                     const uint64_t *seg_size, const uint32_t *seg_tensor_id, int n_seg, float sigma,
+                                     float clip_total, uint64_t total_batch, uint64_t seed, uint64_t step,
+                                     const uint64_t *step_dev, float lr, float momentum, hipStream_t s)
+{
+    const float inv_batch = 1.0f / (float)total_batch;
+    const float scale = sigma > 0.0f ? sigma * clip_total : 0.0f;
+    for (int s0 = 0; s0 < n_seg; s0 += FLAT_SEG_MAX) {
+        FlatArgs fa;
+        fa.n_seg = n_seg - s0 < FLAT_SEG_MAX ? n_seg - s0 : FLAT_SEG_MAX;
+        unsigned int blocks = 0;
+        for (int k = 0; k < FLAT_SEG_MAX; ++k) {
+            const bool live = k < fa.n_seg;
+            fa.begin[k] = live ? seg_begin[s0 + k] : 0;
+            fa.size[k] = live ? (unsigned int)seg_size[s0 + k] : 0;
+            fa.tensor_id[k] = live ? seg_tensor_id[s0 + k] : 0;
+            fa.first_block[k] = blocks;
+            if (live) blocks += (unsigned int)((seg_size[s0 + k] + FLAT_BLOCK - 1) / FLAT_BLOCK);
+        }
+        fa.first_block[FLAT_SEG_MAX] = blocks;
+        const unsigned long long *sd = reinterpret_cast<const unsigned long long *>(step_dev);
+        const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32), st = (uint32_t)step;
+        const bool noise = sigma > 0.0f;
+        if (theta) {
+            if (noise) hipLaunchKernelGGL((noise_finalize_flat_kernel<true, true>), dim3(blocks), dim3(256), 0, s, acc, out, theta, vbuf, fa, scale, inv_batch, lr, momentum, k0, k1, st, sd);
+            else hipLaunchKernelGGL((noise_finalize_flat_kernel<false, true>), dim3(blocks), dim3(256), 0, s, acc, out, theta, vbuf, fa, scale, inv_batch, lr, momentum, k0, k1, st, sd);
+        } else {
+            if (noise) hipLaunchKernelGGL((noise_finalize_flat_kernel<true, false>), dim3(blocks), dim3(256), 0, s, acc, out, theta, vbuf, fa, scale, inv_batch, lr, momentum, k0, k1, st, sd);
+            else hipLaunchKernelGGL((noise_finalize_flat_kernel<false, false>), dim3(blocks), dim3(256), 0, s, acc, out, theta, vbuf, fa, scale, inv_batch, lr, momentum, k0, k1, st, sd);
+        }
+        const dp_status stt = check_launch("noise_finalize_flat");
+        if (stt != DP_OK) return stt;
+    }
+    return DP_OK;
 }
 
 __global__ void __launch_bounds__(256) philox_raw_kernel(uint32_t *__restrict__ raw, size_t p, uint32_t k0,

@@ -21,10 +21,6 @@ import torch
 
 from . import binding as B
 
-_HBM = 8.0e12
-_MFMA = {"bf16": 2.5e15, "f32": 157.3e12}
-
-
 def _pad4(v: int) -> int:
     return (v + 3) & ~3
 
@@ -46,7 +42,7 @@ class PrivatiseStep:
         self.pw = [B.dp_weight_count(d) for d in self.descs]
         self.pb = [B.dp_bias_count(d) for d in self.descs]
         self.group_of_layer = list(wl.group_of_layer)
-        self.group_clip = [float(c) for c in wl.group_clip]
+        self.group_clip, self.clip_total = B.dp_group_clip_bounds(wl.clip_c, wl.n_groups)
         self.n_groups = wl.n_groups
         self.form = [self._choose(l, mode) for l in self.layers]
 
@@ -66,6 +62,11 @@ class PrivatiseStep:
             if self.form[i] == "materialise":
                 self.p_mat = pos
         self.p_total = max(pos, 4)
+        # every tensor of the flat vector with its Philox tensor id (2*layer weight, 2*layer+1 bias), in
+        # the order they lie in memory: the table of the one-launch finalize
+        tensors = sorted([(self.off_w[i], self.pw[i], 2 * i) for i in range(L)] +
+                         [(self.off_b[i], self.pb[i], 2 * i + 1) for i in range(L) if self.pb[i]])
+        self._tensors = B.TensorTable([t[0] for t in tensors], [t[1] for t in tensors], [t[2] for t in tensors])
         mat = [i for i in order if self.form[i] == "materialise"]
         self._segments = B.SegmentTable([self.off_w[i] for i in mat], [self.group_of_layer[i] for i in mat],
                                         [self.group_clip[self.group_of_layer[i]] for i in mat]) if mat else None
@@ -102,6 +103,11 @@ class PrivatiseStep:
         self._last = 0                           # copy used by the most recent micro-step
         self.graph = None
         self.micro_steps_done = 0
+        # Optimiser-step counter: the `step` word of the Philox counters.  The kernels read it from a device
+        # word, so a captured graph draws fresh noise on every replay; finalize() advances it, `step` mirrors
+        # it on the host.  Two optimiser steps never share a noise draw.
+        self.step = int(wl.step)
+        self._step_dev = torch.tensor([self.step], dtype=torch.int64, device=dev)
         # optional timing probe (bench.py): an object with arm(variant, flops, bytes) that asks the
         # library to bracket the next contraction kernel with a pair of events
         self.probe = None
@@ -174,6 +180,11 @@ class PrivatiseStep:
 
     def theta_b(self, li: int) -> Optional[torch.Tensor]:
         return self.theta[self.off_b[li]: self.off_b[li] + self.pb[li]] if self.pb[li] else None
+
+    def set_step(self, step: int):
+        """Set the optimiser-step counter (e.g. when a run is resumed)."""
+        self.step = int(step)
+        self._step_dev.fill_(self.step)
 
     def begin_step(self):
         self.acc.zero_()
@@ -269,11 +280,11 @@ class PrivatiseStep:
         updates those tensors."""
         wl = self.wl
         first = self.micro_steps_done * self.n
-        B.dp_add_example_noise(self.acc_w(li).data_ptr(), self.pw[li], wl.sigma, wl.clip_total, wl.total_batch,
-                               wl.philox_seed, wl.step, 2 * li, first, self.n, stream=st)
+        B.dp_add_example_noise(self.acc_w(li).data_ptr(), self.pw[li], wl.sigma, self.clip_total, wl.total_batch,
+                               wl.philox_seed, 0, 2 * li, first, self.n, step_dev=self._step_dev, stream=st)
         if self.pb[li]:
-            B.dp_add_example_noise(self.acc_b(li).data_ptr(), self.pb[li], wl.sigma, wl.clip_total, wl.total_batch,
-                                   wl.philox_seed, wl.step, 2 * li + 1, first, self.n, stream=st)
+            B.dp_add_example_noise(self.acc_b(li).data_ptr(), self.pb[li], wl.sigma, self.clip_total, wl.total_batch,
+                                   wl.philox_seed, 0, 2 * li + 1, first, self.n, step_dev=self._step_dev, stream=st)
 
     def _drain(self):
         """The current stream waits for every clipped sum issued so far."""
@@ -282,35 +293,21 @@ class PrivatiseStep:
             main.wait_stream(st)
 
     def finalize(self):
-        """H5 on every parameter tensor; the per-tensor calls are independent and go round the side streams."""
+        """H5 on the whole flat parameter vector in one launch (every tensor keeps its own Philox counters),
+        with the SGD step fused in when enable_update() was called; then the step counter advances."""
         wl = self.wl
         self._drain()
-        main = torch.cuda.current_stream()
-        for st in self.side:
-            st.wait_stream(main)
-        k = 0
-        for li in range(len(self.layers)):
-            st = self.side[k % len(self.side)] if self.side else None
-            k += 1
-            self._finalize_tensor(self.off_w[li], self.pw[li], 2 * li, st)
-            if self.pb[li]:
-                self._finalize_tensor(self.off_b[li], self.pb[li], 2 * li + 1, st)
-        for st in self.side:
-            main.wait_stream(st)
-
-    def _finalize_tensor(self, off: int, p: int, tensor_id: int, st):
-        wl = self.wl
-        acc, out = self.acc[off:].data_ptr(), self.out[off:].data_ptr()
         sigma = wl.sigma if self.noise == "once" else 0.0        # per-example form: the noise is already in acc
         if self._update is None:
-            B.dp_add_noise_finalize(acc, out, p, sigma, wl.clip_total, wl.total_batch, wl.philox_seed, wl.step,
-                                    tensor_id, stream=st)
+            B.dp_add_noise_finalize_flat(self.acc, self.out, self._tensors, sigma, self.clip_total, wl.total_batch,
+                                         wl.philox_seed, step_dev=self._step_dev)
         else:
             lr, momentum, keep = self._update
-            B.dp_add_noise_finalize_update(acc, self.theta[off:].data_ptr(),
-                                           self.velocity[off:].data_ptr() if self.velocity is not None else None,
-                                           out if keep else None, p, sigma, wl.clip_total, wl.total_batch,
-                                           wl.philox_seed, wl.step, tensor_id, lr, momentum, stream=st)
+            B.dp_add_noise_finalize_flat(self.acc, self.out if keep else None, self._tensors, sigma, self.clip_total,
+                                         wl.total_batch, wl.philox_seed, step_dev=self._step_dev, theta=self.theta,
+                                         velocity=self.velocity, lr=lr, momentum=momentum)
+        self._step_dev.add_(1)
+        self.step += 1
 
     def run(self, inputs_per_micro_step: Sequence[Sequence]):
         self.begin_step()
@@ -324,14 +321,19 @@ class PrivatiseStep:
         replay() then re-issues every launch without host work.  Only kernels are recorded (the
         accumulator is cleared by a fill kernel, never by a memset node)."""
         assert self.probe is None or not getattr(self.probe, "enabled", False)
+        step0 = self.step
         self.run(inputs_per_micro_step)          # warm-up outside capture (lazy module loads)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             self.run(inputs_per_micro_step)
         self.graph = graph
+        self.set_step(step0)                     # recording consumed no optimiser step
         return graph
 
     def replay(self):
+        """Re-issue the recorded step.  The step counter lives in device memory and is advanced by the graph
+        itself, so every replay draws fresh noise."""
         self.graph.replay()
+        self.step += 1
         return self.out

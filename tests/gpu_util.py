@@ -2,6 +2,10 @@
 import numpy as np
 import torch
 
+import os
+import sys
+import time
+
 F32_TOL = 1e-4      # fp32 paths: relative error bound stated for the build
 BF16_TOL = 2e-2     # paths with bf16 inputs
 
@@ -35,3 +39,16 @@ def assert_close(got, ref, tol, what=""):
     l2, mx = rel_err(got, ref)
     assert l2 <= tol and mx <= tol, f"{what}: rel l2 {l2:.3e}, rel max {mx:.3e} > {tol:.1e}"
     return l2, mx
+
+
+_PROGRESS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+
+
+def progress(msg: str):
+    """A line of progress from a long test: printed, and appended to gpurun_out/test_progress.log when that
+    folder exists (output of a passing test is captured, a file is visible while the test still runs)."""
+    line = f"[{time.strftime('%H:%M:%S')}] {msg}"
+    print(line, flush=True)
+    if os.path.isdir(_PROGRESS):
+        with open(os.path.join(_PROGRESS, "test_progress.log"), "a") as f:
+            f.write(line + "\n")

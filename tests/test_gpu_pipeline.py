@@ -1,6 +1,8 @@
 """GPU parity of the whole path (all five steps through the C ABI) against the fp64 oracle,
 on the five workloads -- full size where the oracle finishes in seconds, otherwise the same
 layer structure on smaller feature maps / fewer examples."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -100,28 +102,62 @@ def test_split_and_resume_gives_same_bits():
 
 
 def test_graph_replay_with_side_streams_matches_eager_every_time():
-    """The whole step recorded into a HIP graph (layers spread over side streams) gives the
-    same bits as the call-by-call path, on every replay, with eager work in between."""
+    """The whole step recorded into a HIP graph (layers spread over side streams) gives the same bits as the
+    call-by-call path at the same optimiser step, on every replay, with eager work in between; consecutive
+    steps draw different noise (the step counter is a device word that the graph itself advances)."""
     wl = get_workload("resnet50", n=4, accum=2, hw=64)
     steps = [[(dev(x, wl.dtype), dev(dy, wl.dtype)) for x, dy in make_inputs(wl, m)] for m in range(wl.accum)]
     eager = dp.PrivatiseStep(wl, streams=1)
-    want = eager.run(steps).clone()
+    want = []
+    for k in range(3):
+        assert eager.step == k
+        want.append(eager.run(steps).clone())
     torch.cuda.synchronize()
+    assert not torch.equal(want[0], want[1]) and not torch.equal(want[1], want[2])
     g = dp.PrivatiseStep(wl, streams=4)
     g.capture(steps)
+    assert g.step == 0
     for rep in range(3):
         g.out.zero_()
         g.acc.fill_(123.0)                 # the graph must clear the accumulator itself
         torch.cuda.synchronize()
         got = g.replay()
         torch.cuda.synchronize()
-        assert torch.equal(got, want), f"replay {rep}"
-        again = eager.run(steps)           # eager work between replays
+        assert torch.equal(got, want[rep]), f"replay {rep}"
+        eager.set_step(rep)                # eager work between replays
+        again = eager.run(steps)
         torch.cuda.synchronize()
-        assert torch.equal(again, want)
+        assert torch.equal(again, want[rep])
+    assert g.step == 3 and int(g._step_dev.item()) == 3
     # multi-stream without a graph as well
     ms = dp.PrivatiseStep(wl, streams=3)
-    assert torch.equal(ms.run(steps), want)
+    assert torch.equal(ms.run(steps), want[0])
+
+
+def test_consecutive_optimiser_steps_draw_fresh_noise_and_match_the_oracle():
+    """Two optimiser steps in a row on the same data: the released gradients carry different noise, and each
+    matches the oracle evaluated at its own step number (eager and graph replay)."""
+    from dataclasses import replace
+    wl = get_workload("conv3x3", n=4, accum=2, hw=14)
+    host_steps = [make_inputs(wl, m) for m in range(wl.accum)]
+    refs = [oracle.privatise(replace(wl, step=wl.step + k), host_steps) for k in range(2)]
+    steps = [[(dev(x), dev(dy)) for x, dy in inputs] for inputs in host_steps]
+    for use_graph in (False, True):
+        ps = dp.PrivatiseStep(wl, streams=2 if use_graph else 1)
+        if use_graph:
+            ps.capture(steps)
+        outs = []
+        for k in range(2):
+            out = ps.replay() if use_graph else ps.run(steps)
+            torch.cuda.synchronize()
+            outs.append(out.clone())
+            for li, l in enumerate(wl.layers):
+                assert_close(host(ps.out_w(li)), refs[k]["out_w"][li], F32_TOL, f"graph={use_graph} step {k} out_w")
+                assert_close(host(ps.out_b(li)), refs[k]["out_b"][li], F32_TOL, f"graph={use_graph} step {k} out_b")
+        diff = host(outs[1] - outs[0])[: ps.pw[0]]
+        # the clipped sums cancel; what is left is the difference of two independent noise draws
+        sigma_c_over_b = wl.sigma * wl.clip_c / wl.total_batch
+        assert abs(diff.std() / (math.sqrt(2.0) * sigma_c_over_b) - 1.0) < 0.05
 
 
 def test_fused_optimiser_update_over_two_steps():
@@ -134,19 +170,22 @@ def test_fused_optimiser_update_over_two_steps():
     rng = np.random.default_rng(23)
     theta0 = rng.standard_normal(ps.p_total).astype(np.float32)
     ps.enable_update(lr=0.05, momentum=0.9, theta=dev(theta0))
+    from dataclasses import replace
+    ref1 = oracle.privatise(replace(wl, step=wl.step + 1), [make_inputs(wl, m) for m in range(wl.accum)])
     ps.run(steps)
     ps.set_lr(0.025)
-    ps.run(steps)                                    # same data and Philox step: same gradient again
+    ps.run(steps)                                    # same data, next optimiser step: fresh noise
     torch.cuda.synchronize()
     for li, l in enumerate(wl.layers):
-        for off, cnt, g in ((ps.off_w[li], ps.pw[li], ref["out_w"][li]), (ps.off_b[li], ps.pb[li], ref["out_b"][li])):
+        for off, cnt, g, g1 in ((ps.off_w[li], ps.pw[li], ref["out_w"][li], ref1["out_w"][li]),
+                                (ps.off_b[li], ps.pb[li], ref["out_b"][li], ref1["out_b"][li])):
             if not cnt:
                 continue
             th, v = theta0[off: off + cnt].astype(np.float64), np.zeros(cnt)
             th, v = oracle.sgd_update(g.reshape(-1), th, v, 0.05, 0.9)
-            th, v = oracle.sgd_update(g.reshape(-1), th, v, 0.025, 0.9)
+            th, v = oracle.sgd_update(g1.reshape(-1), th, v, 0.025, 0.9)
             assert_close(host(ps.theta[off: off + cnt]), th, F32_TOL, f"theta layer {li}")
-            assert_close(host(ps.out[off: off + cnt]), g.reshape(-1), F32_TOL, f"gradient layer {li}")
+            assert_close(host(ps.out[off: off + cnt]), g1.reshape(-1), F32_TOL, f"gradient layer {li}")
 
 
 @pytest.mark.parametrize("streams", [1, 3])

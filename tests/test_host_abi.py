@@ -192,7 +192,7 @@ def test_fused_update_rejects_bad_arguments(lib):
 def test_example_noise_rejects_bad_arguments(lib):
     f = lib.dp_add_example_noise
     def call(acc=FAKE, p=16, sigma=1.0, clip=1.0, batch=8, first=0, cnt=4):
-        return f(acc, p, sigma, clip, batch, 0, 0, 0, first, cnt, None)
+        return f(acc, p, sigma, clip, batch, 0, 0, 0, first, cnt, None, None)
     assert call(acc=None) == B.DP_ERR_INVALID_ARG
     assert call(p=0) == B.DP_ERR_INVALID_ARG
     assert call(sigma=float("nan")) == B.DP_ERR_INVALID_ARG
@@ -225,3 +225,45 @@ def test_clip_accumulate_segments_rejects_bad_tables(lib):
     assert call(groups=(0, 2)) == B.DP_ERR_INVALID_ARG           # group out of range
     assert call(clips=(1.0, 0.0)) == B.DP_ERR_INVALID_ARG
     assert call(n=0) == B.DP_ERR_INVALID_ARG
+
+
+def test_group_clip_bounds_follow_section_3_5(lib):
+    """M groups -> C / sqrt(M) each; the bound on the whole gradient (the noise scale) stays C.  Literal values:
+    these are the library's own numbers, not the oracle's."""
+    gc, tot = dp.dp_group_clip_bounds(1.0, 54)
+    assert len(gc) == 54 and all(abs(c - 0.13608276348795434) < 1e-8 for c in gc)
+    assert abs(tot - 1.0) < 1e-6
+    gc, tot = dp.dp_group_clip_bounds(1.5, 1)
+    assert gc == [1.5] and tot == 1.5
+    gc, tot = dp.dp_group_clip_bounds(0.3, 4)
+    assert all(abs(c - 0.15) < 1e-8 for c in gc) and abs(tot - 0.3) < 1e-7
+    gc, tot = dp.dp_group_clip_bounds(math.inf, 3)
+    assert all(math.isinf(c) for c in gc) and math.isinf(tot)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_group_clip_bounds, 0.0, 4)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_group_clip_bounds, float("nan"), 4)
+    _raises(B.DP_ERR_INVALID_ARG, dp.dp_group_clip_bounds, 1.0, 0)
+    assert lib.dp_group_clip_bounds(1.0, 2, None, None) == B.DP_ERR_INVALID_ARG
+
+
+def test_flat_finalize_rejects_bad_tables(lib):
+    import ctypes as C
+    f = lib.dp_add_noise_finalize_flat
+    def call(begins=(0, 8), sizes=(8, 5), ids=(0, 1), acc=FAKE, out=FAKE, theta=None, vel=None, sigma=1.0, clip=1.0,
+             batch=4, lr=0.1, mom=0.0, step_dev=None):
+        k = len(begins)
+        return f(acc, out, theta, vel, C.cast((C.c_uint64 * k)(*begins), C.c_void_p), C.cast((C.c_uint64 * k)(*sizes), C.c_void_p),
+                 C.cast((C.c_uint32 * k)(*ids), C.c_void_p), k, sigma, clip, batch, 0, 0, step_dev, lr, mom, None)
+    assert call(acc=None) == B.DP_ERR_INVALID_ARG
+    assert call(out=None) == B.DP_ERR_INVALID_ARG                 # no output and no theta: nothing to write
+    assert call(begins=(0, 6)) == B.DP_ERR_INVALID_ARG            # not a multiple of 4
+    assert call(begins=(0, 4)) == B.DP_ERR_INVALID_ARG            # overlaps the first tensor
+    assert call(sizes=(8, 0)) == B.DP_ERR_INVALID_ARG
+    assert call(sizes=(8, 1 << 32)) == B.DP_ERR_UNSUPPORTED
+    assert call(sigma=-1.0) == B.DP_ERR_INVALID_ARG
+    assert call(clip=float("inf")) == B.DP_ERR_INVALID_ARG
+    assert call(batch=0) == B.DP_ERR_INVALID_ARG
+    assert call(vel=FAKE) == B.DP_ERR_INVALID_ARG                 # velocity without theta
+    assert call(theta=FAKE, mom=0.9) == B.DP_ERR_INVALID_ARG      # momentum without a velocity buffer
+    assert call(theta=FAKE, lr=float("nan")) == B.DP_ERR_INVALID_ARG
+    assert call(step_dev=FAKE + 4) == B.DP_ERR_INVALID_ARG        # 8-byte alignment
+    assert lib.dp_add_noise_finalize_flat(FAKE, FAKE, None, None, None, None, None, 1, 1.0, 1.0, 4, 0, 0, None, 0.0, 0.0, None) == B.DP_ERR_INVALID_ARG

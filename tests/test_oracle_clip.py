@@ -43,7 +43,7 @@ def test_every_clipped_example_is_within_bound():
         for seed_step in range(8):
             inputs = make_inputs(wl, seed_step)
             acc_w, acc_b = oracle.new_accumulators(wl.layers)
-            n2, f = oracle.clip_accumulate(wl.layers, inputs, wl.group_of_layer, wl.group_clip, acc_w, acc_b)
+            n2, f = oracle.clip_accumulate(wl.layers, inputs, wl.group_of_layer, oracle.group_bounds(wl.clip_c, wl.n_groups)[0], acc_w, acc_b)
             tot = sum(oracle.sqnorm(a) for a in acc_w) + sum(oracle.sqnorm(a) for a in acc_b if a is not None)
             assert math.sqrt(tot) <= c * (1 + 1e-12)
             if n2[0, 0] > c * c:
@@ -95,7 +95,7 @@ def test_clip_factor_definition_both_branches_and_zero_gradient():
     c = float(np.median(norms[norms > 0]))
     wl = replace(wl, clip_c=c)
     acc_w, acc_b = oracle.new_accumulators(wl.layers)
-    n2, f = oracle.clip_accumulate(wl.layers, inputs, wl.group_of_layer, wl.group_clip, acc_w, acc_b)
+    n2, f = oracle.clip_accumulate(wl.layers, inputs, wl.group_of_layer, oracle.group_bounds(wl.clip_c, wl.n_groups)[0], acc_w, acc_b)
     assert np.allclose(np.sqrt(n2[:, 0]), norms, rtol=1e-13)
     assert f[3, 0] == 1.0 and n2[3, 0] == 0.0
     assert (f[:, 0] < 1).sum() >= 3 and (f[:, 0] == 1).sum() >= 3
@@ -113,12 +113,14 @@ def test_per_group_clipping_respects_the_overall_bound():
     """Section 3.5: M groups each clipped to C/sqrt(M) => sum_g ||clip(g^g)||^2 <= C^2."""
     wl = _wl(clip_mode="per_layer", clip_c=0.3, n=4)
     m = len(wl.layers)
-    assert wl.n_groups == m and all(abs(c - 0.3 / math.sqrt(m)) < 1e-15 for c in wl.group_clip)
-    assert abs(wl.clip_total - 0.3) < 1e-15
+    bounds, total = oracle.group_bounds(0.3, m)
+    assert wl.n_groups == m and len(bounds) == m and all(abs(c - 0.3 / math.sqrt(m)) < 1e-15 for c in bounds)
+    assert abs(total - 0.3) < 1e-15                      # the noise is scaled by the overall bound C, not by C_g
+    assert oracle.group_bounds(1.7, 1) == ([1.7], 1.7)   # one group: the global bound of Section 2
     inputs = make_inputs(wl, 0)
     grads = _per_example_grads(wl, inputs)
     acc_w, acc_b = oracle.new_accumulators(wl.layers)
-    n2, f = oracle.clip_accumulate(wl.layers, inputs, wl.group_of_layer, wl.group_clip, acc_w, acc_b)
+    n2, f = oracle.clip_accumulate(wl.layers, inputs, wl.group_of_layer, oracle.group_bounds(wl.clip_c, wl.n_groups)[0], acc_w, acc_b)
     for i in range(4):
         tot = 0.0
         for g in range(m):
@@ -145,11 +147,11 @@ def test_accumulation_is_linear_permutation_invariant_and_resumable():
         assert np.allclose(a["acc_w"][li], c["acc_w"][li], rtol=1e-12, atol=1e-15)
     # stop after one micro-step, copy the accumulator out and in, continue: same result
     acc_w, acc_b = oracle.new_accumulators(wl.layers)
-    oracle.clip_accumulate(wl.layers, steps[0], wl.group_of_layer, wl.group_clip, acc_w, acc_b)
+    oracle.clip_accumulate(wl.layers, steps[0], wl.group_of_layer, oracle.group_bounds(wl.clip_c, wl.n_groups)[0], acc_w, acc_b)
     saved_w = [x.copy() for x in acc_w]
     saved_b = [None if x is None else x.copy() for x in acc_b]
     for m in (1, 2):
-        oracle.clip_accumulate(wl.layers, steps[m], wl.group_of_layer, wl.group_clip, saved_w, saved_b)
+        oracle.clip_accumulate(wl.layers, steps[m], wl.group_of_layer, oracle.group_bounds(wl.clip_c, wl.n_groups)[0], saved_w, saved_b)
     for li in range(len(wl.layers)):
         assert np.allclose(saved_w[li], a["acc_w"][li], rtol=1e-13, atol=1e-16)
     # threads do not change the result beyond round-off
@@ -165,11 +167,11 @@ def test_output_is_clipped_sum_plus_scaled_noise_over_batch():
     res = oracle.privatise(wl, steps)
     for li, l in enumerate(wl.layers):
         z = oracle.noise_normal(wl.philox_seed, wl.step, 2 * li, l.pw)
-        want = (res["acc_w"][li] + wl.sigma * wl.clip_total * z) / wl.total_batch
+        want = (res["acc_w"][li] + wl.sigma * wl.clip_c * z) / wl.total_batch
         assert np.allclose(res["out_w"][li], want, rtol=1e-14, atol=1e-16)
         if l.pb:
             zb = oracle.noise_normal(wl.philox_seed, wl.step, 2 * li + 1, l.pb)
-            assert np.allclose(res["out_b"][li], (res["acc_b"][li] + wl.sigma * wl.clip_total * zb) / 6,
+            assert np.allclose(res["out_b"][li], (res["acc_b"][li] + wl.sigma * wl.clip_c * zb) / 6,
                                rtol=1e-14, atol=1e-16)
 
 
@@ -178,7 +180,7 @@ def test_expected_norm_of_the_conv3x3_workload():
     wl = get_workload("conv3x3", n=4, accum=1, hw=14)
     inputs = make_inputs(wl, 0)
     acc_w, acc_b = oracle.new_accumulators(wl.layers)
-    n2, _ = oracle.clip_accumulate(wl.layers, inputs, wl.group_of_layer, wl.group_clip, acc_w, acc_b)
+    n2, _ = oracle.clip_accumulate(wl.layers, inputs, wl.group_of_layer, oracle.group_bounds(wl.clip_c, wl.n_groups)[0], acc_w, acc_b)
     valid = sum((14 - abs(kh - 1)) * (14 - abs(kw - 1)) for kh in range(3) for kw in range(3))
     expect = 1e-4 * (64 * 64 * valid + 64 * 196)
     assert np.all(np.abs(n2[:, 0] / expect - 1) < 0.1)

@@ -11,7 +11,6 @@ can be regenerated alone.
 """
 from __future__ import annotations
 
-import math
 from dataclasses import dataclass, field, replace
 from typing import List, Optional, Sequence, Tuple
 
@@ -54,17 +53,6 @@ class Workload:
     @property
     def n_groups(self) -> int:
         return 1 if self.clip_mode == "global" else len(self.layers)
-
-    @property
-    def group_clip(self) -> List[float]:
-        """Per-group bound: C for one group, C/sqrt(M) for M groups (Section 3.5)."""
-        g = self.n_groups
-        return [self.clip_c / math.sqrt(g)] * g
-
-    @property
-    def clip_total(self) -> float:
-        """sqrt(sum_g C_g^2): the bound on the whole clipped gradient, which scales the noise."""
-        return math.sqrt(sum(c * c for c in self.group_clip))
 
     @property
     def n_params(self) -> int:
@@ -112,7 +100,7 @@ def get_workload(name: str, *, n: Optional[int] = None, accum: Optional[int] = N
         wl = Workload(name, layers, 32, 8, "bf16", "global", 1.0, 1.0,
                       tuple("normal" if l.kind == GN else "absnormal" for l in layers), 0.01, 1006)
     elif name == "resnet18_gn":
-        # the CIFAR-10 / chest-CT network of Sections 4.2 and 5: ResNet-18 with GroupNorm, batch 32 x accumulation
+        # the CIFAR-10 / chest-CT network of Sections 3.2 and 3.6: ResNet-18 with GroupNorm, batch 32 x accumulation
         layers = tuple(resnet18_layers(hw or 32, 10, 32))
         wl = Workload(name, layers, 32, 8, "bf16", "global", 1.0, 1.0,
                       tuple("normal" if l.kind == GN else "absnormal" for l in layers), 0.01, 1007)
