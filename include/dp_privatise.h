@@ -135,6 +135,20 @@ dp_status dp_per_example_grad(const dp_layer_desc *desc /*[host]*/, const void *
                               float *g_w, float *g_b, size_t g_stride, float *sqnorm,
                               void *ws, size_t ws_bytes, dp_stream stream);
 
+/* dp_per_example_grad without a workspace argument and without any allocation: for callers that
+ * cannot call hipMalloc or carry a workspace around (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation).  The workspace is a device array built into the library,
+ * dp_static_scratch_bytes() = 32 MiB per GPU, held from the first call on a GPU until the process ends.
+ * Same kernels, same results (bit for bit) as dp_per_example_grad.  The stream's device must be the
+ * current device.  A layer whose dp_workspace_bytes(desc, DP_WS_PER_EXAMPLE_GRAD) exceeds the built-in
+ * size -> DP_ERR_WORKSPACE (nothing is launched).  Every call on one GPU shares that GPU's array:
+ * calls that overlap in time on one GPU (different streams, different host threads) race; issue them
+ * on one stream, or order them with events.  Nothing in the array has to start at zero or survive
+ * between calls.  Calls no hipMalloc / hipFree or other allocating routine.                        */
+size_t dp_static_scratch_bytes(void);
+dp_status dp_per_example_grad_static(const dp_layer_desc *desc /*[host]*/, const void *x, const void *dy,
+                                     float *g_w, float *g_b, size_t g_stride, float *sqnorm, dp_stream stream);
+
 /* The same per-example call without the per-layer reduction: the partial squared norms of the layer
  * stay in the workspace, ws[0 .. n * count) as a row-major [n, count] float matrix with
  * count = dp_norm_partial_count(desc, g_w != NULL), until the workspace is used again.

@@ -55,6 +55,8 @@ def load_library():
         "dp_workspace_bytes": (sz, [dpp, it]),
         "dp_kernel_variant": (C.c_char_p, [dpp, it]),
         "dp_per_example_grad": (it, [dpp, vp, vp, vp, vp, sz, vp, vp, sz, vp]),
+        "dp_static_scratch_bytes": (sz, []),
+        "dp_per_example_grad_static": (it, [dpp, vp, vp, vp, vp, sz, vp, vp]),
         "dp_norms": (it, [vp, vp, it, it, it, vp, vp]),
         "dp_norm_partial_count": (sz, [dpp, it]),
         "dp_per_example_grad_partials": (it, [dpp, vp, vp, vp, vp, sz, vp, sz, vp]),
@@ -81,6 +83,7 @@ def load_library():
 
 
 EXPORTED = ("dp_group_clip_bounds", "dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
+            "dp_static_scratch_bytes", "dp_per_example_grad_static",
             "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_segments", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
             "dp_add_noise_finalize_flat", "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
@@ -154,6 +157,15 @@ def dp_per_example_grad(desc, x, dy, g_w, g_b, sqnorm, ws, g_stride: int = 0, ws
     _check(load_library().dp_per_example_grad(C.byref(desc), _ptr(x), _ptr(dy), _ptr(g_w), _ptr(g_b), g_stride,
                                               _ptr(sqnorm), _ptr(ws),
                                               _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream)))
+
+
+def dp_static_scratch_bytes() -> int:
+    return int(load_library().dp_static_scratch_bytes())
+
+
+def dp_per_example_grad_static(desc, x, dy, g_w, g_b, sqnorm, g_stride: int = 0, stream=None):
+    _check(load_library().dp_per_example_grad_static(C.byref(desc), _ptr(x), _ptr(dy), _ptr(g_w), _ptr(g_b), g_stride,
+                                                     _ptr(sqnorm), _stream(stream)))
 
 
 def dp_norm_partial_count(desc, materialise: bool) -> int:
