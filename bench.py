@@ -54,7 +54,7 @@ class Probe:
         self.pairs = {}     # variant -> list of (start, stop, flops, in_bytes)
         self.enabled = False
 
-    def arm(self, variant, flops, nbytes):
+    def arm(self, variant, flops, nbytes, n_layers=1):
         import torch
         import paper_2109_12191_amd as dp
         if not self.enabled:
@@ -63,15 +63,15 @@ class Probe:
         b = torch.cuda.Event(enable_timing=True)
         a.record()          # creates the HIP handles; the library records both again
         b.record()
-        self.pairs.setdefault(variant, []).append((a, b, flops, nbytes))
+        self.pairs.setdefault(variant, []).append((a, b, flops, nbytes, n_layers))
         dp.dp_profile_next_contraction(a, b)
 
     def summary(self):
         out = {}
         for variant, lst in self.pairs.items():
-            ms = sum(a.elapsed_time(b) for a, b, _, _ in lst)
+            ms = sum(p[0].elapsed_time(p[1]) for p in lst)
             out[variant] = dict(launches=len(lst), total_ms=ms, flops=sum(p[2] for p in lst),
-                                bytes=sum(p[3] for p in lst))
+                                bytes=sum(p[3] for p in lst), layers=sum(p[4] for p in lst))
         return out
 
 

@@ -107,8 +107,11 @@ size_t dp_workspace_bytes(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_
 
 /* Name of the kernel variant that dp_per_example_grad (use = DP_WS_PER_EXAMPLE_GRAD) or
  * dp_clip_accumulate_recompute (use = DP_WS_RECOMPUTE) launches for this descriptor, e.g.
- * "conv_contract<bf16,128x128,per_example>"; "" on a bad descriptor.  Pure host; lets a
- * profiler's per-kernel rows be tied to layers.  The string is static.                       */
+ * "conv_contract<bf16,128x128,per_example>"; "" on a bad descriptor.  With DP_VARIANT_SHARED or-ed
+ * into `use`: the variant the layer runs as inside a batch call of several layers (tiling is chosen
+ * differently when a launch is shared); layers with equal names then share one launch, at most 16
+ * per launch.  Pure host; lets a profiler's per-kernel rows be tied to layers.  The string is static. */
+#define DP_VARIANT_SHARED 2
 const char *dp_kernel_variant(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_use*/);
 
 /* H1 (+ the layer's share of H2): per-example weight gradients of one layer
@@ -158,6 +161,31 @@ dp_status dp_per_example_grad_static(const dp_layer_desc *desc /*[host]*/, const
 size_t dp_norm_partial_count(const dp_layer_desc *desc, int materialise);
 dp_status dp_per_example_grad_partials(const dp_layer_desc *desc, const void *x, const void *dy, float *g_w, float *g_b,
                                        size_t g_stride, void *ws, size_t ws_bytes, dp_stream stream);
+
+/* H1 and the per-layer part of H2 for SEVERAL layers in one call: for every layer l the result of
+ * dp_per_example_grad(&descs[l], x[l], dy[l], g_w[l], g_b[l], g_stride, sqnorm[l], ws[l], ws_bytes[l])
+ * (same definition, Section 2; the numbers may differ from the single-layer call in the last bits, since
+ * sums may be split differently).  Layers that run the same kernel share ONE launch, so a launch has
+ * enough workgroups to fill the chip even when a micro-step holds one example (the batch-size-one
+ * regime of Section 2), and the per-layer reductions of all layers are one launch.  Fixed summation
+ * order: the same inputs give the same bits on every call.
+ * descs [host] n_layers descriptors, all with the same n.  x, dy, sqnorm, ws [host] arrays of n_layers
+ * device pointers; g_w, g_b [host] arrays of device pointers or NULL (= no layer materialises), entry NULL
+ * = that layer does not; sqnorm[l] [device] [n], overwritten; ws[l] at least dp_workspace_bytes(&descs[l],
+ * DP_WS_PER_EXAMPLE_GRAD), one workspace per layer (they are in use at the same time).  Every argument of
+ * every layer is validated before anything is launched.                                              */
+dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *const *x, const void *const *dy,
+                                    float *const *g_w, float *const *g_b, size_t g_stride, float *const *sqnorm,
+                                    void *const *ws, const size_t *ws_bytes, int n_layers, dp_stream stream);
+
+/* H4, recomputing form, for several layers in one call: for every layer l what
+ * dp_clip_accumulate_recompute(&descs[l], x[l], dy[l], sqnorm[l], clip_c[l], acc_w[l], acc_b[l], ws[l], ws_bytes[l])
+ * computes, with the layers that run the same kernel sharing one launch.  sqnorm[l] [device] [n]: squared norms
+ * of layer l's clipping group; clip_c [host] n_layers bounds; acc_b may be NULL when no layer has a bias.  */
+dp_status dp_clip_accumulate_recompute_batch(const dp_layer_desc *descs, const void *const *x, const void *const *dy,
+                                             const float *const *sqnorm, const float *clip_c, float *const *acc_w,
+                                             float *const *acc_b, void *const *ws, const size_t *ws_bytes, int n_layers,
+                                             dp_stream stream);
 
 /* group_sqnorm[g, i] = sum over the layers l of group g, in order, of sum_c partials[l][i * counts[l] + c].
  * partials [host] array of n_layers device pointers (4-byte aligned); counts, group_of_layer [host]

@@ -10,6 +10,7 @@ DP_DENSE, DP_CONV2D, DP_GN_AFFINE = 0, 1, 2
 DP_F32, DP_BF16 = 0, 1
 DP_NCHW, DP_NHWC = 0, 1
 DP_WS_PER_EXAMPLE_GRAD, DP_WS_RECOMPUTE = 0, 1
+DP_VARIANT_SHARED = 2
 
 _STATUS_NAMES = {1: "DP_ERR_INVALID_ARG", 2: "DP_ERR_UNSUPPORTED", 3: "DP_ERR_WORKSPACE", 4: "DP_ERR_DEVICE"}
 _KINDS = {"dense": DP_DENSE, "conv": DP_CONV2D, "gn": DP_GN_AFFINE}
@@ -61,6 +62,8 @@ def load_library():
         "dp_norm_partial_count": (sz, [dpp, it]),
         "dp_per_example_grad_partials": (it, [dpp, vp, vp, vp, vp, sz, vp, sz, vp]),
         "dp_norms_from_partials": (it, [vp, vp, vp, it, it, it, vp, vp]),
+        "dp_per_example_grad_batch": (it, [vp, vp, vp, vp, vp, sz, vp, vp, vp, it, vp]),
+        "dp_clip_accumulate_recompute_batch": (it, [vp, vp, vp, vp, vp, vp, vp, vp, vp, it, vp]),
         "dp_clip_factors": (it, [vp, fl, it, vp, vp]),
         "dp_clip_accumulate": (it, [vp, sz, vp, fl, it, sz, vp, vp]),
         "dp_clip_accumulate_segments": (it, [vp, sz, vp, it, vp, vp, vp, it, it, sz, vp, vp]),
@@ -85,6 +88,7 @@ def load_library():
 EXPORTED = ("dp_group_clip_bounds", "dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_static_scratch_bytes", "dp_per_example_grad_static",
             "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
+            "dp_per_example_grad_batch", "dp_clip_accumulate_recompute_batch",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_segments", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
             "dp_add_noise_finalize_flat", "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
 
@@ -195,6 +199,45 @@ def dp_norms_from_partials(table: "PartialTable", n: int, n_groups: int, group_s
     _check(load_library().dp_norms_from_partials(C.cast(table.ptrs, C.c_void_p), C.cast(table.counts, C.c_void_p),
                                                  C.cast(table.groups, C.c_void_p), table.n_layers, n, n_groups,
                                                  _ptr(group_sqnorm), _stream(stream)))
+
+
+class LayerBatch:
+    """Host arrays for the batch calls over a fixed set of layers: descriptors, workspaces, and (re)settable
+    pointer arrays.  Pointers are plain integers (device addresses); None becomes NULL."""
+
+    def __init__(self, descs, ws_ptrs, ws_bytes):
+        k = len(descs)
+        self.n_layers = k
+        self.descs = (LayerDesc * k)(*descs)
+        self.ws = (C.c_void_p * k)(*[int(p) for p in ws_ptrs])
+        self.ws_bytes = (C.c_size_t * k)(*[int(b) for b in ws_bytes])
+
+    def ptrs(self, values):
+        assert len(values) == self.n_layers
+        return (C.c_void_p * self.n_layers)(*[(None if v is None else int(v)) for v in values])
+
+    def floats(self, values):
+        assert len(values) == self.n_layers
+        return (C.c_float * self.n_layers)(*[float(v) for v in values])
+
+
+def dp_per_example_grad_batch(batch: "LayerBatch", x, dy, g_w, g_b, sqnorm, g_stride: int = 0, stream=None):
+    """x, dy, sqnorm: ctypes pointer arrays from batch.ptrs(); g_w, g_b: the same or None."""
+    _check(load_library().dp_per_example_grad_batch(C.cast(batch.descs, C.c_void_p), C.cast(x, C.c_void_p),
+                                                    C.cast(dy, C.c_void_p),
+                                                    None if g_w is None else C.cast(g_w, C.c_void_p),
+                                                    None if g_b is None else C.cast(g_b, C.c_void_p), g_stride,
+                                                    C.cast(sqnorm, C.c_void_p), C.cast(batch.ws, C.c_void_p),
+                                                    C.cast(batch.ws_bytes, C.c_void_p), batch.n_layers, _stream(stream)))
+
+
+def dp_clip_accumulate_recompute_batch(batch: "LayerBatch", x, dy, sqnorm, clip_c, acc_w, acc_b, stream=None):
+    _check(load_library().dp_clip_accumulate_recompute_batch(C.cast(batch.descs, C.c_void_p), C.cast(x, C.c_void_p),
+                                                             C.cast(dy, C.c_void_p), C.cast(sqnorm, C.c_void_p),
+                                                             C.cast(clip_c, C.c_void_p), C.cast(acc_w, C.c_void_p),
+                                                             None if acc_b is None else C.cast(acc_b, C.c_void_p),
+                                                             C.cast(batch.ws, C.c_void_p), C.cast(batch.ws_bytes, C.c_void_p),
+                                                             batch.n_layers, _stream(stream)))
 
 
 def dp_norms(layer_sqnorm, group_of_layer, n_layers: int, n: int, n_groups: int, group_sqnorm, stream=None):

@@ -1,11 +1,15 @@
 // C ABI of libdp_privatise: argument validation (all on the host, before any launch) and
 // dispatch to the kernels.  See include/dp_privatise.h for the contract of every call.
 #include "internal.h"
+#include "group.h"
 
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
+
+#define DP_TRY_ST(expr) do { dp_status st__ = (expr); if (st__ != DP_OK) return st__; } while (0)
 
 namespace dp {
 
@@ -37,6 +41,47 @@ dp_status check_launch(const char *what)
 {
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(DP_ERR_DEVICE, "%s: launch failed: %s", what, hipGetErrorString(e));
+    return DP_OK;
+}
+
+// ---- grouped launches (group.h)
+static thread_local LaunchQueue *g_queue = nullptr;
+LaunchQueue *open_queue() { return g_queue; }
+void set_open_queue(LaunchQueue *q) { g_queue = q; }
+int crowd_hint() { return g_queue ? g_queue->crowd : 0; }
+
+dp_status flush_queue(LaunchQueue &q)
+{
+    set_open_queue(nullptr);                         // from here on everything is launched at once
+    std::vector<char> done(q.main.size(), 0);
+    std::vector<char> args;
+    std::vector<unsigned> blocks;
+    for (size_t i = 0; i < q.main.size(); ++i) {
+        if (done[i]) continue;
+        const LaunchQueue::Item &first = q.main[i];
+        // every held launch of the same kernel, in the order they were submitted, GROUP_MAX per launch
+        args.clear(); blocks.clear();
+        auto fire = [&]() -> dp_status {
+            if (blocks.empty()) return DP_OK;
+            profile_begin(q.stream);
+            const dp_status st = first.go(first.fn, args.data(), blocks.data(), (int)blocks.size(), first.threads, first.lds, q.stream);
+            profile_end(q.stream);
+            args.clear(); blocks.clear();
+            return st != DP_OK ? st : check_launch(first.what);
+        };
+        for (size_t j = i; j < q.main.size(); ++j) {
+            const LaunchQueue::Item &it = q.main[j];
+            if (done[j] || it.fn != first.fn || it.lds != first.lds || it.threads != first.threads) continue;
+            done[j] = 1;
+            args.insert(args.end(), it.args.begin(), it.args.end());
+            blocks.push_back(it.blocks);
+            if ((int)blocks.size() == GROUP_MAX) DP_TRY_ST(fire());
+        }
+        DP_TRY_ST(fire());
+    }
+    q.main.clear();
+    for (auto &fn : q.post) DP_TRY_ST(fn());
+    q.post.clear();
     return DP_OK;
 }
 
@@ -195,8 +240,10 @@ const char *dp_kernel_variant(const dp_layer_desc *desc, int use)
 {
     Geo g;
     if (make_geo(desc, g) != DP_OK) return "";
+    const bool shared = (use & DP_VARIANT_SHARED) != 0;
+    use &= ~DP_VARIANT_SHARED;
     const int mode = use == DP_WS_RECOMPUTE ? MODE_WEIGHTED : MODE_NORM;
-    if (g.kind == DP_CONV2D) return conv_variant_name(g, mode);
+    if (g.kind == DP_CONV2D) return conv_variant_name(g, mode, shared);
     if (g.kind == DP_DENSE) return g.bf16 ? "dense<bf16>" : "dense<f32>";
     return g.bf16 ? "gn_affine<bf16>" : "gn_affine<f32>";
 }
@@ -264,6 +311,112 @@ dp_status dp_per_example_grad_partials(const dp_layer_desc *desc, const void *x,
     if (g.kind == DP_CONV2D) return launch_conv(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
     if (g.kind == DP_DENSE) return launch_dense(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
     return launch_gn(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
+}
+
+// Work per workgroup a batch call plans for, in units of one 128x128x64 chunk: the convolutions' multiply-adds
+// spread over about three rounds of workgroups on 256 compute units, but neither so little that a workgroup's
+// start-up dominates nor so much that one workgroup becomes the critical path.
+static int batch_target(const std::vector<Geo> &geo)
+{
+    if (geo.size() < 2) return 0;
+    double macs = 0.0;
+    for (const Geo &g : geo)
+        if (g.kind == DP_CONV2D) macs += (double)g.n * g.cout * g.cin * g.kh * g.kw * g.oh * g.ow;
+    const double per_wg = macs / (128.0 * 128.0 * 64.0) / 768.0;
+    return per_wg < 4.0 ? 4 : (per_wg > 64.0 ? 64 : (int)per_wg);
+}
+
+dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *const *x, const void *const *dy,
+                                    float *const *g_w, float *const *g_b, size_t g_stride, float *const *sqnorm,
+                                    void *const *ws, const size_t *ws_bytes, int n_layers, dp_stream stream)
+{
+    if (!descs || !x || !dy || !sqnorm || !ws || !ws_bytes)
+        return fail(DP_ERR_INVALID_ARG, "descs, x, dy, sqnorm, ws and ws_bytes must be non-NULL host arrays");
+    if (n_layers < 1) return fail(DP_ERR_INVALID_ARG, "n_layers = %d (need >= 1)", n_layers);
+    std::vector<Geo> geo((size_t)n_layers);
+    for (int l = 0; l < n_layers; ++l) {             // everything is validated before anything is launched
+        Geo &g = geo[(size_t)l];
+        DP_TRY(make_geo(&descs[l], g));
+        if (g.n != geo[0].n) return fail(DP_ERR_INVALID_ARG, "layer %d: n = %d differs from layer 0's %d", l, g.n, geo[0].n);
+        DP_TRY(check_ptr(x[l], "x[l]", true));
+        DP_TRY(check_ptr(dy[l], "dy[l]", true));
+        float *gw = g_w ? g_w[l] : nullptr, *gb = g_b ? g_b[l] : nullptr;
+        DP_TRY(check_ptr(gw, "g_w[l]", false));
+        DP_TRY(check_ptr(gb, "g_b[l]", false));
+        DP_TRY(check_ptr(sqnorm[l], "sqnorm[l]", true, 4));
+        if (gw && g.pb && !gb) return fail(DP_ERR_INVALID_ARG, "layer %d: g_w given but g_b is NULL for a layer with a bias", l);
+        if (!gw && gb) return fail(DP_ERR_INVALID_ARG, "layer %d: g_b given without g_w", l);
+        if (g_stride) {
+            if (g_stride % 4) return fail(DP_ERR_INVALID_ARG, "g_stride must be a multiple of 4");
+            if (gw && (g_stride < g.pw || g_stride < g.pb)) return fail(DP_ERR_INVALID_ARG, "layer %d: g_stride smaller than the tensor", l);
+        }
+        DP_TRY(check_ws(g, MODE_NORM, ws[l], ws_bytes[l]));
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    g_err[0] = 0;
+    LaunchQueue q;
+    q.stream = s;
+    q.crowd = batch_target(geo);
+    set_open_queue(&q);
+    std::vector<const float *> parts((size_t)n_layers);
+    std::vector<int32_t> counts((size_t)n_layers);
+    dp_status st = DP_OK;
+    for (int l = 0; l < n_layers && st == DP_OK; ++l) {
+        const Geo &g = geo[(size_t)l];
+        float *gw = g_w ? g_w[l] : nullptr, *gb = g_b ? g_b[l] : nullptr;
+        const int mode = gw ? MODE_MATERIALISE : MODE_NORM;
+        // sqnorm == nullptr: the kernels leave their partial sums at the start of the workspace
+        if (g.kind == DP_CONV2D) st = launch_conv(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
+        else if (g.kind == DP_DENSE) st = launch_dense(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
+        else st = launch_gn(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
+        parts[(size_t)l] = static_cast<const float *>(ws[l]);
+        counts[(size_t)l] = (int32_t)norm_partial_count_for(g, mode);       // the plan in force inside this batch
+    }
+    if (st == DP_OK) st = flush_queue(q);
+    set_open_queue(nullptr);
+    if (st != DP_OK) return st;
+    return launch_layer_norms(parts.data(), counts.data(), sqnorm, n_layers, geo[0].n, s);
+}
+
+dp_status dp_clip_accumulate_recompute_batch(const dp_layer_desc *descs, const void *const *x, const void *const *dy,
+                                             const float *const *sqnorm, const float *clip_c, float *const *acc_w,
+                                             float *const *acc_b, void *const *ws, const size_t *ws_bytes, int n_layers,
+                                             dp_stream stream)
+{
+    if (!descs || !x || !dy || !sqnorm || !clip_c || !acc_w || !ws || !ws_bytes)
+        return fail(DP_ERR_INVALID_ARG, "descs, x, dy, sqnorm, clip_c, acc_w, ws and ws_bytes must be non-NULL host arrays");
+    if (n_layers < 1) return fail(DP_ERR_INVALID_ARG, "n_layers = %d (need >= 1)", n_layers);
+    std::vector<Geo> geo((size_t)n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        Geo &g = geo[(size_t)l];
+        DP_TRY(make_geo(&descs[l], g));
+        DP_TRY(check_ptr(x[l], "x[l]", true));
+        DP_TRY(check_ptr(dy[l], "dy[l]", true));
+        DP_TRY(check_ptr(sqnorm[l], "sqnorm[l]", true, 4));
+        DP_TRY(check_ptr(acc_w[l], "acc_w[l]", true));
+        float *ab = acc_b ? acc_b[l] : nullptr;
+        DP_TRY(check_ptr(ab, "acc_b[l]", g.pb != 0));
+        if (!g.pb && ab) return fail(DP_ERR_INVALID_ARG, "layer %d: acc_b given for a layer without bias", l);
+        DP_TRY(check_clip(clip_c[l]));
+        DP_TRY(check_ws(g, MODE_WEIGHTED, ws[l], ws_bytes[l]));
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    g_err[0] = 0;
+    LaunchQueue q;
+    q.stream = s;
+    q.crowd = batch_target(geo);
+    set_open_queue(&q);
+    dp_status st = DP_OK;
+    for (int l = 0; l < n_layers && st == DP_OK; ++l) {
+        const Geo &g = geo[(size_t)l];
+        float *ab = acc_b ? acc_b[l] : nullptr;
+        if (g.kind == DP_CONV2D) st = launch_conv(g, MODE_WEIGHTED, x[l], dy[l], acc_w[l], ab, 0, nullptr, sqnorm[l], clip_c[l], ws[l], s);
+        else if (g.kind == DP_DENSE) st = launch_dense(g, MODE_WEIGHTED, x[l], dy[l], acc_w[l], ab, 0, nullptr, sqnorm[l], clip_c[l], ws[l], s);
+        else st = launch_gn(g, MODE_WEIGHTED, x[l], dy[l], acc_w[l], ab, 0, nullptr, sqnorm[l], clip_c[l], ws[l], s);
+    }
+    if (st == DP_OK) st = flush_queue(q);
+    set_open_queue(nullptr);
+    return st;
 }
 
 dp_status dp_norms_from_partials(const float *const *partials, const int32_t *counts, const int32_t *group_of_layer,

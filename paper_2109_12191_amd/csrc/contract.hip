@@ -33,8 +33,10 @@
 // The bias gradient db_i[m] = sum_k dY_i[m, k] rides along as one more MFMA against a
 // register of ones in the workgroups of tile column 0.
 #include "internal.h"
+#include "group.h"
 #include "pieces.h"
 
+#include <atomic>
 #include <cstdio>
 #include <type_traits>
 
@@ -74,65 +76,150 @@ __device__ __forceinline__ int ceil_div(int a, int b) { return (a >= 0) ? (a + b
 
 // Epilogue of one finished tile held in the MFMA accumulator layout (full K of one example, or
 // the weighted sum over examples): squared norm + optional store, or add into the accumulator.
-template <int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS, int NACC>
-__device__ __forceinline__ void tile_epilogue(const f32x16 (&acc)[NACC], const ConvArgs &a, int i, int tile, int tiles,
-                                              int m0, int n0, int wm, int wn, int lane, bool bias_here, float *red)
+//
+// In the accumulator layout register r of a lane is row (r >> 2) * 8 + (r & 3) (+ 4 for the upper half
+// of the wave) and column lane & 31 of a 32x32 block, so the address of a value is a wave-uniform part
+// (example, block, r: scalar arithmetic) plus a per-lane byte offset that never changes.  Tiles that
+// lie wholly inside the matrix -- all of them when the channel counts are multiples of the tile --
+// take that path: one store per value and no per-value compares or branches.  Ragged tiles check every
+// value (rows / columns beyond the matrix hold no gradient: neither stored nor counted in the norm).
+// Global accesses whose address is a wave-uniform base (scalar register pair) plus a 32-bit per-lane byte
+// offset: no vector address arithmetic at all.  `base` must be the same in every lane.
+__device__ __forceinline__ unsigned long long uniform_bits(const void *p)
 {
+    const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ void store_f32_uniform_base(unsigned long long base, unsigned byte_off, float v)
+{
+    asm volatile("global_store_dword %0, %1, %2" ::"v"(byte_off), "v"(v), "s"(base) : "memory");
+}
+__device__ __forceinline__ float load_f32_uniform_base(unsigned long long base, unsigned byte_off)
+{
+    float v;
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(v) : "v"(byte_off), "s"(base) : "memory");
+    return v;                               // valid only after wait_loaded()
+}
+// wait for every outstanding load; the values pass through so that no use can move above the wait
+__device__ __forceinline__ void wait_loaded(float (&v)[16])
+{
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]), "+v"(v[8]),
+                   "+v"(v[9]), "+v"(v[10]), "+v"(v[11]), "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])
+                 :
+                 : "memory");
+}
+
+// Per-example mode returns this thread's share of the tile's squared norm (the caller reduces it: every
+// (example, tile) owns four partial-norm slots, one per wave).
+template <int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS, int NACC>
+__device__ __forceinline__ float tile_epilogue(const f32x16 (&acc)[NACC], const ConvArgs &a, int i, int m0, int n0, int wm,
+                                               int wn, int lane, bool bias_here)
+{
+    constexpr int WAVES_M = 4 / WAVES_N;
+    constexpr int MT = WAVES_M * TM * 32, NT = WAVES_N * TN * 32;
+    const int cout = __builtin_amdgcn_readfirstlane(a.cout), J = __builtin_amdgcn_readfirstlane(a.J);
+    m0 = __builtin_amdgcn_readfirstlane(m0);
+    n0 = __builtin_amdgcn_readfirstlane(n0);
+    const bool inside_tile = m0 + MT <= cout && n0 + NT <= J;            // uniform
+    // per lane: row and column of register 0 of block (0, 0) of this wave
+    const int m_lane = m0 + wm * TM * 32 + (lane >> 5) * 4, j_lane = n0 + wn * TN * 32 + (lane & 31);
+    const unsigned lane_off = ((unsigned)(m_lane - m0) * (unsigned)J + (unsigned)(j_lane - n0)) * 4u;   // bytes from the tile's corner
+    float ss = 0.0f;
     if constexpr (!WEIGHTED) {
-        float ss = 0.0f;
         const bool store = a.out_w != nullptr;
+        const unsigned long long corner = uniform_bits(a.out_w + (size_t)i * a.out_stride_w + (size_t)m0 * J + n0);
+        if (inside_tile) {
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
+            for (int t = 0; t < TM * TN; ++t)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int j = n0 + (wn * TN + tn) * 32 + (lane & 31);
+                for (int r = 0; r < 16; ++r) ss += acc[t][r] * acc[t][r];
+            if (store) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float v = acc[tm * TN + tn][r];
-                    ss += v * v;                      // rows / columns beyond the matrix are exact zeros
-                    if (store) {
-                        const int m = m0 + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                        if (m < a.cout && j < a.J) a.out_w[(size_t)i * a.out_stride_w + (size_t)m * a.J + j] = v;
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            store_f32_uniform_base(corner + 4ull * ((unsigned)(tm * 32 + (r >> 2) * 8 + (r & 3)) * (unsigned)J + (unsigned)(tn * 32)),
+                                                   lane_off, acc[tm * TN + tn][r]);
+            }
+        } else {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int j = j_lane + tn * 32;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float v = acc[tm * TN + tn][r];
+                        const int m = m_lane + tm * 32 + (r >> 2) * 8 + (r & 3);
+                        const bool inside = m < cout && j < J;
+                        ss += inside ? v * v : 0.0f;
+                        if (store && inside) a.out_w[(size_t)i * a.out_stride_w + (size_t)m * J + j] = v;
                     }
                 }
-            }
-            if constexpr (BIAS) {
+        }
+        if constexpr (BIAS) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
                 if (bias_here && (lane & 31) == 0) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const float v = acc[TM * TN + tm][r];
-                        ss += v * v;
-                        const int m = m0 + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                        if (store && m < a.cout) a.out_b[(size_t)i * a.out_stride_b + m] = v;
+                        const int m = m_lane + tm * 32 + (r >> 2) * 8 + (r & 3);
+                        ss += m < cout ? v * v : 0.0f;
+                        if (store && m < cout) a.out_b[(size_t)i * a.out_stride_b + m] = v;
                     }
                 }
             }
         }
-        const float tot = block_sum<4>(ss, red);
-        if (threadIdx.x == 0) a.partials[(size_t)i * tiles + tile] = tot;
     } else {
+        const unsigned long long corner = uniform_bits(a.out_w + (size_t)m0 * J + n0);
+        if (inside_tile) {
+            // all loads of a block first, then the adds and stores
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
+            for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int j = n0 + (wn * TN + tn) * 32 + (lane & 31);
+                for (int tn = 0; tn < TN; ++tn) {
+                    float old[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                    if (m < a.cout && j < a.J) a.out_w[(size_t)m * a.J + j] += acc[tm * TN + tn][r];
+                    for (int r = 0; r < 16; ++r)
+                        old[r] = load_f32_uniform_base(corner + 4ull * ((unsigned)(tm * 32 + (r >> 2) * 8 + (r & 3)) * (unsigned)J + (unsigned)(tn * 32)), lane_off);
+                    wait_loaded(old);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        store_f32_uniform_base(corner + 4ull * ((unsigned)(tm * 32 + (r >> 2) * 8 + (r & 3)) * (unsigned)J + (unsigned)(tn * 32)),
+                                               lane_off, old[r] + acc[tm * TN + tn][r]);
                 }
-            }
-            if constexpr (BIAS) {
+        } else {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int j = j_lane + tn * 32;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = m_lane + tm * 32 + (r >> 2) * 8 + (r & 3);
+                        if (m < cout && j < J) a.out_w[(size_t)m * J + j] += acc[tm * TN + tn][r];
+                    }
+                }
+        }
+        if constexpr (BIAS) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
                 if (bias_here && (lane & 31) == 0) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int m = m0 + (wm * TM + tm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                        if (m < a.cout) a.out_b[m] += acc[TM * TN + tm][r];
+                        const int m = m_lane + tm * 32 + (r >> 2) * 8 + (r & 3);
+                        if (m < cout) a.out_b[m] += acc[TM * TN + tm][r];
                     }
                 }
             }
         }
     }
+    return ss;
 }
 
 // Workgroup tile MT x NT = (WAVES_M*TM*32) x (WAVES_N*TN*32), WAVES_M*WAVES_N = 4 waves.
@@ -189,8 +276,10 @@ __device__ __noinline__ void slow_stage_b(char *lds, const typename ElemTraits<B
 // LOADER 1 / 2: general geometry with stride 1 / 2 (any other stride runs LOADER 1 with every
 // chunk staged element by element).
 template <bool BF16, int WAVES_M, int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS, int LOADER>
-__global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArgs a)
+__global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const Grouped<ConvArgs> grp)
 {
+    unsigned bid;                                   // workgroup number within this workgroup's layer
+    const ConvArgs &a = grp.a[group_pick(grp, bid)];
     typedef typename ElemTraits<BF16>::type E;
     constexpr int KC = ElemTraits<BF16>::KC;
     constexpr int EPP = ElemTraits<BF16>::EPP;
@@ -216,7 +305,7 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
         total = ex_groups * tiles * a.ksplit;
     }
     const int per_xcd = (total + 7) >> 3;
-    const int wg = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int wg = (int)(bid & 7u) * per_xcd + (int)(bid >> 3);
     if (wg >= total) return;
     int split;
     if constexpr (WEIGHTED) {
@@ -542,7 +631,12 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
         // compiler from hoisting ~100 registers of addresses across the MFMA loop.
         int m0v = __builtin_amdgcn_readfirstlane(m0), n0v = __builtin_amdgcn_readfirstlane(n0);
         asm volatile("" : "+s"(m0v), "+s"(n0v));
-        tile_epilogue<WAVES_N, TM, TN, WEIGHTED, BIAS>(acc, a, i, tile, tiles, m0v, n0v, wm, wn, lane, bias_here, red);
+        const float ss = tile_epilogue<WAVES_N, TM, TN, WEIGHTED, BIAS>(acc, a, i, m0v, n0v, wm, wn, lane, bias_here);
+        if constexpr (!WEIGHTED) {
+            // four partial-norm slots per (example, tile): this kernel fills the first with the workgroup's sum
+            const float tot = block_sum<4>(ss, red);
+            if (threadIdx.x < 4) a.partials[((size_t)i * tiles + tile) * 4 + threadIdx.x] = threadIdx.x == 0 ? tot : 0.0f;
+        }
     };
 
     // MFMAs of one chunk out of one LDS buffer; then, in per-example mode without K slices, the
@@ -645,6 +739,345 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const ConvArg
         for (int r = 0; r < 16; ++r) mine[(t * 16 + r) * THREADS + threadIdx.x] = acc[t][r];
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same contraction for the geometry of LOADER 0 (bf16, one long row of S >= 64 elements per
+// channel, S even, no bias: the 1x1 stride-1 convolutions, and strided ones after the subsampling
+// pre-pass) with the operands streamed global -> LDS by gfx950's 16-byte LDS-direct loads.
+//
+// Nothing is staged through registers: a wave instruction moves 64 x 16 bytes = eight 128-byte rows
+// of one operand straight into LDS (lane L's 16 bytes land at base + 16 L).  The lane chooses WHICH
+// piece of the row it fetches, so the bank-conflict-free layout is a permutation done on the global
+// side: row r keeps its piece p in slot p ^ ((r >> 1) & 7); the MFMA operand reads of 16 consecutive
+// rows at one k then touch 16 distinct 16-byte bank groups, with no padding in LDS.
+// A load's address is a wave-uniform base (example, chunk: scalar registers) plus a per-lane byte
+// offset that never changes (row and piece), so a chunk's loads cost no vector arithmetic.
+// With no registers tied up by staging the pipeline is STAGES deep: the loads of chunk c + STAGES - 1
+// are issued before the MFMAs of chunk c, one barrier per chunk; a workgroup that takes several
+// examples in a row keeps that stream going across their boundaries (the epilogue of one example
+// runs while the next one's chunks are in flight).  These layers are bound by HBM, and what a compute
+// unit can keep in flight is what its LDS holds: STAGES - 1 chunks per workgroup.
+// The wait for a chunk is a counted s_waitcnt vmcnt(N): every thread issues exactly the same number of
+// LDS-direct loads per chunk, and loads complete in order.
+// Rows beyond the matrix (ragged tiles) fetch a valid row instead; the epilogues leave them out of the
+// norm and never store them.  Only the last chunk of an example can reach beyond the row (S % 64 != 0):
+// its pieces at k >= S fetch an earlier piece of the row (nothing is read beyond the tensor) and are
+// overwritten with zeros in LDS, the surplus of a partial last piece likewise, in an extra
+// barrier-separated step; and that chunk runs only the MFMA steps that hold data.  The partial last
+// piece of the tensor's very last row gets its valid bytes through registers.
+// Weighted form: the clip factor is applied in fp32 to the finished per-example tile (a second set of
+// accumulators), acc_total += f_i * acc_i -- no second rounding of dY to bf16.
+// lane L: LDS[lds_base + 16 L .. +16) <- 16 bytes at base + byte_off.  base and lds_base are wave-uniform
+// (already in scalar registers).
+__device__ __forceinline__ void lds_direct_16(unsigned long long base, unsigned byte_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int TM, int TN, bool WEIGHTED, int STAGES>
+__global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ? 2 : 1)) conv_flat_kernel(const Grouped<ConvArgs> grp)
+{
+    typedef uint16_t E;
+    constexpr int KC = 64, EPP = 8;
+    constexpr int MT = 2 * TM * 32, NT = 2 * TN * 32;
+    constexpr int ROWS = MT + NT;                        // LDS rows of 128 bytes per stage: A rows, then B rows
+    constexpr int STAGE_BYTES = ROWS * 128;
+    constexpr int NLD = ROWS / 32;                       // LDS-direct loads per thread and chunk
+    constexpr int NLA = MT / 32;                         // of which the first NLA fetch rows of A (dY)
+    constexpr int NACC = TM * TN;
+    static_assert(STAGES >= 2 && STAGES <= 5, "pipeline depth");
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    unsigned bid;
+    const ConvArgs &a = grp.a[group_pick(grp, bid)];
+
+    const int tiles = a.tiles_m * a.tiles_n;
+    int total, tile, unit;
+    if constexpr (WEIGHTED) {
+        total = tiles * a.ksplit;
+    } else {
+        const int ex_groups = (a.n + a.ex_per_wg - 1) / a.ex_per_wg;
+        total = ex_groups * tiles * a.ksplit;
+    }
+    const int per_xcd = (total + 7) >> 3;
+    const int wg = (int)(bid & 7u) * per_xcd + (int)(bid >> 3);
+    if (wg >= total) return;
+    int split;
+    if constexpr (WEIGHTED) {
+        tile = wg / a.ksplit;
+        split = wg - tile * a.ksplit;
+        unit = 0;
+    } else {
+        split = wg % a.ksplit;
+        const int r = wg / a.ksplit;
+        unit = r / tiles;
+        tile = r - unit * tiles;
+    }
+    const int tile_m = tile / a.tiles_n, tile_n = tile - tile_m * a.tiles_n;
+    const int m0 = __builtin_amdgcn_readfirstlane(tile_m * MT), n0 = __builtin_amdgcn_readfirstlane(tile_n * NT);
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    int i_begin, i_end, c_begin, c_end;
+    if constexpr (WEIGHTED) {
+        i_begin = split * a.ex_per_split;
+        i_end = min(a.n, i_begin + a.ex_per_split);
+        c_begin = 0;
+        c_end = a.chunks_per_ex;
+    } else {
+        i_begin = unit * a.ex_per_wg;
+        i_end = min(a.n, i_begin + a.ex_per_wg);
+        c_begin = split * a.chunks_per_split;
+        c_end = min(a.chunks_per_ex, c_begin + a.chunks_per_split);
+    }
+    i_begin = __builtin_amdgcn_readfirstlane(i_begin);
+    c_begin = __builtin_amdgcn_readfirstlane(c_begin);
+    c_end = __builtin_amdgcn_readfirstlane(c_end);
+    const int cpe = c_end - c_begin;
+    const int n_chunks = __builtin_amdgcn_readfirstlane((i_end - i_begin) * cpe);
+
+    const int S = __builtin_amdgcn_readfirstlane(a.S);
+    const int cout = __builtin_amdgcn_readfirstlane(a.cout), J = __builtin_amdgcn_readfirstlane(a.J);
+    const int n_examples = __builtin_amdgcn_readfirstlane(a.n), chunks_per_ex = __builtin_amdgcn_readfirstlane(a.chunks_per_ex);
+    const int ksplit = __builtin_amdgcn_readfirstlane(a.ksplit);
+    const size_t x_ex = (size_t)a.cin * S, dy_ex = (size_t)cout * S;
+    const E *xg = static_cast<const E *>(a.x), *dyg = static_cast<const E *>(a.dy);
+    // the last chunk of an example when the row does not end on a chunk boundary: only some K steps hold data
+    const int last_valid = S - (chunks_per_ex - 1) * KC;              // elements of a row in the last chunk: 1 .. 64
+    const bool has_tail = last_valid < KC;
+    const int tail = S & 7;                                           // elements of a row's partial last piece (0: none)
+    const int last_ksteps = (last_valid + 15) >> 4;                   // MFMA steps of 16 that hold data in the last chunk
+
+    // ---- this thread's NLD loads of a chunk: load q of wave w fills rows [(4 q + w) 8, +8) of the stage
+    // (loads q < NLA are rows of A, the rest rows of B); lane -> row rb = lane / 8 of those, slot = lane % 8,
+    // piece p = slot ^ ((row >> 1) & 7)
+    unsigned byte_off[NLD];      // of the row's piece within one example's operand, at chunk 0
+    unsigned tail_off[NLD];      // what the last chunk fetches instead, relative to the START OF THE PREVIOUS CHUNK
+    unsigned stand_off[NLD];     // the stand-in (last piece of the previous chunk), relative to the same
+    unsigned guard_mask = 0;     // bit q: load q is the partial last piece of its operand's last row (its own row, or as
+                                 // stand-in for a row beyond the matrix): in the last example it would read past the tensor
+    const int rb = lane >> 3, slot = lane & 7;
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) {
+        const int row = (4 * q + wave) * 8 + rb;
+        const int pk = (slot ^ ((row >> 1) & 7)) * EPP;
+        int r;                                            // row of the operand; rows beyond the matrix fetch its last row
+        bool last_row;
+        if (q < NLA) {
+            r = min(m0 + row, cout - 1);
+            last_row = m0 + row >= cout - 1;
+        } else {
+            r = min(n0 + row - MT, J - 1);
+            last_row = n0 + row - MT >= J - 1;
+        }
+        const unsigned row_byte = (unsigned)r * (unsigned)S * 2u;
+        byte_off[q] = row_byte + (unsigned)pk * 2u;
+        // last chunk: pieces that start at or beyond the row's end fetch the last piece of the chunk before
+        // (inside the tensor; their K steps are never computed or are masked); all others their own piece
+        stand_off[q] = row_byte + 2u * (KC - EPP);
+        tail_off[q] = pk < last_valid ? byte_off[q] + 2u * KC : stand_off[q];
+        if (last_row && pk < last_valid && pk + EPP > last_valid) guard_mask |= 1u << q;
+    }
+
+    // ---- the stream of chunks to fetch: scalar base addresses advanced by constants
+    unsigned long long ga = uniform_bits(dyg + (size_t)i_begin * dy_ex + (size_t)c_begin * KC);
+    unsigned long long gb = uniform_bits(xg + (size_t)i_begin * x_ex + (size_t)c_begin * KC);
+    const unsigned long long a_jump = (unsigned long long)(dy_ex - (size_t)cpe * KC) * 2ull;      // from an example's last chunk to the next one's first
+    const unsigned long long b_jump = (unsigned long long)(x_ex - (size_t)cpe * KC) * 2ull;
+    const unsigned lds_wave = __builtin_amdgcn_readfirstlane((unsigned)(size_t)lds + (unsigned)wave * 1024u);
+    int f_i = i_begin, f_c = c_begin;                     // next chunk to fetch
+    unsigned f_dst = lds_wave;                            // where it goes: its stage, this wave's kilobyte
+    auto fetch = [&]() {
+        if (!(has_tail && f_c == chunks_per_ex - 1)) {
+#pragma unroll
+            for (int q = 0; q < NLD; ++q) lds_direct_16(q < NLA ? ga : gb, byte_off[q], f_dst + q * 4096);
+        } else {
+            // offsets are unsigned, so those of the last chunk count from the start of the chunk before it.  The partial
+            // last piece of the tensor's very last row would read past the tensor: it fetches the stand-in as well.
+            const unsigned guard = (tail && f_i == n_examples - 1) ? guard_mask : 0u;
+#pragma unroll
+            for (int q = 0; q < NLD; ++q)
+                lds_direct_16((q < NLA ? ga : gb) - 2ull * KC, ((guard >> q) & 1u) ? stand_off[q] : tail_off[q], f_dst + q * 4096);
+        }
+        ga += 2ull * KC;
+        gb += 2ull * KC;
+        f_dst += STAGE_BYTES;
+        if (f_dst >= lds_wave + STAGES * STAGE_BYTES) f_dst = lds_wave;
+        if (++f_c == c_end) { f_c = c_begin; ++f_i; ga += a_jump; gb += b_jump; }
+    };
+
+    // the tensor's very last row, last example: its partial last piece fetched a stand-in; the valid dwords
+    // come through registers (taken by at most two workgroups of a launch), between two barriers
+    auto fix_very_last = [&](int stage) {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            if ((guard_mask >> q) & 1u) {
+                uint32_t *d4 = reinterpret_cast<uint32_t *>(lds + stage * STAGE_BYTES + (4 * q + wave) * 1024 + lane * 16);
+                const char *ex = reinterpret_cast<const char *>(q < NLA ? dyg + (size_t)(n_examples - 1) * dy_ex
+                                                                        : xg + (size_t)(n_examples - 1) * x_ex);
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(ex + byte_off[q] + (size_t)(chunks_per_ex - 1) * KC * 2);
+#pragma unroll
+                for (int d = 0; d < 3; ++d)
+                    if (2 * d < tail) d4[d] = src[d];
+            }
+        }
+    };
+
+    f32x16 acc[NACC];
+    f32x16 tot[WEIGHTED ? NACC : 1];
+#pragma unroll
+    for (int t = 0; t < NACC; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+    if constexpr (WEIGHTED) {
+#pragma unroll
+        for (int t = 0; t < NACC; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tot[t][r] = 0.0f;
+    }
+
+    // operand reads: lane -> row (lane & 31) of a 32-row block, K step ks -> pieces 2 ks + (lane >> 5), swizzled
+    int koff[4];
+    {
+        const int t16 = (((lane >> 5) ^ ((lane >> 1) & 7)) & 7) * 16;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) koff[ks] = (ks * 32) ^ t16;
+    }
+    const int a_row = (wm * TM * 32 + (lane & 31)) * 128;
+    const int b_row = (MT + wn * TN * 32 + (lane & 31)) * 128;
+    // the last K step of an example's last chunk: elements at or beyond the row's end are zeroed in registers
+    // (lane holds elements (lane >> 5) * 8 .. +8 of the step); dword d keeps its low / high half or nothing
+    uint32_t kmask[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const int e0 = (last_ksteps - 1) * 16 + (lane >> 5) * 8 + 2 * d;
+        kmask[d] = (e0 < last_valid ? 0x0000FFFFu : 0u) | (e0 + 1 < last_valid ? 0xFFFF0000u : 0u);
+    }
+
+    // MFMAs of one full chunk: the operand reads of two K steps are issued together, ahead of their MFMAs
+    auto compute = [&](int stage) {
+        const char *base = lds + stage * STAGE_BYTES;
+        constexpr int KB = (TM * TN > 1) ? 2 : 4;        // K steps whose operand reads are issued together
+#pragma unroll
+        for (int k0 = 0; k0 < 4; k0 += KB) {
+            uint4 fa[KB][TM], fb[KB][TN];
+#pragma unroll
+            for (int kk = 0; kk < KB; ++kk) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) fa[kk][tm] = *reinterpret_cast<const uint4 *>(base + a_row + tm * 32 * 128 + koff[k0 + kk]);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) fb[kk][tn] = *reinterpret_cast<const uint4 *>(base + b_row + tn * 32 * 128 + koff[k0 + kk]);
+            }
+#pragma unroll
+            for (int kk = 0; kk < KB; ++kk)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm * TN + tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, fa[kk][tm]), __builtin_bit_cast(bf16x8, fb[kk][tn]), acc[tm * TN + tn], 0, 0, 0);
+        }
+    };
+    // the same for an example's last chunk when the row ends inside it
+    auto compute_tail = [&](int stage) {
+        const char *base = lds + stage * STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < last_ksteps) {                       // uniform
+                uint4 fa[TM], fb[TN];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) fa[tm] = *reinterpret_cast<const uint4 *>(base + a_row + tm * 32 * 128 + koff[ks]);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) fb[tn] = *reinterpret_cast<const uint4 *>(base + b_row + tn * 32 * 128 + koff[ks]);
+                if (ks == last_ksteps - 1) {
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) { fa[tm].x &= kmask[0]; fa[tm].y &= kmask[1]; fa[tm].z &= kmask[2]; fa[tm].w &= kmask[3]; }
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) { fb[tn].x &= kmask[0]; fb[tn].y &= kmask[1]; fb[tn].z &= kmask[2]; fb[tn].w &= kmask[3]; }
+                }
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm * TN + tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, fa[tm]), __builtin_bit_cast(bf16x8, fb[tn]), acc[tm * TN + tn], 0, 0, 0);
+            }
+        }
+    };
+
+    // per-example mode: norm share of every wave into its own slot (no barrier), optional store
+    auto finish = [&](int i) {
+        const float ss = tile_epilogue<2, TM, TN, false, false>(acc, a, i, m0, n0, wm, wn, lane, false);
+        const float ws = wave_sum(ss);
+        if (lane == 0) a.partials[((size_t)i * tiles + tile) * 4 + wave] = ws;
+    };
+
+    // ---- pipeline: chunks c+1 .. c+STAGES-2 are in flight while chunk c is in the MFMAs
+    int fetched = 0;
+#pragma unroll
+    for (int s0 = 0; s0 < STAGES - 1; ++s0)
+        if (fetched < n_chunks) { fetch(); ++fetched; }
+    int ex = i_begin, chunk_in_ex = 0, stage = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        // chunk c has landed when at most the loads issued after it are outstanding
+        const int newer = fetched - c - 1;                // chunks issued after chunk c: 0 .. STAGES-2
+        if (STAGES > 4 && newer >= 3) wait_vmcnt<3 * NLD>();
+        else if (STAGES > 3 && newer == 2) wait_vmcnt<2 * NLD>();
+        else if (STAGES > 2 && newer == 1) wait_vmcnt<NLD>();
+        else wait_vmcnt<0>();
+        __syncthreads();                                  // everyone's loads of chunk c are in LDS; chunk c-1 has been read
+        if (fetched < n_chunks) { fetch(); ++fetched; }   // into the stage chunk c-1 used
+        const bool last_chunk = has_tail && c_begin + chunk_in_ex == chunks_per_ex - 1;      // uniform
+        if (last_chunk) {
+            if (tail && ex == n_examples - 1 && (m0 + MT >= cout || n0 + NT >= J)) {           // uniform, rare
+                fix_very_last(stage);
+                __syncthreads();
+            }
+            compute_tail(stage);
+        } else {
+            compute(stage);
+        }
+        if (++stage == STAGES) stage = 0;
+        if (++chunk_in_ex == cpe) {
+            chunk_in_ex = 0;
+            if constexpr (WEIGHTED) {
+                const float f = clip_factor(a.group_sqnorm[ex], a.clip_c);
+#pragma unroll
+                for (int t = 0; t < NACC; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) { tot[t][r] += f * acc[t][r]; acc[t][r] = 0.0f; }
+            } else if (ksplit == 1) {
+                finish(ex);
+#pragma unroll
+                for (int t = 0; t < NACC; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+            }
+            ++ex;
+        }
+    }
+
+    if constexpr (WEIGHTED) {
+        if (ksplit == 1) {
+            tile_epilogue<2, TM, TN, true, false>(tot, a, 0, m0, n0, wm, wn, lane, false);
+            return;
+        }
+    } else if (ksplit == 1) {
+        return;
+    }
+    // slices of one tile meet in the workspace (conv_fixup_kernel adds them in slice order)
+    const int group = WEIGHTED ? tile : (unit * tiles + tile);
+    float *mine = a.ws_part + ((size_t)group * ksplit + split) * (NACC * 16 * THREADS);
+#pragma unroll
+    for (int t = 0; t < NACC; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mine[(t * 16 + r) * THREADS + threadIdx.x] = WEIGHTED ? tot[t][r] : acc[t][r];
+}
+
 // Slices of one tile meet here.  The sum over slices is elementwise, so it is spread over many
 // small workgroups: one per (tile, 32x32 accumulator block t, four of its sixteen registers).
 // Each thread adds its four values over the slices in slice order (same bits every run) with
@@ -707,7 +1140,7 @@ __global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const ConvArgs a)
             if constexpr (WEIGHTED) {
                 if (ok) a.out_w[(size_t)m * a.J + j] += v[rr];
             } else {
-                ss += v[rr] * v[rr];
+                ss += ok ? v[rr] * v[rr] : 0.0f;
                 if (ok && a.out_w) a.out_w[(size_t)i * a.out_stride_w + (size_t)m * a.J + j] = v[rr];
             }
         } else if (bias_lane) {
@@ -743,9 +1176,16 @@ struct FullPlan {
     int h, w, oh, ow;
 };
 
+// Whether plans are made for a launch shared with many other workgroups (a batch call): then a layer
+// need not fill the chip by itself, so K is sliced only when a workgroup's walk would get very long and
+// example ranges of the weighted form are as long as they can be.  Workspace sizes cover both cases.
+static thread_local int tl_forced_crowd = -1;
+static int plan_crowd() { return tl_forced_crowd >= 0 ? tl_forced_crowd : crowd_hint(); }
+
 static FullPlan full_plan(const Geo &g, int mode)
 {
     FullPlan p;
+    const int crowd = plan_crowd();                  // 0, or the 128x128x64 chunks of work a workgroup should get
     const int J = g.cin * g.kh * g.kw;
     const int S = g.oh * g.ow;
     const bool flat = (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0);
@@ -755,7 +1195,7 @@ static FullPlan full_plan(const Geo &g, int mode)
     p.chunks_per_ex = (int)(((long long)p.oh * p.kcolsp + kc - 1) / kc);
 
     p.shape = (g.cout > 64 && J > 64) ? T128 : T64;
-    if (p.shape == T128 && mode != MODE_WEIGHTED && p.chunks_per_ex >= 8) {
+    if (p.shape == T128 && mode != MODE_WEIGHTED && p.chunks_per_ex >= 8 && !crowd) {
         // long K and few 128x128 tiles: 64x64 tiles give four times the (example, tile) units, so K
         // needs no (or less) slicing and far fewer partial tiles travel through the workspace
         const long long t128 = (long long)((g.cout + 127) / 128) * ((J + 127) / 128);
@@ -773,6 +1213,10 @@ static FullPlan full_plan(const Geo &g, int mode)
         // example ranges: enough workgroups to fill the chip, with the partial tiles that are
         // written and read back (cache-resident in practice) kept below ~100 MB
         long long want = (512 + tiles - 1) / tiles;
+        if (crowd) {                                     // example ranges of about twice the target
+            const long long per = (long long)2 * crowd * (p.shape == T64 ? 4 : 1);
+            want = ((long long)g.n * p.chunks_per_ex + per - 1) / per;
+        }
         const long long cap = (long long)(96.0e6 / (4.0 * (double)tiles * (double)tile_floats));
         if (want > cap) want = cap;
         if (want > g.n) want = g.n;
@@ -782,7 +1226,20 @@ static FullPlan full_plan(const Geo &g, int mode)
         p.groups = tiles;
     } else {
         const long long units = (long long)g.n * tiles;
-        if (units < 512 && p.chunks_per_ex >= 8) {
+        if (crowd) {
+            const int tgt = crowd * (p.shape == T64 ? 4 : 1);     // chunks of this tile shape per workgroup
+            if (p.chunks_per_ex > tgt + tgt / 2) {
+                const long long want = (p.chunks_per_ex + tgt - 1) / tgt;
+                p.chunks_per_split = (int)((p.chunks_per_ex + want - 1) / want);
+                p.ksplit = (p.chunks_per_ex + p.chunks_per_split - 1) / p.chunks_per_split;
+            } else {
+                // short K: a workgroup takes several examples in a row (its loads stream across the boundaries)
+                long long e = (tgt + p.chunks_per_ex / 2) / p.chunks_per_ex;
+                if (e > 16) e = 16;
+                if (e > g.n) e = g.n;
+                p.ex_per_wg = (int)(e < 1 ? 1 : e);
+            }
+        } else if (units < 512 && p.chunks_per_ex >= 8) {
             // few tiles, long K: slice K so that about 256 workgroups run (one per CU: measured best when several
             // layers share the chip; more slices mean more partial tiles through the workspace)
             long long want = 256 / units;
@@ -819,6 +1276,12 @@ static bool packed_weighted(const Geo &g, int mode, PackPlan &pp, Geo &g2)
     const int shape = (g.cout > 64 && J > 64) ? T128 : T64;
     const long long tiles = (long long)((g.cout + kTileM[shape] - 1) / kTileM[shape]) * ((J + kTileN[shape] - 1) / kTileN[shape]);
     long long groups = (256 + tiles - 1) / tiles;
+    if (plan_crowd()) {
+        // sharing the launch with other layers: example ranges of about twice the target number of chunks
+        const long long sp = ((long long)g.oh * g.ow + 7) / 8 * 8;
+        const long long per = (long long)2 * plan_crowd() * (shape == T64 ? 4 : 1) * 64;
+        groups = ((long long)g.n * sp + per - 1) / per;
+    }
     if (groups > g.n) groups = g.n;
     if (groups < 1) groups = 1;
     pp = pack_plan(g, (int)groups);
@@ -858,7 +1321,7 @@ static size_t align16(size_t b) { return (b + 15) & ~(size_t)15; }
 static size_t norm_partials_per_example(const FullPlan &f)
 {
     const size_t tiles = (size_t)f.tiles_m * f.tiles_n;
-    return f.ksplit > 1 ? tiles * f.nacc * FIX_PARTS : tiles;
+    return f.ksplit > 1 ? tiles * f.nacc * FIX_PARTS : tiles * 4;     // unsliced: a slot per wave
 }
 static size_t norm_partials(const Geo &g, const FullPlan &f) { return (size_t)g.n * norm_partials_per_example(f); }
 
@@ -868,9 +1331,19 @@ static size_t conv_ws_bytes_mode(const Geo &g, int mode);
 // One per-example workspace serves norm-only and materialising calls (they may take different routes).
 size_t conv_ws_bytes(const Geo &g, int mode)
 {
-    if (mode == MODE_WEIGHTED) return conv_ws_bytes_mode(g, mode);
-    const size_t a = conv_ws_bytes_mode(g, MODE_NORM), b = conv_ws_bytes_mode(g, MODE_MATERIALISE);
-    return a > b ? a : b;
+    size_t need = 0;
+    const int saved = tl_forced_crowd;
+    for (int crowd = 0; crowd <= 4; crowd += 4) {   // a call alone and a call inside a batch (smallest target: most slices)
+        tl_forced_crowd = crowd;
+        size_t b = conv_ws_bytes_mode(g, mode == MODE_WEIGHTED ? MODE_WEIGHTED : MODE_NORM);
+        if (mode != MODE_WEIGHTED) {
+            const size_t m = conv_ws_bytes_mode(g, MODE_MATERIALISE);
+            if (m > b) b = m;
+        }
+        if (b > need) need = b;
+    }
+    tl_forced_crowd = saved;
+    return need;
 }
 
 static size_t conv_ws_bytes_mode(const Geo &g, int mode)
@@ -900,25 +1373,46 @@ size_t conv_norm_partial_count(const Geo &g, int mode)
     return norm_partials_per_example(full_plan(g, mode));
 }
 
-const char *conv_variant_name(const Geo &g, int mode)
+// loader of the contraction kernel for a geometry as the kernel sees it
+static int loader_of(const Geo &g)
 {
+    const bool flat = (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0);
+    return (flat && (!g.bf16 || (g.oh * g.ow) % 2 == 0)) ? 0 : (g.stride == 2 ? 2 : 1);
+}
+
+// `shared` = as planned inside a batch call (the launch is shared with other layers).  Two layers with the
+// same name run the same kernel instantiation, so a batch call puts them into one launch.
+const char *conv_variant_name(const Geo &g, int mode, bool shared)
+{
+    const int saved = tl_forced_crowd;
+    tl_forced_crowd = shared ? 32 : 0;
+    struct Restore { int v; ~Restore() { tl_forced_crowd = v; } } restore{saved};
+    c3_set_forced_crowd(shared ? 32 : 0);
+    struct Restore3 { ~Restore3() { c3_set_forced_crowd(-1); } } restore3;
     if (gram_norm_applicable(g, mode)) return "conv_gram_norm<bf16>";
     if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);
     struct Names {
-        char v[2][2][2][2][64];
+        char v[2][2][2][2][3][72];
         Names()
         {
+            static const char *const ld[3] = {"", ",gather", ",gather2"};
             for (int b = 0; b < 2; ++b)
                 for (int s = 0; s < 2; ++s)
                     for (int w = 0; w < 2; ++w)
                         for (int bi = 0; bi < 2; ++bi)
-                            snprintf(v[b][s][w][bi], 64, "conv_contract<%s,%s,%s%s>", b ? "bf16" : "f32", kTileName[s],
-                                     w ? "weighted" : "per_example", bi ? ",bias" : "");
+                            for (int l = 0; l < 3; ++l)
+                                snprintf(v[b][s][w][bi][l], 72, "conv_contract<%s,%s,%s%s%s>", b ? "bf16" : "f32", kTileName[s],
+                                         w ? "weighted" : "per_example", bi ? ",bias" : "", ld[l]);
         }
     };
     static const Names names;               // initialised once, thread-safe
-    const FullPlan f = full_plan(g, mode);
-    return names.v[g.bf16 ? 1 : 0][f.shape][mode == MODE_WEIGHTED ? 1 : 0][g.has_bias ? 1 : 0];
+    // the geometry the contraction kernel really sees (packed or subsampled operands are one long aligned row)
+    Geo ge = g, g2;
+    PackPlan pp;
+    if (packed_weighted(g, mode, pp, g2)) ge = g2;
+    else if (subsampled(g, mode, g2)) ge = g2;
+    const FullPlan f = full_plan(ge, mode);
+    return names.v[g.bf16 ? 1 : 0][f.shape][mode == MODE_WEIGHTED ? 1 : 0][g.has_bias ? 1 : 0][loader_of(ge)];
 }
 
 template <int WM, int WN, int TM, int TN>
@@ -934,23 +1428,22 @@ static void launch_fixup(const ConvArgs &a, bool weighted, bool bias, unsigned g
 }
 
 template <bool BF16, int WM, int WN, int TM, int TN, int SIMPLE>
-static void launch_shape2(const ConvArgs &a, bool weighted, bool bias, unsigned blocks, hipStream_t s)
+static const void *kernel_of2(bool weighted, bool bias)
 {
     if (weighted) {
-        if (bias) hipLaunchKernelGGL((conv_contract_kernel<BF16, WM, WN, TM, TN, true, true, SIMPLE>), dim3(blocks), dim3(THREADS), 0, s, a);
-        else hipLaunchKernelGGL((conv_contract_kernel<BF16, WM, WN, TM, TN, true, false, SIMPLE>), dim3(blocks), dim3(THREADS), 0, s, a);
-    } else {
-        if (bias) hipLaunchKernelGGL((conv_contract_kernel<BF16, WM, WN, TM, TN, false, true, SIMPLE>), dim3(blocks), dim3(THREADS), 0, s, a);
-        else hipLaunchKernelGGL((conv_contract_kernel<BF16, WM, WN, TM, TN, false, false, SIMPLE>), dim3(blocks), dim3(THREADS), 0, s, a);
+        if (bias) return reinterpret_cast<const void *>(&conv_contract_kernel<BF16, WM, WN, TM, TN, true, true, SIMPLE>);
+        return reinterpret_cast<const void *>(&conv_contract_kernel<BF16, WM, WN, TM, TN, true, false, SIMPLE>);
     }
+    if (bias) return reinterpret_cast<const void *>(&conv_contract_kernel<BF16, WM, WN, TM, TN, false, true, SIMPLE>);
+    return reinterpret_cast<const void *>(&conv_contract_kernel<BF16, WM, WN, TM, TN, false, false, SIMPLE>);
 }
 
 template <bool BF16, int WM, int WN, int TM, int TN>
-static void launch_shape(const ConvArgs &a, int loader, bool weighted, bool bias, unsigned blocks, hipStream_t s)
+static const void *kernel_of(int loader, bool weighted, bool bias)
 {
-    if (loader == 0) launch_shape2<BF16, WM, WN, TM, TN, 0>(a, weighted, bias, blocks, s);
-    else if (loader == 1) launch_shape2<BF16, WM, WN, TM, TN, 1>(a, weighted, bias, blocks, s);
-    else launch_shape2<BF16, WM, WN, TM, TN, 2>(a, weighted, bias, blocks, s);
+    if (loader == 0) return kernel_of2<BF16, WM, WN, TM, TN, 0>(weighted, bias);
+    if (loader == 1) return kernel_of2<BF16, WM, WN, TM, TN, 1>(weighted, bias);
+    return kernel_of2<BF16, WM, WN, TM, TN, 2>(weighted, bias);
 }
 
 static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
@@ -1022,32 +1515,45 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
     else total = (long long)((g.n + f.ex_per_wg - 1) / f.ex_per_wg) * tiles * f.ksplit;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     const bool bias = g.has_bias != 0;
-    const bool flat = (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0);
-    const int loader = (flat && (!g.bf16 || a.S % 2 == 0)) ? 0 : (g.stride == 2 ? 2 : 1);
+    const int loader = loader_of(g);
     a.force_slow = (g.stride > 2) ? 1 : 0;
-    profile_begin(s);
-    if (g.bf16) {
-        switch (f.shape) {
-        case T64: launch_shape<true, 2, 2, 1, 1>(a, loader, weighted, bias, blocks, s); break;
-        default: launch_shape<true, 2, 2, 2, 2>(a, loader, weighted, bias, blocks, s); break;
+    const void *fn;
+    unsigned lds_bytes = 0;
+    if (g.bf16 && loader == 0 && !bias && a.S >= 64) {
+        // aligned one-row-per-channel geometry: operands go global -> LDS directly.  Two workgroups per compute unit
+        // (64 KB of LDS each): 64x64 tiles four stages deep, 128x128 tiles two stages deep (measured: a second
+        // resident workgroup hides more than two more stages do).
+        if (f.shape == T64) {
+            fn = weighted ? reinterpret_cast<const void *>(&conv_flat_kernel<1, 1, true, 4>) : reinterpret_cast<const void *>(&conv_flat_kernel<1, 1, false, 4>);
+            lds_bytes = 4 * 128 * 128;
+        } else {
+            fn = weighted ? reinterpret_cast<const void *>(&conv_flat_kernel<2, 2, true, 2>) : reinterpret_cast<const void *>(&conv_flat_kernel<2, 2, false, 2>);
+            lds_bytes = 2 * 256 * 128;
         }
-    } else {
-        if (f.shape == T64) launch_shape<false, 2, 2, 1, 1>(a, loader, weighted, bias, blocks, s);
-        else launch_shape<false, 2, 2, 2, 2>(a, loader, weighted, bias, blocks, s);
-    }
-    profile_end(s);
-    dp_status st = check_launch("conv_contract");
+        static std::atomic<bool> attr_done[2][2];        // zero-initialised; setting the attribute twice is harmless
+        if (!attr_done[f.shape][weighted ? 1 : 0].load()) {
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+                return fail(DP_ERR_DEVICE, "conv_flat: cannot reserve %u bytes of LDS", lds_bytes);
+            attr_done[f.shape][weighted ? 1 : 0].store(true);
+        }
+    } else if (g.bf16) fn = (f.shape == T64) ? kernel_of<true, 2, 2, 1, 1>(loader, weighted, bias) : kernel_of<true, 2, 2, 2, 2>(loader, weighted, bias);
+    else fn = (f.shape == T64) ? kernel_of<false, 2, 2, 1, 1>(loader, weighted, bias) : kernel_of<false, 2, 2, 2, 2>(loader, weighted, bias);
+    dp_status st = submit_main<ConvArgs>(fn, a, blocks, THREADS, lds_bytes, s, "conv_contract");
     if (st != DP_OK) return st;
-    if (f.ksplit > 1) {
-        switch (f.shape) {
-        case T64: launch_fixup<2, 2, 1, 1>(a, weighted, bias, f.groups * f.nacc * FIX_PARTS, s); break;
-        default: launch_fixup<2, 2, 2, 2>(a, weighted, bias, f.groups * f.nacc * FIX_PARTS, s); break;
+    // what follows the main kernel: at once, or after the grouped launch of a batch call
+    const int shape = f.shape, ksplit = f.ksplit, per_example = (int)norm_partials_per_example(f), n = g.n;
+    const unsigned fix_blocks = (unsigned)(f.groups * f.nacc * FIX_PARTS);
+    return submit_post([=]() -> dp_status {
+        dp_status st2 = DP_OK;
+        if (ksplit > 1) {
+            if (shape == T64) launch_fixup<2, 2, 1, 1>(a, weighted, bias, fix_blocks, s);
+            else launch_fixup<2, 2, 2, 2>(a, weighted, bias, fix_blocks, s);
+            st2 = check_launch("conv_fixup");
+            if (st2 != DP_OK) return st2;
         }
-        st = check_launch("conv_fixup");
-        if (st != DP_OK) return st;
-    }
-    if (!weighted && sqnorm) st = launch_sum_partials(a.partials, g.n, (int)norm_partials_per_example(f), sqnorm, s);
-    return st;
+        if (!weighted && sqnorm) st2 = launch_sum_partials(a.partials, n, per_example, sqnorm, s);
+        return st2;
+    });
 }
 
 }  // namespace dp

@@ -22,6 +22,7 @@
 // K may be sliced over workgroups (few tiles, long K): slices store their accumulators in the
 // workspace and a second kernel adds them in slice order, so results are run-to-run identical.
 #include "internal.h"
+#include "group.h"
 #include "pieces.h"
 
 #include <cstdio>
@@ -189,8 +190,10 @@ __device__ __forceinline__ void c3_add_to_accumulator(const f32x16 (&acc)[9], co
 enum { C3_FULL = 0, C3_SLICED = 1, C3_WEIGHTED = 2 };
 
 template <int W, int MODE, int STRIDE>
-__global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
+__global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3Args> grp)
 {
+    unsigned bid;                                     // workgroup number within this workgroup's layer
+    const C3Args &a = grp.a[group_pick(grp, bid)];
     constexpr bool WEIGHTED = MODE == C3_WEIGHTED;
     using C = C3Cfg<W, STRIDE>;
     constexpr int XB = 6;                             // X pieces per thread in flight at once
@@ -203,7 +206,7 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const C3Args a)
     const int tiles = a.tiles_co * a.tiles_ci;
     const int total = (WEIGHTED ? 1 : a.n) * tiles * a.ksplit;
     const int per_xcd = (total + 7) >> 3;
-    const int wg = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int wg = (int)(bid & 7u) * per_xcd + (int)(bid >> 3);
     if (wg >= total) return;
     const int split = wg % a.ksplit;
     const int unit = wg / a.ksplit;                   // (example, tile); weighted: tile
@@ -554,6 +557,10 @@ size_t c3_split_bytes(const Geo &g)
     return (size_t)g.n * g.cin * g.h * (2 * owp + 8) * sizeof(uint16_t);
 }
 
+// plans inside a batch call (the launch is shared with other layers) differ; workspace sizes cover both
+thread_local int c3_forced_crowd = -1;
+int c3_plan_crowd() { return c3_forced_crowd >= 0 ? c3_forced_crowd : crowd_hint(); }
+
 C3Plan c3_plan(const Geo &g, int mode)
 {
     C3Plan p;
@@ -565,9 +572,14 @@ C3Plan c3_plan(const Geo &g, int mode)
     p.chunks_per_split = p.chunks;
     p.ex_per_split = g.n;
     const long long tiles = (long long)p.tiles_co * p.tiles_ci;
+    // inside a batch call: chunks per workgroup to plan for (a chunk here is about eight 128x128x64 chunks of work, but
+    // slices cost a second pass over partial blocks: only very long walks are cut)
+    const int crowd = c3_plan_crowd(), tgt = crowd ? (crowd / 2 > 1 ? crowd / 2 : 1) : 0;
     if (mode == MODE_WEIGHTED) {
-        // example ranges: about 256 workgroups, partial blocks in the workspace kept below ~100 MB
+        // example ranges: about 256 workgroups, partial blocks in the workspace kept below ~100 MB; in a launch
+        // shared with other layers, ranges of about 96 chunks
         long long want = (256 + tiles - 1) / tiles;
+        if (crowd) want = ((long long)g.n * p.chunks + 2 * tgt - 1) / (2 * tgt);
         const long long cap = (long long)(96.0e6 / (4.0 * 9 * 16 * C3_THREADS * (double)tiles));
         if (want > cap) want = cap;
         if (want > g.n) want = g.n;
@@ -577,8 +589,9 @@ C3Plan c3_plan(const Geo &g, int mode)
         return p;
     }
     const long long units = (long long)g.n * tiles;
-    if (units < 128 && p.chunks > 1) {
+    if (p.chunks > 1 && (crowd ? p.chunks > tgt + tgt / 2 : units < 128)) {
         long long want = (128 + units - 1) / units;
+        if (crowd) want = (p.chunks + tgt - 1) / tgt;
         if (want > p.chunks) want = p.chunks;
         p.chunks_per_split = (int)((p.chunks + want - 1) / want);
         p.ksplit = (p.chunks + p.chunks_per_split - 1) / p.chunks_per_split;
@@ -595,15 +608,14 @@ template <int W, int MODE, int STRIDE>
 dp_status c3_launch_mode(const C3Args &a, unsigned blocks, hipStream_t s)
 {
     using C = C3Cfg<W, STRIDE>;
+    const void *fn = reinterpret_cast<const void *>(&conv3x3_kernel<W, MODE, STRIDE>);
     static bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&conv3x3_kernel<W, MODE, STRIDE>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS) != hipSuccess)
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS) != hipSuccess)
             return fail(DP_ERR_DEVICE, "conv3x3: cannot reserve %d bytes of LDS", C::LDS);
         attr_done = true;
     }
-    hipLaunchKernelGGL((conv3x3_kernel<W, MODE, STRIDE>), dim3(blocks), dim3(C3_THREADS), C::LDS, s, a);
-    return check_launch("conv3x3");
+    return submit_main<C3Args>(fn, a, blocks, C3_THREADS, C::LDS, s, "conv3x3");
 }
 
 template <int W, int STRIDE>
@@ -617,6 +629,8 @@ dp_status c3_launch_w(const C3Args &a, bool weighted, unsigned blocks, hipStream
 }
 
 }  // namespace
+
+void c3_set_forced_crowd(int v) { c3_forced_crowd = v; }
 
 bool conv3x3_applicable(const Geo &g, int mode)
 {
@@ -642,7 +656,20 @@ bool conv3x3_applicable(const Geo &g, int mode)
     return (long long)g.n * g.cin * g.h * g.w < (1ll << 31) && (long long)g.n * g.cout * g.h * g.w < (1ll << 31);
 }
 
+static size_t conv3x3_ws_bytes_plan(const Geo &g, int mode);
+
 size_t conv3x3_ws_bytes(const Geo &g, int mode)
+{
+    const int saved = c3_forced_crowd;
+    c3_forced_crowd = 0;
+    const size_t alone = conv3x3_ws_bytes_plan(g, mode);
+    c3_forced_crowd = 4;                             // smallest target: most slices
+    const size_t shared = conv3x3_ws_bytes_plan(g, mode);
+    c3_forced_crowd = saved;
+    return alone > shared ? alone : shared;
+}
+
+static size_t conv3x3_ws_bytes_plan(const Geo &g, int mode)
 {
     const C3Plan p = c3_plan(g, mode);
     const size_t tiles = (size_t)p.tiles_co * p.tiles_ci;
@@ -720,7 +747,6 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
         if (st != DP_OK) return st;
         a.x = reinterpret_cast<const uint16_t *>(w);
     }
-    profile_begin(s);
     if (g.stride == 2) {
         if (g.ow == 7) st = c3_launch_w<7, 2>(a, weighted, blocks, s);
         else st = c3_launch_w<14, 2>(a, weighted, blocks, s);
@@ -735,18 +761,21 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
         default: st = c3_launch_w<56, 1>(a, weighted, blocks, s); break;
         }
     }
-    profile_end(s);
     if (st != DP_OK) return st;
-    if (p.ksplit > 1) {
-        const unsigned fix_blocks = (unsigned)(units * 9 * C3_FIX_PARTS);
-        if (weighted) hipLaunchKernelGGL(conv3x3_fixup_kernel<true>, dim3(fix_blocks), dim3(C3_THREADS), 0, s, a);
-        else hipLaunchKernelGGL(conv3x3_fixup_kernel<false>, dim3(fix_blocks), dim3(C3_THREADS), 0, s, a);
-        st = check_launch("conv3x3_fixup");
-        if (st != DP_OK) return st;
-    }
-    if (!weighted && sqnorm)
-        st = launch_sum_partials(a.partials, g.n, p.tiles_co * p.tiles_ci * (int)c3_partials_per_unit(p), sqnorm, s);
-    return st;
+    // what follows the main kernel: at once, or after the grouped launch of a batch call
+    const int ksplit = p.ksplit, n = g.n, per_example = p.tiles_co * p.tiles_ci * (int)c3_partials_per_unit(p);
+    const unsigned fix_blocks = (unsigned)(units * 9 * C3_FIX_PARTS);
+    return submit_post([=]() -> dp_status {
+        dp_status st2 = DP_OK;
+        if (ksplit > 1) {
+            if (weighted) hipLaunchKernelGGL(conv3x3_fixup_kernel<true>, dim3(fix_blocks), dim3(C3_THREADS), 0, s, a);
+            else hipLaunchKernelGGL(conv3x3_fixup_kernel<false>, dim3(fix_blocks), dim3(C3_THREADS), 0, s, a);
+            st2 = check_launch("conv3x3_fixup");
+            if (st2 != DP_OK) return st2;
+        }
+        if (!weighted && sqnorm) st2 = launch_sum_partials(a.partials, n, per_example, sqnorm, s);
+        return st2;
+    });
 }
 
 }  // namespace dp

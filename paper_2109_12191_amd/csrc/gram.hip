@@ -215,7 +215,9 @@ dp_status launch_gram_norm(const Geo &g, const void *x, const void *dy, float *s
     a.out = static_cast<float *>(ws);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + gram_align16((size_t)g.n * GR_PARTS * sizeof(float)));
     profile_begin(s);
+    profile_begin(s);
     hipLaunchKernelGGL(gram_partial_kernel, dim3((unsigned)(g.n * (a.sa + a.sb))), dim3(GR_THREADS), 0, s, a);
+    profile_end(s);
     profile_end(s);
     dp_status st = check_launch("gram_partial");
     if (st != DP_OK) return st;

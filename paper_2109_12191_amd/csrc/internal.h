@@ -32,7 +32,8 @@ struct Geo {
 enum Mode { MODE_NORM = 0, MODE_MATERIALISE = 1, MODE_WEIGHTED = 2 };
 
 size_t conv_ws_bytes(const Geo &g, int mode);
-const char *conv_variant_name(const Geo &g, int mode);
+const char *conv_variant_name(const Geo &g, int mode, bool shared);
+void c3_set_forced_crowd(int v);      // conv3x3.hip: plan as alone (0), as in a shared launch (1), or by the open batch (-1)
 dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
                       hipStream_t s);
@@ -87,6 +88,8 @@ dp_status launch_norms(const float *layer_sqnorm, const int32_t *group_of_layer,
                        int n_groups, float *group_sqnorm, hipStream_t s);
 dp_status launch_norms_from_partials(const float *const *partials, const int32_t *counts, const int32_t *group_of_layer,
                                      int n_layers, int n, int n_groups, float *group_sqnorm, hipStream_t s);
+dp_status launch_layer_norms(const float *const *partials, const int32_t *counts, float *const *out, int n_layers, int n,
+                             hipStream_t s);
 dp_status launch_clip_factors(const float *sqnorm, float clip_c, int n, float *f, hipStream_t s);
 dp_status launch_clip_accumulate(const float *g, size_t stride, const float *sqnorm, float clip_c, int n,
                                  size_t p, float *acc, hipStream_t s);

@@ -105,6 +105,50 @@ dp_status launch_norms_from_partials(const float *const *partials, const int32_t
     return DP_OK;
 }
 
+// Per-layer squared norms of several layers from the partial sums their contraction kernels left in
+// their workspaces: out[l][i] = sum_c partials[l][i * count[l] + c].  One wavefront per (layer,
+// example), fixed order.  Used by the batch calls: one launch for all their layers.
+struct LayerNormArgs {
+    const float *ptr[NP_MAX];
+    float *out[NP_MAX];
+    int count[NP_MAX];
+    int n;
+};
+
+__global__ void __launch_bounds__(256) layer_norms_kernel(const LayerNormArgs a)
+{
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int l = blockIdx.y;
+    if (i >= a.n) return;
+    const int cnt = a.count[l];
+    const float *p = a.ptr[l] + (size_t)i * cnt;
+    float s = 0.0f;
+    for (int c = lane; c < cnt; c += 64) s += p[c];
+    s = wave_sum(s);
+    if (lane == 0) a.out[l][i] = s;
+}
+
+dp_status launch_layer_norms(const float *const *partials, const int32_t *counts, float *const *out, int n_layers, int n,
+                             hipStream_t s)
+{
+    for (int l0 = 0; l0 < n_layers; l0 += NP_MAX) {
+        LayerNormArgs a;
+        const int cnt = n_layers - l0 < NP_MAX ? n_layers - l0 : NP_MAX;
+        for (int l = 0; l < NP_MAX; ++l) {
+            const bool live = l < cnt;
+            a.ptr[l] = live ? partials[l0 + l] : nullptr;
+            a.out[l] = live ? out[l0 + l] : nullptr;
+            a.count[l] = live ? counts[l0 + l] : 0;
+        }
+        a.n = n;
+        hipLaunchKernelGGL(layer_norms_kernel, dim3((n + 3) / 4, cnt), dim3(256), 0, s, a);
+        const dp_status st = check_launch("layer_norms");
+        if (st != DP_OK) return st;
+    }
+    return DP_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 // H3
 __global__ void __launch_bounds__(256) clip_factors_kernel(const float *__restrict__ sqnorm, float clip_c, int n,

@@ -2,8 +2,8 @@
 
 This class owns device buffers (allocated through torch) and issues the library calls in
 order; it performs no arithmetic of its own.  Per micro-step:
-    dp_per_example_grad_partials (every layer)  ->  dp_norms_from_partials  ->  dp_clip_accumulate (materialised
-    layers) and dp_clip_accumulate_recompute (the rest);
+    dp_per_example_grad_batch (one call per group of layers that run the same kernel)  ->  dp_norms  ->
+    dp_clip_accumulate (materialised layers) and dp_clip_accumulate_recompute_batch (the rest);
 once per optimiser step: dp_add_noise_finalize per parameter tensor.
 
 Each layer uses one of the two forms of the clipped sum.  "materialise" keeps the layer's
@@ -88,10 +88,15 @@ class PrivatiseStep:
         need = [max(16, B.dp_workspace_bytes(d, B.DP_WS_PER_EXAMPLE_GRAD),
                     B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE) if form == "recompute" else 0)
                 for d, form in zip(self.descs, self.form)]
-        # a workspace per layer: a layer's partial squared norms stay at its start until dp_norms_from_partials
+        # a workspace per layer (the layers of a phase are in flight together)
         self._ws = [[torch.empty(b, dtype=torch.uint8, device=dev) for b in need] for _ in range(self.copies)]
-        counts = [B.dp_norm_partial_count(d, form == "materialise") for d, form in zip(self.descs, self.form)]
-        self._partials = [B.PartialTable([w.data_ptr() for w in wss], counts, self.group_of_layer) for wss in self._ws]
+        self._layer_sqnorm = [torch.zeros((L, self.n), dtype=f32, device=dev) for _ in range(self.copies)]
+        # Layers that run the same kernel variant go to the library in ONE batch call, which puts them into one
+        # launch (at most 16 per launch): per phase a micro-step is a dozen launches, not a hundred.
+        self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD | B.DP_VARIANT_SHARED),
+                         B.dp_kernel_variant(d, B.DP_WS_RECOMPUTE | B.DP_VARIANT_SHARED)) for d in self.descs]
+        self._groups_a = self._make_groups(range(L), 0)
+        self._groups_b = self._make_groups([i for i in range(L) if self.form[i] == "recompute"], 1)
         # side streams: `side` for the per-example phase, `side_b` for the clipped-sum phase
         self.side = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
         self.side_b = [torch.cuda.Stream(device=dev) for _ in range(max(2, self.n_streams // 2))] if self.n_streams > 1 else []
@@ -112,8 +117,6 @@ class PrivatiseStep:
         # library to bracket the next contraction kernel with a pair of events
         self.probe = None
         esize = 2 if wl.dtype == "bf16" else 4
-        self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD), B.dp_kernel_variant(d, B.DP_WS_RECOMPUTE))
-                        for d in self.descs]
         # algorithmic work of one call per layer: (flop, HBM bytes of the per-example call, HBM bytes of the
         # recomputing clipped-sum call).  Bytes = the operands read once, plus the per-example gradients
         # written when the layer materialises them, or the accumulator read and written by form (b).
@@ -122,24 +125,64 @@ class PrivatiseStep:
                       l.in_bytes(esize) * wl.n + 8 * (pw + pb))
                      for l, pw, pb, form in zip(self.layers, self.pw, self.pb, self.form)]
 
-    def _arm(self, li: int, use: int):
-        if self.probe is not None and self.layers[li].kind == "conv":
-            self.probe.arm(self.variant[li][use], self.work[li][0], self.work[li][1 + use])
+    def _make_groups(self, layer_ids, use: int):
+        """Groups of at most 16 layers with the same kernel variant for phase `use` (0: per-example gradients,
+        1: recomputing clipped sum), largest total work first.  Each group: dict(layers, name, batch per copy,
+        constant pointer arrays)."""
+        by_name = {}
+        for li in layer_ids:
+            key = self.variant[li][use] + ("|mat" if (use == 0 and self.form[li] == "materialise") else "")
+            by_name.setdefault(key, []).append(li)
+        groups = []
+        for key, ids in by_name.items():
+            for k in range(0, len(ids), 16):
+                part = ids[k: k + 16]
+                name = key.split("|")[0]
+                if len(part) == 1:           # a single layer is planned as a launch of its own
+                    name = B.dp_kernel_variant(self.descs[part[0]], B.DP_WS_RECOMPUTE if use else B.DP_WS_PER_EXAMPLE_GRAD)
+                g = dict(layers=part, name=name, conv=all(self.layers[i].kind == "conv" for i in part))
+                g["batch"] = [B.LayerBatch([self.descs[i] for i in part], [self._ws[c][i].data_ptr() for i in part],
+                                           [self._ws[c][i].numel() for i in part]) for c in range(self.copies)]
+                if use == 0:
+                    g["sq"] = [g["batch"][c].ptrs([self._layer_sqnorm[c][i].data_ptr() for i in part])
+                               for c in range(self.copies)]
+                    mat = [self.form[i] == "materialise" for i in part]
+                    g["gw"] = [g["batch"][c].ptrs([self._g[c][:, self.off_w[i]:].data_ptr() if m else None
+                                                   for i, m in zip(part, mat)]) for c in range(self.copies)] if any(mat) else None
+                    g["gb"] = [g["batch"][c].ptrs([self._g[c][:, self.off_b[i]:].data_ptr() if (m and self.pb[i]) else None
+                                                   for i, m in zip(part, mat)]) for c in range(self.copies)] if any(mat) else None
+                else:
+                    g["sq"] = [g["batch"][c].ptrs([self._group_sqnorm[c][self.group_of_layer[i]].data_ptr() for i in part])
+                               for c in range(self.copies)]
+                    g["clip"] = g["batch"][0].floats([self.group_clip[self.group_of_layer[i]] for i in part])
+                    g["acc_w"] = g["batch"][0].ptrs([self.acc[self.off_w[i]:].data_ptr() for i in part])
+                    g["acc_b"] = g["batch"][0].ptrs([self.acc[self.off_b[i]:].data_ptr() if self.pb[i] else None
+                                                     for i in part])
+                g["flops"] = sum(self.layers[i].flops for i in part) * self.n
+                groups.append(g)
+        groups.sort(key=lambda g: -g["flops"])
+        return groups
+
+    def _arm(self, group, use: int):
+        if self.probe is not None and group["conv"]:
+            self.probe.arm(group["name"], sum(self.work[i][0] for i in group["layers"]),
+                           sum(self.work[i][1 + use] for i in group["layers"]), len(group["layers"]))
 
     def _choose(self, layer, mode: str) -> str:
         if mode in ("materialise", "recompute"):
             return mode
         if mode != "auto":
             raise ValueError(mode)
-        # Cost model fitted to measured kernel times on MI355X (micro-batch n):
-        #   materialise: the [n, P] fp32 gradients are written by the contraction's epilogue and
-        #     read back by the streaming accumulate -- 8 n P bytes at ~3 TB/s effective;
-        #   recompute: a second (clip-weighted) contraction plus the packing / slice-sum kernels
-        #     around it -- ~40 us of fixed cost plus the layer's flops at ~100 TFLOP/s sustained.
-        # Layers with more than about a million parameters (late stages, the classifier) recompute.
+        # Cost model fitted to measured kernel times on MI355X (micro-batch n, layers launched in groups):
+        #   materialise: the [n, P] fp32 gradients are written by the contraction's epilogue and read back by the
+        #     streaming accumulate -- 8 n P bytes at ~5 TB/s;
+        #   recompute: a second (clip-weighted) contraction -- ~10 us of fixed cost (packing, slice sums), the
+        #     layer's inputs once more at ~4 TB/s and its flops at ~300 TFLOP/s sustained.
+        # Layers with more than about half a million parameters (stage 4, the classifier) recompute.
         p = layer.pw + layer.pb
-        materialise = 8.0 * p * self.n / 3.0e12
-        recompute = 40.0e-6 + layer.flops * self.n / 100.0e12
+        esize = 2 if self.wl.dtype == "bf16" else 4
+        materialise = 8.0 * p * self.n / 5.0e12
+        recompute = 10.0e-6 + layer.in_bytes(esize) * self.n / 4.0e12 + layer.flops * self.n / 300.0e12
         return "materialise" if materialise <= recompute else "recompute"
 
     # ---- views of one layer's tensors in the flat vectors
@@ -191,9 +234,6 @@ class PrivatiseStep:
         self.micro_steps_done = 0
         self._b_done = [None] * self.copies
 
-    def _stream_of(self, li: int):
-        return self.side[li % self.n_streams] if self.side else None
-
     def micro_step(self, inputs: Sequence):
         """inputs: per layer (x, dy) device tensors of the workload's dtype, n examples each.
 
@@ -215,23 +255,17 @@ class PrivatiseStep:
             if self._b_done[c] is not None:           # this copy's previous clipped sum has finished
                 for ev in self._b_done[c]:
                     st.wait_event(ev)
-        for li in range(L):
-            x, dy = inputs[li]
-            st = self._stream_of(li)
-            ws = wss[li]
-            self._arm(li, 0)
-            if self.form[li] == "materialise":
-                g_w = g_buf[:, self.off_w[li]:]
-                g_b = g_buf[:, self.off_b[li]:] if self.pb[li] else None
-                B.dp_per_example_grad_partials(self.descs[li], x, dy, g_w.data_ptr(),
-                                               g_b.data_ptr() if g_b is not None else None,
-                                               ws, g_stride=gs, ws_bytes=ws.numel(), stream=st)
-            else:
-                B.dp_per_example_grad_partials(self.descs[li], x, dy, None, None, ws,
-                                               ws_bytes=ws.numel(), stream=st)
+        for gi, grp in enumerate(self._groups_a):
+            st = self.side[gi % self.n_streams] if self.side else None
+            bt = grp["batch"][c]
+            xs = bt.ptrs([inputs[i][0].data_ptr() for i in grp["layers"]])
+            dys = bt.ptrs([inputs[i][1].data_ptr() for i in grp["layers"]])
+            self._arm(grp, 0)
+            B.dp_per_example_grad_batch(bt, xs, dys, grp["gw"][c] if grp["gw"] else None,
+                                        grp["gb"][c] if grp["gb"] else None, grp["sq"][c], g_stride=gs, stream=st)
         for st in self.side:
             main.wait_stream(st)
-        B.dp_norms_from_partials(self._partials[c], self.n, self.n_groups, gsq)
+        B.dp_norms(self._layer_sqnorm[c], self.group_of_layer_dev, L, self.n, self.n_groups, gsq)
         # ---- phase B
         for st in self.side_b:
             st.wait_stream(main)
@@ -250,22 +284,17 @@ class PrivatiseStep:
             for li in range(L):
                 if self.form[li] == "materialise":
                     self._example_noise(li, sb[0] if sb else None)
-        k = 0
-        for li in range(L):
-            if self.form[li] != "recompute":
-                continue
-            x, dy = inputs[li]
-            g = self.group_of_layer[li]
-            ws = wss[li]
-            st = sb[(1 + k) % len(sb)] if sb else None
-            k += 1
-            self._arm(li, 1)
-            B.dp_clip_accumulate_recompute(self.descs[li], x, dy, gsq[g], self.group_clip[g],
-                                           self.acc_w(li).data_ptr(),
-                                           self.acc_b(li).data_ptr() if self.pb[li] else None,
-                                           ws, ws_bytes=ws.numel(), stream=st)
+        for gi, grp in enumerate(self._groups_b):
+            st = sb[(1 + gi) % len(sb)] if sb else None
+            bt = grp["batch"][c]
+            xs = bt.ptrs([inputs[i][0].data_ptr() for i in grp["layers"]])
+            dys = bt.ptrs([inputs[i][1].data_ptr() for i in grp["layers"]])
+            self._arm(grp, 1)
+            B.dp_clip_accumulate_recompute_batch(bt, xs, dys, grp["sq"][c], grp["clip"], grp["acc_w"], grp["acc_b"],
+                                                 stream=st)
             if self.noise == "per_example":
-                self._example_noise(li, st)
+                for li in grp["layers"]:
+                    self._example_noise(li, st)
         if sb:
             evs = []
             for st in sb:

@@ -558,3 +558,92 @@ def test_flat_finalize_gives_the_bits_of_one_call_per_tensor(with_update):
         g = host(want)
         for b, sz in zip(begins, sizes):
             assert_close(host(th2[b: b + sz]), th0[b: b + sz].astype(np.float64) - 0.05 * g[b: b + sz], F32_TOL, "theta")
+
+
+BATCH_LAYERS = [
+    conv(64, 256, 1, 1, 28), conv(256, 64, 1, 1, 28), conv(64, 64, 1, 1, 28),          # 1x1, aligned rows
+    conv(160, 136, 1, 1, 28), conv(130, 200, 1, 1, 14),                               # 128x128 tiles when the launch is shared
+    conv(96, 72, 1, 1, 7, bias=True), conv(33, 65, 1, 1, 15),                          # odd S: gather loader, bias
+    conv(64, 64, 3, 1, 28), conv(64, 128, 3, 1, 28), conv(128, 64, 3, 1, 14),          # raw-row 3x3 kernels
+    conv(48, 80, 1, 2, 14), conv(128, 128, 3, 2, 28), conv(3, 64, 7, 2, 64),           # strided, long K
+    conv(256, 512, 1, 1, 7), conv(512, 256, 3, 1, 7),                                  # Gram-route norms
+    dense(100, 36), gn_affine(32, 10, 8),
+]
+
+
+@pytest.mark.parametrize("n", [1, 5])
+@pytest.mark.parametrize("materialise", [False, True])
+def test_batch_call_matches_the_single_layer_calls_and_the_oracle(n, materialise):
+    """dp_per_example_grad_batch: many layers in one call (layers of one kernel share a launch, tiling chosen for a
+    shared launch): every layer's gradients and norms against the single-layer call and against the oracle."""
+    dtype = "bf16"
+    ins = [_inputs(l, n, 900 + k, dtype) for k, l in enumerate(BATCH_LAYERS)]
+    descs = [dp.make_desc(l, n, dtype) for l in BATCH_LAYERS]
+    xs = [dev(x, dtype) for x, _ in ins]
+    dys = [dev(dy, dtype) for _, dy in ins]
+    wss = [torch.empty(max(16, dp.dp_workspace_bytes(d)), dtype=torch.uint8, device="cuda:0") for d in descs]
+    sq = torch.full((len(descs), n), -1.0, device="cuda:0")
+    gws = [torch.full((n, l.pw), 7.0, device="cuda:0") for l in BATCH_LAYERS]
+    gbs = [torch.full((n, max(l.pb, 1)), 7.0, device="cuda:0") for l in BATCH_LAYERS]
+    batch = dp.LayerBatch(descs, [w.data_ptr() for w in wss], [w.numel() for w in wss])
+    for rep in range(2):                                   # twice: same bits on every call
+        dp.dp_per_example_grad_batch(batch, batch.ptrs([t.data_ptr() for t in xs]), batch.ptrs([t.data_ptr() for t in dys]),
+                                     batch.ptrs([t.data_ptr() for t in gws]) if materialise else None,
+                                     batch.ptrs([t.data_ptr() if l.pb else None for t, l in zip(gbs, BATCH_LAYERS)]) if materialise else None,
+                                     batch.ptrs([sq[k].data_ptr() for k in range(len(descs))]))
+        torch.cuda.synchronize()
+        if rep == 0:
+            first = (sq.clone(), [g.clone() for g in gws])
+        else:
+            assert torch.equal(sq, first[0]) and all(torch.equal(a, b) for a, b in zip(gws, first[1]))
+    for k, l in enumerate(BATCH_LAYERS):
+        x, dy = ins[k]
+        ref_w, ref_b, ref_n2 = _oracle_grads(l, x, dy)
+        assert np.allclose(host(sq[k]), ref_n2, rtol=BF16_TOL, atol=0), (k, l, host(sq[k]), ref_n2)
+        gw1, gb1, sq1 = _run_per_example(l, x, dy, dtype, materialise=materialise)
+        assert np.allclose(host(sq[k]), sq1, rtol=3e-5, atol=0), (k, l)
+        if materialise:
+            for i in range(n):
+                assert_close(host(gws[k][i]), ref_w[i], BF16_TOL, f"layer {k} dW[{i}]")
+                if l.pb:
+                    assert_close(host(gbs[k][i, :l.pb]), ref_b[i], BF16_TOL, f"layer {k} db[{i}]")
+            assert_close(host(gws[k]), gw1, 2e-5, f"layer {k} against the single-layer call")
+
+
+@pytest.mark.parametrize("n", [1, 6])
+def test_recompute_batch_call_matches_the_single_layer_calls_and_the_oracle(n):
+    dtype = "bf16"
+    rng = np.random.default_rng(61)
+    layers = BATCH_LAYERS
+    ins = [_inputs(l, n, 950 + k, dtype) for k, l in enumerate(layers)]
+    descs = [dp.make_desc(l, n, dtype) for l in layers]
+    xs = [dev(x, dtype) for x, _ in ins]
+    dys = [dev(dy, dtype) for _, dy in ins]
+    wss = [torch.empty(max(16, dp.dp_workspace_bytes(d, dp.DP_WS_RECOMPUTE)), dtype=torch.uint8, device="cuda:0") for d in descs]
+    n2 = (rng.uniform(0.4, 2.0, (len(layers), n)) ** 2).astype(np.float32)          # both clip branches
+    n2d = dev(n2)
+    clips = [1.0 + 0.1 * (k % 3) for k in range(len(layers))]
+    acc0 = [rng.standard_normal(l.pw).astype(np.float32) * 1e-3 for l in layers]
+    accb0 = [rng.standard_normal(max(l.pb, 1)).astype(np.float32) * 1e-3 for l in layers]
+    acc_w = [dev(a) for a in acc0]
+    acc_b = [dev(a) for a in accb0]
+    batch = dp.LayerBatch(descs, [w.data_ptr() for w in wss], [w.numel() for w in wss])
+    dp.dp_clip_accumulate_recompute_batch(batch, batch.ptrs([t.data_ptr() for t in xs]), batch.ptrs([t.data_ptr() for t in dys]),
+                                          batch.ptrs([n2d[k].data_ptr() for k in range(len(layers))]), batch.floats(clips),
+                                          batch.ptrs([t.data_ptr() for t in acc_w]),
+                                          batch.ptrs([t.data_ptr() if l.pb else None for t, l in zip(acc_b, layers)]))
+    torch.cuda.synchronize()
+    for k, l in enumerate(layers):
+        x, dy = ins[k]
+        f = np.array([oracle.clip_factor(float(v), clips[k]) for v in n2[k]])
+        ref_w, ref_b, _ = _oracle_grads(l, x, dy)
+        want = (f[:, None] * ref_w).sum(axis=0)
+        assert_close(host(acc_w[k]) - acc0[k], want, BF16_TOL, f"layer {k} {l} weighted sum")
+        if l.pb:
+            assert_close(host(acc_b[k])[:l.pb] - accb0[k][:l.pb], (f[:, None] * ref_b).sum(axis=0), BF16_TOL, f"layer {k} bias")
+        # the single-layer call
+        one = dev(acc0[k])
+        oneb = dev(accb0[k])
+        dp.dp_clip_accumulate_recompute(descs[k], xs[k], dys[k], n2d[k], clips[k], one, oneb if l.pb else None, wss[k])
+        torch.cuda.synchronize()
+        assert_close(host(acc_w[k]) - acc0[k], host(one) - acc0[k], 1e-4, f"layer {k} against the single-layer call")
