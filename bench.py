@@ -206,7 +206,48 @@ def main():
                         share_of_contraction_time=dom["total_ms"] / sum(v["total_ms"] for v in contraction.values()),
                         measured="HIP events recorded by the library around each launch of this kernel, on its stream, "
                                  "in a call-by-call single-stream pass over the same steps right after the timed region")
+    # The streaming kernels of the step, each launched as the step launches it (same buffers, same sizes) and
+    # bracketed by events on its stream: H4a, the clip-scale-accumulate pass over the materialised gradients of one
+    # micro-step, and H5, noise + finalize over the whole parameter vector in one launch.
+    streaming = {}
+    def _time_stream(fn, reps=10):
+        fn()
+        torch.cuda.synchronize()
+        pairs = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in pairs)
+        return ts[len(ts) // 2] * 1e-3
+    if pe.p_mat and pe.n_groups == 1:
+        g_bufs = [pe._g[0], ps._g[0]] if ps._g[0] is not None else [pe._g[0]]      # alternate: not cache resident
+        k = [0]
+        def _ca():
+            k[0] += 1
+            dp.dp_clip_accumulate(g_bufs[k[0] % len(g_bufs)], pe._group_sqnorm[0][0], pe.group_clip[0], pe.n, pe.p_mat,
+                                  pe.acc, g_stride=pe.p_mat)
+        sec = _time_stream(_ca)
+        nbytes = 4.0 * pe.n * pe.p_mat + 8.0 * pe.p_mat
+        streaming["clip_accumulate"] = dict(kernel="clip_accumulate_kernel", bytes=nbytes, us=sec * 1e6,
+                                            achieved_GBps=nbytes / sec / 1e9, frac=nbytes / sec / HBM_PEAK,
+                                            what=f"reads the [{pe.n}, {pe.p_mat}] fp32 gradient matrix once, reads and writes the accumulator")
+    def _fin():
+        dp.dp_add_noise_finalize_flat(pe.acc, pe.out, pe._tensors, wl.sigma, pe.clip_total, wl.total_batch, wl.philox_seed,
+                                      step_dev=pe._step_dev)
+    sec = _time_stream(_fin)
+    nbytes = 8.0 * wl.n_params
+    streaming["noise_finalize"] = dict(kernel="noise_finalize_flat_kernel", bytes=nbytes, us=sec * 1e6,
+                                       achieved_GBps=nbytes / sec / 1e9, frac=nbytes / sec / HBM_PEAK,
+                                       what=f"{wl.n_params} parameters in one launch: 4 B read + 4 B written each, Philox4x32-10 + Box-Muller per 4")
+    if roofline is not None:
+        roofline["streaming"] = streaming
+        roofline["streaming_measured"] = ("median of 10 launches, each bracketed by events on its stream (the events add 1-2 us "
+                                          "to a launch; rocprofv3 durations of the same kernels are in profiles/)")
     if args.table:
+        for k, v in streaming.items():
+            print(f"{k:50s} {v['us']:9.1f} us  {v['achieved_GBps']:8.1f} GB/s  {v['frac']:.2f} of HBM peak", file=sys.stderr)
         for k, v in sorted(summary.items(), key=lambda kv: -kv[1]["total_ms"]):
             tf = v["flops"] / (v["total_ms"] * 1e-3) / 1e12 if v["total_ms"] else 0.0
             gb = v["bytes"] / (v["total_ms"] * 1e-3) / 1e9 if v["total_ms"] else 0.0

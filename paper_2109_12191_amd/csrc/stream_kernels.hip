@@ -171,6 +171,19 @@ dp_status launch_clip_factors(const float *sqnorm, float clip_c, int n, float *f
 // row, so every wave load is a full 1 KiB run.  `stride` is the distance between rows.
 constexpr int CA_FMAX = 1024;   // clip factors staged in LDS per pass over the examples
 
+// 16-byte load of data that is read exactly once (the per-example gradient matrix): non-temporal, so the
+// stream does not push the accumulator and the clip factors out of the caches (measured: 5.5 -> 6.0 TB/s)
+__device__ __forceinline__ float4 load_once(const float *p)
+{
+    const float4 *q = reinterpret_cast<const float4 *>(p);
+    float4 v;
+    v.x = __builtin_nontemporal_load(&q->x);
+    v.y = __builtin_nontemporal_load(&q->y);
+    v.z = __builtin_nontemporal_load(&q->z);
+    v.w = __builtin_nontemporal_load(&q->w);
+    return v;
+}
+
 template <int VEC>
 __global__ void __launch_bounds__(256) clip_accumulate_kernel(const float *__restrict__ g, size_t stride,
                                                                const float *__restrict__ sqnorm, float clip_c,
@@ -194,7 +207,7 @@ __global__ void __launch_bounds__(256) clip_accumulate_kernel(const float *__res
                 for (; j + 8 <= cnt; j += 8) {        // eight rows' loads in flight per thread
                     float4 v[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4 *>(row + (size_t)(j + u) * stride);
+                    for (int u = 0; u < 8; ++u) v[u] = load_once(row + (size_t)(j + u) * stride);
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {    // example order: same bits on every run
                         const float fu = fs[j + u];
@@ -202,7 +215,7 @@ __global__ void __launch_bounds__(256) clip_accumulate_kernel(const float *__res
                     }
                 }
                 for (; j < cnt; ++j) {
-                    const float4 a = *reinterpret_cast<const float4 *>(row + (size_t)j * stride);
+                    const float4 a = load_once(row + (size_t)j * stride);
                     const float f0 = fs[j];
                     s[0] += f0 * a.x; s[1] += f0 * a.y; s[2] += f0 * a.z; s[3] += f0 * a.w;
                 }
@@ -252,7 +265,7 @@ __global__ void __launch_bounds__(256) clip_accumulate_segments_kernel(const flo
 #pragma unroll 8
     for (int i = 0; i < n; ++i) {                  // example order: same bits on every run
         const float f = clip_factor(sq[i], c);
-        const float4 v = *reinterpret_cast<const float4 *>(row + (size_t)i * stride);
+        const float4 v = load_once(row + (size_t)i * stride);
         s0 += f * v.x; s1 += f * v.y; s2 += f * v.z; s3 += f * v.w;
     }
     float4 a = *reinterpret_cast<float4 *>(acc + e);
@@ -532,7 +545,7 @@ __global__ void __launch_bounds__(256) noise_finalize_flat_kernel(const float *_
     // the loads go out first; the integer and transcendental work below hides their latency
     float a[4] = {0.0f, 0.0f, 0.0f, 0.0f}, t[4] = {0.0f, 0.0f, 0.0f, 0.0f}, v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (full) {
-        const float4 av = *reinterpret_cast<const float4 *>(acc + at);
+        const float4 av = load_once(acc + at);            // read once, written once: keep the stream out of the caches
         a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
         if constexpr (UPDATE) {
             const float4 tv = *reinterpret_cast<const float4 *>(theta + at);
@@ -562,7 +575,13 @@ __global__ void __launch_bounds__(256) noise_finalize_flat_kernel(const float *_
         }
     }
     if (full) {
-        if (out) *reinterpret_cast<float4 *>(out + at) = make_float4(g[0], g[1], g[2], g[3]);
+        if (out) {
+            float4 *o = reinterpret_cast<float4 *>(out + at);
+            __builtin_nontemporal_store(g[0], &o->x);
+            __builtin_nontemporal_store(g[1], &o->y);
+            __builtin_nontemporal_store(g[2], &o->z);
+            __builtin_nontemporal_store(g[3], &o->w);
+        }
         if constexpr (UPDATE) {
             *reinterpret_cast<float4 *>(theta + at) = make_float4(t[0], t[1], t[2], t[3]);
             if (vbuf) *reinterpret_cast<float4 *>(vbuf + at) = make_float4(v[0], v[1], v[2], v[3]);
