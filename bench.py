@@ -118,6 +118,8 @@ def main():
                     help="examples of micro-batch 0 the oracle is timed on (32 = about 10 s on 16 cores)")
     ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
     ap.add_argument("--streams", type=int, default=8, help="side streams for independent layers")
+    ap.add_argument("--batching", default="variant", choices=("variant", "all"),
+                    help="layers per batch call: those of one kernel variant, or all layers of a phase")
     ap.add_argument("--noise", default="once", choices=["once", "per_example"],
                     help="once: N(0, sigma^2 C^2) in finalize; per_example: every clipped example brings N(0, sigma^2 C^2/|B|)")
     ap.add_argument("--fused-update", action="store_true",
@@ -137,7 +139,8 @@ def main():
     dp.load_library()
     device = torch.device("cuda:0")
     wl = get_workload(args.workload, n=args.n, accum=args.accum, hw=args.hw)
-    ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=args.streams, noise=args.noise)
+    ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=args.streams, noise=args.noise,
+                          batching=args.batching)
     inputs = make_device_inputs(wl, wl.accum, device)
     if args.fused_update:
         ps.enable_update(lr=0.1, momentum=0.9, keep_gradient=False)

@@ -173,10 +173,23 @@ dp_status dp_per_example_grad_partials(const dp_layer_desc *desc, const void *x,
  * device pointers; g_w, g_b [host] arrays of device pointers or NULL (= no layer materialises), entry NULL
  * = that layer does not; sqnorm[l] [device] [n], overwritten; ws[l] at least dp_workspace_bytes(&descs[l],
  * DP_WS_PER_EXAMPLE_GRAD), one workspace per layer (they are in use at the same time).  Every argument of
- * every layer is validated before anything is launched.                                              */
+ * every layer is validated before anything is launched.
+ * sqnorm may be NULL: then the per-layer reduction is left to the caller, who collects the partial sums of
+ * several batch calls (one per stream, say) and reduces them all in one dp_layer_norms_from_partials launch.
+ * Layer l's partial squared norms stay at the start of its workspace, ws[l][0 .. n * partial_counts[l]) as a
+ * row-major [n, partial_counts[l]] float matrix, until that workspace is used again.
+ * partial_counts [host] n_layers ints, written by the call (the count depends on how the batch was planned),
+ * or NULL when not wanted; required when sqnorm is NULL.                                               */
 dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *const *x, const void *const *dy,
                                     float *const *g_w, float *const *g_b, size_t g_stride, float *const *sqnorm,
-                                    void *const *ws, const size_t *ws_bytes, int n_layers, dp_stream stream);
+                                    void *const *ws, const size_t *ws_bytes, int32_t *partial_counts, int n_layers,
+                                    dp_stream stream);
+
+/* Per-layer part of H2 from partial sums: sqnorm[l][i] = sum_c partials[l][i * counts[l] + c], c in order, for
+ * n_layers layers in one launch (64 layers per launch beyond that).  partials, sqnorm [host] arrays of n_layers
+ * device pointers (4-byte aligned), counts [host] n_layers ints >= 1; sqnorm[l] [device] [n], overwritten.   */
+dp_status dp_layer_norms_from_partials(const float *const *partials, const int32_t *counts, float *const *sqnorm,
+                                       int n_layers, int n, dp_stream stream);
 
 /* H4, recomputing form, for several layers in one call: for every layer l what
  * dp_clip_accumulate_recompute(&descs[l], x[l], dy[l], sqnorm[l], clip_c[l], acc_w[l], acc_b[l], ws[l], ws_bytes[l])

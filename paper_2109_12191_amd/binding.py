@@ -62,7 +62,8 @@ def load_library():
         "dp_norm_partial_count": (sz, [dpp, it]),
         "dp_per_example_grad_partials": (it, [dpp, vp, vp, vp, vp, sz, vp, sz, vp]),
         "dp_norms_from_partials": (it, [vp, vp, vp, it, it, it, vp, vp]),
-        "dp_per_example_grad_batch": (it, [vp, vp, vp, vp, vp, sz, vp, vp, vp, it, vp]),
+        "dp_per_example_grad_batch": (it, [vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, it, vp]),
+        "dp_layer_norms_from_partials": (it, [vp, vp, vp, it, it, vp]),
         "dp_clip_accumulate_recompute_batch": (it, [vp, vp, vp, vp, vp, vp, vp, vp, vp, it, vp]),
         "dp_clip_factors": (it, [vp, fl, it, vp, vp]),
         "dp_clip_accumulate": (it, [vp, sz, vp, fl, it, sz, vp, vp]),
@@ -88,7 +89,7 @@ def load_library():
 EXPORTED = ("dp_group_clip_bounds", "dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_static_scratch_bytes", "dp_per_example_grad_static",
             "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
-            "dp_per_example_grad_batch", "dp_clip_accumulate_recompute_batch",
+            "dp_per_example_grad_batch", "dp_layer_norms_from_partials", "dp_clip_accumulate_recompute_batch",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_segments", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
             "dp_add_noise_finalize_flat", "dp_philox_raw", "dp_profile_next_contraction", "dp_last_error", "dp_version")
 
@@ -211,6 +212,7 @@ class LayerBatch:
         self.descs = (LayerDesc * k)(*descs)
         self.ws = (C.c_void_p * k)(*[int(p) for p in ws_ptrs])
         self.ws_bytes = (C.c_size_t * k)(*[int(b) for b in ws_bytes])
+        self.partial_counts = (C.c_int32 * k)()          # written by dp_per_example_grad_batch
 
     def ptrs(self, values):
         assert len(values) == self.n_layers
@@ -222,13 +224,23 @@ class LayerBatch:
 
 
 def dp_per_example_grad_batch(batch: "LayerBatch", x, dy, g_w, g_b, sqnorm, g_stride: int = 0, stream=None):
-    """x, dy, sqnorm: ctypes pointer arrays from batch.ptrs(); g_w, g_b: the same or None."""
+    """x, dy: ctypes pointer arrays from batch.ptrs(); g_w, g_b, sqnorm: the same or None (sqnorm None: the
+    per-layer reduction is left to dp_layer_norms_from_partials).  batch.partial_counts receives the number of
+    partial sums per example each layer left at the start of its workspace."""
     _check(load_library().dp_per_example_grad_batch(C.cast(batch.descs, C.c_void_p), C.cast(x, C.c_void_p),
                                                     C.cast(dy, C.c_void_p),
                                                     None if g_w is None else C.cast(g_w, C.c_void_p),
                                                     None if g_b is None else C.cast(g_b, C.c_void_p), g_stride,
-                                                    C.cast(sqnorm, C.c_void_p), C.cast(batch.ws, C.c_void_p),
-                                                    C.cast(batch.ws_bytes, C.c_void_p), batch.n_layers, _stream(stream)))
+                                                    None if sqnorm is None else C.cast(sqnorm, C.c_void_p),
+                                                    C.cast(batch.ws, C.c_void_p), C.cast(batch.ws_bytes, C.c_void_p),
+                                                    C.cast(batch.partial_counts, C.c_void_p), batch.n_layers,
+                                                    _stream(stream)))
+
+
+def dp_layer_norms_from_partials(partials, counts, sqnorm, n_layers: int, n: int, stream=None):
+    """partials, sqnorm: ctypes arrays of n_layers device pointers; counts: ctypes int32 array."""
+    _check(load_library().dp_layer_norms_from_partials(C.cast(partials, C.c_void_p), C.cast(counts, C.c_void_p),
+                                                       C.cast(sqnorm, C.c_void_p), n_layers, n, _stream(stream)))
 
 
 def dp_clip_accumulate_recompute_batch(batch: "LayerBatch", x, dy, sqnorm, clip_c, acc_w, acc_b, stream=None):

@@ -53,33 +53,36 @@ int crowd_hint() { return g_queue ? g_queue->crowd : 0; }
 dp_status flush_queue(LaunchQueue &q)
 {
     set_open_queue(nullptr);                         // from here on everything is launched at once
-    std::vector<char> done(q.main.size(), 0);
     std::vector<char> args;
     std::vector<unsigned> blocks;
-    for (size_t i = 0; i < q.main.size(); ++i) {
-        if (done[i]) continue;
-        const LaunchQueue::Item &first = q.main[i];
-        // every held launch of the same kernel, in the order they were submitted, GROUP_MAX per launch
-        args.clear(); blocks.clear();
-        auto fire = [&]() -> dp_status {
-            if (blocks.empty()) return DP_OK;
-            profile_begin(q.stream);
-            const dp_status st = first.go(first.fn, args.data(), blocks.data(), (int)blocks.size(), first.threads, first.lds, q.stream);
-            profile_end(q.stream);
+    for (int tier = 0; tier < TIER_COUNT; ++tier) {
+        std::vector<LaunchQueue::Item> &held = q.tier[tier];
+        std::vector<char> done(held.size(), 0);
+        for (size_t i = 0; i < held.size(); ++i) {
+            if (done[i]) continue;
+            const LaunchQueue::Item &first = held[i];
+            // every held launch of the same kernel, in the order they were submitted, GROUP_MAX per launch
             args.clear(); blocks.clear();
-            return st != DP_OK ? st : check_launch(first.what);
-        };
-        for (size_t j = i; j < q.main.size(); ++j) {
-            const LaunchQueue::Item &it = q.main[j];
-            if (done[j] || it.fn != first.fn || it.lds != first.lds || it.threads != first.threads) continue;
-            done[j] = 1;
-            args.insert(args.end(), it.args.begin(), it.args.end());
-            blocks.push_back(it.blocks);
-            if ((int)blocks.size() == GROUP_MAX) DP_TRY_ST(fire());
+            auto fire = [&]() -> dp_status {
+                if (blocks.empty()) return DP_OK;
+                if (tier == TIER_MAIN) profile_begin(q.stream);
+                const dp_status st = first.go(first.fn, args.data(), blocks.data(), (int)blocks.size(), first.threads, first.lds, q.stream);
+                if (tier == TIER_MAIN) profile_end(q.stream);
+                args.clear(); blocks.clear();
+                return st != DP_OK ? st : check_launch(first.what);
+            };
+            for (size_t j = i; j < held.size(); ++j) {
+                const LaunchQueue::Item &it = held[j];
+                if (done[j] || it.fn != first.fn || it.lds != first.lds || it.threads != first.threads) continue;
+                done[j] = 1;
+                args.insert(args.end(), it.args.begin(), it.args.end());
+                blocks.push_back(it.blocks);
+                if ((int)blocks.size() == GROUP_MAX) DP_TRY_ST(fire());
+            }
+            DP_TRY_ST(fire());
         }
-        DP_TRY_ST(fire());
+        held.clear();
     }
-    q.main.clear();
     for (auto &fn : q.post) DP_TRY_ST(fn());
     q.post.clear();
     return DP_OK;
@@ -328,10 +331,13 @@ static int batch_target(const std::vector<Geo> &geo)
 
 dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *const *x, const void *const *dy,
                                     float *const *g_w, float *const *g_b, size_t g_stride, float *const *sqnorm,
-                                    void *const *ws, const size_t *ws_bytes, int n_layers, dp_stream stream)
+                                    void *const *ws, const size_t *ws_bytes, int32_t *partial_counts, int n_layers,
+                                    dp_stream stream)
 {
-    if (!descs || !x || !dy || !sqnorm || !ws || !ws_bytes)
-        return fail(DP_ERR_INVALID_ARG, "descs, x, dy, sqnorm, ws and ws_bytes must be non-NULL host arrays");
+    if (!descs || !x || !dy || !ws || !ws_bytes)
+        return fail(DP_ERR_INVALID_ARG, "descs, x, dy, ws and ws_bytes must be non-NULL host arrays");
+    if (!sqnorm && !partial_counts)
+        return fail(DP_ERR_INVALID_ARG, "sqnorm is NULL (reduction left to the caller) but partial_counts is NULL too");
     if (n_layers < 1) return fail(DP_ERR_INVALID_ARG, "n_layers = %d (need >= 1)", n_layers);
     std::vector<Geo> geo((size_t)n_layers);
     for (int l = 0; l < n_layers; ++l) {             // everything is validated before anything is launched
@@ -343,7 +349,7 @@ dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *cons
         float *gw = g_w ? g_w[l] : nullptr, *gb = g_b ? g_b[l] : nullptr;
         DP_TRY(check_ptr(gw, "g_w[l]", false));
         DP_TRY(check_ptr(gb, "g_b[l]", false));
-        DP_TRY(check_ptr(sqnorm[l], "sqnorm[l]", true, 4));
+        if (sqnorm) DP_TRY(check_ptr(sqnorm[l], "sqnorm[l]", true, 4));
         if (gw && g.pb && !gb) return fail(DP_ERR_INVALID_ARG, "layer %d: g_w given but g_b is NULL for a layer with a bias", l);
         if (!gw && gb) return fail(DP_ERR_INVALID_ARG, "layer %d: g_b given without g_w", l);
         if (g_stride) {
@@ -375,7 +381,27 @@ dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *cons
     if (st == DP_OK) st = flush_queue(q);
     set_open_queue(nullptr);
     if (st != DP_OK) return st;
+    if (partial_counts)
+        for (int l = 0; l < n_layers; ++l) partial_counts[l] = counts[(size_t)l];
+    if (!sqnorm) return DP_OK;
     return launch_layer_norms(parts.data(), counts.data(), sqnorm, n_layers, geo[0].n, s);
+}
+
+dp_status dp_layer_norms_from_partials(const float *const *partials, const int32_t *counts, float *const *sqnorm,
+                                       int n_layers, int n, dp_stream stream)
+{
+    if (!partials || !counts || !sqnorm)
+        return fail(DP_ERR_INVALID_ARG, "partials, counts and sqnorm must be non-NULL host arrays");
+    if (n_layers < 1 || n < 1) return fail(DP_ERR_INVALID_ARG, "n_layers (%d) and n (%d) must be >= 1", n_layers, n);
+    for (int l = 0; l < n_layers; ++l) {
+        if (!partials[l] || (reinterpret_cast<uintptr_t>(partials[l]) & 3u))
+            return fail(DP_ERR_INVALID_ARG, "partials[%d] is NULL or not 4-byte aligned", l);
+        if (!sqnorm[l] || (reinterpret_cast<uintptr_t>(sqnorm[l]) & 3u))
+            return fail(DP_ERR_INVALID_ARG, "sqnorm[%d] is NULL or not 4-byte aligned", l);
+        if (counts[l] < 1) return fail(DP_ERR_INVALID_ARG, "counts[%d] = %d (need >= 1)", l, counts[l]);
+    }
+    g_err[0] = 0;
+    return launch_layer_norms(partials, counts, sqnorm, n_layers, n, static_cast<hipStream_t>(stream));
 }
 
 dp_status dp_clip_accumulate_recompute_batch(const dp_layer_desc *descs, const void *const *x, const void *const *dy,

@@ -1086,15 +1086,17 @@ constexpr int FIX_R = 4;                       // accumulator registers per fixu
 constexpr int FIX_PARTS = 16 / FIX_R;
 
 template <int WAVES_M, int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS>
-__global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const ConvArgs a)
+__global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const Grouped<ConvArgs> grp)
 {
     constexpr int MT = WAVES_M * TM * 32, NT = WAVES_N * TN * 32;
     constexpr int NACC = TM * TN + (BIAS ? TM : 0);
     __shared__ float red[4];
+    unsigned bid;
+    const ConvArgs &a = grp.a[group_pick(grp, bid)];
     const int tiles = a.tiles_m * a.tiles_n;
-    const int part = blockIdx.x % FIX_PARTS;
-    const int t = (blockIdx.x / FIX_PARTS) % NACC;
-    const int group = blockIdx.x / (FIX_PARTS * NACC);
+    const int part = bid % FIX_PARTS;
+    const int t = (bid / FIX_PARTS) % NACC;
+    const int group = bid / (FIX_PARTS * NACC);
     const int i = WEIGHTED ? 0 : group / tiles;
     const int tile = WEIGHTED ? group : group - i * tiles;
     const int tile_m = tile / a.tiles_n, tile_n = tile - tile_m * a.tiles_n;
@@ -1154,7 +1156,7 @@ __global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const ConvArgs a)
     }
     if constexpr (!WEIGHTED) {
         const float tot = block_sum<4>(ss, red);
-        if (threadIdx.x == 0) a.partials[blockIdx.x] = tot;
+        if (threadIdx.x == 0) a.partials[bid] = tot;
     }
 }
 
@@ -1416,15 +1418,14 @@ const char *conv_variant_name(const Geo &g, int mode, bool shared)
 }
 
 template <int WM, int WN, int TM, int TN>
-static void launch_fixup(const ConvArgs &a, bool weighted, bool bias, unsigned groups, hipStream_t s)
+static const void *fixup_of(bool weighted, bool bias)
 {
     if (weighted) {
-        if (bias) hipLaunchKernelGGL((conv_fixup_kernel<WM, WN, TM, TN, true, true>), dim3(groups), dim3(THREADS), 0, s, a);
-        else hipLaunchKernelGGL((conv_fixup_kernel<WM, WN, TM, TN, true, false>), dim3(groups), dim3(THREADS), 0, s, a);
-    } else {
-        if (bias) hipLaunchKernelGGL((conv_fixup_kernel<WM, WN, TM, TN, false, true>), dim3(groups), dim3(THREADS), 0, s, a);
-        else hipLaunchKernelGGL((conv_fixup_kernel<WM, WN, TM, TN, false, false>), dim3(groups), dim3(THREADS), 0, s, a);
+        if (bias) return reinterpret_cast<const void *>(&conv_fixup_kernel<WM, WN, TM, TN, true, true>);
+        return reinterpret_cast<const void *>(&conv_fixup_kernel<WM, WN, TM, TN, true, false>);
     }
+    if (bias) return reinterpret_cast<const void *>(&conv_fixup_kernel<WM, WN, TM, TN, false, true>);
+    return reinterpret_cast<const void *>(&conv_fixup_kernel<WM, WN, TM, TN, false, false>);
 }
 
 template <bool BF16, int WM, int WN, int TM, int TN, int SIMPLE>
@@ -1540,20 +1541,17 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
     else fn = (f.shape == T64) ? kernel_of<false, 2, 2, 1, 1>(loader, weighted, bias) : kernel_of<false, 2, 2, 2, 2>(loader, weighted, bias);
     dp_status st = submit_main<ConvArgs>(fn, a, blocks, THREADS, lds_bytes, s, "conv_contract");
     if (st != DP_OK) return st;
-    // what follows the main kernel: at once, or after the grouped launch of a batch call
-    const int shape = f.shape, ksplit = f.ksplit, per_example = (int)norm_partials_per_example(f), n = g.n;
-    const unsigned fix_blocks = (unsigned)(f.groups * f.nacc * FIX_PARTS);
-    return submit_post([=]() -> dp_status {
-        dp_status st2 = DP_OK;
-        if (ksplit > 1) {
-            if (shape == T64) launch_fixup<2, 2, 1, 1>(a, weighted, bias, fix_blocks, s);
-            else launch_fixup<2, 2, 2, 2>(a, weighted, bias, fix_blocks, s);
-            st2 = check_launch("conv_fixup");
-            if (st2 != DP_OK) return st2;
-        }
-        if (!weighted && sqnorm) st2 = launch_sum_partials(a.partials, n, per_example, sqnorm, s);
-        return st2;
-    });
+    // what follows the main kernel: at once, or after the grouped launches of a batch call
+    if (f.ksplit > 1) {
+        const unsigned fix_blocks = (unsigned)(f.groups * f.nacc * FIX_PARTS);
+        const void *fix = (f.shape == T64) ? fixup_of<2, 2, 1, 1>(weighted, bias) : fixup_of<2, 2, 2, 2>(weighted, bias);
+        st = submit_kernel<ConvArgs>(TIER_POST, fix, a, fix_blocks, THREADS, 0, s, "conv_fixup");
+        if (st != DP_OK) return st;
+    }
+    if (weighted || !sqnorm) return DP_OK;
+    const int per_example = (int)norm_partials_per_example(f), n = g.n;
+    const float *partials = a.partials;
+    return submit_post([=]() -> dp_status { return launch_sum_partials(partials, n, per_example, sqnorm, s); });
 }
 
 }  // namespace dp

@@ -446,11 +446,23 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3
 // out[row][OWP+8 .. 2 OWP+8) = E[c] = X[row][2c]; zero where the column is outside the row.  `rows` =
 // n * cin * hin rows of `win` (even) elements; one thread per 16-byte output piece, which needs
 // the high (O') or low (E) halves of eight consecutive dwords of the input row.
-__global__ void __launch_bounds__(256) deinterleave2_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ out,
-                                                            long long rows, int win, int owp)
+struct DeintArgs {
+    const uint16_t *x;
+    uint16_t *out;
+    long long rows;
+    int win, owp;
+};
+
+__global__ void __launch_bounds__(256) deinterleave2_kernel(const Grouped<DeintArgs> grp)
 {
+    unsigned bid;
+    const DeintArgs &a = grp.a[group_pick(grp, bid)];
+    const uint16_t *__restrict__ x = a.x;
+    uint16_t *__restrict__ out = a.out;
+    const long long rows = a.rows;
+    const int win = a.win, owp = a.owp;
     const int xpr = (2 * owp + 8) / 8, opr = (owp + 8) / 8;
-    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long q = (long long)bid * 256 + threadIdx.x;
     if (q >= rows * xpr) return;
     const long long row = q / xpr;
     const int pc = (int)(q - row * xpr);
@@ -476,13 +488,15 @@ __global__ void __launch_bounds__(256) deinterleave2_kernel(const uint16_t *__re
 constexpr int C3_FIX_R = 4, C3_FIX_PARTS = 16 / C3_FIX_R;
 
 template <bool WEIGHTED>
-__global__ void __launch_bounds__(C3_THREADS) conv3x3_fixup_kernel(const C3Args a)
+__global__ void __launch_bounds__(C3_THREADS) conv3x3_fixup_kernel(const Grouped<C3Args> grp)
 {
     __shared__ float red[4];
+    unsigned bid;
+    const C3Args &a = grp.a[group_pick(grp, bid)];
     const int tiles = a.tiles_co * a.tiles_ci;
-    const int part = blockIdx.x % C3_FIX_PARTS;
-    const int t = (blockIdx.x / C3_FIX_PARTS) % 9;
-    const int unit = blockIdx.x / (C3_FIX_PARTS * 9);             // (example, tile); weighted: tile
+    const int part = bid % C3_FIX_PARTS;
+    const int t = (bid / C3_FIX_PARTS) % 9;
+    const int unit = bid / (C3_FIX_PARTS * 9);                    // (example, tile); weighted: tile
     const int i = WEIGHTED ? 0 : unit / tiles, tile = unit - i * tiles;
     const int tco = tile / a.tiles_ci, tci = tile - tco * a.tiles_ci;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -529,7 +543,7 @@ __global__ void __launch_bounds__(C3_THREADS) conv3x3_fixup_kernel(const C3Args 
     }
     if constexpr (!WEIGHTED) {
         const float tot = block_sum<4>(ss, red);
-        if (threadIdx.x == 0) a.partials[blockIdx.x] = tot;
+        if (threadIdx.x == 0) a.partials[bid] = tot;
     }
 }
 
@@ -741,9 +755,10 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
         const int owp = (g.ow + 7) / 8 * 8;
         const long long rows = (long long)g.n * g.cin * g.h;
         const long long pieces = rows * ((2 * owp + 8) / 8);
-        hipLaunchKernelGGL(deinterleave2_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, a.x,
-                           reinterpret_cast<uint16_t *>(w), rows, g.w, owp);
-        st = check_launch("deinterleave2");
+        DeintArgs da;
+        da.x = a.x; da.out = reinterpret_cast<uint16_t *>(w); da.rows = rows; da.win = g.w; da.owp = owp;
+        st = submit_kernel<DeintArgs>(TIER_PRE, reinterpret_cast<const void *>(&deinterleave2_kernel), da,
+                                      (unsigned)((pieces + 255) / 256), 256, 0, s, "deinterleave2");
         if (st != DP_OK) return st;
         a.x = reinterpret_cast<const uint16_t *>(w);
     }
@@ -763,19 +778,17 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     }
     if (st != DP_OK) return st;
     // what follows the main kernel: at once, or after the grouped launch of a batch call
-    const int ksplit = p.ksplit, n = g.n, per_example = p.tiles_co * p.tiles_ci * (int)c3_partials_per_unit(p);
-    const unsigned fix_blocks = (unsigned)(units * 9 * C3_FIX_PARTS);
-    return submit_post([=]() -> dp_status {
-        dp_status st2 = DP_OK;
-        if (ksplit > 1) {
-            if (weighted) hipLaunchKernelGGL(conv3x3_fixup_kernel<true>, dim3(fix_blocks), dim3(C3_THREADS), 0, s, a);
-            else hipLaunchKernelGGL(conv3x3_fixup_kernel<false>, dim3(fix_blocks), dim3(C3_THREADS), 0, s, a);
-            st2 = check_launch("conv3x3_fixup");
-            if (st2 != DP_OK) return st2;
-        }
-        if (!weighted && sqnorm) st2 = launch_sum_partials(a.partials, n, per_example, sqnorm, s);
-        return st2;
-    });
+    if (p.ksplit > 1) {
+        const unsigned fix_blocks = (unsigned)(units * 9 * C3_FIX_PARTS);
+        const void *fix = weighted ? reinterpret_cast<const void *>(&conv3x3_fixup_kernel<true>)
+                                   : reinterpret_cast<const void *>(&conv3x3_fixup_kernel<false>);
+        st = submit_kernel<C3Args>(TIER_POST, fix, a, fix_blocks, C3_THREADS, 0, s, "conv3x3_fixup");
+        if (st != DP_OK) return st;
+    }
+    if (weighted || !sqnorm) return DP_OK;
+    const int n = g.n, per_example = p.tiles_co * p.tiles_ci * (int)c3_partials_per_unit(p);
+    const float *partials = a.partials;
+    return submit_post([=]() -> dp_status { return launch_sum_partials(partials, n, per_example, sqnorm, s); });
 }
 
 }  // namespace dp

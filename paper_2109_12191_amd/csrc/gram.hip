@@ -15,6 +15,7 @@
 // its partial 64x64 Gram (accumulator register layout) in the workspace.  Kernel 2: one
 // workgroup per example adds the slices in order, multiplies the Grams element by element and
 // reduces.  Fixed order everywhere: same bits on every run.
+#include "group.h"
 #include "internal.h"
 #include "pieces.h"
 
@@ -128,11 +129,13 @@ __device__ __forceinline__ void gram_part_im2col(f32x16 &acc, const GramArgs &a,
     }
 }
 
-__global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const GramArgs a)
+__global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const Grouped<GramArgs> grp)
 {
     __shared__ __attribute__((aligned(16))) char lds[64 * GR_PT];
+    unsigned bid;
+    const GramArgs &a = grp.a[group_pick(grp, bid)];
     const int slots = a.sa + a.sb;
-    const int i = blockIdx.x / slots, s = blockIdx.x - i * slots;
+    const int i = bid / slots, s = bid - i * slots;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kb = wave >> 1, kb2 = wave & 1;
     f32x16 gm;
@@ -146,7 +149,7 @@ __global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const GramArgs
                   lane);
     else
         gram_part_im2col(gm, a, i, (s - a.sa) * GR_CB, min(a.cb, (s - a.sa + 1) * GR_CB), lds, kb, kb2, lane);
-    float *mine = a.part + (size_t)blockIdx.x * 4096;
+    float *mine = a.part + (size_t)bid * 4096;
 #pragma unroll
     for (int r = 0; r < 16; ++r) mine[r * GR_THREADS + threadIdx.x] = gm[r];
 }
@@ -156,10 +159,12 @@ __global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const GramArgs
 constexpr int GR_PARTS = 16;
 constexpr int GR_SA_MAX = 16, GR_SB_MAX = 40;      // slices of 256 rows: Cout <= 4096, Cin*k*k <= 10240
 
-__global__ void __launch_bounds__(GR_THREADS) gram_combine_kernel(const GramArgs a)
+__global__ void __launch_bounds__(GR_THREADS) gram_combine_kernel(const Grouped<GramArgs> grp)
 {
     __shared__ float red[4];
-    const int i = blockIdx.x / GR_PARTS, r = blockIdx.x - i * GR_PARTS;
+    unsigned bid;
+    const GramArgs &a = grp.a[group_pick(grp, bid)];
+    const int i = bid / GR_PARTS, r = bid - i * GR_PARTS;
     const float *base = a.part + (size_t)i * (a.sa + a.sb) * 4096 + r * GR_THREADS + threadIdx.x;
     float va[GR_SA_MAX], vb[GR_SB_MAX];            // all loads in flight together
 #pragma unroll
@@ -172,7 +177,7 @@ __global__ void __launch_bounds__(GR_THREADS) gram_combine_kernel(const GramArgs
 #pragma unroll
     for (int s = 0; s < GR_SB_MAX; ++s) gb += vb[s];
     const float tot = block_sum<4>(ga * gb, red);
-    if (threadIdx.x == 0) a.out[blockIdx.x] = tot;
+    if (threadIdx.x == 0) a.out[bid] = tot;
 }
 
 int gram_rows_b(const Geo &g) { return g.cin * g.kh * g.kw; }
@@ -214,17 +219,16 @@ dp_status launch_gram_norm(const Geo &g, const void *x, const void *dy, float *s
     // the partial norms [n][16] sit at the start of the workspace, the partial Grams after them
     a.out = static_cast<float *>(ws);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + gram_align16((size_t)g.n * GR_PARTS * sizeof(float)));
-    profile_begin(s);
-    profile_begin(s);
-    hipLaunchKernelGGL(gram_partial_kernel, dim3((unsigned)(g.n * (a.sa + a.sb))), dim3(GR_THREADS), 0, s, a);
-    profile_end(s);
-    profile_end(s);
-    dp_status st = check_launch("gram_partial");
+    // the kernel remap of the contraction launches does not apply here: any workgroup count will do
+    dp_status st = submit_kernel<GramArgs>(TIER_MAIN, reinterpret_cast<const void *>(&gram_partial_kernel), a,
+                                           (unsigned)(g.n * (a.sa + a.sb)), GR_THREADS, 0, s, "gram_partial");
     if (st != DP_OK) return st;
-    hipLaunchKernelGGL(gram_combine_kernel, dim3((unsigned)(g.n * GR_PARTS)), dim3(GR_THREADS), 0, s, a);
-    st = check_launch("gram_combine");
+    st = submit_kernel<GramArgs>(TIER_POST, reinterpret_cast<const void *>(&gram_combine_kernel), a,
+                                 (unsigned)(g.n * GR_PARTS), GR_THREADS, 0, s, "gram_combine");
     if (st != DP_OK || !sqnorm) return st;
-    return launch_sum_partials(a.out, g.n, GR_PARTS, sqnorm, s);
+    const float *parts = a.out;
+    const int n = g.n;
+    return submit_post([=]() -> dp_status { return launch_sum_partials(parts, n, GR_PARTS, sqnorm, s); });
 }
 
 size_t gram_norm_partial_count(void) { return GR_PARTS; }

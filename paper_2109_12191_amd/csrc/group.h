@@ -12,10 +12,12 @@
 // MFMAs and epilogues of different workgroups overlap, and a one-example micro-step is a handful of
 // launches instead of a hundred.
 //
-// On the host, launchers hand their main kernel to submit_main(): with no queue open it is launched
-// at once (a group of one); inside a batch call (LaunchQueue open on this thread) it is held back
-// until flush(), which groups the held launches by kernel, launches them, and then runs the deferred
-// follow-up launches (slice sums, partial-norm reductions) in the order they were registered.
+// On the host, launchers hand their kernels to submit_kernel() with a tier: operand pre-passes
+// (TIER_PRE), the contraction itself (TIER_MAIN, also submit_main()), the sums over K slices
+// (TIER_POST).  With no queue open a kernel is launched at once (a group of one); inside a batch call
+// (LaunchQueue open on this thread) it is held back until flush(), which launches tier after tier,
+// the held launches of a tier grouped by kernel, and then runs the deferred follow-up calls
+// (partial-norm reductions) in the order they were registered.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -51,6 +53,8 @@ __device__ __forceinline__ int group_pick(const Grouped<Args> &g, unsigned &bid)
 }
 #endif
 
+enum { TIER_PRE = 0, TIER_MAIN = 1, TIER_POST = 2, TIER_COUNT = 3 };
+
 struct LaunchQueue {
     struct Item {
         const void *fn;                 // kernel
@@ -60,7 +64,7 @@ struct LaunchQueue {
                         unsigned lds, hipStream_t s);
         const char *what;
     };
-    std::vector<Item> main;
+    std::vector<Item> tier[TIER_COUNT];
     std::vector<std::function<dp_status()>> post;
     hipStream_t stream = nullptr;
     int crowd = 0;                      // > 0: launches are shared with other layers; the work a workgroup should
@@ -98,17 +102,17 @@ dp_status launch_grouped(const void *fn, const char *args, const unsigned *block
     return DP_OK;
 }
 
-// Main kernel of a launcher: at once, or held back for the batch call's grouped launch.
-// `blocks` must be a multiple of 8.  The kernel is bracketed by the benchmark timing aid when armed.
+// A kernel of a launcher: at once, or held back for the batch call's grouped launch of its tier.
+// A TIER_MAIN kernel is bracketed by the benchmark timing aid when armed.
 template <typename Args>
-dp_status submit_main(const void *fn, const Args &a, unsigned blocks, unsigned threads, unsigned lds, hipStream_t s,
-                      const char *what)
+dp_status submit_kernel(int tier, const void *fn, const Args &a, unsigned blocks, unsigned threads, unsigned lds,
+                        hipStream_t s, const char *what)
 {
     LaunchQueue *q = open_queue();
     if (!q) {
-        profile_begin(s);
+        if (tier == TIER_MAIN) profile_begin(s);
         const dp_status st = launch_grouped<Args>(fn, reinterpret_cast<const char *>(&a), &blocks, 1, threads, lds, s);
-        profile_end(s);
+        if (tier == TIER_MAIN) profile_end(s);
         return st != DP_OK ? st : check_launch(what);
     }
     LaunchQueue::Item it;
@@ -116,11 +120,19 @@ dp_status submit_main(const void *fn, const Args &a, unsigned blocks, unsigned t
     it.args.assign(reinterpret_cast<const char *>(&a), reinterpret_cast<const char *>(&a) + sizeof(Args));
     it.go = &launch_grouped<Args>;
     it.what = what;
-    q->main.push_back(std::move(it));
+    q->tier[tier].push_back(std::move(it));
     return DP_OK;
 }
 
-// A follow-up launch that must come after the main kernel: at once, or after the batch's grouped launches.
+// The contraction kernel of a launcher.  `blocks` must be a multiple of 8 (the XCD remap relies on it).
+template <typename Args>
+dp_status submit_main(const void *fn, const Args &a, unsigned blocks, unsigned threads, unsigned lds, hipStream_t s,
+                      const char *what)
+{
+    return submit_kernel<Args>(TIER_MAIN, fn, a, blocks, threads, lds, s, what);
+}
+
+// A follow-up call that must come after every kernel of the layer: at once, or after the batch's grouped launches.
 inline dp_status submit_post(std::function<dp_status()> fn)
 {
     LaunchQueue *q = open_queue();

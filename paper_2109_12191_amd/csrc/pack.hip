@@ -9,6 +9,7 @@
 // size or parity of S.  The clip factor is applied here, in fp32, and rounded to bf16 once
 // (nearest even) -- the same arithmetic the in-kernel scaling performs.
 // `grp` splits the examples into ranges that different workgroups contract (the K slices).
+#include "group.h"
 #include "internal.h"
 
 namespace dp {
@@ -27,9 +28,11 @@ struct PackArgs {
     long long x_pieces, dy_pieces;
 };
 
-__global__ void __launch_bounds__(256) pack_weighted_kernel(const PackArgs a)
+__global__ void __launch_bounds__(256) pack_weighted_kernel(const Grouped<PackArgs> layers)
 {
-    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    unsigned bid;
+    const PackArgs &a = layers.a[group_pick(layers, bid)];
+    const long long q = (long long)bid * 256 + threadIdx.x;
     uint32_t out[4] = {0u, 0u, 0u, 0u};
     if (q < a.x_pieces) {
         const int kk8 = (int)(q % a.kg8);
@@ -92,15 +95,27 @@ __global__ void __launch_bounds__(256) pack_weighted_kernel(const PackArgs a)
 // Strided 1x1 convolutions only look at every stride-th row and column of X: this copies those
 // into a compact [n*cin][OH*OW] tensor so that the contraction runs its plain aligned loader on
 // half (a quarter, with both strides) of the bytes.  One thread per pair of output elements.
-__global__ void __launch_bounds__(256) subsample_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ out,
-                                                        long long rows, int h, int w, int oh, int ow, int stride)
+struct SubArgs {
+    const uint16_t *x;
+    uint16_t *out;
+    long long rows;
+    int h, w, oh, ow, stride;
+};
+
+__global__ void __launch_bounds__(256) subsample_kernel(const Grouped<SubArgs> grp)
 {
-    const int S = oh * ow, pairs = (S + 1) / 2;
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    unsigned bid;
+    const SubArgs &a = grp.a[group_pick(grp, bid)];
+    const uint16_t *__restrict__ x = a.x;
+    uint16_t *__restrict__ out = a.out;
+    const long long rows = a.rows;
+    const int w = a.w, ow = a.ow, stride = a.stride;
+    const int S = a.oh * ow, pairs = (S + 1) / 2;
+    const long long t = (long long)bid * 256 + threadIdx.x;
     if (t >= rows * pairs) return;
     const long long row = t / pairs;
     const int k = (int)(t - row * pairs) * 2;
-    const uint16_t *src = x + (size_t)row * h * w;
+    const uint16_t *src = x + (size_t)row * a.h * w;
     const int r0 = k / ow, c0 = k - r0 * ow;
     const uint32_t lo = src[(size_t)r0 * stride * w + c0 * stride];
     uint16_t *dst = out + (size_t)row * S + k;
@@ -122,13 +137,12 @@ dp_status launch_subsample(const Geo &g, const void *x, void *out, hipStream_t s
     const long long threads = rows * ((g.oh * g.ow + 1) / 2);
     const long long blocks = (threads + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return fail(DP_ERR_UNSUPPORTED, "subsample: layer too large");
-    hipLaunchKernelGGL(subsample_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const uint16_t *>(x),
-                       static_cast<uint16_t *>(out), rows, g.h, g.w, g.oh, g.ow, g.stride);
-    return check_launch("subsample");
+    SubArgs a;
+    a.x = static_cast<const uint16_t *>(x); a.out = static_cast<uint16_t *>(out); a.rows = rows;
+    a.h = g.h; a.w = g.w; a.oh = g.oh; a.ow = g.ow; a.stride = g.stride;
+    return submit_kernel<SubArgs>(TIER_PRE, reinterpret_cast<const void *>(&subsample_kernel), a, (unsigned)blocks, 256, 0,
+                                  s, "subsample");
 }
-
-namespace {
-}  // namespace
 
 PackPlan pack_plan(const Geo &g, int groups)
 {
@@ -161,8 +175,8 @@ dp_status launch_pack_weighted(const Geo &g, const PackPlan &p, const void *x, c
     a.dy_pieces = (long long)p.groups * g.cout * a.kg8;
     const long long blocks = (a.x_pieces + a.dy_pieces + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return fail(DP_ERR_UNSUPPORTED, "pack: layer too large");
-    hipLaunchKernelGGL(pack_weighted_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
-    return check_launch("pack_weighted");
+    return submit_kernel<PackArgs>(TIER_PRE, reinterpret_cast<const void *>(&pack_weighted_kernel), a, (unsigned)blocks,
+                                   256, 0, s, "pack_weighted");
 }
 
 }  // namespace dp

@@ -26,9 +26,16 @@ def _pad4(v: int) -> int:
 
 
 class PrivatiseStep:
-    def __init__(self, wl, device: str = "cuda:0", mode: str = "auto", streams: int = 1, noise: str = "once"):
+    def __init__(self, wl, device: str = "cuda:0", mode: str = "auto", streams: int = 1, noise: str = "once",
+                 batching: str = "variant"):
         B.load_library()
         self.wl = wl
+        if batching not in ("variant", "all"):
+            raise ValueError(batching)
+        # "variant": one batch call per kernel variant, spread over the side streams (large micro-batches: the
+        # launches are long and overlap); "all": one batch call per phase with every layer in it, so that also the
+        # pre-passes and slice sums of all layers share launches (one-example micro-steps: launches are what costs)
+        self.batching = batching
         if noise not in ("once", "per_example"):
             raise ValueError(noise)
         # "once": N(0, sigma^2 C^2) added in finalize (first equation of the Algorithm section);
@@ -95,6 +102,11 @@ class PrivatiseStep:
         # launch (at most 16 per launch): per phase a micro-step is a dozen launches, not a hundred.
         self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD | B.DP_VARIANT_SHARED),
                          B.dp_kernel_variant(d, B.DP_WS_RECOMPUTE | B.DP_VARIANT_SHARED)) for d in self.descs]
+        import ctypes
+        self._partial_counts = (ctypes.c_int32 * L)()
+        self._partials = [(ctypes.c_void_p * L)(*[self._ws[c][i].data_ptr() for i in range(L)]) for c in range(self.copies)]
+        self._layer_sqnorm_ptrs = [(ctypes.c_void_p * L)(*[self._layer_sqnorm[c][i].data_ptr() for i in range(L)])
+                                   for c in range(self.copies)]
         self._groups_a = self._make_groups(range(L), 0)
         self._groups_b = self._make_groups([i for i in range(L) if self.form[i] == "recompute"], 1)
         # side streams: `side` for the per-example phase, `side_b` for the clipped-sum phase
@@ -132,11 +144,14 @@ class PrivatiseStep:
         by_name = {}
         for li in layer_ids:
             key = self.variant[li][use] + ("|mat" if (use == 0 and self.form[li] == "materialise") else "")
+            if self.batching == "all":
+                key = "all layers"
             by_name.setdefault(key, []).append(li)
         groups = []
         for key, ids in by_name.items():
-            for k in range(0, len(ids), 16):
-                part = ids[k: k + 16]
+            width = len(ids) if self.batching == "all" else 16
+            for k in range(0, len(ids), width):
+                part = ids[k: k + width]
                 name = key.split("|")[0]
                 if len(part) == 1:           # a single layer is planned as a launch of its own
                     name = B.dp_kernel_variant(self.descs[part[0]], B.DP_WS_RECOMPUTE if use else B.DP_WS_PER_EXAMPLE_GRAD)
@@ -144,8 +159,7 @@ class PrivatiseStep:
                 g["batch"] = [B.LayerBatch([self.descs[i] for i in part], [self._ws[c][i].data_ptr() for i in part],
                                            [self._ws[c][i].numel() for i in part]) for c in range(self.copies)]
                 if use == 0:
-                    g["sq"] = [g["batch"][c].ptrs([self._layer_sqnorm[c][i].data_ptr() for i in part])
-                               for c in range(self.copies)]
+                    g["counted"] = False
                     mat = [self.form[i] == "materialise" for i in part]
                     g["gw"] = [g["batch"][c].ptrs([self._g[c][:, self.off_w[i]:].data_ptr() if m else None
                                                    for i, m in zip(part, mat)]) for c in range(self.copies)] if any(mat) else None
@@ -262,9 +276,15 @@ class PrivatiseStep:
             dys = bt.ptrs([inputs[i][1].data_ptr() for i in grp["layers"]])
             self._arm(grp, 0)
             B.dp_per_example_grad_batch(bt, xs, dys, grp["gw"][c] if grp["gw"] else None,
-                                        grp["gb"][c] if grp["gb"] else None, grp["sq"][c], g_stride=gs, stream=st)
+                                        grp["gb"][c] if grp["gb"] else None, None, g_stride=gs, stream=st)
+            if not grp["counted"]:                     # how many partial sums per example each layer leaves behind
+                for k, i in enumerate(grp["layers"]):
+                    self._partial_counts[i] = bt.partial_counts[k]
+                grp["counted"] = True
         for st in self.side:
             main.wait_stream(st)
+        # H2: every layer's partial sums -> per-layer norms in one launch, per-group norms in a second
+        B.dp_layer_norms_from_partials(self._partials[c], self._partial_counts, self._layer_sqnorm_ptrs[c], L, self.n)
         B.dp_norms(self._layer_sqnorm[c], self.group_of_layer_dev, L, self.n, self.n_groups, gsq)
         # ---- phase B
         for st in self.side_b:

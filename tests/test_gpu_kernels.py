@@ -78,7 +78,7 @@ CONV_CASES = [
     ("long K several chunks", conv(8, 24, 3, 1, 40, bias=True), 2),
     ("256 x 64 output", conv(40, 200, 1, 1, 12), 3),
     ("64 x 256 output", conv(30, 48, 3, 1, 12, bias=True), 3),
-    ("wide tile long K sliced", conv(24, 64, 3, 1, 56), 1),
+    ("3x3 long K sliced", conv(24, 64, 3, 1, 56), 1),
     ("many examples per workgroup", conv(8, 8, 1, 1, 4, bias=True), 1700),
     ("3x3 s1 odd width 7", conv(72, 136, 3, 1, 7), 5),
     ("3x3 s2 odd width 15->8", conv(16, 80, 3, 2, 15), 3),
@@ -229,8 +229,8 @@ RECOMPUTE_CASES = [
     ("conv 3x3 s2", conv(24, 40, 3, 2, 14), 5),
     ("conv small long K", conv(8, 24, 3, 1, 40, bias=True), 3),
     ("conv many examples", conv(64, 200, 1, 1, 7), 40),
-    ("conv wide tile", conv(30, 48, 3, 1, 12, bias=True), 6),
-    ("conv tall tile", conv(40, 200, 1, 1, 12), 6),
+    ("conv 3x3 biased small", conv(30, 48, 3, 1, 12, bias=True), 6),
+    ("conv 1x1 cout 200", conv(40, 200, 1, 1, 12), 6),
     ("dense", dense(300, 37, tokens=2), 7),
     ("dense fc", dense(784, 256), 6),
     ("gn", gn_affine(16, 9, 4), 6),
@@ -608,6 +608,41 @@ def test_batch_call_matches_the_single_layer_calls_and_the_oracle(n, materialise
                 if l.pb:
                     assert_close(host(gbs[k][i, :l.pb]), ref_b[i], BF16_TOL, f"layer {k} db[{i}]")
             assert_close(host(gws[k]), gw1, 2e-5, f"layer {k} against the single-layer call")
+
+
+@pytest.mark.parametrize("n", [1, 5])
+def test_batch_calls_with_the_reduction_left_to_one_launch(n):
+    """Two batch calls that leave their partial sums in the workspaces (sqnorm NULL), then ONE
+    dp_layer_norms_from_partials over the layers of both: the norms of the oracle, and the bits of the batch call
+    that reduces by itself."""
+    dtype = "bf16"
+    ins = [_inputs(l, n, 900 + k, dtype) for k, l in enumerate(BATCH_LAYERS)]
+    descs = [dp.make_desc(l, n, dtype) for l in BATCH_LAYERS]
+    xs = [dev(x, dtype) for x, _ in ins]
+    dys = [dev(dy, dtype) for _, dy in ins]
+    wss = [torch.empty(max(16, dp.dp_workspace_bytes(d)), dtype=torch.uint8, device="cuda:0") for d in descs]
+    L = len(descs)
+    halves = [list(range(0, L, 2)), list(range(1, L, 2))]
+    sq = torch.full((L, n), -1.0, device="cuda:0")
+    sq_own = torch.full((L, n), -2.0, device="cuda:0")
+    import ctypes
+    counts = (ctypes.c_int32 * L)()
+    for ids in halves:
+        batch = dp.LayerBatch([descs[i] for i in ids], [wss[i].data_ptr() for i in ids], [wss[i].numel() for i in ids])
+        args = (batch, batch.ptrs([xs[i].data_ptr() for i in ids]), batch.ptrs([dys[i].data_ptr() for i in ids]), None, None)
+        dp.dp_per_example_grad_batch(*args, batch.ptrs([sq_own[i].data_ptr() for i in ids]))
+        torch.cuda.synchronize()
+        dp.dp_per_example_grad_batch(*args, None)
+        for k, i in enumerate(ids):
+            counts[i] = batch.partial_counts[k]
+            assert counts[i] >= 1
+    dp.dp_layer_norms_from_partials((ctypes.c_void_p * L)(*[w.data_ptr() for w in wss]), counts,
+                                    (ctypes.c_void_p * L)(*[sq[i].data_ptr() for i in range(L)]), L, n)
+    torch.cuda.synchronize()
+    assert torch.equal(sq, sq_own)
+    for k, l in enumerate(BATCH_LAYERS):
+        ref_n2 = _oracle_grads(l, *ins[k])[2]
+        assert np.allclose(host(sq[k]), ref_n2, rtol=BF16_TOL, atol=0), (k, l, host(sq[k]), ref_n2)
 
 
 @pytest.mark.parametrize("n", [1, 6])
