@@ -118,6 +118,8 @@ def main():
                     help="examples of micro-batch 0 the oracle is timed on (32 = about 10 s on 16 cores)")
     ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
     ap.add_argument("--streams", type=int, default=8, help="side streams for independent layers")
+    ap.add_argument("--lanes", default="balanced", choices=("round_robin", "balanced"),
+                    help="how the batch calls of a phase are dealt to the side streams")
     ap.add_argument("--batching", default="variant", choices=("variant", "all"),
                     help="layers per batch call: those of one kernel variant, or all layers of a phase")
     ap.add_argument("--noise", default="once", choices=["once", "per_example"],
@@ -140,7 +142,7 @@ def main():
     device = torch.device("cuda:0")
     wl = get_workload(args.workload, n=args.n, accum=args.accum, hw=args.hw)
     ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=args.streams, noise=args.noise,
-                          batching=args.batching)
+                          batching=args.batching, lanes=args.lanes)
     inputs = make_device_inputs(wl, wl.accum, device)
     if args.fused_update:
         ps.enable_update(lr=0.1, momentum=0.9, keep_gradient=False)

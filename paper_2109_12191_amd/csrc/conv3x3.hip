@@ -588,7 +588,10 @@ C3Plan c3_plan(const Geo &g, int mode)
     const long long tiles = (long long)p.tiles_co * p.tiles_ci;
     // inside a batch call: chunks per workgroup to plan for (a chunk here is about eight 128x128x64 chunks of work, but
     // slices cost a second pass over partial blocks: only very long walks are cut)
-    const int crowd = c3_plan_crowd(), tgt = crowd ? (crowd / 2 > 1 ? crowd / 2 : 1) : 0;
+    int crowd = c3_plan_crowd(), tgt = crowd ? (crowd / 2 > 1 ? crowd / 2 : 1) : 0;
+    // a layer that is small even chunk by chunk (micro-steps of one or two examples): a chunk per workgroup, the
+    // walk of a workgroup is what such a launch waits for
+    if (crowd && mode != MODE_WEIGHTED && (long long)g.n * tiles * p.chunks <= 128) tgt = 1;
     if (mode == MODE_WEIGHTED) {
         // example ranges: about 256 workgroups, partial blocks in the workspace kept below ~100 MB; in a launch
         // shared with other layers, ranges of about 96 chunks

@@ -27,7 +27,7 @@ def _pad4(v: int) -> int:
 
 class PrivatiseStep:
     def __init__(self, wl, device: str = "cuda:0", mode: str = "auto", streams: int = 1, noise: str = "once",
-                 batching: str = "variant"):
+                 batching: str = "variant", lanes: str = "balanced"):
         B.load_library()
         self.wl = wl
         if batching not in ("variant", "all"):
@@ -36,6 +36,9 @@ class PrivatiseStep:
         # launches are long and overlap); "all": one batch call per phase with every layer in it, so that also the
         # pre-passes and slice sums of all layers share launches (one-example micro-steps: launches are what costs)
         self.batching = batching
+        if lanes not in ("round_robin", "balanced"):
+            raise ValueError(lanes)
+        self.lanes = lanes                     # how the batch calls of a phase are dealt to the side streams
         if noise not in ("once", "per_example"):
             raise ValueError(noise)
         # "once": N(0, sigma^2 C^2) added in finalize (first equation of the Algorithm section);
@@ -175,6 +178,13 @@ class PrivatiseStep:
                 g["flops"] = sum(self.layers[i].flops for i in part) * self.n
                 groups.append(g)
         groups.sort(key=lambda g: -g["flops"])
+        # side stream of each group: longest first onto the least loaded stream (a launch costs a few microseconds
+        # however small it is)
+        load = [0.0] * max(1, self.n_streams)
+        for gi, g in enumerate(groups):
+            k = load.index(min(load)) if self.lanes == "balanced" else gi % max(1, self.n_streams)
+            g["lane"] = k
+            load[k] += g["flops"] / 150.0e12 + 8.0e-6
         return groups
 
     def _arm(self, group, use: int):
@@ -270,7 +280,7 @@ class PrivatiseStep:
                 for ev in self._b_done[c]:
                     st.wait_event(ev)
         for gi, grp in enumerate(self._groups_a):
-            st = self.side[gi % self.n_streams] if self.side else None
+            st = self.side[grp["lane"]] if self.side else None
             bt = grp["batch"][c]
             xs = bt.ptrs([inputs[i][0].data_ptr() for i in grp["layers"]])
             dys = bt.ptrs([inputs[i][1].data_ptr() for i in grp["layers"]])
