@@ -59,6 +59,9 @@ def _load():
     lib.orc_clip_accumulate.restype = C.c_int
     lib.orc_clip_accumulate.argtypes = [lp, C.c_int, C.POINTER(fp), C.POINTER(fp), C.c_int, C.c_int, dp,
                                         C.POINTER(dp), C.POINTER(dp), dp, dp, C.c_int]
+    lib.orc_clip_accumulate_units.restype = C.c_int
+    lib.orc_clip_accumulate_units.argtypes = [lp, C.c_int, C.POINTER(fp), C.POINTER(fp), C.c_int, C.c_int, C.c_int, dp,
+                                              C.POINTER(dp), C.POINTER(dp), dp, dp, C.c_int]
     lib.orc_weighted_sum_elems.restype = None
     lib.orc_weighted_sum_elems.argtypes = [lp, fp, fp, C.c_int, dp, C.POINTER(C.c_size_t), C.c_size_t,
                                            C.c_int, dp]
@@ -174,6 +177,67 @@ def clip_accumulate(layers, inputs, group_of_layer: Sequence[int], group_clip: S
     if rc != 0:
         raise RuntimeError("orc_clip_accumulate failed")
     return n2, f
+
+
+def clip_accumulate_units(layers, inputs, unit: int, group_of_layer: Sequence[int], group_clip: Sequence[float],
+                          acc_w: List[np.ndarray], acc_b: List[Optional[np.ndarray]], threads: int = 0):
+    """One micro-step with clipping units of `unit` consecutive examples (the micro-batching of the GPU baseline,
+    Abstract and Table 1): adds sum_u clip(mean of unit u's gradients) into acc_w / acc_b.
+    Returns (n2 [n/unit, G], f [n/unit, G])."""
+    lib = _load()
+    nl = len(layers)
+    n = int(inputs[0][0].shape[0])
+    ng = len(group_clip)
+    arr = (_Layer * nl)(*[_c_layer(l, g) for l, g in zip(layers, group_of_layer)])
+    xs = [_f32(x) for x, _ in inputs]
+    dys = [_f32(dy) for _, dy in inputs]
+    fpp = C.POINTER(C.c_float)
+    dpp = C.POINTER(C.c_double)
+    xp = (fpp * nl)(*[_fp(a) for a in xs])
+    dyp = (fpp * nl)(*[_fp(a) for a in dys])
+    awp = (dpp * nl)(*[_dp(a) for a in acc_w])
+    abp = (dpp * nl)(*[(_dp(a) if a is not None else C.cast(None, dpp)) for a in acc_b])
+    gc = np.asarray(group_clip, dtype=np.float64)
+    if unit < 1 or n % unit:
+        raise ValueError("n must be a multiple of the clipping unit")
+    n2 = np.empty((n // unit, ng), dtype=np.float64)
+    f = np.empty((n // unit, ng), dtype=np.float64)
+    rc = lib.orc_clip_accumulate_units(arr, nl, xp, dyp, n, int(unit), ng, _dp(gc), awp, abp, _dp(n2), _dp(f), threads)
+    if rc != 0:
+        raise RuntimeError("orc_clip_accumulate_units failed")
+    return n2, f
+
+
+def unit_mean_grad(layer, x, dy, unit: int):
+    """Mean of the per-example gradients of each clipping unit: ([n/unit, pw], [n/unit, pb] or None)."""
+    n = int(x.shape[0])
+    rows_w, rows_b = [], []
+    for u in range(n // unit):
+        gs = [example_grad(layer, x[i], dy[i]) for i in range(u * unit, (u + 1) * unit)]
+        rows_w.append(sum(g[0] for g in gs) / unit)
+        rows_b.append(sum(g[1] for g in gs) / unit if layer.pb else None)
+    return np.stack(rows_w).reshape(n // unit, -1), (np.stack(rows_b) if layer.pb else None)
+
+
+def privatise_units(wl, inputs_per_micro_step, unit: int, threads: int = 0):
+    """Whole optimiser step with clipping units of `unit` examples: sum over units of the clipped unit means, noise
+    N(0, sigma^2 C^2) once, divided by the NUMBER OF UNITS in the step (each unit is one clipped contribution of
+    norm at most C, as an example is in Section 2's first equation).  Same tensor ids as privatise()."""
+    layers = list(wl.layers)
+    group_clip, clip_total = group_bounds(wl.clip_c, wl.n_groups)
+    acc_w, acc_b = new_accumulators(layers)
+    n2s, fs = [], []
+    for inputs in inputs_per_micro_step:
+        n2, f = clip_accumulate_units(layers, inputs, unit, wl.group_of_layer, group_clip, acc_w, acc_b, threads)
+        n2s.append(n2)
+        fs.append(f)
+    n_units = wl.total_batch // unit
+    out_w, out_b = [], []
+    for li, l in enumerate(layers):
+        out_w.append(noise_finalize(acc_w[li], wl.sigma, clip_total, n_units, wl.philox_seed, wl.step, 2 * li))
+        out_b.append(noise_finalize(acc_b[li], wl.sigma, clip_total, n_units, wl.philox_seed, wl.step, 2 * li + 1)
+                     if acc_b[li] is not None else None)
+    return dict(acc_w=acc_w, acc_b=acc_b, out_w=out_w, out_b=out_b, n2=n2s, f=fs)
 
 
 def weighted_sum_elems(layer, x, dy, f, idx, bias: bool = False) -> np.ndarray:

@@ -344,6 +344,93 @@ int orc_clip_accumulate(const orc_layer *layers, int n_layers,
     return failed ? -1 : 0;
 }
 
+int orc_clip_accumulate_units(const orc_layer *layers, int n_layers,
+                              const float *const *x, const float *const *dy, int n, int unit,
+                              int n_groups, const double *group_clip,
+                              double *const *acc_w, double *const *acc_b,
+                              double *n2_out, double *f_out, int threads)
+{
+    if (!layers || n_layers <= 0 || n <= 0 || unit <= 0 || n % unit || n_groups <= 0 || !group_clip) return -1;
+    for (int l = 0; l < n_layers; ++l)
+        if (layers[l].group < 0 || layers[l].group >= n_groups) return -1;
+    const int units = n / unit;
+    if (threads <= 0) threads = orc_max_threads();
+    if (threads > units) threads = units;
+
+    size_t *off_w = (size_t *)malloc(sizeof(size_t) * (size_t)n_layers);
+    size_t *off_b = (size_t *)malloc(sizeof(size_t) * (size_t)n_layers);
+    if (!off_w || !off_b) { free(off_w); free(off_b); return -1; }
+    size_t total = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        off_w[l] = total; total += orc_w_elems(&layers[l]);
+        off_b[l] = total; total += orc_b_elems(&layers[l]);
+    }
+    int failed = 0;
+
+#pragma omp parallel num_threads(threads)
+    {
+        double *g = (double *)malloc(sizeof(double) * total);      /* one example's gradient */
+        double *gbar = (double *)malloc(sizeof(double) * total);   /* the unit's mean gradient */
+        double *mine = (double *)calloc(total, sizeof(double));    /* this thread's clipped sum */
+        double *n2 = (double *)malloc(sizeof(double) * (size_t)n_groups);
+        double *f = (double *)malloc(sizeof(double) * (size_t)n_groups);
+        if (!g || !gbar || !mine || !n2 || !f) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 1)
+            for (int u = 0; u < units; ++u) {
+                /* (a) mean of the unit's per-example gradients */
+                for (size_t e = 0; e < total; ++e) gbar[e] = 0.0;
+                for (int k = 0; k < unit; ++k) {
+                    const int i = u * unit + k;
+                    for (int l = 0; l < n_layers; ++l) {
+                        const orc_layer *L = &layers[l];
+                        orc_example_grad(L, x[l] + (size_t)i * orc_x_elems(L),
+                                         dy[l] + (size_t)i * orc_dy_elems(L),
+                                         g + off_w[l], orc_b_elems(L) ? g + off_b[l] : NULL);
+                    }
+                    for (size_t e = 0; e < total; ++e) gbar[e] += g[e];
+                }
+                for (size_t e = 0; e < total; ++e) gbar[e] /= (double)unit;
+                /* (b) squared norm per clipping group, (c) factor, (d) clipped sum */
+                for (int q = 0; q < n_groups; ++q) n2[q] = 0.0;
+                for (int l = 0; l < n_layers; ++l) {
+                    const orc_layer *L = &layers[l];
+                    n2[L->group] += orc_sqnorm(gbar + off_w[l], orc_w_elems(L));
+                    n2[L->group] += orc_sqnorm(gbar + off_b[l], orc_b_elems(L));
+                }
+                for (int q = 0; q < n_groups; ++q) f[q] = orc_clip_factor(n2[q], group_clip[q]);
+                for (int l = 0; l < n_layers; ++l) {
+                    const orc_layer *L = &layers[l];
+                    const double fl = f[L->group];
+                    const size_t cnt = orc_w_elems(L) + orc_b_elems(L);
+                    for (size_t e = 0; e < cnt; ++e) mine[off_w[l] + e] += fl * gbar[off_w[l] + e];
+                }
+                for (int q = 0; q < n_groups; ++q) {
+                    if (n2_out) n2_out[(size_t)u * n_groups + q] = n2[q];
+                    if (f_out) f_out[(size_t)u * n_groups + q] = f[q];
+                }
+            }
+#pragma omp critical
+            {
+                for (int l = 0; l < n_layers; ++l) {
+                    const orc_layer *L = &layers[l];
+                    const size_t pw = orc_w_elems(L), pb = orc_b_elems(L);
+                    for (size_t e = 0; e < pw; ++e) acc_w[l][e] += mine[off_w[l] + e];
+                    if (pb && acc_b && acc_b[l])
+                        for (size_t e = 0; e < pb; ++e) acc_b[l][e] += mine[off_b[l] + e];
+                }
+            }
+        }
+        free(g); free(gbar); free(mine); free(n2); free(f);
+    }
+    free(off_w); free(off_b);
+    return failed ? -1 : 0;
+}
+
 void orc_weighted_sum_elems(const orc_layer *l, const float *x, const float *dy, int n,
                             const double *f, const size_t *idx, size_t n_idx, int is_bias,
                             double *out)

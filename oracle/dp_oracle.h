@@ -21,7 +21,9 @@
  * differences, library GEMM / autograd special cases, closed-form norms, the clip
  * invariant, noise moments; for the per-example noise form its moments, the independence of
  * the examples' draws and the documented counter / key words; for the SGD step the closed-form
- * momentum series and a library optimiser.  No function here is "parity unpinned".
+ * momentum series and a library optimiser; for clipping units the unit-of-one case, a worked
+ * scalar example, a library autograd mean-loss gradient and the sum-form identity.  No function
+ * here is "parity unpinned".
  */
 #ifndef DP_ORACLE_H
 #define DP_ORACLE_H
@@ -87,6 +89,19 @@ int orc_clip_accumulate(const orc_layer *layers, int n_layers,
                         int n_groups, const double *group_clip,
                         double *const *acc_w, double *const *acc_b,
                         double *n2, double *f, int threads);
+
+/* The same micro-step with CLIPPING UNITS of `unit` consecutive examples (the micro-batching of the
+ * GPU baseline, Abstract and Table 1: the gradient of a micro-batch is clipped instead of the gradient
+ * of each example).  For each unit u = examples [u*unit, (u+1)*unit):
+ *   gbar_u = 1/unit * sum of the unit's per-example gradients (the gradient of the unit's mean loss),
+ *   per-group squared norms of gbar_u, factors, then acc += f * gbar_u.
+ * n must be a multiple of unit; n2 and f (may be NULL) have n/unit rows.  unit == 1 is
+ * orc_clip_accumulate.  Returns 0, or -1 on a bad argument / allocation failure.               */
+int orc_clip_accumulate_units(const orc_layer *layers, int n_layers,
+                              const float *const *x, const float *const *dy, int n, int unit,
+                              int n_groups, const double *group_clip,
+                              double *const *acc_w, double *const *acc_b,
+                              double *n2, double *f, int threads);
 
 /* Selected elements of sum_i f[i] * g_i for one layer (weights if is_bias == 0). */
 void orc_weighted_sum_elems(const orc_layer *l, const float *x, const float *dy, int n,
