@@ -200,6 +200,25 @@ dp_status dp_clip_accumulate_recompute_batch(const dp_layer_desc *descs, const v
                                              float *const *acc_b, void *const *ws, const size_t *ws_bytes, int n_layers,
                                              dp_stream stream);
 
+/* H1 + H2 for CLIPPING UNITS of several examples (the micro-batching of the GPU baseline in the Abstract and
+ * Table 1: the gradient of a micro-batch of clip_unit examples is clipped instead of each example's).  Unit u
+ * holds the consecutive examples [u * clip_unit, (u + 1) * clip_unit); the call gives, per unit, the SUM of its
+ * per-example gradients (definitions as in dp_per_example_grad; the contraction runs over the unit's examples as
+ * well as its positions) and the squared norm of that sum:
+ *   g_w / g_b  [device] unit u's sums at g_w + u * stride_w, g_b + u * stride_b (n / clip_unit rows), or NULL
+ *   sqnorm     [device] [n / clip_unit], ||S_u||^2; may be NULL only if g_w is given
+ * The rest of the path then treats a unit like an example.  With gbar_u = S_u / clip_unit the unit's mean,
+ *   sum_u clip(gbar_u, C) = 1/clip_unit * sum_u clip(S_u, clip_unit * C),
+ * so H3/H4 run on the sums with the bound clip_unit * C, H5 with clip_total = clip_unit * C and
+ * total_batch = clip_unit * (number of units) = the number of examples: the result is
+ * (N(0, sigma^2 C^2) + sum_u clip(gbar_u, C)) / (number of units).
+ * desc->n must be a multiple of clip_unit (else DP_ERR_INVALID_ARG); clip_unit == 1 is dp_per_example_grad.
+ * ws: at least dp_unit_workspace_bytes(desc, clip_unit) (0 on a bad descriptor / unit).  Other arguments and
+ * errors as dp_per_example_grad.                                                                       */
+size_t dp_unit_workspace_bytes(const dp_layer_desc *desc /*[host]*/, int clip_unit);
+dp_status dp_unit_grad(const dp_layer_desc *desc /*[host]*/, int clip_unit, const void *x, const void *dy, float *g_w,
+                       float *g_b, size_t g_stride, float *sqnorm, void *ws, size_t ws_bytes, dp_stream stream);
+
 /* group_sqnorm[g, i] = sum over the layers l of group g, in order, of sum_c partials[l][i * counts[l] + c].
  * partials [host] array of n_layers device pointers (4-byte aligned); counts, group_of_layer [host]
  * arrays of n_layers ints; group_sqnorm [device] [n_groups, n], overwritten.                       */

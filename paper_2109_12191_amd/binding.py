@@ -60,6 +60,8 @@ def load_library():
         "dp_per_example_grad_static": (it, [dpp, vp, vp, vp, vp, sz, vp, vp]),
         "dp_norms": (it, [vp, vp, it, it, it, vp, vp]),
         "dp_norm_partial_count": (sz, [dpp, it]),
+        "dp_unit_workspace_bytes": (sz, [dpp, it]),
+        "dp_unit_grad": (it, [dpp, it, vp, vp, vp, vp, sz, vp, vp, sz, vp]),
         "dp_per_example_grad_partials": (it, [dpp, vp, vp, vp, vp, sz, vp, sz, vp]),
         "dp_norms_from_partials": (it, [vp, vp, vp, it, it, it, vp, vp]),
         "dp_per_example_grad_batch": (it, [vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, it, vp]),
@@ -88,6 +90,7 @@ def load_library():
 
 EXPORTED = ("dp_group_clip_bounds", "dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_static_scratch_bytes", "dp_per_example_grad_static",
+            "dp_unit_workspace_bytes", "dp_unit_grad",
             "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
             "dp_per_example_grad_batch", "dp_layer_norms_from_partials", "dp_clip_accumulate_recompute_batch",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_segments", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
@@ -200,6 +203,17 @@ def dp_norms_from_partials(table: "PartialTable", n: int, n_groups: int, group_s
     _check(load_library().dp_norms_from_partials(C.cast(table.ptrs, C.c_void_p), C.cast(table.counts, C.c_void_p),
                                                  C.cast(table.groups, C.c_void_p), table.n_layers, n, n_groups,
                                                  _ptr(group_sqnorm), _stream(stream)))
+
+
+def dp_unit_workspace_bytes(desc: LayerDesc, clip_unit: int) -> int:
+    return int(load_library().dp_unit_workspace_bytes(C.byref(desc), clip_unit))
+
+
+def dp_unit_grad(desc: LayerDesc, clip_unit: int, x, dy, g_w, g_b, sqnorm, ws, g_stride: int = 0, stream=None):
+    """Sums of the per-example gradients over clipping units of clip_unit consecutive examples, and the squared
+    norms of the sums ([n / clip_unit])."""
+    _check(load_library().dp_unit_grad(C.byref(desc), clip_unit, _ptr(x), _ptr(dy), _ptr(g_w), _ptr(g_b), g_stride,
+                                       _ptr(sqnorm), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 class LayerBatch:

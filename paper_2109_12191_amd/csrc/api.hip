@@ -316,6 +316,69 @@ dp_status dp_per_example_grad_partials(const dp_layer_desc *desc, const void *x,
     return launch_gn(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
 }
 
+// ---- clipping units of several examples ----------------------------------------------------
+
+// Geometry of a call with clipping units.  A dense layer's unit sum is the per-example gradient of one
+// example that holds the tokens of the whole unit ([n, t, k] read as [n / unit, unit * t, k]).
+static dp_status unit_geo(const dp_layer_desc *desc, int clip_unit, Geo &g)
+{
+    DP_TRY(make_geo(desc, g));
+    if (clip_unit < 1) return fail(DP_ERR_INVALID_ARG, "clip_unit = %d (need >= 1)", clip_unit);
+    if (g.n % clip_unit) return fail(DP_ERR_INVALID_ARG, "n = %d is not a multiple of clip_unit = %d", g.n, clip_unit);
+    if (g.kind == DP_DENSE) {
+        if ((long long)desc->h * clip_unit > 0x7FFFFFFFll) return fail(DP_ERR_UNSUPPORTED, "dense layer: unit * tokens too large");
+        dp_layer_desc d2 = *desc;
+        d2.n = desc->n / clip_unit;
+        d2.h = desc->h * clip_unit;
+        DP_TRY(make_geo(&d2, g));
+    }
+    return DP_OK;
+}
+
+static size_t unit_ws_need(const Geo &g, int kind, int clip_unit)
+{
+    if (kind == DP_DENSE) return dense_ws_bytes(g, MODE_NORM);          // g is already the reshaped layer
+    if (kind == DP_CONV2D) return conv_unit_ws_bytes(g, clip_unit);
+    return gn_unit_ws_bytes(g, clip_unit);
+}
+
+size_t dp_unit_workspace_bytes(const dp_layer_desc *desc, int clip_unit)
+{
+    Geo g;
+    if (unit_geo(desc, clip_unit, g) != DP_OK) return 0;
+    if (clip_unit == 1) return dp_workspace_bytes(desc, DP_WS_PER_EXAMPLE_GRAD);
+    return unit_ws_need(g, desc->kind, clip_unit);
+}
+
+dp_status dp_unit_grad(const dp_layer_desc *desc, int clip_unit, const void *x, const void *dy, float *g_w,
+                                  float *g_b, size_t g_stride, float *sqnorm, void *ws, size_t ws_bytes, dp_stream stream)
+{
+    Geo g;
+    DP_TRY(unit_geo(desc, clip_unit, g));
+    if (clip_unit == 1) return dp_per_example_grad(desc, x, dy, g_w, g_b, g_stride, sqnorm, ws, ws_bytes, stream);
+    DP_TRY(check_ptr(x, "x", true));
+    DP_TRY(check_ptr(dy, "dy", true));
+    DP_TRY(check_ptr(g_w, "g_w", false));
+    DP_TRY(check_ptr(g_b, "g_b", false));
+    DP_TRY(check_ptr(sqnorm, "sqnorm", g_w == nullptr, 4));
+    if (g_w && g.pb && !g_b) return fail(DP_ERR_INVALID_ARG, "g_w given but g_b is NULL for a layer with a bias");
+    if (!g_w && g_b) return fail(DP_ERR_INVALID_ARG, "g_b given without g_w");
+    if (g_stride) {
+        if (g_stride % 4) return fail(DP_ERR_INVALID_ARG, "g_stride must be a multiple of 4");
+        if (g_stride < g.pw || g_stride < g.pb) return fail(DP_ERR_INVALID_ARG, "g_stride smaller than the tensor");
+    }
+    const size_t need = unit_ws_need(g, desc->kind, clip_unit);
+    if (need && (!ws || ws_bytes < need))
+        return fail(DP_ERR_WORKSPACE, "workspace of %zu bytes needed (dp_unit_workspace_bytes), %zu given", need, ws ? ws_bytes : (size_t)0);
+    if (need && !aligned16(ws)) return fail(DP_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    g_err[0] = 0;
+    const int mode = g_w ? MODE_MATERIALISE : MODE_NORM;
+    if (g.kind == DP_DENSE) return launch_dense(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
+    if (g.kind == DP_CONV2D) return launch_conv_units(g, clip_unit, x, dy, g_w, g_b, g_stride, sqnorm, ws, s);
+    return launch_gn_units(g, clip_unit, x, dy, g_w, g_b, g_stride, sqnorm, ws, s);
+}
+
 // Work per workgroup a batch call plans for, in units of one 128x128x64 chunk: the convolutions' multiply-adds
 // spread over about three rounds of workgroups on 256 compute units, but neither so little that a workgroup's
 // start-up dominates nor so much that one workgroup becomes the critical path.

@@ -64,6 +64,8 @@ struct ConvArgs {
     int ex_per_split;                 // weighted mode
     int ex_per_wg;                    // per-example mode, ksplit == 1: consecutive examples per workgroup
     int force_slow;                   // stride other than 1 or 2: stage every chunk element by element
+    int unit_major;                   // weighted mode: every example range keeps its own result (clipping units): the
+                                      // slices always go to the workspace, ordered (range, tile); no clip factors
 };
 
 struct ColInfo {
@@ -549,7 +551,7 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const Grouped
     auto stage = [&](const RawSet &R, char *bufA, char *bufB) {
         const int i = R.i, c = R.c, k0 = c * KC;
         float f = 1.0f;
-        if constexpr (WEIGHTED) f = clip_factor(a.group_sqnorm[i], a.clip_c);
+        if constexpr (WEIGHTED) f = a.group_sqnorm ? clip_factor(a.group_sqnorm[i], a.clip_c) : 1.0f;
         if (all_slow) {
             slow_stage_a<BF16, MT, WEIGHTED>(bufA, dyg + (size_t)i * dy_ex, a.cout, a.S, a.oh, a.ow, a.kcolsp, m0, k0, f);
             slow_stage_b<BF16, NT>(bufB, xg + (size_t)i * x_ex, cols, a.h, a.w, a.oh, a.ow, a.stride, a.kcolsp, k0);
@@ -724,7 +726,7 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const Grouped
         __syncthreads();
     }
 
-    if (a.ksplit == 1) {
+    if (a.ksplit == 1 && !(WEIGHTED && a.unit_major)) {
         if constexpr (WEIGHTED) finish(0);
         return;
     }
@@ -732,7 +734,8 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const Grouped
     // ---- slices of one tile meet in the workspace; a second kernel (conv_fixup_kernel) adds
     // them in slice order and runs the epilogue.  Plain stores: the kernel boundary orders them.
     const int group = WEIGHTED ? tile : (unit * tiles + tile);     // ex_per_wg == 1 when K is sliced
-    float *mine = a.ws_part + ((size_t)group * a.ksplit + split) * (NACC * 16 * THREADS);
+    const size_t slot = (WEIGHTED && a.unit_major) ? (size_t)split * tiles + tile : (size_t)group * a.ksplit + split;
+    float *mine = a.ws_part + slot * (NACC * 16 * THREADS);
 #pragma unroll
     for (int t = 0; t < NACC; ++t)
 #pragma unroll
@@ -1045,7 +1048,7 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
         if (++chunk_in_ex == cpe) {
             chunk_in_ex = 0;
             if constexpr (WEIGHTED) {
-                const float f = clip_factor(a.group_sqnorm[ex], a.clip_c);
+                const float f = a.group_sqnorm ? clip_factor(a.group_sqnorm[ex], a.clip_c) : 1.0f;
 #pragma unroll
                 for (int t = 0; t < NACC; ++t)
 #pragma unroll
@@ -1062,7 +1065,7 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
     }
 
     if constexpr (WEIGHTED) {
-        if (ksplit == 1) {
+        if (ksplit == 1 && !a.unit_major) {
             tile_epilogue<2, TM, TN, true, false>(tot, a, 0, m0, n0, wm, wn, lane, false);
             return;
         }
@@ -1071,7 +1074,8 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
     }
     // slices of one tile meet in the workspace (conv_fixup_kernel adds them in slice order)
     const int group = WEIGHTED ? tile : (unit * tiles + tile);
-    float *mine = a.ws_part + ((size_t)group * ksplit + split) * (NACC * 16 * THREADS);
+    const size_t part = (WEIGHTED && a.unit_major) ? (size_t)split * tiles + tile : (size_t)group * ksplit + split;
+    float *mine = a.ws_part + part * (NACC * 16 * THREADS);
 #pragma unroll
     for (int t = 0; t < NACC; ++t)
 #pragma unroll
@@ -1449,7 +1453,39 @@ static const void *kernel_of(int loader, bool weighted, bool bias)
 
 static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                                   size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c,
-                                  void *ws, hipStream_t s);
+                                  void *ws, hipStream_t s, int unit = 0);
+
+// The plan of the clip-weighted kernel with one example range per clipping unit.
+static FullPlan unit_plan(const Geo &g, int unit)
+{
+    FullPlan f = full_plan(g, MODE_WEIGHTED);
+    const int tiles = f.tiles_m * f.tiles_n;
+    f.ex_per_split = unit;
+    f.ksplit = g.n / unit;
+    f.groups = tiles;
+    f.part_floats = (size_t)tiles * f.ksplit * f.nacc * 16 * THREADS;
+    return f;
+}
+
+size_t conv_unit_ws_bytes(const Geo &g, int unit)
+{
+    if (conv3x3_applicable(g, MODE_WEIGHTED)) return conv3x3_unit_ws_bytes(g, unit);
+    const FullPlan f = unit_plan(g, unit);
+    const size_t units = (size_t)(g.n / unit), tiles = (size_t)f.tiles_m * f.tiles_n;
+    return align16(units * tiles * f.nacc * FIX_PARTS * sizeof(float)) + f.part_floats * sizeof(float);
+}
+
+// Sums of the per-example gradients over clipping units of `unit` consecutive examples, and their squared norms:
+// the clip-weighted kernel with factor 1 and one example range per unit (K runs over the unit's examples and
+// positions), whose slices the per-example slice-sum kernel then treats as "examples".
+dp_status launch_conv_units(const Geo &g, int unit, const void *x, const void *dy, float *out_w, float *out_b,
+                            size_t out_stride, float *sqnorm, void *ws, hipStream_t s)
+{
+    const int mode = out_w ? MODE_MATERIALISE : MODE_NORM;
+    if (conv3x3_applicable(g, MODE_WEIGHTED))
+        return launch_conv3x3(g, mode, x, dy, out_w, out_stride, sqnorm, nullptr, 0.0f, ws, s, unit);
+    return launch_conv_impl(g, mode, x, dy, out_w, out_b, out_stride, sqnorm, nullptr, 0.0f, ws, s, unit);
+}
 
 dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
@@ -1485,11 +1521,13 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
 
 static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
                                   size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c,
-                                  void *ws, hipStream_t s)
+                                  void *ws, hipStream_t s, int unit)
 {
-    const FullPlan f = full_plan(g, mode);
-    const bool weighted = mode == MODE_WEIGHTED;
+    // unit > 0: `mode` says whether the unit sums are stored; the kernel that runs is the weighted one
+    const FullPlan f = unit ? unit_plan(g, unit) : full_plan(g, mode);
+    const bool weighted = mode == MODE_WEIGHTED || unit > 0;
     ConvArgs a;
+    a.unit_major = unit ? 1 : 0;
     a.x = x; a.dy = dy;
     a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = f.h; a.w = f.w; a.kh = g.kh; a.kw = g.kw;
     a.stride = g.stride; a.pad = g.pad; a.oh = f.oh; a.ow = f.ow;
@@ -1506,11 +1544,15 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
     const int tiles = f.tiles_m * f.tiles_n;
     char *w = static_cast<char *>(ws);
     a.partials = nullptr;
+    const size_t unit_partials = (size_t)tiles * f.nacc * FIX_PARTS;      // per unit, from the slice-sum kernel
     if (!weighted) {
         a.partials = reinterpret_cast<float *>(w);
         w += align16(norm_partials(g, f) * sizeof(float));
+    } else if (unit) {
+        a.partials = reinterpret_cast<float *>(w);
+        w += align16((size_t)(g.n / unit) * unit_partials * sizeof(float));
     }
-    a.ws_part = (f.ksplit > 1) ? reinterpret_cast<float *>(w) : nullptr;
+    a.ws_part = (f.ksplit > 1 || unit) ? reinterpret_cast<float *>(w) : nullptr;
     long long total;
     if (weighted) total = (long long)tiles * f.ksplit;
     else total = (long long)((g.n + f.ex_per_wg - 1) / f.ex_per_wg) * tiles * f.ksplit;
@@ -1542,6 +1584,18 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
     dp_status st = submit_main<ConvArgs>(fn, a, blocks, THREADS, lds_bytes, s, "conv_contract");
     if (st != DP_OK) return st;
     // what follows the main kernel: at once, or after the grouped launches of a batch call
+    if (unit) {
+        // every unit's slice is finished like an unsliced example: stored (if wanted) and squared
+        ConvArgs u = a;
+        u.n = g.n / unit; u.ksplit = 1;
+        const unsigned fix_blocks = (unsigned)((size_t)u.n * unit_partials);
+        const void *fix = (f.shape == T64) ? fixup_of<2, 2, 1, 1>(false, bias) : fixup_of<2, 2, 2, 2>(false, bias);
+        st = submit_kernel<ConvArgs>(TIER_POST, fix, u, fix_blocks, THREADS, 0, s, "conv_fixup");
+        if (st != DP_OK || !sqnorm) return st;
+        const float *partials = a.partials;
+        const int units = u.n, per = (int)unit_partials;
+        return submit_post([=]() -> dp_status { return launch_sum_partials(partials, units, per, sqnorm, s); });
+    }
     if (f.ksplit > 1) {
         const unsigned fix_blocks = (unsigned)(f.groups * f.nacc * FIX_PARTS);
         const void *fix = (f.shape == T64) ? fixup_of<2, 2, 1, 1>(weighted, bias) : fixup_of<2, 2, 2, 2>(weighted, bias);

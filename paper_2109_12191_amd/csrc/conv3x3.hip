@@ -47,6 +47,8 @@ struct C3Args {
     int chunks;                       // ceil(H / R)
     int ksplit, chunks_per_split;     // per-example mode: K slices
     int ex_per_split;                 // weighted mode: examples per workgroup (ksplit = example ranges)
+    int unit_major;                   // weighted mode: every example range keeps its own result (clipping units): the
+                                      // slices always go to the workspace, ordered (range, tile)
 };
 
 constexpr int odd16(int bytes) { return ((bytes / 16) | 1) * 16; }
@@ -240,7 +242,7 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3
     for (int i = i_first; i < i_last; ++i) {
     const int x_base = i * x_ex, dy_base = i * dy_ex;
     float f = 1.0f;
-    if constexpr (WEIGHTED) f = clip_factor(a.group_sqnorm[i], a.clip_c);
+    if constexpr (WEIGHTED) f = a.group_sqnorm ? clip_factor(a.group_sqnorm[i], a.clip_c) : 1.0f;
     for (int chunk = c_begin; chunk < c_end; ++chunk) {
         const int oh0 = chunk * C::R;
         if (chunk != c_begin || i != i_first) __syncthreads();    // everyone is done reading the previous chunk
@@ -431,10 +433,11 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3
 
     if constexpr (MODE == C3_FULL) {
         c3_epilogue(acc, a, i_first, unit, co0, ci0, wm, wn, lane, red, lds);
-    } else if (WEIGHTED && a.ksplit == 1) {
+    } else if (WEIGHTED && a.ksplit == 1 && !a.unit_major) {
         c3_add_to_accumulator(acc, a, co0, ci0, wm, wn, lane, lds);
     } else {
-        float *mine = a.ws_part + ((size_t)unit * a.ksplit + split) * (9 * 16 * C3_THREADS);
+        const size_t slot = (WEIGHTED && a.unit_major) ? (size_t)split * tiles + tile : (size_t)unit * a.ksplit + split;
+        float *mine = a.ws_part + slot * (9 * 16 * C3_THREADS);
 #pragma unroll
         for (int t = 0; t < 9; ++t)
 #pragma unroll
@@ -725,12 +728,23 @@ const char *conv3x3_variant_name(const Geo &g, int mode)
     return names.v[g.stride == 2 ? 1 : 0][mode == MODE_WEIGHTED ? 1 : 0][slot];
 }
 
-dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
-                         float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s)
+// workspace of a call with clipping units: [units, tiles, 36] partial norms, then one accumulator block per (unit, tile)
+size_t conv3x3_unit_ws_bytes(const Geo &g, int unit)
 {
-    const bool weighted = mode == MODE_WEIGHTED;
-    const C3Plan p = c3_plan(g, mode);
+    const size_t tiles = (size_t)((g.cout + 63) / 64) * ((g.cin + 63) / 64), units = (size_t)(g.n / unit);
+    return c3_align16(units * tiles * 9 * C3_FIX_PARTS * sizeof(float)) + units * tiles * 9 * 16 * C3_THREADS * sizeof(float);
+}
+
+dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
+                         float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s, int unit)
+{
+    // unit > 0 (stride 1 only): sums over clipping units.  The clip-weighted kernel runs with factor 1 and one
+    // example range per unit; the per-example slice-sum kernel then finishes every unit's block like an example's.
+    const bool weighted = mode == MODE_WEIGHTED || unit > 0;
+    C3Plan p = c3_plan(g, weighted ? MODE_WEIGHTED : mode);
+    if (unit) { p.ex_per_split = unit; p.ksplit = g.n / unit; }
     C3Args a;
+    a.unit_major = unit ? 1 : 0;
     a.x = static_cast<const uint16_t *>(x);
     a.dy = static_cast<const uint16_t *>(dy);
     a.out_w = out_w;
@@ -747,9 +761,12 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     if (!weighted) {
         a.partials = reinterpret_cast<float *>(w);
         w += c3_align16(units * c3_partials_per_unit(p) * sizeof(float));
+    } else if (unit) {
+        a.partials = reinterpret_cast<float *>(w);
+        w += c3_align16((size_t)(g.n / unit) * tiles * 9 * C3_FIX_PARTS * sizeof(float));
     }
-    a.ws_part = p.ksplit > 1 ? reinterpret_cast<float *>(w) : nullptr;
-    if (p.ksplit > 1) w += units * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float);
+    a.ws_part = (p.ksplit > 1 || unit) ? reinterpret_cast<float *>(w) : nullptr;
+    if (p.ksplit > 1 || unit) w += units * p.ksplit * 9 * 16 * C3_THREADS * sizeof(float);
     const long long total = (long long)units * p.ksplit;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     dp_status st;
@@ -781,6 +798,17 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     }
     if (st != DP_OK) return st;
     // what follows the main kernel: at once, or after the grouped launch of a batch call
+    if (unit) {
+        C3Args u = a;
+        u.n = g.n / unit; u.ksplit = 1;
+        const size_t per_unit = tiles * 9 * C3_FIX_PARTS;
+        st = submit_kernel<C3Args>(TIER_POST, reinterpret_cast<const void *>(&conv3x3_fixup_kernel<false>), u,
+                                   (unsigned)((size_t)u.n * per_unit), C3_THREADS, 0, s, "conv3x3_fixup");
+        if (st != DP_OK || !sqnorm) return st;
+        const float *partials = a.partials;
+        const int n_units = u.n, per = (int)per_unit;
+        return submit_post([=]() -> dp_status { return launch_sum_partials(partials, n_units, per, sqnorm, s); });
+    }
     if (p.ksplit > 1) {
         const unsigned fix_blocks = (unsigned)(units * 9 * C3_FIX_PARTS);
         const void *fix = weighted ? reinterpret_cast<const void *>(&conv3x3_fixup_kernel<true>)

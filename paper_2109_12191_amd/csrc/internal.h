@@ -44,7 +44,17 @@ bool conv3x3_applicable(const Geo &g, int mode);
 size_t conv3x3_ws_bytes(const Geo &g, int mode);
 const char *conv3x3_variant_name(const Geo &g, int mode);
 dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
-                         float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s);
+                         float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s, int unit = 0);
+size_t conv3x3_unit_ws_bytes(const Geo &g, int unit);
+
+// Sums of the per-example gradients over clipping units of `unit` consecutive examples (n a multiple of unit), and
+// their squared norms [n / unit]; out_w / out_b rows are units.
+size_t conv_unit_ws_bytes(const Geo &g, int unit);
+dp_status launch_conv_units(const Geo &g, int unit, const void *x, const void *dy, float *out_w, float *out_b,
+                            size_t out_stride, float *sqnorm, void *ws, hipStream_t s);
+size_t gn_unit_ws_bytes(const Geo &g, int unit);
+dp_status launch_gn_units(const Geo &g, int unit, const void *x, const void *dy, float *out_w, float *out_b,
+                          size_t out_stride, float *sqnorm, void *ws, hipStream_t s);
 
 // Packed operands of the clip-weighted contraction (pack.hip): K-contiguous, aligned, dY
 // pre-scaled by the clip factors; `groups` example ranges of `eg` examples, rows of `kg` elements.

@@ -395,4 +395,63 @@ dp_status launch_gn(const Geo &g, int mode, const void *x, const void *dy, float
     return launch_sum_partials(a.partials, g.n, g.gn_groups, sqnorm, s);
 }
 
+// Clipping units: rows[u*unit .. (u+1)*unit) of the per-example scale / shift gradients are added (in example
+// order), stored if wanted, and squared.  One workgroup per (256 channels, unit).
+struct UnitRowsArgs {
+    const float *gw, *gb;          // [n, c] per-example gradients
+    float *out_w, *out_b;          // unit sums (may be null)
+    size_t out_stride_w, out_stride_b;
+    float *partials;               // [units, gridDim.x]
+    int c, unit;
+};
+
+__global__ void __launch_bounds__(256) unit_rows_kernel(const UnitRowsArgs a)
+{
+    __shared__ float red[4];
+    const int c = blockIdx.x * 256 + threadIdx.x, u = blockIdx.y;
+    float sw = 0.0f, sb = 0.0f;
+    if (c < a.c) {
+        for (int e = 0; e < a.unit; ++e) {
+            const size_t row = (size_t)(u * a.unit + e) * a.c + c;
+            sw += a.gw[row];
+            sb += a.gb[row];
+        }
+        if (a.out_w) {
+            a.out_w[(size_t)u * a.out_stride_w + c] = sw;
+            a.out_b[(size_t)u * a.out_stride_b + c] = sb;
+        }
+    }
+    const float tot = block_sum<4>(sw * sw + sb * sb, red);
+    if (threadIdx.x == 0) a.partials[(size_t)u * gridDim.x + blockIdx.x] = tot;
+}
+
+static size_t gn_unit_head(const Geo &g) { return gn_ws_bytes(g, MODE_WEIGHTED); }
+
+size_t gn_unit_ws_bytes(const Geo &g, int unit)
+{
+    return gn_unit_head(g) + (size_t)(g.n / unit) * ((g.cin + 255) / 256) * sizeof(float);
+}
+
+dp_status launch_gn_units(const Geo &g, int unit, const void *x, const void *dy, float *out_w, float *out_b,
+                          size_t out_stride, float *sqnorm, void *ws, hipStream_t s)
+{
+    // per-example gradients into the workspace (where the clip-weighted call keeps them), then the unit sums
+    const size_t head = (((size_t)g.n * g.gn_groups * sizeof(float)) + 15) & ~(size_t)15;
+    float *gw = reinterpret_cast<float *>(static_cast<char *>(ws) + head);
+    float *gb = gw + (size_t)g.n * g.cin;
+    dp_status st = launch_gn(g, MODE_MATERIALISE, x, dy, gw, gb, (size_t)g.cin, nullptr, nullptr, 0.0f, ws, s);
+    if (st != DP_OK) return st;
+    UnitRowsArgs a;
+    a.gw = gw; a.gb = gb; a.out_w = out_w; a.out_b = out_b;
+    a.out_stride_w = out_stride ? out_stride : g.pw;
+    a.out_stride_b = out_stride ? out_stride : g.pb;
+    a.partials = reinterpret_cast<float *>(static_cast<char *>(ws) + gn_unit_head(g));
+    a.c = g.cin; a.unit = unit;
+    const int blocks = (g.cin + 255) / 256, units = g.n / unit;
+    hipLaunchKernelGGL(unit_rows_kernel, dim3(blocks, units), dim3(256), 0, s, a);
+    st = check_launch("unit_rows");
+    if (st != DP_OK || !sqnorm) return st;
+    return launch_sum_partials(a.partials, units, blocks, sqnorm, s);
+}
+
 }  // namespace dp
