@@ -118,6 +118,8 @@ def main():
                     help="examples of micro-batch 0 the oracle is timed on (32 = about 10 s on 16 cores)")
     ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
     ap.add_argument("--streams", type=int, default=8, help="side streams for independent layers")
+    ap.add_argument("--clip-unit", type=int, default=1,
+                    help="examples per clipping unit (1: every example is clipped; 2, 4: the micro-batch clipping of the GPU baseline)")
     ap.add_argument("--lanes", default="balanced", choices=("round_robin", "balanced"),
                     help="how the batch calls of a phase are dealt to the side streams")
     ap.add_argument("--batching", default="variant", choices=("variant", "all"),
@@ -142,7 +144,7 @@ def main():
     device = torch.device("cuda:0")
     wl = get_workload(args.workload, n=args.n, accum=args.accum, hw=args.hw)
     ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=args.streams, noise=args.noise,
-                          batching=args.batching, lanes=args.lanes)
+                          batching=args.batching, lanes=args.lanes, clip_unit=args.clip_unit)
     inputs = make_device_inputs(wl, wl.accum, device)
     if args.fused_update:
         ps.enable_update(lr=0.1, momentum=0.9, keep_gradient=False)
@@ -167,7 +169,7 @@ def main():
 
     # Roofline of the dominant kernel: the same steps issued call by call on ONE stream right
     # after the timed region, every contraction kernel bracketed by events on that stream.
-    pe = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=1, noise=args.noise)
+    pe = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=1, noise=args.noise, clip_unit=args.clip_unit)
     probe = Probe()
     pe.probe = probe
     pe.run(inputs)
@@ -231,13 +233,13 @@ def main():
         k = [0]
         def _ca():
             k[0] += 1
-            dp.dp_clip_accumulate(g_bufs[k[0] % len(g_bufs)], pe._group_sqnorm[0][0], pe.group_clip[0], pe.n, pe.p_mat,
+            dp.dp_clip_accumulate(g_bufs[k[0] % len(g_bufs)], pe._group_sqnorm[0][0], pe.group_clip[0], pe.rows, pe.p_mat,
                                   pe.acc, g_stride=pe.p_mat)
         sec = _time_stream(_ca)
-        nbytes = 4.0 * pe.n * pe.p_mat + 8.0 * pe.p_mat
+        nbytes = 4.0 * pe.rows * pe.p_mat + 8.0 * pe.p_mat
         streaming["clip_accumulate"] = dict(kernel="clip_accumulate_kernel", bytes=nbytes, us=sec * 1e6,
                                             achieved_GBps=nbytes / sec / 1e9, frac=nbytes / sec / HBM_PEAK,
-                                            what=f"reads the [{pe.n}, {pe.p_mat}] fp32 gradient matrix once, reads and writes the accumulator")
+                                            what=f"reads the [{pe.rows}, {pe.p_mat}] fp32 gradient matrix once, reads and writes the accumulator")
     def _fin():
         dp.dp_add_noise_finalize_flat(pe.acc, pe.out, pe._tensors, wl.sigma, pe.clip_total, wl.total_batch, wl.philox_seed,
                                       step_dev=pe._step_dev)
@@ -276,7 +278,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {len(wl.layers)} layers, {wl.n_params} parameters, micro-batch {wl.n} x "
                                f"{wl.accum} accumulation = {wl.total_batch} examples/step, {wl.clip_mode} clipping "
-                               f"C={wl.clip_c}, sigma={wl.sigma}, {wl.dtype} inputs, fp32 accumulators",
+                               f"C={wl.clip_c}, sigma={wl.sigma}, {wl.dtype} inputs, fp32 accumulators"
+                               + (f", clipping units of {args.clip_unit} examples" if args.clip_unit > 1 else ""),
                    "clipped_sum_forms": {f: ps.form.count(f) for f in sorted(set(ps.form))},
                    "issue": "host calls" if args.no_graph else f"HIP graph, {args.streams} side streams",
                    "finalize": "noise + SGD-momentum update fused" if args.fused_update else "noise + divide by |B|",

@@ -27,7 +27,7 @@ def _pad4(v: int) -> int:
 
 class PrivatiseStep:
     def __init__(self, wl, device: str = "cuda:0", mode: str = "auto", streams: int = 1, noise: str = "once",
-                 batching: str = "variant", lanes: str = "balanced"):
+                 batching: str = "variant", lanes: str = "balanced", clip_unit: int = 1):
         B.load_library()
         self.wl = wl
         if batching not in ("variant", "all"):
@@ -47,12 +47,25 @@ class PrivatiseStep:
         self.device = torch.device(device)
         self.layers = list(wl.layers)
         self.n = wl.n
+        # Clipping units of several consecutive examples (the micro-batching of the GPU baseline, Abstract and
+        # Table 1): the path runs on the unit SUMS with every bound multiplied by the unit size, which gives
+        # (noise + sum of the clipped unit means) / (number of units); a unit is one row wherever an example is.
+        self.clip_unit = int(clip_unit)
+        if self.clip_unit < 1 or wl.n % self.clip_unit:
+            raise ValueError("the micro-step size must be a multiple of clip_unit")
+        if self.clip_unit > 1 and noise != "once":
+            raise ValueError("per-example noise is defined for units of one example")
+        self.rows = wl.n // self.clip_unit
         L = len(self.layers)
         self.descs = [B.make_desc(l, wl.n, wl.dtype) for l in self.layers]
         self.pw = [B.dp_weight_count(d) for d in self.descs]
         self.pb = [B.dp_bias_count(d) for d in self.descs]
         self.group_of_layer = list(wl.group_of_layer)
         self.group_clip, self.clip_total = B.dp_group_clip_bounds(wl.clip_c, wl.n_groups)
+        if self.clip_unit > 1:
+            self.group_clip = [c * self.clip_unit for c in self.group_clip]
+            self.clip_total *= self.clip_unit
+            mode = "materialise"                   # the unit sums are 1/unit of the per-example matrix: keep them
         self.n_groups = wl.n_groups
         self.form = [self._choose(l, mode) for l in self.layers]
 
@@ -91,16 +104,17 @@ class PrivatiseStep:
         # exists twice and micro-steps alternate between the copies.
         self.n_streams = max(1, int(streams))
         self.copies = 2 if self.n_streams > 1 else 1
-        self._g = [torch.zeros((self.n, self.p_mat), dtype=f32, device=dev) if self.p_mat else None
+        self._g = [torch.zeros((self.rows, self.p_mat), dtype=f32, device=dev) if self.p_mat else None
                    for _ in range(self.copies)]
-        self._group_sqnorm = [torch.zeros((self.n_groups, self.n), dtype=f32, device=dev) for _ in range(self.copies)]
+        self._group_sqnorm = [torch.zeros((self.n_groups, self.rows), dtype=f32, device=dev) for _ in range(self.copies)]
         self.group_of_layer_dev = torch.tensor(self.group_of_layer, dtype=torch.int32, device=dev)
         need = [max(16, B.dp_workspace_bytes(d, B.DP_WS_PER_EXAMPLE_GRAD),
-                    B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE) if form == "recompute" else 0)
+                    B.dp_workspace_bytes(d, B.DP_WS_RECOMPUTE) if form == "recompute" else 0,
+                    B.dp_unit_workspace_bytes(d, self.clip_unit) if self.clip_unit > 1 else 0)
                 for d, form in zip(self.descs, self.form)]
         # a workspace per layer (the layers of a phase are in flight together)
         self._ws = [[torch.empty(b, dtype=torch.uint8, device=dev) for b in need] for _ in range(self.copies)]
-        self._layer_sqnorm = [torch.zeros((L, self.n), dtype=f32, device=dev) for _ in range(self.copies)]
+        self._layer_sqnorm = [torch.zeros((L, self.rows), dtype=f32, device=dev) for _ in range(self.copies)]
         # Layers that run the same kernel variant go to the library in ONE batch call, which puts them into one
         # launch (at most 16 per launch): per phase a micro-step is a dozen launches, not a hundred.
         self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD | B.DP_VARIANT_SHARED),
@@ -279,7 +293,14 @@ class PrivatiseStep:
             if self._b_done[c] is not None:           # this copy's previous clipped sum has finished
                 for ev in self._b_done[c]:
                     st.wait_event(ev)
-        for gi, grp in enumerate(self._groups_a):
+        if self.clip_unit > 1:
+            # unit sums and their norms, layer by layer over the side streams
+            for li in range(L):
+                st = self.side[li % self.n_streams] if self.side else None
+                B.dp_unit_grad(self.descs[li], self.clip_unit, inputs[li][0], inputs[li][1], g_buf[:, self.off_w[li]:],
+                               g_buf[:, self.off_b[li]:] if self.pb[li] else None, self._layer_sqnorm[c][li], wss[li],
+                               g_stride=gs, stream=st)
+        for gi, grp in enumerate(self._groups_a if self.clip_unit == 1 else ()):
             st = self.side[grp["lane"]] if self.side else None
             bt = grp["batch"][c]
             xs = bt.ptrs([inputs[i][0].data_ptr() for i in grp["layers"]])
@@ -294,8 +315,9 @@ class PrivatiseStep:
         for st in self.side:
             main.wait_stream(st)
         # H2: every layer's partial sums -> per-layer norms in one launch, per-group norms in a second
-        B.dp_layer_norms_from_partials(self._partials[c], self._partial_counts, self._layer_sqnorm_ptrs[c], L, self.n)
-        B.dp_norms(self._layer_sqnorm[c], self.group_of_layer_dev, L, self.n, self.n_groups, gsq)
+        if self.clip_unit == 1:
+            B.dp_layer_norms_from_partials(self._partials[c], self._partial_counts, self._layer_sqnorm_ptrs[c], L, self.n)
+        B.dp_norms(self._layer_sqnorm[c], self.group_of_layer_dev, L, self.rows, self.n_groups, gsq)
         # ---- phase B
         for st in self.side_b:
             st.wait_stream(main)
@@ -304,11 +326,11 @@ class PrivatiseStep:
             st0 = sb[0] if sb else None
             if self.n_groups == 1:
                 # one clipping group: every materialised tensor shares the factors -> one pass
-                B.dp_clip_accumulate(g_buf, gsq[0], self.group_clip[0], self.n, self.p_mat,
+                B.dp_clip_accumulate(g_buf, gsq[0], self.group_clip[0], self.rows, self.p_mat,
                                      self.acc, g_stride=gs, stream=st0)
             else:
                 # several clipping groups: one launch over all materialised tensors, a segment per layer
-                B.dp_clip_accumulate_segments(g_buf, gsq, self.n_groups, self._segments, self.n, self.p_mat,
+                B.dp_clip_accumulate_segments(g_buf, gsq, self.n_groups, self._segments, self.rows, self.p_mat,
                                               self.acc, g_stride=gs, stream=st0)
         if self.noise == "per_example":
             for li in range(L):

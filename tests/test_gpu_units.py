@@ -144,3 +144,30 @@ def test_whole_step_with_units_matches_the_oracle(clip_mode, dtype):
         assert_close(host(out[offs[k][0]:offs[k][0] + l.pw]), ref["out_w"][k].reshape(-1), tol, f"layer {k} released gradient")
         if l.pb:
             assert_close(host(out[offs[k][1]:offs[k][1] + l.pb]), ref["out_b"][k], tol, f"layer {k} released bias gradient")
+
+
+def test_pipeline_with_units_matches_the_oracle_eager_and_graph():
+    """PrivatiseStep(clip_unit=4): side streams, two buffer copies, graph replay; against oracle.privatise_units."""
+    from workloads import make_inputs
+    unit = 4
+    layers = _net()
+    wl = Workload("small", layers, 8, 3, "bf16", "global", 0.05, 0.9, tuple("normal" for _ in layers), 0.05, 321)
+    steps = [make_inputs(wl, m) for m in range(wl.accum)]
+    ref = oracle.privatise_units(wl, steps, unit)
+    assert any((f < 1).any() for f in ref["f"])
+    dev_steps = [[(dev(x, wl.dtype), dev(dy, wl.dtype)) for x, dy in inputs] for inputs in steps]
+    for streams in (1, 4):
+        ps = dp.PrivatiseStep(wl, streams=streams, clip_unit=unit)
+        assert all(f == "materialise" for f in ps.form)
+        ps.run(dev_steps)
+        torch.cuda.synchronize()
+        for k, l in enumerate(layers):
+            assert_close(host(ps.out_w(k)), ref["out_w"][k].reshape(-1), BF16_TOL, f"streams {streams} layer {k}")
+            if l.pb:
+                assert_close(host(ps.out_b(k)), ref["out_b"][k], BF16_TOL, f"streams {streams} layer {k} bias")
+        eager = ps.out.clone()
+    ps.set_step(wl.step)
+    ps.capture(dev_steps)
+    ps.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(ps.out, eager)
