@@ -28,13 +28,15 @@ MFMA_PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, 
 HBM_PEAK = 8.0e12
 
 # HBM bytes per launch of the contraction variants from the two rocprofv3 --pmc runs summarised in
-# profiles/conv_contract_resnet50_hbm_traffic.txt: mean FETCH_SIZE and WRITE_SIZE per dispatch in KiB, each
-# scaled by what the same counter reads for clip_accumulate_kernel (a plain streaming kernel of known size in
-# the same runs: FETCH_SIZE reads half of its bytes, WRITE_SIZE all of them).
+# profiles/contraction_resnet50_hbm_traffic.txt: mean FETCH_SIZE and WRITE_SIZE per dispatch in KiB (a dispatch is one
+# grouped launch: all layers of the variant in a micro-step), each scaled by what the same counter reads for plain
+# streaming kernels of known size in the same runs (clip_accumulate_kernel and noise_finalize_flat_kernel, 16 bytes
+# per lane like the contraction's loads: FETCH_SIZE reads half of their bytes, WRITE_SIZE all of them).
 PMC_FETCH_SCALE, PMC_WRITE_SCALE = 2.0, 1.0
 PMC_KIB_PER_LAUNCH = {          # variant -> (FETCH_SIZE, WRITE_SIZE)
-    "conv_contract<bf16,64x64,per_example>": (23197.0, 9217.0),
-    "conv_contract<bf16,128x128,per_example>": (8535.0, 37812.0),
+    "conv_contract<bf16,128x128,per_example>": (204460.7, 292967.9),
+    "conv_contract<bf16,64x64,per_example>": (201189.5, 12813.6),
+    "conv_contract<bf16,128x128,weighted>": (138401.4, 41440.0),
 }
 
 
@@ -204,7 +206,7 @@ def main():
                         frac=byte_rate / HBM_PEAK if hbm_bound else flop_rate / peak,
                         traffic=measured_traffic(dom_name) if (args.workload == "resnet50" and args.mode == "auto" and args.n is None
                                                                and args.hw is None and args.accum is None) else None,
-                        traffic_unit="HBM bytes per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see profiles/)",
+                        traffic_unit="HBM bytes per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, see profiles/contraction_resnet50_hbm_traffic.txt)",
                         kernel=dom_name, launches=dom["launches"], avg_launch_us=dom["total_ms"] * 1e3 / dom["launches"],
                         algorithmic_bytes_per_launch=dom["bytes"] / dom["launches"],
                         algorithmic_flop_per_launch=dom["flops"] / dom["launches"],

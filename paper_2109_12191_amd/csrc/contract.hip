@@ -97,6 +97,12 @@ __device__ __forceinline__ void store_f32_uniform_base(unsigned long long base, 
 {
     asm volatile("global_store_dword %0, %1, %2" ::"v"(byte_off), "v"(v), "s"(base) : "memory");
 }
+// the same store with the non-temporal hint: per-example gradients are written once and read back much later by the
+// streaming accumulate, so they should not push the operands (re-read by the neighbouring tiles) out of L2
+__device__ __forceinline__ void store_f32_uniform_base_nt(unsigned long long base, unsigned byte_off, float v)
+{
+    asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(byte_off), "v"(v), "s"(base) : "memory");
+}
 __device__ __forceinline__ float load_f32_uniform_base(unsigned long long base, unsigned byte_off)
 {
     float v;
@@ -144,8 +150,8 @@ __device__ __forceinline__ float tile_epilogue(const f32x16 (&acc)[NACC], const 
                     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
-                            store_f32_uniform_base(corner + 4ull * ((unsigned)(tm * 32 + (r >> 2) * 8 + (r & 3)) * (unsigned)J + (unsigned)(tn * 32)),
-                                                   lane_off, acc[tm * TN + tn][r]);
+                            store_f32_uniform_base_nt(corner + 4ull * ((unsigned)(tm * 32 + (r >> 2) * 8 + (r & 3)) * (unsigned)J + (unsigned)(tn * 32)),
+                                                      lane_off, acc[tm * TN + tn][r]);
             }
         } else {
 #pragma unroll
