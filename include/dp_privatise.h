@@ -219,6 +219,13 @@ size_t dp_unit_workspace_bytes(const dp_layer_desc *desc /*[host]*/, int clip_un
 dp_status dp_unit_grad(const dp_layer_desc *desc /*[host]*/, int clip_unit, const void *x, const void *dy, float *g_w,
                        float *g_b, size_t g_stride, float *sqnorm, void *ws, size_t ws_bytes, dp_stream stream);
 
+/* dp_unit_grad for several layers in one call (clip_unit >= 2): layers that run the same kernel share one launch,
+ * and the per-layer reductions of all layers are one launch.  Arrays as in dp_per_example_grad_batch; g_w / g_b
+ * rows and sqnorm[l] entries are units (n / clip_unit of them); ws[l] at least dp_unit_workspace_bytes.       */
+dp_status dp_unit_grad_batch(const dp_layer_desc *descs, int clip_unit, const void *const *x, const void *const *dy,
+                             float *const *g_w, float *const *g_b, size_t g_stride, float *const *sqnorm,
+                             void *const *ws, const size_t *ws_bytes, int n_layers, dp_stream stream);
+
 /* group_sqnorm[g, i] = sum over the layers l of group g, in order, of sum_c partials[l][i * counts[l] + c].
  * partials [host] array of n_layers device pointers (4-byte aligned); counts, group_of_layer [host]
  * arrays of n_layers ints; group_sqnorm [device] [n_groups, n], overwritten.                       */

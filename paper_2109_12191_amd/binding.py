@@ -62,6 +62,7 @@ def load_library():
         "dp_norm_partial_count": (sz, [dpp, it]),
         "dp_unit_workspace_bytes": (sz, [dpp, it]),
         "dp_unit_grad": (it, [dpp, it, vp, vp, vp, vp, sz, vp, vp, sz, vp]),
+        "dp_unit_grad_batch": (it, [vp, it, vp, vp, vp, vp, sz, vp, vp, vp, it, vp]),
         "dp_per_example_grad_partials": (it, [dpp, vp, vp, vp, vp, sz, vp, sz, vp]),
         "dp_norms_from_partials": (it, [vp, vp, vp, it, it, it, vp, vp]),
         "dp_per_example_grad_batch": (it, [vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, it, vp]),
@@ -90,7 +91,7 @@ def load_library():
 
 EXPORTED = ("dp_group_clip_bounds", "dp_weight_count", "dp_bias_count", "dp_workspace_bytes", "dp_kernel_variant", "dp_per_example_grad", "dp_norms",
             "dp_static_scratch_bytes", "dp_per_example_grad_static",
-            "dp_unit_workspace_bytes", "dp_unit_grad",
+            "dp_unit_workspace_bytes", "dp_unit_grad", "dp_unit_grad_batch",
             "dp_norm_partial_count", "dp_per_example_grad_partials", "dp_norms_from_partials",
             "dp_per_example_grad_batch", "dp_layer_norms_from_partials", "dp_clip_accumulate_recompute_batch",
             "dp_clip_factors", "dp_clip_accumulate", "dp_clip_accumulate_segments", "dp_clip_accumulate_recompute", "dp_add_noise_finalize", "dp_add_noise_finalize_update", "dp_add_example_noise",
@@ -249,6 +250,16 @@ def dp_per_example_grad_batch(batch: "LayerBatch", x, dy, g_w, g_b, sqnorm, g_st
                                                     C.cast(batch.ws, C.c_void_p), C.cast(batch.ws_bytes, C.c_void_p),
                                                     C.cast(batch.partial_counts, C.c_void_p), batch.n_layers,
                                                     _stream(stream)))
+
+
+def dp_unit_grad_batch(batch: "LayerBatch", clip_unit: int, x, dy, g_w, g_b, sqnorm, g_stride: int = 0, stream=None):
+    """dp_unit_grad for the layers of a LayerBatch; x, dy, sqnorm: ctypes pointer arrays from batch.ptrs()."""
+    _check(load_library().dp_unit_grad_batch(C.cast(batch.descs, C.c_void_p), clip_unit, C.cast(x, C.c_void_p),
+                                             C.cast(dy, C.c_void_p),
+                                             None if g_w is None else C.cast(g_w, C.c_void_p),
+                                             None if g_b is None else C.cast(g_b, C.c_void_p), g_stride,
+                                             C.cast(sqnorm, C.c_void_p), C.cast(batch.ws, C.c_void_p),
+                                             C.cast(batch.ws_bytes, C.c_void_p), batch.n_layers, _stream(stream)))
 
 
 def dp_layer_norms_from_partials(partials, counts, sqnorm, n_layers: int, n: int, stream=None):

@@ -450,6 +450,71 @@ dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *cons
     return launch_layer_norms(parts.data(), counts.data(), sqnorm, n_layers, geo[0].n, s);
 }
 
+dp_status dp_unit_grad_batch(const dp_layer_desc *descs, int clip_unit, const void *const *x, const void *const *dy,
+                             float *const *g_w, float *const *g_b, size_t g_stride, float *const *sqnorm,
+                             void *const *ws, const size_t *ws_bytes, int n_layers, dp_stream stream)
+{
+    if (!descs || !x || !dy || !sqnorm || !ws || !ws_bytes)
+        return fail(DP_ERR_INVALID_ARG, "descs, x, dy, sqnorm, ws and ws_bytes must be non-NULL host arrays");
+    if (n_layers < 1) return fail(DP_ERR_INVALID_ARG, "n_layers = %d (need >= 1)", n_layers);
+    if (clip_unit < 2) return fail(DP_ERR_INVALID_ARG, "clip_unit = %d (need >= 2; units of one example: dp_per_example_grad_batch)", clip_unit);
+    std::vector<Geo> geo((size_t)n_layers);
+    for (int l = 0; l < n_layers; ++l) {             // everything is validated before anything is launched
+        Geo &g = geo[(size_t)l];
+        DP_TRY(unit_geo(&descs[l], clip_unit, g));
+        if (descs[l].n != descs[0].n) return fail(DP_ERR_INVALID_ARG, "layer %d: n = %d differs from layer 0's %d", l, descs[l].n, descs[0].n);
+        DP_TRY(check_ptr(x[l], "x[l]", true));
+        DP_TRY(check_ptr(dy[l], "dy[l]", true));
+        float *gw = g_w ? g_w[l] : nullptr, *gb = g_b ? g_b[l] : nullptr;
+        DP_TRY(check_ptr(gw, "g_w[l]", false));
+        DP_TRY(check_ptr(gb, "g_b[l]", false));
+        DP_TRY(check_ptr(sqnorm[l], "sqnorm[l]", true, 4));
+        if (gw && g.pb && !gb) return fail(DP_ERR_INVALID_ARG, "layer %d: g_w given but g_b is NULL for a layer with a bias", l);
+        if (!gw && gb) return fail(DP_ERR_INVALID_ARG, "layer %d: g_b given without g_w", l);
+        if (g_stride) {
+            if (g_stride % 4) return fail(DP_ERR_INVALID_ARG, "g_stride must be a multiple of 4");
+            if (gw && (g_stride < g.pw || g_stride < g.pb)) return fail(DP_ERR_INVALID_ARG, "layer %d: g_stride smaller than the tensor", l);
+        }
+        const size_t need = unit_ws_need(g, descs[l].kind, clip_unit);
+        if (need && (!ws[l] || ws_bytes[l] < need))
+            return fail(DP_ERR_WORKSPACE, "layer %d: workspace of %zu bytes needed (dp_unit_workspace_bytes), %zu given", l, need,
+                        ws[l] ? ws_bytes[l] : (size_t)0);
+        if (need && !aligned16(ws[l])) return fail(DP_ERR_INVALID_ARG, "layer %d: workspace is not 16-byte aligned", l);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    g_err[0] = 0;
+    const int units = descs[0].n / clip_unit;
+    LaunchQueue q;
+    q.stream = s;
+    q.crowd = batch_target(geo);
+    set_open_queue(&q);
+    std::vector<const float *> parts((size_t)n_layers);
+    std::vector<int32_t> counts((size_t)n_layers);
+    dp_status st = DP_OK;
+    for (int l = 0; l < n_layers && st == DP_OK; ++l) {
+        const Geo &g = geo[(size_t)l];
+        float *gw = g_w ? g_w[l] : nullptr, *gb = g_b ? g_b[l] : nullptr;
+        const int mode = gw ? MODE_MATERIALISE : MODE_NORM;
+        parts[(size_t)l] = static_cast<const float *>(ws[l]);
+        // sqnorm == nullptr: the partial sums stay in the workspace for the one reduction launch below
+        if (g.kind == DP_CONV2D) {
+            counts[(size_t)l] = (int32_t)conv_unit_norm_partial_count(g, clip_unit);     // the plan in force inside this batch
+            st = launch_conv_units(g, clip_unit, x[l], dy[l], gw, gb, g_stride, nullptr, ws[l], s);
+        } else if (g.kind == DP_DENSE) {
+            counts[(size_t)l] = (int32_t)dense_norm_partial_count(g, mode);
+            st = launch_dense(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
+        } else {
+            counts[(size_t)l] = (int32_t)gn_unit_norm_partial_count(g);
+            parts[(size_t)l] = gn_unit_partials(g, ws[l]);
+            st = launch_gn_units(g, clip_unit, x[l], dy[l], gw, gb, g_stride, nullptr, ws[l], s);
+        }
+    }
+    if (st == DP_OK) st = flush_queue(q);
+    set_open_queue(nullptr);
+    if (st != DP_OK) return st;
+    return launch_layer_norms(parts.data(), counts.data(), sqnorm, n_layers, units, s);
+}
+
 dp_status dp_layer_norms_from_partials(const float *const *partials, const int32_t *counts, float *const *sqnorm,
                                        int n_layers, int n, dp_stream stream)
 {

@@ -64,8 +64,8 @@ struct ConvArgs {
     int ex_per_split;                 // weighted mode
     int ex_per_wg;                    // per-example mode, ksplit == 1: consecutive examples per workgroup
     int force_slow;                   // stride other than 1 or 2: stage every chunk element by element
-    int unit_major;                   // weighted mode: every example range keeps its own result (clipping units): the
-                                      // slices always go to the workspace, ordered (range, tile); no clip factors
+    int unit_major;                   // weighted mode, > 0: clipping units, each made of unit_major example ranges; the
+                                      // ranges' blocks always go to the workspace, ordered (unit, tile, range in unit)
 };
 
 struct ColInfo {
@@ -740,7 +740,11 @@ __global__ void __launch_bounds__(THREADS, 2) conv_contract_kernel(const Grouped
     // ---- slices of one tile meet in the workspace; a second kernel (conv_fixup_kernel) adds
     // them in slice order and runs the epilogue.  Plain stores: the kernel boundary orders them.
     const int group = WEIGHTED ? tile : (unit * tiles + tile);     // ex_per_wg == 1 when K is sliced
-    const size_t slot = (WEIGHTED && a.unit_major) ? (size_t)split * tiles + tile : (size_t)group * a.ksplit + split;
+    size_t slot = (size_t)group * a.ksplit + split;
+    if (WEIGHTED && a.unit_major) {                       // (unit, tile, range within the unit)
+        const int u = split / a.unit_major;
+        slot = ((size_t)u * tiles + tile) * a.unit_major + (split - u * a.unit_major);
+    }
     float *mine = a.ws_part + slot * (NACC * 16 * THREADS);
 #pragma unroll
     for (int t = 0; t < NACC; ++t)
@@ -1080,7 +1084,11 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
     }
     // slices of one tile meet in the workspace (conv_fixup_kernel adds them in slice order)
     const int group = WEIGHTED ? tile : (unit * tiles + tile);
-    const size_t part = (WEIGHTED && a.unit_major) ? (size_t)split * tiles + tile : (size_t)group * ksplit + split;
+    size_t part = (size_t)group * ksplit + split;
+    if (WEIGHTED && a.unit_major) {                       // (unit, tile, range within the unit)
+        const int u = split / a.unit_major;
+        part = ((size_t)u * tiles + tile) * a.unit_major + (split - u * a.unit_major);
+    }
     float *mine = a.ws_part + part * (NACC * 16 * THREADS);
 #pragma unroll
     for (int t = 0; t < NACC; ++t)
@@ -1466,8 +1474,16 @@ static FullPlan unit_plan(const Geo &g, int unit)
 {
     FullPlan f = full_plan(g, MODE_WEIGHTED);
     const int tiles = f.tiles_m * f.tiles_n;
-    f.ex_per_split = unit;
-    f.ksplit = g.n / unit;
+    // a range is a whole unit, unless that leaves too few workgroups walking too long: then the largest divisor
+    // of the unit that gives about 256 of them (down to one example per range)
+    int e = unit;
+    while (e > 1 && (long long)tiles * (g.n / e) < 256 && (long long)e * f.chunks_per_ex > 32) {
+        int d = e - 1;
+        while (unit % d) --d;
+        e = d;
+    }
+    f.ex_per_split = e;
+    f.ksplit = g.n / e;
     f.groups = tiles;
     f.part_floats = (size_t)tiles * f.ksplit * f.nacc * 16 * THREADS;
     return f;
@@ -1479,6 +1495,14 @@ size_t conv_unit_ws_bytes(const Geo &g, int unit)
     const FullPlan f = unit_plan(g, unit);
     const size_t units = (size_t)(g.n / unit), tiles = (size_t)f.tiles_m * f.tiles_n;
     return align16(units * tiles * f.nacc * FIX_PARTS * sizeof(float)) + f.part_floats * sizeof(float);
+}
+
+// partial squared norms per unit left at the start of the workspace by a call with clipping units
+size_t conv_unit_norm_partial_count(const Geo &g, int unit)
+{
+    if (conv3x3_applicable(g, MODE_WEIGHTED)) return conv3x3_unit_norm_partial_count(g);
+    const FullPlan f = unit_plan(g, unit);
+    return (size_t)f.tiles_m * f.tiles_n * f.nacc * FIX_PARTS;
 }
 
 // Sums of the per-example gradients over clipping units of `unit` consecutive examples, and their squared norms:
@@ -1533,7 +1557,7 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
     const FullPlan f = unit ? unit_plan(g, unit) : full_plan(g, mode);
     const bool weighted = mode == MODE_WEIGHTED || unit > 0;
     ConvArgs a;
-    a.unit_major = unit ? 1 : 0;
+    a.unit_major = unit ? unit / f.ex_per_split : 0;
     a.x = x; a.dy = dy;
     a.n = g.n; a.cin = g.cin; a.cout = g.cout; a.h = f.h; a.w = f.w; a.kh = g.kh; a.kw = g.kw;
     a.stride = g.stride; a.pad = g.pad; a.oh = f.oh; a.ow = f.ow;
@@ -1593,7 +1617,7 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
     if (unit) {
         // every unit's slice is finished like an unsliced example: stored (if wanted) and squared
         ConvArgs u = a;
-        u.n = g.n / unit; u.ksplit = 1;
+        u.n = g.n / unit; u.ksplit = a.unit_major;
         const unsigned fix_blocks = (unsigned)((size_t)u.n * unit_partials);
         const void *fix = (f.shape == T64) ? fixup_of<2, 2, 1, 1>(false, bias) : fixup_of<2, 2, 2, 2>(false, bias);
         st = submit_kernel<ConvArgs>(TIER_POST, fix, u, fix_blocks, THREADS, 0, s, "conv_fixup");

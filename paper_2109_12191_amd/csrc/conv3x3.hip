@@ -735,6 +735,11 @@ size_t conv3x3_unit_ws_bytes(const Geo &g, int unit)
     return c3_align16(units * tiles * 9 * C3_FIX_PARTS * sizeof(float)) + units * tiles * 9 * 16 * C3_THREADS * sizeof(float);
 }
 
+size_t conv3x3_unit_norm_partial_count(const Geo &g)
+{
+    return (size_t)((g.cout + 63) / 64) * ((g.cin + 63) / 64) * 9 * C3_FIX_PARTS;
+}
+
 dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, float *out_w, size_t out_stride,
                          float *sqnorm, const float *group_sqnorm, float clip_c, void *ws, hipStream_t s, int unit)
 {

@@ -52,6 +52,10 @@ size_t conv3x3_unit_ws_bytes(const Geo &g, int unit);
 size_t conv_unit_ws_bytes(const Geo &g, int unit);
 dp_status launch_conv_units(const Geo &g, int unit, const void *x, const void *dy, float *out_w, float *out_b,
                             size_t out_stride, float *sqnorm, void *ws, hipStream_t s);
+size_t conv_unit_norm_partial_count(const Geo &g, int unit);
+size_t conv3x3_unit_norm_partial_count(const Geo &g);
+const float *gn_unit_partials(const Geo &g, const void *ws);
+size_t gn_unit_norm_partial_count(const Geo &g);
 size_t gn_unit_ws_bytes(const Geo &g, int unit);
 dp_status launch_gn_units(const Geo &g, int unit, const void *x, const void *dy, float *out_w, float *out_b,
                           size_t out_stride, float *sqnorm, void *ws, hipStream_t s);

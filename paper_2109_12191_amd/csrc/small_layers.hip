@@ -432,6 +432,9 @@ size_t gn_unit_ws_bytes(const Geo &g, int unit)
     return gn_unit_head(g) + (size_t)(g.n / unit) * ((g.cin + 255) / 256) * sizeof(float);
 }
 
+const float *gn_unit_partials(const Geo &g, const void *ws) { return reinterpret_cast<const float *>(static_cast<const char *>(ws) + gn_unit_head(g)); }
+size_t gn_unit_norm_partial_count(const Geo &g) { return (size_t)((g.cin + 255) / 256); }
+
 dp_status launch_gn_units(const Geo &g, int unit, const void *x, const void *dy, float *out_w, float *out_b,
                           size_t out_stride, float *sqnorm, void *ws, hipStream_t s)
 {

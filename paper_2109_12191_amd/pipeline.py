@@ -126,6 +126,7 @@ class PrivatiseStep:
                                    for c in range(self.copies)]
         self._groups_a = self._make_groups(range(L), 0)
         self._groups_b = self._make_groups([i for i in range(L) if self.form[i] == "recompute"], 1)
+        self._groups_u = self._make_groups(range(L), 2) if self.clip_unit > 1 else []
         # side streams: `side` for the per-example phase, `side_b` for the clipped-sum phase
         self.side = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
         self.side_b = [torch.cuda.Stream(device=dev) for _ in range(max(2, self.n_streams // 2))] if self.n_streams > 1 else []
@@ -160,7 +161,7 @@ class PrivatiseStep:
         constant pointer arrays)."""
         by_name = {}
         for li in layer_ids:
-            key = self.variant[li][use] + ("|mat" if (use == 0 and self.form[li] == "materialise") else "")
+            key = self.variant[li][1 if use == 2 else use] + ("|mat" if (use == 0 and self.form[li] == "materialise") else "")
             if self.batching == "all":
                 key = "all layers"
             by_name.setdefault(key, []).append(li)
@@ -175,7 +176,10 @@ class PrivatiseStep:
                 g = dict(layers=part, name=name, conv=all(self.layers[i].kind == "conv" for i in part))
                 g["batch"] = [B.LayerBatch([self.descs[i] for i in part], [self._ws[c][i].data_ptr() for i in part],
                                            [self._ws[c][i].numel() for i in part]) for c in range(self.copies)]
-                if use == 0:
+                if use == 2:
+                    g["usq"] = [g["batch"][c].ptrs([self._layer_sqnorm[c][i].data_ptr() for i in part])
+                                for c in range(self.copies)]
+                if use != 1:
                     g["counted"] = False
                     mat = [self.form[i] == "materialise" for i in part]
                     g["gw"] = [g["batch"][c].ptrs([self._g[c][:, self.off_w[i]:].data_ptr() if m else None
@@ -294,12 +298,15 @@ class PrivatiseStep:
                 for ev in self._b_done[c]:
                     st.wait_event(ev)
         if self.clip_unit > 1:
-            # unit sums and their norms, layer by layer over the side streams
-            for li in range(L):
-                st = self.side[li % self.n_streams] if self.side else None
-                B.dp_unit_grad(self.descs[li], self.clip_unit, inputs[li][0], inputs[li][1], g_buf[:, self.off_w[li]:],
-                               g_buf[:, self.off_b[li]:] if self.pb[li] else None, self._layer_sqnorm[c][li], wss[li],
-                               g_stride=gs, stream=st)
+            # unit sums and their norms: one batch call per kernel variant of the clip-weighted form (the kernels
+            # that run), dealt to the side streams
+            for grp in self._groups_u:
+                st = self.side[grp["lane"]] if self.side else None
+                bt = grp["batch"][c]
+                xs = bt.ptrs([inputs[i][0].data_ptr() for i in grp["layers"]])
+                dys = bt.ptrs([inputs[i][1].data_ptr() for i in grp["layers"]])
+                B.dp_unit_grad_batch(bt, self.clip_unit, xs, dys, grp["gw"][c], grp["gb"][c], grp["usq"][c], g_stride=gs,
+                                     stream=st)
         for gi, grp in enumerate(self._groups_a if self.clip_unit == 1 else ()):
             st = self.side[grp["lane"]] if self.side else None
             bt = grp["batch"][c]

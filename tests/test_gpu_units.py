@@ -70,6 +70,49 @@ def test_unit_sums_and_norms_match_the_oracle(name, layer, dtype, unit, units, m
                 assert_close(host(gb[u, :layer.pb]) / unit, mean_b[u], tol, f"{name} unit {u} db")
 
 
+@pytest.mark.parametrize("unit,units", [(2, 3), (4, 1)])
+def test_unit_batch_call_matches_the_oracle_and_the_single_layer_calls(unit, units):
+    """dp_unit_grad_batch over all bf16 geometries of UNIT_CASES at once (layers of one kernel share a launch)."""
+    cases = [c for c in UNIT_CASES if c[2] == "bf16"]
+    n = unit * units
+    layers = [c[1] for c in cases]
+    ins = [_inputs(l, n, 5200 + k, "bf16") for k, l in enumerate(layers)]
+    descs = [dp.make_desc(l, n, "bf16") for l in layers]
+    xs = [dev(x, "bf16") for x, _ in ins]
+    dys = [dev(dy, "bf16") for _, dy in ins]
+    wss = [torch.empty(max(16, dp.dp_unit_workspace_bytes(d, unit)), dtype=torch.uint8, device="cuda:0") for d in descs]
+    sq = torch.full((len(layers), units), -1.0, device="cuda:0")
+    gws = [torch.full((units, l.pw), 7.0, device="cuda:0") for l in layers]
+    gbs = [torch.full((units, max(l.pb, 1)), 7.0, device="cuda:0") for l in layers]
+    batch = dp.LayerBatch(descs, [w.data_ptr() for w in wss], [w.numel() for w in wss])
+    for rep in range(2):                                   # twice: same bits on every call
+        dp.dp_unit_grad_batch(batch, unit, batch.ptrs([t.data_ptr() for t in xs]), batch.ptrs([t.data_ptr() for t in dys]),
+                              batch.ptrs([t.data_ptr() for t in gws]),
+                              batch.ptrs([t.data_ptr() if l.pb else None for t, l in zip(gbs, layers)]),
+                              batch.ptrs([sq[k].data_ptr() for k in range(len(layers))]))
+        torch.cuda.synchronize()
+        if rep == 0:
+            first = (sq.clone(), [g.clone() for g in gws])
+        else:
+            assert torch.equal(sq, first[0]) and all(torch.equal(a, b) for a, b in zip(gws, first[1]))
+    for k, l in enumerate(layers):
+        x, dy = ins[k]
+        mean_w, mean_b = oracle.unit_mean_grad(l, x, dy, unit)
+        want_n2 = np.array([oracle.sqnorm(mean_w[u]) + (oracle.sqnorm(mean_b[u]) if l.pb else 0.0) for u in range(units)])
+        assert np.allclose(host(sq[k]) / unit ** 2, want_n2, rtol=BF16_TOL, atol=0), (cases[k][0], host(sq[k]) / unit ** 2, want_n2)
+        for u in range(units):
+            assert_close(host(gws[k][u]) / unit, mean_w[u], BF16_TOL, f"{cases[k][0]} unit {u} dW")
+            if l.pb:
+                assert_close(host(gbs[k][u, :l.pb]) / unit, mean_b[u], BF16_TOL, f"{cases[k][0]} unit {u} db")
+        one = torch.zeros((units, l.pw), device="cuda:0")
+        oneb = torch.zeros((units, max(l.pb, 1)), device="cuda:0")
+        sq1 = torch.zeros(units, device="cuda:0")
+        dp.dp_unit_grad(descs[k], unit, xs[k], dys[k], one, oneb if l.pb else None, sq1, wss[k])
+        torch.cuda.synchronize()
+        assert_close(host(gws[k]), host(one), 2e-5, f"{cases[k][0]} against the single-layer call")
+        assert np.allclose(host(sq[k]), host(sq1), rtol=3e-5, atol=0)
+
+
 def test_unit_call_rejects_bad_arguments():
     l = conv(64, 64, 1, 1, 12)
     d = dp.make_desc(l, 6, "bf16")
