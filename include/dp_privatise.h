@@ -54,9 +54,14 @@ typedef enum {
 
 typedef enum { DP_DENSE = 0, DP_CONV2D = 1, DP_GN_AFFINE = 2 } dp_kind;
 typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
-typedef enum { DP_NCHW = 0, DP_NHWC = 1 } dp_layout;   /* DP_NHWC: DP_ERR_UNSUPPORTED in this build */
+typedef enum { DP_NCHW = 0, DP_NHWC = 1 } dp_layout;   /* activations channels-first or channels-last */
 
 /* One parameterised layer and the micro-batch it is evaluated on.
+ * Layout DP_NCHW as written below; DP_NHWC: conv2d / gn_affine activations and output gradients are
+ * x [n, h, w, cin], dy [n, oh, ow, cout] (parameter gradients keep their [cout, cin, kh, kw] order; a dense
+ * layer is the same in both).  Channels-last inputs are transposed into the end of the workspace by a
+ * pre-pass and the kernels read the copy: dp_workspace_bytes grows by the size of both tensors, the
+ * results are bit for bit those of the channels-first call.
  *   dense     : x [n, h, cin], dy [n, h, cout]; h = tokens per example, w = 1
  *   conv2d    : x [n, cin, h, w], dy [n, cout, oh, ow], oh = (h + 2 pad - kh)/stride + 1;
  *               cross-correlation, zero padding, dilation 1, groups 1

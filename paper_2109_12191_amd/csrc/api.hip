@@ -99,13 +99,13 @@ static dp_status make_geo(const dp_layer_desc *d, Geo &g)
         return fail(DP_ERR_INVALID_ARG, "unknown layer kind %d", d->kind);
     if (d->in_dtype != DP_F32 && d->in_dtype != DP_BF16)
         return fail(DP_ERR_INVALID_ARG, "unknown input dtype %d", d->in_dtype);
-    if (d->layout == DP_NHWC) return fail(DP_ERR_UNSUPPORTED, "NHWC activations are not supported by this build");
-    if (d->layout != DP_NCHW) return fail(DP_ERR_INVALID_ARG, "unknown layout %d", d->layout);
+    if (d->layout != DP_NCHW && d->layout != DP_NHWC) return fail(DP_ERR_INVALID_ARG, "unknown layout %d", d->layout);
     if (d->n < 1) return fail(DP_ERR_INVALID_ARG, "n = %d examples (need >= 1)", d->n);
     if (d->cin < 1 || d->cout < 1 || d->h < 1 || d->w < 1)
         return fail(DP_ERR_INVALID_ARG, "non-positive dimension (cin %d cout %d h %d w %d)", d->cin, d->cout, d->h, d->w);
     memset(&g, 0, sizeof(g));
     g.kind = d->kind; g.bf16 = d->in_dtype == DP_BF16; g.n = d->n;
+    g.nhwc = (d->layout == DP_NHWC && d->kind != DP_DENSE) ? 1 : 0;       // a dense layer's [n, tokens, features] is the same in both
     g.cin = d->cin; g.cout = d->cout; g.h = d->h; g.w = d->w;
     g.kh = g.kw = 1; g.stride = 1; g.pad = 0; g.oh = d->h; g.ow = d->w;
     g.has_bias = d->has_bias ? 1 : 0;
@@ -147,13 +147,51 @@ static dp_status make_geo(const dp_layer_desc *d, Geo &g)
     return DP_OK;
 }
 
-static size_t ws_bytes_for(const Geo &g, int mode)
+// Channels-last inputs are transposed into the end of the workspace before anything else reads them.
+static size_t align16_api(size_t b) { return (b + 15) & ~(size_t)15; }
+static size_t layout_copy_bytes(const Geo &g)
+{
+    if (!g.nhwc) return 0;
+    const size_t es = g.bf16 ? 2 : 4;
+    return align16_api((size_t)g.n * g.x_elems * es) + align16_api((size_t)g.n * g.dy_elems * es);
+}
+
+static size_t ws_kernels_for(const Geo &g, int mode)
 {
     size_t b;
     if (g.kind == DP_CONV2D) b = conv_ws_bytes(g, mode);
     else if (g.kind == DP_DENSE) b = dense_ws_bytes(g, mode);
     else b = gn_ws_bytes(g, mode);
-    return (b + 15) & ~(size_t)15;
+    return align16_api(b);
+}
+
+static size_t ws_bytes_for(const Geo &g, int mode) { return ws_kernels_for(g, mode) + layout_copy_bytes(g); }
+
+// x, dy as the kernels read them: the caller's tensors, or their channels-first copies behind the first
+// `kernels_bytes` bytes of the workspace
+static dp_status channels_first_inputs(const Geo &g, size_t kernels_bytes, const void *&x, const void *&dy, void *ws, hipStream_t s)
+{
+    if (!g.nhwc) return DP_OK;
+    const int es = g.bf16 ? 2 : 4;
+    char *xt = static_cast<char *>(ws) + kernels_bytes;
+    char *dyt = xt + align16_api((size_t)g.n * g.x_elems * es);
+    dp_status st = launch_to_channels_first(x, xt, g.n, g.h * g.w, g.cin, es, s);
+    if (st != DP_OK) return st;
+    st = launch_to_channels_first(dy, dyt, g.n, g.oh * g.ow, g.cout, es, s);
+    x = xt;
+    dy = dyt;
+    return st;
+}
+
+// One layer's kernels for a per-example call (mode NORM / MATERIALISE) or the recomputing clipped sum (WEIGHTED)
+static dp_status launch_layer(const Geo &g, int mode, const void *x, const void *dy, float *out_w, float *out_b,
+                              size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
+                              hipStream_t s)
+{
+    DP_TRY_ST(channels_first_inputs(g, ws_kernels_for(g, mode == MODE_WEIGHTED ? MODE_WEIGHTED : MODE_NORM), x, dy, ws, s));
+    if (g.kind == DP_CONV2D) return launch_conv(g, mode, x, dy, out_w, out_b, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
+    if (g.kind == DP_DENSE) return launch_dense(g, mode, x, dy, out_w, out_b, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
+    return launch_gn(g, mode, x, dy, out_w, out_b, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);
 }
 
 // Tensors that are read or written with 16-byte accesses need 16-byte alignment; the small
@@ -272,9 +310,7 @@ dp_status dp_per_example_grad(const dp_layer_desc *desc, const void *x, const vo
     const int mode = g_w ? MODE_MATERIALISE : MODE_NORM;
     hipStream_t s = static_cast<hipStream_t>(stream);
     g_err[0] = 0;
-    if (g.kind == DP_CONV2D) return launch_conv(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
-    if (g.kind == DP_DENSE) return launch_dense(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
-    return launch_gn(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
+    return launch_layer(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
 }
 
 static size_t norm_partial_count_for(const Geo &g, int mode)
@@ -311,9 +347,7 @@ dp_status dp_per_example_grad_partials(const dp_layer_desc *desc, const void *x,
     hipStream_t s = static_cast<hipStream_t>(stream);
     g_err[0] = 0;
     // sqnorm == nullptr: the kernels leave their partial sums at the start of the workspace
-    if (g.kind == DP_CONV2D) return launch_conv(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
-    if (g.kind == DP_DENSE) return launch_dense(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
-    return launch_gn(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
+    return launch_layer(g, mode, x, dy, g_w, g_b, g_stride, nullptr, nullptr, 0.0f, ws, s);
 }
 
 // ---- clipping units of several examples ----------------------------------------------------
@@ -335,11 +369,22 @@ static dp_status unit_geo(const dp_layer_desc *desc, int clip_unit, Geo &g)
     return DP_OK;
 }
 
-static size_t unit_ws_need(const Geo &g, int kind, int clip_unit)
+static size_t unit_ws_kernels(const Geo &g, int kind, int clip_unit)
 {
-    if (kind == DP_DENSE) return dense_ws_bytes(g, MODE_NORM);          // g is already the reshaped layer
-    if (kind == DP_CONV2D) return conv_unit_ws_bytes(g, clip_unit);
-    return gn_unit_ws_bytes(g, clip_unit);
+    if (kind == DP_DENSE) return align16_api(dense_ws_bytes(g, MODE_NORM));          // g is already the reshaped layer
+    if (kind == DP_CONV2D) return align16_api(conv_unit_ws_bytes(g, clip_unit));
+    return align16_api(gn_unit_ws_bytes(g, clip_unit));
+}
+static size_t unit_ws_need(const Geo &g, int kind, int clip_unit) { return unit_ws_kernels(g, kind, clip_unit) + layout_copy_bytes(g); }
+
+static dp_status launch_layer_units(const Geo &g, int clip_unit, const void *x, const void *dy, float *g_w, float *g_b,
+                                    size_t g_stride, float *sqnorm, void *ws, hipStream_t s)
+{
+    DP_TRY_ST(channels_first_inputs(g, unit_ws_kernels(g, g.kind, clip_unit), x, dy, ws, s));
+    if (g.kind == DP_DENSE)
+        return launch_dense(g, g_w ? MODE_MATERIALISE : MODE_NORM, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
+    if (g.kind == DP_CONV2D) return launch_conv_units(g, clip_unit, x, dy, g_w, g_b, g_stride, sqnorm, ws, s);
+    return launch_gn_units(g, clip_unit, x, dy, g_w, g_b, g_stride, sqnorm, ws, s);
 }
 
 size_t dp_unit_workspace_bytes(const dp_layer_desc *desc, int clip_unit)
@@ -373,10 +418,7 @@ dp_status dp_unit_grad(const dp_layer_desc *desc, int clip_unit, const void *x, 
     if (need && !aligned16(ws)) return fail(DP_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(stream);
     g_err[0] = 0;
-    const int mode = g_w ? MODE_MATERIALISE : MODE_NORM;
-    if (g.kind == DP_DENSE) return launch_dense(g, mode, x, dy, g_w, g_b, g_stride, sqnorm, nullptr, 0.0f, ws, s);
-    if (g.kind == DP_CONV2D) return launch_conv_units(g, clip_unit, x, dy, g_w, g_b, g_stride, sqnorm, ws, s);
-    return launch_gn_units(g, clip_unit, x, dy, g_w, g_b, g_stride, sqnorm, ws, s);
+    return launch_layer_units(g, clip_unit, x, dy, g_w, g_b, g_stride, sqnorm, ws, s);
 }
 
 // Work per workgroup a batch call plans for, in units of one 128x128x64 chunk: the convolutions' multiply-adds
@@ -435,9 +477,7 @@ dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *cons
         float *gw = g_w ? g_w[l] : nullptr, *gb = g_b ? g_b[l] : nullptr;
         const int mode = gw ? MODE_MATERIALISE : MODE_NORM;
         // sqnorm == nullptr: the kernels leave their partial sums at the start of the workspace
-        if (g.kind == DP_CONV2D) st = launch_conv(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
-        else if (g.kind == DP_DENSE) st = launch_dense(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
-        else st = launch_gn(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
+        st = launch_layer(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
         parts[(size_t)l] = static_cast<const float *>(ws[l]);
         counts[(size_t)l] = (int32_t)norm_partial_count_for(g, mode);       // the plan in force inside this batch
     }
@@ -499,14 +539,14 @@ dp_status dp_unit_grad_batch(const dp_layer_desc *descs, int clip_unit, const vo
         // sqnorm == nullptr: the partial sums stay in the workspace for the one reduction launch below
         if (g.kind == DP_CONV2D) {
             counts[(size_t)l] = (int32_t)conv_unit_norm_partial_count(g, clip_unit);     // the plan in force inside this batch
-            st = launch_conv_units(g, clip_unit, x[l], dy[l], gw, gb, g_stride, nullptr, ws[l], s);
+            st = launch_layer_units(g, clip_unit, x[l], dy[l], gw, gb, g_stride, nullptr, ws[l], s);
         } else if (g.kind == DP_DENSE) {
             counts[(size_t)l] = (int32_t)dense_norm_partial_count(g, mode);
-            st = launch_dense(g, mode, x[l], dy[l], gw, gb, g_stride, nullptr, nullptr, 0.0f, ws[l], s);
+            st = launch_layer_units(g, clip_unit, x[l], dy[l], gw, gb, g_stride, nullptr, ws[l], s);
         } else {
             counts[(size_t)l] = (int32_t)gn_unit_norm_partial_count(g);
             parts[(size_t)l] = gn_unit_partials(g, ws[l]);
-            st = launch_gn_units(g, clip_unit, x[l], dy[l], gw, gb, g_stride, nullptr, ws[l], s);
+            st = launch_layer_units(g, clip_unit, x[l], dy[l], gw, gb, g_stride, nullptr, ws[l], s);
         }
     }
     if (st == DP_OK) st = flush_queue(q);
@@ -564,9 +604,7 @@ dp_status dp_clip_accumulate_recompute_batch(const dp_layer_desc *descs, const v
     for (int l = 0; l < n_layers && st == DP_OK; ++l) {
         const Geo &g = geo[(size_t)l];
         float *ab = acc_b ? acc_b[l] : nullptr;
-        if (g.kind == DP_CONV2D) st = launch_conv(g, MODE_WEIGHTED, x[l], dy[l], acc_w[l], ab, 0, nullptr, sqnorm[l], clip_c[l], ws[l], s);
-        else if (g.kind == DP_DENSE) st = launch_dense(g, MODE_WEIGHTED, x[l], dy[l], acc_w[l], ab, 0, nullptr, sqnorm[l], clip_c[l], ws[l], s);
-        else st = launch_gn(g, MODE_WEIGHTED, x[l], dy[l], acc_w[l], ab, 0, nullptr, sqnorm[l], clip_c[l], ws[l], s);
+        st = launch_layer(g, MODE_WEIGHTED, x[l], dy[l], acc_w[l], ab, 0, nullptr, sqnorm[l], clip_c[l], ws[l], s);
     }
     if (st == DP_OK) st = flush_queue(q);
     set_open_queue(nullptr);
@@ -674,9 +712,7 @@ dp_status dp_clip_accumulate_recompute(const dp_layer_desc *desc, const void *x,
     DP_TRY(check_ws(g, MODE_WEIGHTED, ws, ws_bytes));
     hipStream_t s = static_cast<hipStream_t>(stream);
     g_err[0] = 0;
-    if (g.kind == DP_CONV2D) return launch_conv(g, MODE_WEIGHTED, x, dy, acc_w, acc_b, 0, nullptr, sqnorm, clip_c, ws, s);
-    if (g.kind == DP_DENSE) return launch_dense(g, MODE_WEIGHTED, x, dy, acc_w, acc_b, 0, nullptr, sqnorm, clip_c, ws, s);
-    return launch_gn(g, MODE_WEIGHTED, x, dy, acc_w, acc_b, 0, nullptr, sqnorm, clip_c, ws, s);
+    return launch_layer(g, MODE_WEIGHTED, x, dy, acc_w, acc_b, 0, nullptr, sqnorm, clip_c, ws, s);
 }
 
 dp_status dp_add_noise_finalize(const float *acc, float *out, size_t p, float sigma, float clip_total,

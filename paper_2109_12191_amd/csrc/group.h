@@ -12,9 +12,9 @@
 // MFMAs and epilogues of different workgroups overlap, and a one-example micro-step is a handful of
 // launches instead of a hundred.
 //
-// On the host, launchers hand their kernels to submit_kernel() with a tier: operand pre-passes
-// (TIER_PRE), the contraction itself (TIER_MAIN, also submit_main()), the sums over K slices
-// (TIER_POST).  With no queue open a kernel is launched at once (a group of one); inside a batch call
+// On the host, launchers hand their kernels to submit_kernel() with a tier: layout changes of the
+// inputs (TIER_LAYOUT), operand pre-passes (TIER_PRE), the contraction itself (TIER_MAIN, also
+// submit_main()), the sums over K slices (TIER_POST).  With no queue open a kernel is launched at once (a group of one); inside a batch call
 // (LaunchQueue open on this thread) it is held back until flush(), which launches tier after tier,
 // the held launches of a tier grouped by kernel, and then runs the deferred follow-up calls
 // (partial-norm reductions) in the order they were registered.
@@ -53,7 +53,7 @@ __device__ __forceinline__ int group_pick(const Grouped<Args> &g, unsigned &bid)
 }
 #endif
 
-enum { TIER_PRE = 0, TIER_MAIN = 1, TIER_POST = 2, TIER_COUNT = 3 };
+enum { TIER_LAYOUT = 0, TIER_PRE = 1, TIER_MAIN = 2, TIER_POST = 3, TIER_COUNT = 4 };
 
 struct LaunchQueue {
     struct Item {

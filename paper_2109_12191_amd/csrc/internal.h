@@ -24,6 +24,7 @@ struct Geo {
     int cin, cout, h, w, kh, kw, stride, pad, oh, ow;
     int has_bias, gn_groups;
     float gn_eps;
+    int nhwc;               // conv / GroupNorm inputs arrive channels-last; the kernels read a transposed copy
     size_t pw, pb;          // weight / bias parameter counts
     size_t x_elems, dy_elems;   // per example
 };
@@ -76,6 +77,9 @@ size_t conv_norm_partial_count(const Geo &g, int mode);
 size_t conv3x3_norm_partial_count(const Geo &g);
 size_t dense_norm_partial_count(const Geo &g, int mode);
 size_t gn_norm_partial_count(const Geo &g);
+
+// [n][positions][channels] -> [n][channels][positions], elements of 2 or 4 bytes (pack.hip): channels-last inputs
+dp_status launch_to_channels_first(const void *in, void *out, int n, int positions, int channels, int elem_bytes, hipStream_t s);
 
 // compact copy of the rows / columns a strided 1x1 convolution reads: out[n*cin][OH*OW] (pack.hip)
 dp_status launch_subsample(const Geo &g, const void *x, void *out, hipStream_t s);

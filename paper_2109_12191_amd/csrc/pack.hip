@@ -131,6 +131,56 @@ __global__ void __launch_bounds__(256) subsample_kernel(const Grouped<SubArgs> g
 
 }  // namespace
 
+namespace {
+
+// Channels-last inputs: [n][positions][channels] -> [n][channels][positions], 32 x 32 tiles through LDS (both the
+// reads and the writes are runs of 32 consecutive elements).  One workgroup of 256 threads per tile.
+struct TrArgs {
+    const void *in;
+    void *out;
+    int positions, channels, tiles_p, tiles_c;
+};
+
+template <typename T>
+__global__ void __launch_bounds__(256) channels_first_kernel(const Grouped<TrArgs> layers)
+{
+    __shared__ T tile[32][33];
+    unsigned bid;
+    const TrArgs &a = layers.a[group_pick(layers, bid)];
+    const int per_ex = a.tiles_p * a.tiles_c;
+    const int i = (int)(bid / (unsigned)per_ex), t = (int)(bid - (unsigned)i * (unsigned)per_ex);
+    const int tc = t / a.tiles_p, tp = t - tc * a.tiles_p;
+    const size_t ex = (size_t)i * a.positions * a.channels;
+    const T *in = static_cast<const T *>(a.in) + ex;
+    T *out = static_cast<T *>(a.out) + ex;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int p = tp * 32 + r, c = tc * 32 + tx;
+        if (p < a.positions && c < a.channels) tile[r][tx] = in[(size_t)p * a.channels + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int c = tc * 32 + r, p = tp * 32 + tx;
+        if (p < a.positions && c < a.channels) out[(size_t)c * a.positions + p] = tile[tx][r];
+    }
+}
+
+}  // namespace
+
+dp_status launch_to_channels_first(const void *in, void *out, int n, int positions, int channels, int elem_bytes, hipStream_t s)
+{
+    TrArgs a;
+    a.in = in; a.out = out; a.positions = positions; a.channels = channels;
+    a.tiles_p = (positions + 31) / 32; a.tiles_c = (channels + 31) / 32;
+    const long long blocks = (long long)n * a.tiles_p * a.tiles_c;
+    if (blocks > 0x7FFFFFFFll) return fail(DP_ERR_UNSUPPORTED, "channels-last input too large");
+    const void *fn = elem_bytes == 2 ? reinterpret_cast<const void *>(&channels_first_kernel<uint16_t>)
+                                     : reinterpret_cast<const void *>(&channels_first_kernel<uint32_t>);
+    return submit_kernel<TrArgs>(TIER_LAYOUT, fn, a, (unsigned)blocks, 256, 0, s, "channels_first");
+}
+
 dp_status launch_subsample(const Geo &g, const void *x, void *out, hipStream_t s)
 {
     const long long rows = (long long)g.n * g.cin;

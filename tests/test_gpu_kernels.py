@@ -560,6 +560,57 @@ def test_flat_finalize_gives_the_bits_of_one_call_per_tensor(with_update):
             assert_close(host(th2[b: b + sz]), th0[b: b + sz].astype(np.float64) - 0.05 * g[b: b + sz], F32_TOL, "theta")
 
 
+NHWC_CASES = [
+    ("1x1 aligned rows bf16", conv(64, 160, 1, 1, 12), "bf16"),
+    ("3x3 raw rows bf16", conv(64, 64, 3, 1, 14), "bf16"),
+    ("3x3 stride 2 bias fp32", conv(12, 20, 3, 2, 11, bias=True), "f32"),
+    ("7x7 stem bf16", conv(3, 32, 7, 2, 30), "bf16"),
+    ("groupnorm fp32", gn_affine(32, 10, 8), "f32"),
+    ("dense bf16 (no channel axis to move)", dense(100, 36), "bf16"),
+]
+
+
+@pytest.mark.parametrize("name,layer,dtype", NHWC_CASES, ids=[c[0] for c in NHWC_CASES])
+def test_channels_last_inputs_give_the_bits_of_channels_first(name, layer, dtype):
+    """DP_NHWC: x [n, h, w, cin], dy [n, oh, ow, cout].  Per-example gradients, norms, the recomputing clipped sum and
+    unit sums: the oracle's values, and the very bits of the channels-first call on the same numbers."""
+    n = 4
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
+    x, dy = _inputs(layer, n, 8800, dtype)
+    last = (lambda a: np.ascontiguousarray(np.moveaxis(a, 1, -1))) if layer.kind != "dense" else (lambda a: a)
+    ref_w, ref_b, ref_n2 = _oracle_grads(layer, x, dy)
+    results = []
+    for layout, xs, dys in ((dp.DP_NCHW, x, dy), (dp.DP_NHWC, last(x), last(dy))):
+        d = dp.make_desc(layer, n, dtype, layout=layout)
+        xd, dyd = dev(xs, dtype), dev(dys, dtype)
+        ws = torch.empty(max(16, dp.dp_workspace_bytes(d), dp.dp_workspace_bytes(d, dp.DP_WS_RECOMPUTE),
+                             dp.dp_unit_workspace_bytes(d, 2)), dtype=torch.uint8, device="cuda:0")
+        gw = torch.full((n, layer.pw), 7.0, device="cuda:0")
+        gb = torch.full((n, max(layer.pb, 1)), 7.0, device="cuda:0")
+        sq = torch.full((n,), -1.0, device="cuda:0")
+        dp.dp_per_example_grad(d, xd, dyd, gw, gb if layer.pb else None, sq, ws)
+        sq_only = torch.full((n,), -1.0, device="cuda:0")
+        dp.dp_per_example_grad(d, xd, dyd, None, None, sq_only, ws)
+        acc_w = torch.zeros(layer.pw, device="cuda:0")
+        acc_b = torch.zeros(max(layer.pb, 1), device="cuda:0")
+        n2 = dev((np.array([0.5, 1.0, 1.5, 2.0]) ** 2 * float(ref_n2.mean())).astype(np.float32))
+        dp.dp_clip_accumulate_recompute(d, xd, dyd, n2, math.sqrt(float(ref_n2.mean())), acc_w, acc_b if layer.pb else None, ws)
+        uw = torch.zeros((n // 2, layer.pw), device="cuda:0")
+        ub = torch.zeros((n // 2, max(layer.pb, 1)), device="cuda:0")
+        usq = torch.zeros(n // 2, device="cuda:0")
+        dp.dp_unit_grad(d, 2, xd, dyd, uw, ub if layer.pb else None, usq, ws)
+        torch.cuda.synchronize()
+        results.append((gw, gb, sq, sq_only, acc_w, acc_b, uw, ub, usq))
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
+    gw, gb, sq = results[1][:3]
+    assert np.allclose(host(sq), ref_n2, rtol=tol, atol=0)
+    for i in range(n):
+        assert_close(host(gw[i]), ref_w[i], tol, f"{name} dW[{i}]")
+        if layer.pb:
+            assert_close(host(gb[i, :layer.pb]), ref_b[i], tol, f"{name} db[{i}]")
+
+
 BATCH_LAYERS = [
     conv(64, 256, 1, 1, 28), conv(256, 64, 1, 1, 28), conv(64, 64, 1, 1, 28),          # 1x1, aligned rows
     conv(160, 136, 1, 1, 28), conv(130, 200, 1, 1, 14),                               # 128x128 tiles when the launch is shared

@@ -79,9 +79,16 @@ def test_per_example_grad_argument_errors(lib):
         d = dp.make_desc(conv(8, 8, 3, 1, 8, bias=True), 4)
         setattr(d, field, val)
         _raises(B.DP_ERR_INVALID_ARG, call, d)
+    # channels-last inputs are read through a transposed copy in the workspace: both tensors more of it
     d = dp.make_desc(conv(8, 8, 3, 1, 8), 4)
+    plain = dp.dp_workspace_bytes(d)
     d.layout = dp.DP_NHWC
-    _raises(B.DP_ERR_UNSUPPORTED, call, d)
+    assert dp.dp_workspace_bytes(d) == plain + 2 * 4 * 8 * 8 * 8 * 4
+    _raises(B.DP_ERR_WORKSPACE, call, d, wb=plain)
+    d = dp.make_desc(dense(8, 4), 2)
+    plain = dp.dp_workspace_bytes(d)
+    d.layout = dp.DP_NHWC                                                 # a dense layer has no channel axis to move
+    assert dp.dp_workspace_bytes(d) == plain
     d = dp.make_desc(conv(8, 8, 3, 1, 8), 4)
     d.kh = 20                                                             # kernel larger than padded input
     _raises(B.DP_ERR_INVALID_ARG, call, d)
