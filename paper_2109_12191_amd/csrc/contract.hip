@@ -121,7 +121,8 @@ __device__ __forceinline__ void wait_loaded(float (&v)[16])
 
 // Per-example mode returns this thread's share of the tile's squared norm (the caller reduces it: every
 // (example, tile) owns four partial-norm slots, one per wave).
-template <int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS, int NACC>
+// EXACT: the host only sends layers whose tiles are all whole (no ragged path, MT / NT below are not used).
+template <int WAVES_N, int TM, int TN, bool WEIGHTED, bool BIAS, bool EXACT = false, int NACC>
 __device__ __forceinline__ float tile_epilogue(const f32x16 (&acc)[NACC], const ConvArgs &a, int i, int m0, int n0, int wm,
                                                int wn, int lane, bool bias_here)
 {
@@ -130,7 +131,7 @@ __device__ __forceinline__ float tile_epilogue(const f32x16 (&acc)[NACC], const 
     const int cout = __builtin_amdgcn_readfirstlane(a.cout), J = __builtin_amdgcn_readfirstlane(a.J);
     m0 = __builtin_amdgcn_readfirstlane(m0);
     n0 = __builtin_amdgcn_readfirstlane(n0);
-    const bool inside_tile = m0 + MT <= cout && n0 + NT <= J;            // uniform
+    const bool inside_tile = EXACT || (m0 + MT <= cout && n0 + NT <= J);            // uniform
     // per lane: row and column of register 0 of block (0, 0) of this wave
     const int m_lane = m0 + wm * TM * 32 + (lane >> 5) * 4, j_lane = n0 + wn * TN * 32 + (lane & 31);
     const unsigned lane_off = ((unsigned)(m_lane - m0) * (unsigned)J + (unsigned)(j_lane - n0)) * 4u;   // bytes from the tile's corner
@@ -791,18 +792,25 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int TM, int TN, bool WEIGHTED, int STAGES>
-__global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ? 2 : 1)) conv_flat_kernel(const Grouped<ConvArgs> grp)
+// WM x 2 waves (WM = 2: 256 threads; WM = 4: 512 threads, a 256 x 128 tile whose eight waves share the X rows: a quarter
+// fewer operand bytes into LDS per multiply-add, and with three stages in 144 KB two chunks are in flight instead of the
+// one each that two resident 128 x 128 workgroups have -- the per-example form of these layers waits on memory, and what a
+// compute unit keeps in flight is what its LDS holds).  WM = 4: whole tiles only, K never sliced, per-example form.
+template <int WM, int TM, int TN, bool WEIGHTED, int STAGES>
+__global__ void __launch_bounds__(WM * 128, (STAGES * (WM * TM + 2 * TN) * 4 <= 64 ? 2 : 1)) conv_flat_kernel(const Grouped<ConvArgs> grp)
 {
     typedef uint16_t E;
     constexpr int KC = 64, EPP = 8;
-    constexpr int MT = 2 * TM * 32, NT = 2 * TN * 32;
+    constexpr int NWAVES = WM * 2;
+    constexpr int MT = WM * TM * 32, NT = 2 * TN * 32;
     constexpr int ROWS = MT + NT;                        // LDS rows of 128 bytes per stage: A rows, then B rows
     constexpr int STAGE_BYTES = ROWS * 128;
-    constexpr int NLD = ROWS / 32;                       // LDS-direct loads per thread and chunk
-    constexpr int NLA = MT / 32;                         // of which the first NLA fetch rows of A (dY)
+    constexpr int NLD = ROWS / (8 * NWAVES);             // LDS-direct loads per thread and chunk (eight rows per wave instruction)
+    constexpr int NLA = MT / (8 * NWAVES);               // of which the first NLA fetch rows of A (dY)
     constexpr int NACC = TM * TN;
     static_assert(STAGES >= 2 && STAGES <= 5, "pipeline depth");
+    static_assert(ROWS % (8 * NWAVES) == 0 && MT % (8 * NWAVES) == 0, "whole wave instructions");
+    static_assert(WM == 2 || !WEIGHTED, "the wide workgroup is the per-example form");
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     unsigned bid;
@@ -876,7 +884,7 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
     const int rb = lane >> 3, slot = lane & 7;
 #pragma unroll
     for (int q = 0; q < NLD; ++q) {
-        const int row = (4 * q + wave) * 8 + rb;
+        const int row = (NWAVES * q + wave) * 8 + rb;
         const int pk = (slot ^ ((row >> 1) & 7)) * EPP;
         int r;                                            // row of the operand; rows beyond the matrix fetch its last row
         bool last_row;
@@ -907,14 +915,14 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
     auto fetch = [&]() {
         if (!(has_tail && f_c == chunks_per_ex - 1)) {
 #pragma unroll
-            for (int q = 0; q < NLD; ++q) lds_direct_16(q < NLA ? ga : gb, byte_off[q], f_dst + q * 4096);
+            for (int q = 0; q < NLD; ++q) lds_direct_16(q < NLA ? ga : gb, byte_off[q], f_dst + q * (NWAVES * 1024));
         } else {
             // offsets are unsigned, so those of the last chunk count from the start of the chunk before it.  The partial
             // last piece of the tensor's very last row would read past the tensor: it fetches the stand-in as well.
             const unsigned guard = (tail && f_i == n_examples - 1) ? guard_mask : 0u;
 #pragma unroll
             for (int q = 0; q < NLD; ++q)
-                lds_direct_16((q < NLA ? ga : gb) - 2ull * KC, ((guard >> q) & 1u) ? stand_off[q] : tail_off[q], f_dst + q * 4096);
+                lds_direct_16((q < NLA ? ga : gb) - 2ull * KC, ((guard >> q) & 1u) ? stand_off[q] : tail_off[q], f_dst + q * (NWAVES * 1024));
         }
         ga += 2ull * KC;
         gb += 2ull * KC;
@@ -929,7 +937,7 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
             if ((guard_mask >> q) & 1u) {
-                uint32_t *d4 = reinterpret_cast<uint32_t *>(lds + stage * STAGE_BYTES + (4 * q + wave) * 1024 + lane * 16);
+                uint32_t *d4 = reinterpret_cast<uint32_t *>(lds + stage * STAGE_BYTES + (NWAVES * q + wave) * 1024 + lane * 16);
                 const char *ex = reinterpret_cast<const char *>(q < NLA ? dyg + (size_t)(n_examples - 1) * dy_ex
                                                                         : xg + (size_t)(n_examples - 1) * x_ex);
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(ex + byte_off[q] + (size_t)(chunks_per_ex - 1) * KC * 2);
@@ -1024,9 +1032,9 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
 
     // per-example mode: norm share of every wave into its own slot (no barrier), optional store
     auto finish = [&](int i) {
-        const float ss = tile_epilogue<2, TM, TN, false, false>(acc, a, i, m0, n0, wm, wn, lane, false);
+        const float ss = tile_epilogue<2, TM, TN, false, false, (WM != 2)>(acc, a, i, m0, n0, wm, wn, lane, false);
         const float ws = wave_sum(ss);
-        if (lane == 0) a.partials[((size_t)i * tiles + tile) * 4 + wave] = ws;
+        if (lane == 0) a.partials[((size_t)i * tiles + tile) * NWAVES + wave] = ws;
     };
 
     // ---- pipeline: chunks c+1 .. c+STAGES-2 are in flight while chunk c is in the MFMAs
@@ -1082,6 +1090,7 @@ __global__ void __launch_bounds__(THREADS, (STAGES * (TM == 1 ? 16 : 32) <= 64 ?
     } else if (ksplit == 1) {
         return;
     }
+    if constexpr (WM != 2) return;                        // never sliced (the host plans it so)
     // slices of one tile meet in the workspace (conv_fixup_kernel adds them in slice order)
     const int group = WEIGHTED ? tile : (unit * tiles + tile);
     size_t part = (size_t)group * ksplit + split;
@@ -1180,10 +1189,10 @@ __global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const Grouped<ConvA
 
 // ------------------------------------------------------------------------------------ host
 
-enum TileShape { T64 = 0, T128 = 1 };
-static const int kTileM[2] = {64, 128};
-static const int kTileN[2] = {64, 128};
-static const char *kTileName[2] = {"64x64", "128x128"};
+enum TileShape { T64 = 0, T128 = 1, T256x128 = 2 };
+static const int kTileM[3] = {64, 128, 256};
+static const int kTileN[3] = {64, 128, 128};
+static const char *kTileName[3] = {"64x64", "128x128", "256x128"};
 
 struct FullPlan {
     int shape, tiles_m, tiles_n;
@@ -1201,6 +1210,13 @@ struct FullPlan {
 // example ranges of the weighted form are as long as they can be.  Workspace sizes cover both cases.
 static thread_local int tl_forced_crowd = -1;
 static int plan_crowd() { return tl_forced_crowd >= 0 ? tl_forced_crowd : crowd_hint(); }
+
+// geometry of the LDS-direct kernel: bf16, one aligned row of S >= 64 (even) elements per channel, no bias
+static bool flat_direct(const Geo &g)
+{
+    const bool flat = (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0);
+    return g.bf16 && flat && !g.has_bias && (g.oh * g.ow) % 2 == 0 && g.oh * g.ow >= 64;
+}
 
 static FullPlan full_plan(const Geo &g, int mode)
 {
@@ -1221,6 +1237,12 @@ static FullPlan full_plan(const Geo &g, int mode)
         const long long t128 = (long long)((g.cout + 127) / 128) * ((J + 127) / 128);
         if ((long long)g.n * t128 < 512) p.shape = T64;
     }
+    // 256 x 128 tiles, eight waves, three stages, one workgroup per compute unit: the per-example form of aligned 1x1
+    // layers with short K (at most 7 chunks: never sliced below) whose tiles are all whole, when the layer still has
+    // a few hundred (example, tile) units
+    if (p.shape == T128 && mode != MODE_WEIGHTED && flat_direct(g) && g.cout % 256 == 0 && J % 128 == 0 && p.chunks_per_ex <= 7 &&
+        (long long)g.n * (g.cout / 256) * (J / 128) >= 128)
+        p.shape = T256x128;
     p.tiles_m = (g.cout + kTileM[p.shape] - 1) / kTileM[p.shape];
     p.tiles_n = (J + kTileN[p.shape] - 1) / kTileN[p.shape];
     const int tiles = p.tiles_m * p.tiles_n;
@@ -1247,7 +1269,9 @@ static FullPlan full_plan(const Geo &g, int mode)
     } else {
         const long long units = (long long)g.n * tiles;
         if (crowd) {
-            const int tgt = crowd * (p.shape == T64 ? 4 : 1);     // chunks of this tile shape per workgroup
+            // chunks of this tile shape per workgroup (a 256 x 128 chunk is two units of work; at least 8 of them, so
+            // that K is not sliced)
+            const int tgt = p.shape == T256x128 ? (crowd / 2 > 8 ? crowd / 2 : 8) : crowd * (p.shape == T64 ? 4 : 1);
             if (p.chunks_per_ex > tgt + tgt / 2) {
                 const long long want = (p.chunks_per_ex + tgt - 1) / tgt;
                 p.chunks_per_split = (int)((p.chunks_per_ex + want - 1) / want);
@@ -1341,7 +1365,7 @@ static size_t align16(size_t b) { return (b + 15) & ~(size_t)15; }
 static size_t norm_partials_per_example(const FullPlan &f)
 {
     const size_t tiles = (size_t)f.tiles_m * f.tiles_n;
-    return f.ksplit > 1 ? tiles * f.nacc * FIX_PARTS : tiles * 4;     // unsliced: a slot per wave
+    return f.ksplit > 1 ? tiles * f.nacc * FIX_PARTS : tiles * (f.shape == T256x128 ? 8 : 4);     // unsliced: a slot per wave
 }
 static size_t norm_partials(const Geo &g, const FullPlan &f) { return (size_t)g.n * norm_partials_per_example(f); }
 
@@ -1412,12 +1436,12 @@ const char *conv_variant_name(const Geo &g, int mode, bool shared)
     if (gram_norm_applicable(g, mode)) return "conv_gram_norm<bf16>";
     if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);
     struct Names {
-        char v[2][2][2][2][3][72];
+        char v[2][3][2][2][3][72];
         Names()
         {
             static const char *const ld[3] = {"", ",gather", ",gather2"};
             for (int b = 0; b < 2; ++b)
-                for (int s = 0; s < 2; ++s)
+                for (int s = 0; s < 3; ++s)
                     for (int w = 0; w < 2; ++w)
                         for (int bi = 0; bi < 2; ++bi)
                             for (int l = 0; l < 3; ++l)
@@ -1596,14 +1620,17 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
         // aligned one-row-per-channel geometry: operands go global -> LDS directly.  Two workgroups per compute unit
         // (64 KB of LDS each): 64x64 tiles four stages deep, 128x128 tiles two stages deep (measured: a second
         // resident workgroup hides more than two more stages do).
-        if (f.shape == T64) {
-            fn = weighted ? reinterpret_cast<const void *>(&conv_flat_kernel<1, 1, true, 4>) : reinterpret_cast<const void *>(&conv_flat_kernel<1, 1, false, 4>);
+        if (f.shape == T256x128) {                         // per-example form only (full_plan)
+            fn = reinterpret_cast<const void *>(&conv_flat_kernel<4, 2, 2, false, 3>);
+            lds_bytes = 3 * 384 * 128;
+        } else if (f.shape == T64) {
+            fn = weighted ? reinterpret_cast<const void *>(&conv_flat_kernel<2, 1, 1, true, 4>) : reinterpret_cast<const void *>(&conv_flat_kernel<2, 1, 1, false, 4>);
             lds_bytes = 4 * 128 * 128;
         } else {
-            fn = weighted ? reinterpret_cast<const void *>(&conv_flat_kernel<2, 2, true, 2>) : reinterpret_cast<const void *>(&conv_flat_kernel<2, 2, false, 2>);
+            fn = weighted ? reinterpret_cast<const void *>(&conv_flat_kernel<2, 2, 2, true, 2>) : reinterpret_cast<const void *>(&conv_flat_kernel<2, 2, 2, false, 2>);
             lds_bytes = 2 * 256 * 128;
         }
-        static std::atomic<bool> attr_done[2][2];        // zero-initialised; setting the attribute twice is harmless
+        static std::atomic<bool> attr_done[3][2];        // zero-initialised; setting the attribute twice is harmless
         if (!attr_done[f.shape][weighted ? 1 : 0].load()) {
             if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
                 return fail(DP_ERR_DEVICE, "conv_flat: cannot reserve %u bytes of LDS", lds_bytes);
@@ -1611,7 +1638,7 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
         }
     } else if (g.bf16) fn = (f.shape == T64) ? kernel_of<true, 2, 2, 1, 1>(loader, weighted, bias) : kernel_of<true, 2, 2, 2, 2>(loader, weighted, bias);
     else fn = (f.shape == T64) ? kernel_of<false, 2, 2, 1, 1>(loader, weighted, bias) : kernel_of<false, 2, 2, 2, 2>(loader, weighted, bias);
-    dp_status st = submit_main<ConvArgs>(fn, a, blocks, THREADS, lds_bytes, s, "conv_contract");
+    dp_status st = submit_main<ConvArgs>(fn, a, blocks, f.shape == T256x128 ? 512 : THREADS, lds_bytes, s, "conv_contract");
     if (st != DP_OK) return st;
     // what follows the main kernel: at once, or after the grouped launches of a batch call
     if (unit) {

@@ -30,7 +30,10 @@ def test_resnet50_layers_go_to_the_expected_kernels(wl):
     assert per_example["s2b1.c2"].startswith("conv_contract<bf16,")
     assert weighted["s4b1.c2"].startswith("conv_contract<bf16,")
     # 1x1 convs: general kernel; the classifier: the dense kernels
-    assert per_example["s3b2.c3"] == "conv_contract<bf16,128x128,per_example>"
+    assert per_example["s3b2.c3"] == "conv_contract<bf16,256x128,per_example>"     # 256 -> 1024 on 14x14: whole wide tiles, short K
+    d = dp.make_desc([l for l in wl.layers if l.name == "s2b2.c3"][0], wl.n, wl.dtype)
+    assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD | dp.DP_VARIANT_SHARED) == \
+        "conv_contract<bf16,128x128,per_example>"                                          # 28x28: K too long for the wide tile
     # norm-only calls of the 1x1 convs on 7x7 maps take the Gram route
     for name in ("s4b1.c3", "s4b2.c1", "s4b2.c3", "s4b3.c1", "s4b3.c3"):
         assert per_example[name] == "conv_gram_norm<bf16>", name
