@@ -120,9 +120,12 @@ def main():
     ap.add_argument("--cpu-examples", type=int, default=32,
                     help="examples of micro-batch 0 the oracle is timed on (32 = about 10 s on 16 cores)")
     ap.add_argument("--table", action="store_true", help="per-variant timing table on stderr")
-    ap.add_argument("--streams", type=int, default=8, help="side streams for independent layers")
+    ap.add_argument("--streams", type=int, default=None,
+                    help="side streams for independent layers (default 8; 4 for micro-steps of one or two examples)")
     ap.add_argument("--clip-unit", type=int, default=1,
                     help="examples per clipping unit (1: every example is clipped; 2, 4: the micro-batch clipping of the GPU baseline)")
+    ap.add_argument("--fork", default=None, choices=("micro_step", "step"),
+                    help="whether the side streams wait for the main stream every micro-step or once per step (default: by micro-batch size)")
     ap.add_argument("--lanes", default="balanced", choices=("round_robin", "balanced"),
                     help="how the batch calls of a phase are dealt to the side streams")
     ap.add_argument("--batching", default="variant", choices=("variant", "all"),
@@ -146,8 +149,10 @@ def main():
     dp.load_library()
     device = torch.device("cuda:0")
     wl = get_workload(args.workload, n=args.n, accum=args.accum, hw=args.hw)
+    if args.streams is None:
+        args.streams = 4 if wl.n <= 2 else 8
     ps = dp.PrivatiseStep(wl, device="cuda:0", mode=args.mode, streams=args.streams, noise=args.noise,
-                          batching=args.batching, lanes=args.lanes, clip_unit=args.clip_unit)
+                          batching=args.batching, lanes=args.lanes, clip_unit=args.clip_unit, fork=args.fork)
     inputs = make_device_inputs(wl, wl.accum, device)
     if args.fused_update:
         ps.enable_update(lr=0.1, momentum=0.9, keep_gradient=False)

@@ -25,6 +25,7 @@
 #include "group.h"
 #include "pieces.h"
 
+#include <atomic>
 #include <cstdio>
 
 namespace dp {
@@ -47,6 +48,7 @@ struct C3Args {
     int chunks;                       // ceil(H / R)
     int ksplit, chunks_per_split;     // per-example mode: K slices
     int ex_per_split;                 // weighted mode: examples per workgroup (ksplit = example ranges)
+    int variant;                      // which body conv3x3_any_kernel runs for this layer (C3_ANY_* below)
     int unit_major;                   // weighted mode: every example range keeps its own result (clipping units): the
                                       // slices always go to the workspace, ordered (range, tile)
 };
@@ -191,11 +193,10 @@ __device__ __forceinline__ void c3_add_to_accumulator(const f32x16 (&acc)[9], co
 // is staged; added to the accumulator, or to the workspace when the examples are split into ranges).
 enum { C3_FULL = 0, C3_SLICED = 1, C3_WEIGHTED = 2 };
 
+// What one workgroup does; `bid` is its number within its layer.
 template <int W, int MODE, int STRIDE>
-__global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3Args> grp)
+__device__ __forceinline__ void conv3x3_body(const C3Args &a, const unsigned bid)
 {
-    unsigned bid;                                     // workgroup number within this workgroup's layer
-    const C3Args &a = grp.a[group_pick(grp, bid)];
     constexpr bool WEIGHTED = MODE == C3_WEIGHTED;
     using C = C3Cfg<W, STRIDE>;
     constexpr int XB = 6;                             // X pieces per thread in flight at once
@@ -445,6 +446,55 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3
     }
 }
 
+template <int W, int MODE, int STRIDE>
+__global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3Args> grp)
+{
+    unsigned bid;
+    const C3Args &a = grp.a[group_pick(grp, bid)];
+    conv3x3_body<W, MODE, STRIDE>(a, bid);
+}
+
+// The per-example variants a ResNet of 224 x 224 images needs, in ONE kernel that dispatches on the layer's variant:
+// for micro-steps of one or two examples, where every launch is a few dozen workgroups and costs more than its work.
+// Registers and LDS are those of the largest variant.
+enum { C3_ANY_56_SLICED = 0, C3_ANY_28_SLICED, C3_ANY_28_FULL, C3_ANY_14_FULL, C3_ANY_14_SLICED, C3_ANY_7_FULL,
+       C3_ANY_14S2_SLICED, C3_ANY_14S2_FULL, C3_ANY_7S2_FULL, C3_ANY_COUNT };
+
+__global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_any_kernel(const Grouped<C3Args> grp)
+{
+    unsigned bid;
+    const C3Args &a = grp.a[group_pick(grp, bid)];
+    switch (__builtin_amdgcn_readfirstlane(a.variant)) {
+    case C3_ANY_56_SLICED: conv3x3_body<56, C3_SLICED, 1>(a, bid); break;
+    case C3_ANY_28_SLICED: conv3x3_body<28, C3_SLICED, 1>(a, bid); break;
+    case C3_ANY_28_FULL: conv3x3_body<28, C3_FULL, 1>(a, bid); break;
+    case C3_ANY_14_FULL: conv3x3_body<14, C3_FULL, 1>(a, bid); break;
+    case C3_ANY_14_SLICED: conv3x3_body<14, C3_SLICED, 1>(a, bid); break;
+    case C3_ANY_7_FULL: conv3x3_body<7, C3_FULL, 1>(a, bid); break;
+    case C3_ANY_14S2_SLICED: conv3x3_body<14, C3_SLICED, 2>(a, bid); break;
+    case C3_ANY_14S2_FULL: conv3x3_body<14, C3_FULL, 2>(a, bid); break;
+    default: conv3x3_body<7, C3_FULL, 2>(a, bid); break;
+    }
+}
+
+constexpr int c3_max(int a, int b) { return a > b ? a : b; }
+constexpr int C3_ANY_LDS = c3_max(c3_max(c3_max(C3Cfg<56, 1>::LDS, C3Cfg<28, 1>::LDS), c3_max(C3Cfg<14, 1>::LDS, C3Cfg<7, 1>::LDS)),
+                                  c3_max(C3Cfg<14, 2>::LDS, C3Cfg<7, 2>::LDS));
+
+template <int W, int MODE, int STRIDE> constexpr int c3_any_variant()
+{
+    if (STRIDE == 1) {
+        if (W == 56 && MODE == C3_SLICED) return C3_ANY_56_SLICED;
+        if (W == 28) return MODE == C3_SLICED ? C3_ANY_28_SLICED : (MODE == C3_FULL ? C3_ANY_28_FULL : -1);
+        if (W == 14) return MODE == C3_SLICED ? C3_ANY_14_SLICED : (MODE == C3_FULL ? C3_ANY_14_FULL : -1);
+        if (W == 7 && MODE == C3_FULL) return C3_ANY_7_FULL;
+        return -1;
+    }
+    if (W == 14) return MODE == C3_SLICED ? C3_ANY_14S2_SLICED : (MODE == C3_FULL ? C3_ANY_14S2_FULL : -1);
+    if (W == 7 && MODE == C3_FULL) return C3_ANY_7S2_FULL;
+    return -1;
+}
+
 // Parity split of the rows of X for the stride-2 kernel: out[row][0 .. OWP+8) = O'[c] = X[row][2c - 1],
 // out[row][OWP+8 .. 2 OWP+8) = E[c] = X[row][2c]; zero where the column is outside the row.  `rows` =
 // n * cin * hin rows of `win` (even) elements; one thread per 16-byte output piece, which needs
@@ -628,6 +678,20 @@ template <int W, int MODE, int STRIDE>
 dp_status c3_launch_mode(const C3Args &a, unsigned blocks, hipStream_t s)
 {
     using C = C3Cfg<W, STRIDE>;
+    constexpr int any = c3_any_variant<W, MODE, STRIDE>();
+    if (any >= 0 && fuse_hint()) {
+        // tiny micro-steps: every row width in one launch
+        const void *fn = reinterpret_cast<const void *>(&conv3x3_any_kernel);
+        static std::atomic<bool> any_attr_done;
+        if (!any_attr_done.load()) {
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C3_ANY_LDS) != hipSuccess)
+                return fail(DP_ERR_DEVICE, "conv3x3: cannot reserve %d bytes of LDS", C3_ANY_LDS);
+            any_attr_done.store(true);
+        }
+        C3Args b = a;
+        b.variant = any;
+        return submit_main<C3Args>(fn, b, blocks, C3_THREADS, C3_ANY_LDS, s, "conv3x3");
+    }
     const void *fn = reinterpret_cast<const void *>(&conv3x3_kernel<W, MODE, STRIDE>);
     static bool attr_done = false;
     if (!attr_done) {
@@ -749,6 +813,7 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     C3Plan p = c3_plan(g, weighted ? MODE_WEIGHTED : mode);
     if (unit) { p.ex_per_split = unit; p.ksplit = g.n / unit; }
     C3Args a;
+    a.variant = -1;
     a.unit_major = unit ? 1 : 0;
     a.x = static_cast<const uint16_t *>(x);
     a.dy = static_cast<const uint16_t *>(dy);

@@ -27,7 +27,7 @@ def _pad4(v: int) -> int:
 
 class PrivatiseStep:
     def __init__(self, wl, device: str = "cuda:0", mode: str = "auto", streams: int = 1, noise: str = "once",
-                 batching: str = "variant", lanes: str = "balanced", clip_unit: int = 1):
+                 batching: str = "variant", lanes: str = "balanced", clip_unit: int = 1, fork: Optional[str] = None):
         B.load_library()
         self.wl = wl
         if batching not in ("variant", "all"):
@@ -39,6 +39,13 @@ class PrivatiseStep:
         if lanes not in ("round_robin", "balanced"):
             raise ValueError(lanes)
         self.lanes = lanes                     # how the batch calls of a phase are dealt to the side streams
+        # "micro_step": the side streams of the per-example phase start every micro-step behind everything issued so
+        # far; "step": only the first micro-step of a step does -- later ones follow their own stream's previous
+        # micro-step (and the clipped sum that last read their buffer copy), so they overlap the norm launches and the
+        # clipped sum of the micro-step before.  Worth it when the launches are short (one or two examples each).
+        if fork not in (None, "micro_step", "step"):
+            raise ValueError(fork)
+        self.fork = fork if fork is not None else ("step" if wl.n <= 2 else "micro_step")
         if noise not in ("once", "per_example"):
             raise ValueError(noise)
         # "once": N(0, sigma^2 C^2) added in finalize (first equation of the Algorithm section);
@@ -164,10 +171,15 @@ class PrivatiseStep:
             key = self.variant[li][1 if use == 2 else use] + ("|mat" if (use == 0 and self.form[li] == "materialise") else "")
             if self.batching == "all":
                 key = "all layers"
+            elif self.wl.n <= 2:
+                # micro-steps of one or two examples: the library runs all variants of a kernel family in one launch,
+                # so a family is one batch call
+                if key.startswith("conv3x3_rows<"):
+                    key = "conv3x3_rows"
             by_name.setdefault(key, []).append(li)
         groups = []
         for key, ids in by_name.items():
-            width = len(ids) if self.batching == "all" else 16
+            width = len(ids) if (self.batching == "all" or key == "conv3x3_rows") else 16
             for k in range(0, len(ids), width):
                 part = ids[k: k + width]
                 name = key.split("|")[0]
@@ -293,7 +305,8 @@ class PrivatiseStep:
         main = torch.cuda.current_stream()
         # ---- phase A
         for st in self.side:
-            st.wait_stream(main)
+            if self.fork == "micro_step" or self.micro_steps_done == 0:
+                st.wait_stream(main)
             if self._b_done[c] is not None:           # this copy's previous clipped sum has finished
                 for ev in self._b_done[c]:
                     st.wait_event(ev)
