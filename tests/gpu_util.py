@@ -45,8 +45,8 @@ _PROGRESS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file_
 
 
 def progress(msg: str):
-    """A line of progress from a long test: printed, and appended to gpurun_out/test_progress.log when that
-    folder exists (output of a passing test is captured, a file is visible while the test still runs)."""
+    """A line of progress from a long test: printed, and appended to test_progress.log in the run's output folder
+    when that folder exists (output of a passing test is captured, a file is visible while the test still runs)."""
     line = f"[{time.strftime('%H:%M:%S')}] {msg}"
     print(line, flush=True)
     if os.path.isdir(_PROGRESS):
