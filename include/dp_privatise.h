@@ -117,6 +117,8 @@ size_t dp_workspace_bytes(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_
  * differently when a launch is shared); layers with equal names then share one launch, at most 16
  * per launch.  Pure host; lets a profiler's per-kernel rows be tied to layers.  The string is static. */
 #define DP_VARIANT_SHARED 2
+#define DP_VARIANT_MATERIALISE 4   /* or-ed into DP_WS_PER_EXAMPLE_GRAD: the variant of a call that stores the gradients
+                                      (g_w given); without it the norm-only call, which may take another route */
 const char *dp_kernel_variant(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_use*/);
 
 /* H1 (+ the layer's share of H2): per-example weight gradients of one layer

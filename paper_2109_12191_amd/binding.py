@@ -11,6 +11,7 @@ DP_F32, DP_BF16 = 0, 1
 DP_NCHW, DP_NHWC = 0, 1
 DP_WS_PER_EXAMPLE_GRAD, DP_WS_RECOMPUTE = 0, 1
 DP_VARIANT_SHARED = 2
+DP_VARIANT_MATERIALISE = 4
 
 _STATUS_NAMES = {1: "DP_ERR_INVALID_ARG", 2: "DP_ERR_UNSUPPORTED", 3: "DP_ERR_WORKSPACE", 4: "DP_ERR_DEVICE"}
 _KINDS = {"dense": DP_DENSE, "conv": DP_CONV2D, "gn": DP_GN_AFFINE}

@@ -282,9 +282,9 @@ const char *dp_kernel_variant(const dp_layer_desc *desc, int use)
 {
     Geo g;
     if (make_geo(desc, g) != DP_OK) return "";
-    const bool shared = (use & DP_VARIANT_SHARED) != 0;
-    use &= ~DP_VARIANT_SHARED;
-    const int mode = use == DP_WS_RECOMPUTE ? MODE_WEIGHTED : MODE_NORM;
+    const bool shared = (use & DP_VARIANT_SHARED) != 0, stored = (use & DP_VARIANT_MATERIALISE) != 0;
+    use &= ~(DP_VARIANT_SHARED | DP_VARIANT_MATERIALISE);
+    const int mode = use == DP_WS_RECOMPUTE ? MODE_WEIGHTED : (stored ? MODE_MATERIALISE : MODE_NORM);
     if (g.kind == DP_CONV2D) return conv_variant_name(g, mode, shared);
     if (g.kind == DP_DENSE) return g.bf16 ? "dense<bf16>" : "dense<f32>";
     return g.bf16 ? "gn_affine<bf16>" : "gn_affine<f32>";

@@ -124,8 +124,10 @@ class PrivatiseStep:
         self._layer_sqnorm = [torch.zeros((L, self.rows), dtype=f32, device=dev) for _ in range(self.copies)]
         # Layers that run the same kernel variant go to the library in ONE batch call, which puts them into one
         # launch (at most 16 per launch): per phase a micro-step is a dozen launches, not a hundred.
-        self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD | B.DP_VARIANT_SHARED),
-                         B.dp_kernel_variant(d, B.DP_WS_RECOMPUTE | B.DP_VARIANT_SHARED)) for d in self.descs]
+        self.variant = [(B.dp_kernel_variant(d, B.DP_WS_PER_EXAMPLE_GRAD | B.DP_VARIANT_SHARED |
+                                             (B.DP_VARIANT_MATERIALISE if form == "materialise" else 0)),
+                         B.dp_kernel_variant(d, B.DP_WS_RECOMPUTE | B.DP_VARIANT_SHARED))
+                        for d, form in zip(self.descs, self.form)]
         import ctypes
         self._partial_counts = (ctypes.c_int32 * L)()
         self._partials = [(ctypes.c_void_p * L)(*[self._ws[c][i].data_ptr() for i in range(L)]) for c in range(self.copies)]
@@ -184,7 +186,8 @@ class PrivatiseStep:
                 part = ids[k: k + width]
                 name = key.split("|")[0]
                 if len(part) == 1:           # a single layer is planned as a launch of its own
-                    name = B.dp_kernel_variant(self.descs[part[0]], B.DP_WS_RECOMPUTE if use else B.DP_WS_PER_EXAMPLE_GRAD)
+                    name = B.dp_kernel_variant(self.descs[part[0]], B.DP_WS_RECOMPUTE if use else (
+                        B.DP_WS_PER_EXAMPLE_GRAD | (B.DP_VARIANT_MATERIALISE if self.form[part[0]] == "materialise" else 0)))
                 g = dict(layers=part, name=name, conv=all(self.layers[i].kind == "conv" for i in part))
                 g["batch"] = [B.LayerBatch([self.descs[i] for i in part], [self._ws[c][i].data_ptr() for i in part],
                                            [self._ws[c][i].numel() for i in part]) for c in range(self.copies)]
