@@ -11,6 +11,7 @@
 // `grp` splits the examples into ranges that different workgroups contract (the K slices).
 #include "group.h"
 #include "internal.h"
+#include "pieces.h"
 
 namespace dp {
 
@@ -47,11 +48,19 @@ __global__ void __launch_bounds__(256) pack_weighted_kernel(const Grouped<PackAr
             const int kh = t / a.kw, kw = t - kh * a.kw;
             const uint16_t *src = a.x + ((size_t)i * a.cin + ci) * a.h * a.w;
             if (taps == 1 && a.stride == 1 && a.pad == 0) {
-                // 1x1 stride 1: the im2col row is the channel itself
+                // 1x1 stride 1: the im2col row is the channel itself -- eight consecutive elements from whole dwords
+                // (the run may start on an odd element), element by element only where that window would leave the tensor
+                const long long e0 = ((long long)i * a.cin + ci) * a.S + k0;
+                const int hi = min(8, a.S - k0);
+                if ((e0 & ~1ll) + 10 <= (long long)a.n * a.cin * a.S) {
+                    const Raw<5> raw = piece_load_words(reinterpret_cast<const uint32_t *>(a.x) + (e0 >> 1));
+                    piece_finish<true, 1>(out, raw, (uint32_t)(e0 & 1), 0, hi);
+                } else {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const uint32_t v = (k0 + u < a.S) ? src[k0 + u] : 0u;
-                    out[u >> 1] |= v << ((u & 1) * 16);
+                    for (int u = 0; u < 8; ++u) {
+                        const uint32_t v = (k0 + u < a.S) ? src[k0 + u] : 0u;
+                        out[u >> 1] |= v << ((u & 1) * 16);
+                    }
                 }
                 *reinterpret_cast<uint4 *>(a.xp + q * 8) = make_uint4(out[0], out[1], out[2], out[3]);
                 return;
@@ -82,11 +91,19 @@ __global__ void __launch_bounds__(256) pack_weighted_kernel(const Grouped<PackAr
     if (i < a.n) {
         const float f = clip_factor(a.group_sqnorm[i], a.clip_c);
         const uint16_t *src = a.dy + ((size_t)i * a.cout + co) * a.S;
+        const long long e0 = ((long long)i * a.cout + co) * a.S + k0;
+        const int hi = min(8, a.S - k0);
+        if (hi > 0 && (e0 & ~1ll) + 10 <= (long long)a.n * a.cout * a.S) {
+            const Raw<5> raw = piece_load_words(reinterpret_cast<const uint32_t *>(a.dy) + (e0 >> 1));
+            piece_finish<true, 1>(out, raw, (uint32_t)(e0 & 1), 0, hi);
+            scale_regs<true, 4>(out, f);                 // f * dY in fp32, rounded to bf16 once (nearest even)
+        } else {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            uint32_t v = 0u;
-            if (k0 + u < a.S) v = float_to_bf16_bits(bf16_bits_to_float(src[k0 + u]) * f);
-            out[u >> 1] |= v << ((u & 1) * 16);
+            for (int u = 0; u < 8; ++u) {
+                uint32_t v = 0u;
+                if (k0 + u < a.S) v = float_to_bf16_bits(bf16_bits_to_float(src[k0 + u]) * f);
+                out[u >> 1] |= v << ((u & 1) * 16);
+            }
         }
     }
     *reinterpret_cast<uint4 *>(a.dyp + qd * 8) = make_uint4(out[0], out[1], out[2], out[3]);
