@@ -237,7 +237,7 @@ dp_status dp_profile_next_contraction(void *start, void *stop)
     dp::g_prof_stop = static_cast<hipEvent_t>(stop);
     return DP_OK;
 }
-const char *dp_version(void) { return "0.1 gfx950"; }
+const char *dp_version(void) { return "0.2 gfx950"; }
 
 dp_status dp_group_clip_bounds(float clip_c, int n_groups, float *group_clip, float *clip_total)
 {

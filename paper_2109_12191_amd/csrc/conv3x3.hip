@@ -693,11 +693,11 @@ dp_status c3_launch_mode(const C3Args &a, unsigned blocks, hipStream_t s)
         return submit_main<C3Args>(fn, b, blocks, C3_THREADS, C3_ANY_LDS, s, "conv3x3");
     }
     const void *fn = reinterpret_cast<const void *>(&conv3x3_kernel<W, MODE, STRIDE>);
-    static bool attr_done = false;
-    if (!attr_done) {
+    static std::atomic<bool> attr_done;              // zero-initialised; setting the attribute twice is harmless
+    if (!attr_done.load()) {
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS) != hipSuccess)
             return fail(DP_ERR_DEVICE, "conv3x3: cannot reserve %d bytes of LDS", C::LDS);
-        attr_done = true;
+        attr_done.store(true);
     }
     return submit_main<C3Args>(fn, a, blocks, C3_THREADS, C::LDS, s, "conv3x3");
 }
