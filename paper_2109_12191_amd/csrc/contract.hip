@@ -103,6 +103,21 @@ __device__ __forceinline__ void store_f32_uniform_base_nt(unsigned long long bas
 {
     asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(byte_off), "v"(v), "s"(base) : "memory");
 }
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a constant expression
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+template <int AT>
+__device__ __forceinline__ void store_f32_uniform_base_nt_at(unsigned long long base, unsigned byte_off, float v)
+{
+    static_assert(AT >= 0 && AT < 4096, "immediate offset of a global store");
+    asm volatile("global_store_dword %0, %1, %2 offset:%3 nt" ::"v"(byte_off), "v"(v), "s"(base), "n"(AT) : "memory");
+}
 __device__ __forceinline__ float load_f32_uniform_base(unsigned long long base, unsigned byte_off)
 {
     float v;
@@ -786,10 +801,36 @@ __device__ __forceinline__ void lds_direct_16(unsigned long long base, unsigned 
 {
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base) : "memory");
 }
+// the same with only the lanes of `lanes` (wave-uniform, never empty) taking part: the others fetch nothing and leave
+// their 16 bytes of LDS as they are.  The instruction is issued once either way, so counted waits stay exact.
+__device__ __forceinline__ void lds_direct_16_lanes(unsigned long long base, unsigned byte_off, unsigned lds_base, unsigned long long lanes)
+{
+    unsigned long long saved;
+    asm volatile("s_mov_b32 m0, %3\n\t"
+                 "s_mov_b64 %0, exec\n\t"
+                 "s_mov_b64 exec, %4\n\t"
+                 "global_load_lds_dwordx4 %1, %2\n\t"
+                 "s_mov_b64 exec, %0"
+                 : "=&s"(saved)
+                 : "v"(byte_off), "s"(base), "s"(lds_base), "s"(lanes)
+                 : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Wait until at most `after` (wave-uniform) of this wave's vector memory operations are outstanding, rounded down to
+// a count the instruction can encode (six bits) from a short menu: waiting for more than asked is always safe.
+__device__ __forceinline__ void wait_outstanding(int after)
+{
+    if (after >= 63) wait_vmcnt<63>();
+#define DP_WAIT_STEP(K) else if (after >= K) wait_vmcnt<K>();
+    DP_WAIT_STEP(56) DP_WAIT_STEP(48) DP_WAIT_STEP(40) DP_WAIT_STEP(36) DP_WAIT_STEP(32) DP_WAIT_STEP(24) DP_WAIT_STEP(20)
+    DP_WAIT_STEP(16) DP_WAIT_STEP(12) DP_WAIT_STEP(8) DP_WAIT_STEP(6) DP_WAIT_STEP(4)
+#undef DP_WAIT_STEP
+    else wait_vmcnt<0>();
 }
 
 // WM x 2 waves (WM = 2: 256 threads; WM = 4: 512 threads, a 256 x 128 tile whose eight waves share the X rows: a quarter
@@ -881,6 +922,7 @@ __global__ void __launch_bounds__(WM * 128, (STAGES * (WM * TM + 2 * TN) * 4 <= 
     unsigned stand_off[NLD];     // the stand-in (last piece of the previous chunk), relative to the same
     unsigned guard_mask = 0;     // bit q: load q is the partial last piece of its operand's last row (its own row, or as
                                  // stand-in for a row beyond the matrix): in the last example it would read past the tensor
+    unsigned long long tail_lanes[NLD];   // lanes of load q whose piece starts inside the row in the last chunk (one in eight at least)
     const int rb = lane >> 3, slot = lane & 7;
 #pragma unroll
     for (int q = 0; q < NLD; ++q) {
@@ -901,6 +943,7 @@ __global__ void __launch_bounds__(WM * 128, (STAGES * (WM * TM + 2 * TN) * 4 <= 
         // (inside the tensor; their K steps are never computed or are masked); all others their own piece
         stand_off[q] = row_byte + 2u * (KC - EPP);
         tail_off[q] = pk < last_valid ? byte_off[q] + 2u * KC : stand_off[q];
+        tail_lanes[q] = __ballot(pk < last_valid);
         if (last_row && pk < last_valid && pk + EPP > last_valid) guard_mask |= 1u << q;
     }
 
@@ -922,7 +965,8 @@ __global__ void __launch_bounds__(WM * 128, (STAGES * (WM * TM + 2 * TN) * 4 <= 
             const unsigned guard = (tail && f_i == n_examples - 1) ? guard_mask : 0u;
 #pragma unroll
             for (int q = 0; q < NLD; ++q)
-                lds_direct_16((q < NLA ? ga : gb) - 2ull * KC, ((guard >> q) & 1u) ? stand_off[q] : tail_off[q], f_dst + q * (NWAVES * 1024));
+                lds_direct_16_lanes((q < NLA ? ga : gb) - 2ull * KC, ((guard >> q) & 1u) ? stand_off[q] : tail_off[q], f_dst + q * (NWAVES * 1024),
+                                    tail_lanes[q]);
         }
         ga += 2ull * KC;
         gb += 2ull * KC;
@@ -1030,55 +1074,121 @@ __global__ void __launch_bounds__(WM * 128, (STAGES * (WM * TM + 2 * TN) * 4 <= 
         }
     };
 
-    // per-example mode: norm share of every wave into its own slot (no barrier), optional store
+    // ---- per-example mode, end of an example: norm share of every wave into its own slot (no barrier), optional store.
+    // Whole tiles (all of them when the channel counts are multiples of the tile): a value's address is a scalar base
+    // (example, 32-row block) + a per-lane offset that is fixed for the kernel (register r's row, the lane's column)
+    // + an immediate (32-column block), so a store costs no arithmetic at all.
+    const bool whole_tile = WM != 2 || (m0 + MT <= cout && n0 + NT <= J);                   // uniform
+    float *const out_w = a.out_w;
+    float *const partials = a.partials;
+    const bool store_whole = out_w != nullptr && whole_tile;
+    unsigned row_off[16];
+    {
+        const unsigned lane_off = ((unsigned)(wm * TM * 32 + (lane >> 5) * 4) * (unsigned)J + (unsigned)(wn * TN * 32 + (lane & 31))) * 4u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) row_off[r] = lane_off + (unsigned)((r >> 2) * 8 + (r & 3)) * (unsigned)J * 4u;
+    }
+    const unsigned long long block_bytes = (unsigned long long)J * 128ull;                  // 32 rows of the gradient matrix
+    const unsigned long long out_ex_bytes = uniform_bits(reinterpret_cast<const void *>(a.out_stride_w * sizeof(float)));
+    unsigned long long out_corner = uniform_bits(out_w + (size_t)i_begin * a.out_stride_w + (size_t)m0 * J + n0);
     auto finish = [&](int i) {
-        const float ss = tile_epilogue<2, TM, TN, false, false, (WM != 2)>(acc, a, i, m0, n0, wm, wn, lane, false);
-        const float ws = wave_sum(ss);
-        if (lane == 0) a.partials[((size_t)i * tiles + tile) * NWAVES + wave] = ws;
+        float ss = 0.0f;
+        if (whole_tile) {
+            float part[NACC];                             // one chain of multiply-adds per block: they run interleaved
+#pragma unroll
+            for (int t = 0; t < NACC; ++t) {
+                part[t] = acc[t][0] * acc[t][0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) part[t] += acc[t][r] * acc[t][r];
+            }
+#pragma unroll
+            for (int t = 0; t < NACC; ++t) ss += part[t];
+            if (store_whole) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+                    const unsigned long long base = out_corner + (unsigned long long)tm * block_bytes;
+                    static_for<TN>([&](auto tn_c) {
+                        constexpr int tn = decltype(tn_c)::value;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) store_f32_uniform_base_nt_at<tn * 128>(base, row_off[r], acc[tm * TN + tn][r]);
+                    });
+                }
+            }
+        } else {
+            ss = tile_epilogue<2, TM, TN, false, false, false>(acc, a, i, m0, n0, wm, wn, lane, false);
+        }
+        out_corner += out_ex_bytes;
+        const float ws = wave_sum_last_lane(ss);
+        if (lane == 63) partials[((size_t)i * tiles + tile) * NWAVES + wave] = ws;
     };
 
-    // ---- pipeline: chunks c+1 .. c+STAGES-2 are in flight while chunk c is in the MFMAs
+    // ---- pipeline: chunks c+1 .. c+STAGES-2 are in flight while chunk c is in the MFMAs.  One loop nest per example
+    // (its full chunks, then the partial one) so that the accumulators live in one set of registers.
     int fetched = 0;
 #pragma unroll
     for (int s0 = 0; s0 < STAGES - 1; ++s0)
         if (fetched < n_chunks) { fetch(); ++fetched; }
-    int ex = i_begin, chunk_in_ex = 0, stage = 0;
-    for (int c = 0; c < n_chunks; ++c) {
-        // chunk c has landed when at most the loads issued after it are outstanding
-        const int newer = fetched - c - 1;                // chunks issued after chunk c: 0 .. STAGES-2
-        if (STAGES > 4 && newer >= 3) wait_vmcnt<3 * NLD>();
-        else if (STAGES > 3 && newer == 2) wait_vmcnt<2 * NLD>();
-        else if (STAGES > 2 && newer == 1) wait_vmcnt<NLD>();
-        else wait_vmcnt<0>();
+    int stage = 0, c = 0;
+    // gradient stores this wave issued in each of the last STAGES - 1 steps ([0]: the step before this one) and since the
+    // current step began.  Only epilogues whose store count is certain are entered (whole tiles: one unconditional store
+    // per accumulator register).
+    int stores_in[STAGES - 1], stores_now = 0;
+#pragma unroll
+    for (int k = 0; k < STAGES - 1; ++k) stores_in[k] = 0;
+    const int stores_per_tile = __builtin_amdgcn_readfirstlane((!WEIGHTED && store_whole) ? NACC * 16 : 0);
+    // chunk c becomes current
+    auto begin_step = [&]() {
+#pragma unroll
+        for (int k = STAGES - 2; k > 0; --k) stores_in[k] = stores_in[k - 1];
+        stores_in[0] = stores_now;
+        stores_now = 0;
+        // chunk c has landed when at most the operations issued after its loads are outstanding (the counter covers loads
+        // and stores alike, in issue order): the loads of the chunks fetched since, and the stores of the epilogues that
+        // ran since -- chunk c was fetched STAGES - 1 steps ago, or before the first step
+        int after = (fetched - c - 1) * NLD;
+#pragma unroll
+        for (int k = 0; k < STAGES - 1; ++k) after += stores_in[k];
+        wait_outstanding(after);
         __syncthreads();                                  // everyone's loads of chunk c are in LDS; chunk c-1 has been read
         if (fetched < n_chunks) { fetch(); ++fetched; }   // into the stage chunk c-1 used
-        const bool last_chunk = has_tail && c_begin + chunk_in_ex == chunks_per_ex - 1;      // uniform
-        if (last_chunk) {
-            if (tail && ex == n_examples - 1 && (m0 + MT >= cout || n0 + NT >= J)) {           // uniform, rare
+    };
+    auto end_step = [&]() {
+        ++c;
+        if (++stage == STAGES) stage = 0;
+    };
+    const bool tail_here = has_tail && c_end == chunks_per_ex;                  // this range of chunks ends with the partial one
+    const int full_here = cpe - (tail_here ? 1 : 0);
+    const bool edge_tile = m0 + MT >= cout || n0 + NT >= J;
+    const float *const group_sqnorm = a.group_sqnorm;
+    const float clip_c = a.clip_c;
+    for (int ex = i_begin; ex < i_end; ++ex) {
+#pragma unroll
+        for (int t = 0; t < NACC; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+        for (int ch = 0; ch < full_here; ++ch) {
+            begin_step();
+            compute(stage);
+            end_step();
+        }
+        if (tail_here) {
+            begin_step();
+            if (tail && ex == n_examples - 1 && edge_tile) {                    // uniform, rare
                 fix_very_last(stage);
                 __syncthreads();
             }
             compute_tail(stage);
-        } else {
-            compute(stage);
+            end_step();
         }
-        if (++stage == STAGES) stage = 0;
-        if (++chunk_in_ex == cpe) {
-            chunk_in_ex = 0;
-            if constexpr (WEIGHTED) {
-                const float f = a.group_sqnorm ? clip_factor(a.group_sqnorm[ex], a.clip_c) : 1.0f;
+        if constexpr (WEIGHTED) {
+            const float f = group_sqnorm ? clip_factor(group_sqnorm[ex], clip_c) : 1.0f;
 #pragma unroll
-                for (int t = 0; t < NACC; ++t)
+            for (int t = 0; t < NACC; ++t)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) { tot[t][r] += f * acc[t][r]; acc[t][r] = 0.0f; }
-            } else if (ksplit == 1) {
-                finish(ex);
-#pragma unroll
-                for (int t = 0; t < NACC; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-            }
-            ++ex;
+                for (int r = 0; r < 16; ++r) tot[t][r] += f * acc[t][r];
+        } else if (ksplit == 1) {
+            finish(ex);
+            stores_now = stores_per_tile;
         }
     }
 
@@ -1666,3 +1776,4 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
 }
 
 }  // namespace dp
+

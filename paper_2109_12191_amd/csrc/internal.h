@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libdp_privatise (gfx950 only).
 #pragma once
 
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -146,6 +147,25 @@ __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// The same sum by data-parallel-primitive moves (no trip through LDS), valid in lane 63 only: an inclusive scan inside
+// each row of 16 lanes (shifts by 1, 2, 4, 8 with zeros shifted in), then lane 15 of rows 0 and 2 added into rows 1 and 3,
+// then lane 31 into rows 2 and 3.  Fixed order: the same bits every run.
+__device__ __forceinline__ float wave_sum_last_lane(float v)
+{
+    auto moved = [](float x, auto ctrl, auto rows) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value,
+                                                                     decltype(rows)::value, 0xf, true));
+    };
+    typedef std::integral_constant<int, 0xf> all_rows;
+    v += moved(v, std::integral_constant<int, 0x111>{}, all_rows{});         // row_shr:1
+    v += moved(v, std::integral_constant<int, 0x112>{}, all_rows{});         // row_shr:2
+    v += moved(v, std::integral_constant<int, 0x114>{}, all_rows{});         // row_shr:4
+    v += moved(v, std::integral_constant<int, 0x118>{}, all_rows{});         // row_shr:8
+    v += moved(v, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});   // row_bcast:15 into rows 1, 3
+    v += moved(v, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});   // row_bcast:31 into rows 2, 3
     return v;
 }
 
