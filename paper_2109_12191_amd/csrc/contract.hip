@@ -1297,12 +1297,189 @@ __global__ void __launch_bounds__(THREADS) conv_fixup_kernel(const Grouped<ConvA
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Row-panel form of the per-example contraction for the LOADER 0 geometry with SHORT rows (S a little under 16 KS
+// elements, S = 4 mod 8; the 1x1 layers on 14x14 maps: S = 196).
+//
+// Cutting such rows into 64-element chunks makes every load instruction fetch eight separate 128-byte pieces that
+// straddle cache lines (rows are S * 2 bytes apart); the cache serves that pattern at about a third of the rate of
+// contiguous kilobytes.  But 32 whole rows of one example ARE one contiguous span of 64 S bytes.  So the unit that
+// travels is a block of 32 whole rows, copied as it lies in memory into a slot of a ring in LDS (each wave an eighth
+// of it, 16 bytes per lane), and the workgroup walks a stream of blocks: per example first the eight blocks of its 256
+// dY rows -- wave w keeps block w in REGISTERS as MFMA operands (all KS steps of K: 4 KS registers) -- then eight
+// blocks of 32 X rows each; every wave multiplies its dY rows with each X block (KS MFMAs 32x32x16, the first one
+// onto zero), squares, stores its 32 x 32 piece of the gradient, and forgets it.  The ring is as deep as LDS allows
+// (eleven blocks in flight), the stream runs across example boundaries, one barrier per block.
+// Rows lie S * 2 bytes apart in LDS: a multiple of 8 but not of 16 bytes, so an operand is read as two 8-byte halves,
+// and with S / 2 = 2 mod 4 dwords per row sixteen consecutive rows start in sixteen different pairs of banks.
+// The last K step reads past the row's end (into the next row, or the slot's padding): those elements are cleared in
+// registers, in both operands.
+// Whole tiles only: cout a multiple of 256, J a multiple of 256 (the host plans it so).  Norm partials: one slot per
+// (example, 256 x 256 tile, wave).
+constexpr int PANEL_RING = 12;               // slots of the ring
+constexpr int PANEL_CB = 8;                  // X blocks (32 columns each) per tile
+
+__device__ __forceinline__ uint4 lds_read16_halves(const char *p)         // p: 8-byte aligned
+{
+    const uint2 lo = *reinterpret_cast<const uint2 *>(p), hi = *reinterpret_cast<const uint2 *>(p + 8);
+    return make_uint4(lo.x, lo.y, hi.x, hi.y);
+}
+
+template <int KS>
+__global__ void __launch_bounds__(512, 1) conv_panel_kernel(const Grouped<ConvArgs> grp)
+{
+    typedef uint16_t E;
+    constexpr int R = PANEL_RING, CB = PANEL_CB, STEPS = 8 + CB;
+    constexpr int NL = (KS * 8 + 63) / 64;               // load instructions per wave and block: S / 2 lanes of 16 bytes
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    unsigned bid;
+    const ConvArgs &a = grp.a[group_pick(grp, bid)];
+    const int tiles = a.tiles_m * a.tiles_n;
+    const int ex_groups = (a.n + a.ex_per_wg - 1) / a.ex_per_wg;
+    const int total = ex_groups * tiles;
+    const int per_xcd = (total + 7) >> 3;
+    const int wg = (int)(bid & 7u) * per_xcd + (int)(bid >> 3);
+    if (wg >= total) return;
+    const int unit = wg / tiles, tile = wg - unit * tiles;
+    const int tile_m = tile / a.tiles_n, tile_n = tile - tile_m * a.tiles_n;
+    const int m0 = __builtin_amdgcn_readfirstlane(tile_m * 256), j0 = __builtin_amdgcn_readfirstlane(tile_n * 256);
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int S = __builtin_amdgcn_readfirstlane(a.S), cout = __builtin_amdgcn_readfirstlane(a.cout), J = __builtin_amdgcn_readfirstlane(a.J);
+    const int i_begin = __builtin_amdgcn_readfirstlane(unit * a.ex_per_wg);
+    const int i_end = __builtin_amdgcn_readfirstlane(min(a.n, i_begin + a.ex_per_wg));
+    const int n_blocks = (i_end - i_begin) * STEPS;
+    const unsigned row_bytes = 2u * (unsigned)S, block_bytes = 32u * row_bytes, share = block_bytes / 8u;
+    const unsigned slot_bytes = block_bytes + 64u;       // padding: the last row's last K step reads 24 bytes past it
+    const E *const xg = static_cast<const E *>(a.x), *const dyg = static_cast<const E *>(a.dy);
+    float *const out_w = a.out_w;
+    float *const partials = a.partials;
+    const bool store = out_w != nullptr;
+
+    // ---- the stream of blocks to fetch
+    int f_i = i_begin, f_p = 0, fetched = 0;
+    unsigned f_slot = 0;
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)lds);
+    const unsigned long long lanes_last = __ballot(lane < S / 2 - 64 * (NL - 1));       // never empty (the host checks S)
+    auto fetch = [&]() {
+        const E *src = f_p < 8 ? dyg + ((size_t)f_i * cout + m0 + 32 * f_p) * S
+                               : xg + ((size_t)f_i * J + j0 + 32 * (f_p - 8)) * S;
+        const unsigned long long base = uniform_bits(src) + (unsigned long long)((unsigned)wave * share);
+        const unsigned dst = lds0 + f_slot * slot_bytes + (unsigned)wave * share;
+#pragma unroll
+        for (int q = 0; q < NL; ++q) {
+            if (q < NL - 1) lds_direct_16(base, (unsigned)lane * 16u + q * 1024u, dst + q * 1024u);
+            else lds_direct_16_lanes(base, (unsigned)lane * 16u + q * 1024u, dst + q * 1024u, lanes_last);
+        }
+        if (++f_slot == R) f_slot = 0;
+        if (++f_p == STEPS) { f_p = 0; ++f_i; }
+        ++fetched;
+    };
+
+    // ---- what a wave keeps
+    uint4 afr[KS];                                        // its 32 dY rows as MFMA operands, all of K
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) afr[ks] = make_uint4(0, 0, 0, 0);
+    uint32_t kmask[4];                                    // last K step: lane holds elements (KS-1) 16 + (lane >> 5) 8 .. +8
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const int e0 = (KS - 1) * 16 + (lane >> 5) * 8 + 2 * d;
+        kmask[d] = (e0 < S ? 0x0000FFFFu : 0u) | (e0 + 1 < S ? 0xFFFF0000u : 0u);
+    }
+    const unsigned frag_off = (unsigned)(lane & 31) * row_bytes + (unsigned)(lane >> 5) * 16u;     // K step ks: + 32 ks
+    unsigned row_off[16];                                 // byte offset of register r's value from the 32-column block's corner
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        row_off[r] = ((unsigned)(32 * wave + (lane >> 5) * 4 + (r >> 2) * 8 + (r & 3)) * (unsigned)J + (unsigned)(lane & 31)) * 4u;
+    const unsigned long long out_ex_bytes = uniform_bits(reinterpret_cast<const void *>(a.out_stride_w * sizeof(float)));
+    unsigned long long out_blk = uniform_bits(out_w + (size_t)i_begin * a.out_stride_w + (size_t)m0 * J + j0);
+
+    // ---- counted waits: `issued` counts this wave's vector memory operations; marks[b mod 16] (a few words of LDS of
+    // the wave's own) is its value right after the loads of block b went out; block b has landed when at most
+    // issued - marks[b mod 16] operations are outstanding.  c: the next block to be consumed.
+    int issued = 0, c = 0;
+    int *const marks = reinterpret_cast<int *>(lds + R * slot_bytes) + wave * 16;
+    auto issued_after = [&](int b) { return issued - __builtin_amdgcn_readfirstlane(marks[b & 15]); };
+    // blocks before c are free: fetch while the ring has room
+    auto top_up = [&]() {
+#pragma nounroll
+        while (fetched < n_blocks && fetched - c < R) {
+            const int b = fetched;
+            fetch();
+            issued += NL;
+            marks[b & 15] = issued;
+        }
+    };
+    top_up();
+
+    unsigned c_slot = 0;                                  // slot of block c
+    auto slot_after = [&](unsigned k) { const unsigned t = c_slot + k; return t >= (unsigned)R ? t - (unsigned)R : t; };
+    const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    for (int i = i_begin; i < i_end; ++i) {
+        // ---- the example's eight dY blocks in one step: wave w takes block w into registers
+        wait_outstanding(issued_after(c + 7));
+        __syncthreads();                                  // all eight are in LDS; everything before them has been read
+        top_up();
+        {
+            const char *mine = lds + slot_after((unsigned)wave) * slot_bytes + frag_off;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) afr[ks] = lds_read16_halves(mine + ks * 32);
+            afr[KS - 1].x &= kmask[0]; afr[KS - 1].y &= kmask[1]; afr[KS - 1].z &= kmask[2]; afr[KS - 1].w &= kmask[3];
+        }
+        c += 8;
+        c_slot = slot_after(8);
+
+        // ---- its X blocks two at a time: 32 x 64 values of the gradient per wave and step, four independent chains of MFMAs
+        float ss0 = 0.0f, ss1 = 0.0f;
+#pragma nounroll
+        for (int pair = 0; pair < CB / 2; ++pair) {
+            wait_outstanding(issued_after(c + 1));
+            __syncthreads();
+            top_up();
+            const char *b0 = lds + c_slot * slot_bytes + frag_off, *b1 = lds + slot_after(1) * slot_bytes + frag_off;
+            f32x16 acc[2][2];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                uint4 v0 = lds_read16_halves(b0 + ks * 32), v1 = lds_read16_halves(b1 + ks * 32);
+                if (ks == KS - 1) {
+                    v0.x &= kmask[0]; v0.y &= kmask[1]; v0.z &= kmask[2]; v0.w &= kmask[3];
+                    v1.x &= kmask[0]; v1.y &= kmask[1]; v1.z &= kmask[2]; v1.w &= kmask[3];
+                }
+                acc[0][ks & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afr[ks]), __builtin_bit_cast(bf16x8, v0),
+                                                                        ks < 2 ? zero : acc[0][ks & 1], 0, 0, 0);
+                acc[1][ks & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afr[ks]), __builtin_bit_cast(bf16x8, v1),
+                                                                        ks < 2 ? zero : acc[1][ks & 1], 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (KS > 1) { acc[0][0][r] += acc[0][1][r]; acc[1][0][r] += acc[1][1][r]; }
+                ss0 += acc[0][0][r] * acc[0][0][r];
+                ss1 += acc[1][0][r] * acc[1][0][r];
+            }
+            if (store) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) store_f32_uniform_base_nt_at<0>(out_blk, row_off[r], acc[0][0][r]);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) store_f32_uniform_base_nt_at<128>(out_blk, row_off[r], acc[1][0][r]);
+                issued += 32;
+            }
+            out_blk += 256ull;
+            c += 2;
+            c_slot = slot_after(2);
+        }
+        const float ws = wave_sum_last_lane(ss0 + ss1);
+        if (lane == 63) partials[((size_t)i * tiles + tile) * 8 + wave] = ws;
+        out_blk += out_ex_bytes - 128ull * CB;
+    }
+}
+
 // ------------------------------------------------------------------------------------ host
 
-enum TileShape { T64 = 0, T128 = 1, T256x128 = 2 };
-static const int kTileM[3] = {64, 128, 256};
-static const int kTileN[3] = {64, 128, 128};
-static const char *kTileName[3] = {"64x64", "128x128", "256x128"};
+enum TileShape { T64 = 0, T128 = 1, T256x128 = 2, T256rows = 3 };
+static const int kTileM[4] = {64, 128, 256, 256};
+static const int kTileN[4] = {64, 128, 128, 256};
+static const char *kTileName[4] = {"64x64", "128x128", "256x128", "256x256rows"};
+constexpr int PANEL_KS = 13;                 // K steps the row-panel kernel is built for: 192 < S <= 208
 
 struct FullPlan {
     int shape, tiles_m, tiles_n;
@@ -1353,6 +1530,11 @@ static FullPlan full_plan(const Geo &g, int mode)
     if (p.shape == T128 && mode != MODE_WEIGHTED && flat_direct(g) && g.cout % 256 == 0 && J % 128 == 0 && p.chunks_per_ex <= 7 &&
         (long long)g.n * (g.cout / 256) * (J / 128) >= 128)
         p.shape = T256x128;
+    // whole rows travelling in blocks of 32 (conv_panel_kernel): the same layers when their rows are short and of the
+    // length that kernel's LDS layout wants, and output tiles of 256 x 256 are all whole
+    const bool panel = mode != MODE_WEIGHTED && flat_direct(g) && S % 8 == 4 && S > 16 * (PANEL_KS - 1) && S <= 16 * PANEL_KS &&
+                       g.cout % 256 == 0 && J % 256 == 0 && (long long)g.n * (g.cout / 256) * (J / 256) >= 128;
+    if (panel) p.shape = T256rows;
     p.tiles_m = (g.cout + kTileM[p.shape] - 1) / kTileM[p.shape];
     p.tiles_n = (J + kTileN[p.shape] - 1) / kTileN[p.shape];
     const int tiles = p.tiles_m * p.tiles_n;
@@ -1378,7 +1560,13 @@ static FullPlan full_plan(const Geo &g, int mode)
         p.groups = tiles;
     } else {
         const long long units = (long long)g.n * tiles;
-        if (crowd) {
+        if (p.shape == T256rows) {
+            // a unit (example, tile) is sixteen blocks; two or more in a row hide the filling of the ring
+            long long e = crowd ? 2 : (units + 511) / 512;
+            if (e > 4) e = 4;
+            if (e > g.n) e = g.n;
+            p.ex_per_wg = (int)(e < 1 ? 1 : e);
+        } else if (crowd) {
             // chunks of this tile shape per workgroup (a 256 x 128 chunk is two units of work; at least 8 of them, so
             // that K is not sliced)
             const int tgt = p.shape == T256x128 ? (crowd / 2 > 8 ? crowd / 2 : 8) : crowd * (p.shape == T64 ? 4 : 1);
@@ -1475,7 +1663,7 @@ static size_t align16(size_t b) { return (b + 15) & ~(size_t)15; }
 static size_t norm_partials_per_example(const FullPlan &f)
 {
     const size_t tiles = (size_t)f.tiles_m * f.tiles_n;
-    return f.ksplit > 1 ? tiles * f.nacc * FIX_PARTS : tiles * (f.shape == T256x128 ? 8 : 4);     // unsliced: a slot per wave
+    return f.ksplit > 1 ? tiles * f.nacc * FIX_PARTS : tiles * ((f.shape == T256x128 || f.shape == T256rows) ? 8 : 4);     // unsliced: a slot per wave
 }
 static size_t norm_partials(const Geo &g, const FullPlan &f) { return (size_t)g.n * norm_partials_per_example(f); }
 
@@ -1546,12 +1734,12 @@ const char *conv_variant_name(const Geo &g, int mode, bool shared)
     if (gram_norm_applicable(g, mode)) return "conv_gram_norm<bf16>";
     if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);
     struct Names {
-        char v[2][3][2][2][3][72];
+        char v[2][4][2][2][3][72];
         Names()
         {
             static const char *const ld[3] = {"", ",gather", ",gather2"};
             for (int b = 0; b < 2; ++b)
-                for (int s = 0; s < 3; ++s)
+                for (int s = 0; s < 4; ++s)
                     for (int w = 0; w < 2; ++w)
                         for (int bi = 0; bi < 2; ++bi)
                             for (int l = 0; l < 3; ++l)
@@ -1730,7 +1918,10 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
         // aligned one-row-per-channel geometry: operands go global -> LDS directly.  Two workgroups per compute unit
         // (64 KB of LDS each): 64x64 tiles four stages deep, 128x128 tiles two stages deep (measured: a second
         // resident workgroup hides more than two more stages do).
-        if (f.shape == T256x128) {                         // per-example form only (full_plan)
+        if (f.shape == T256rows) {                         // per-example form only (full_plan)
+            fn = reinterpret_cast<const void *>(&conv_panel_kernel<PANEL_KS>);
+            lds_bytes = (unsigned)PANEL_RING * (64u * (unsigned)a.S + 64u) + 8u * 64u;      // ring + each wave's marks
+        } else if (f.shape == T256x128) {                  // per-example form only (full_plan)
             fn = reinterpret_cast<const void *>(&conv_flat_kernel<4, 2, 2, false, 3>);
             lds_bytes = 3 * 384 * 128;
         } else if (f.shape == T64) {
@@ -1740,15 +1931,17 @@ static dp_status launch_conv_impl(const Geo &g, int mode, const void *x, const v
             fn = weighted ? reinterpret_cast<const void *>(&conv_flat_kernel<2, 2, 2, true, 2>) : reinterpret_cast<const void *>(&conv_flat_kernel<2, 2, 2, false, 2>);
             lds_bytes = 2 * 256 * 128;
         }
-        static std::atomic<bool> attr_done[3][2];        // zero-initialised; setting the attribute twice is harmless
+        static std::atomic<bool> attr_done[4][2];        // zero-initialised; setting the attribute twice is harmless
         if (!attr_done[f.shape][weighted ? 1 : 0].load()) {
-            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            // the row-panel kernel's ring grows with S: reserve for the longest row it takes
+            const unsigned reserve = f.shape == T256rows ? (unsigned)PANEL_RING * (64u * 16u * PANEL_KS + 64u) + 8u * 64u : lds_bytes;
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)reserve) != hipSuccess)
                 return fail(DP_ERR_DEVICE, "conv_flat: cannot reserve %u bytes of LDS", lds_bytes);
             attr_done[f.shape][weighted ? 1 : 0].store(true);
         }
     } else if (g.bf16) fn = (f.shape == T64) ? kernel_of<true, 2, 2, 1, 1>(loader, weighted, bias) : kernel_of<true, 2, 2, 2, 2>(loader, weighted, bias);
     else fn = (f.shape == T64) ? kernel_of<false, 2, 2, 1, 1>(loader, weighted, bias) : kernel_of<false, 2, 2, 2, 2>(loader, weighted, bias);
-    dp_status st = submit_main<ConvArgs>(fn, a, blocks, f.shape == T256x128 ? 512 : THREADS, lds_bytes, s, "conv_contract");
+    dp_status st = submit_main<ConvArgs>(fn, a, blocks, (f.shape == T256x128 || f.shape == T256rows) ? 512 : THREADS, lds_bytes, s, "conv_contract");
     if (st != DP_OK) return st;
     // what follows the main kernel: at once, or after the grouped launches of a batch call
     if (unit) {

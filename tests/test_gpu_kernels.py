@@ -81,6 +81,8 @@ CONV_CASES = [
     ("3x3 long K sliced", conv(24, 64, 3, 1, 56), 1),
     ("many examples per workgroup", conv(8, 8, 1, 1, 4, bias=True), 1700),
     ("256 x 128 tiles eight waves short K with tail", conv(256, 256, 1, 1, 10), 64),
+    ("whole rows in blocks of 32, 14 x 14 maps", conv(256, 512, 1, 1, 14), 64),
+    ("whole rows in blocks of 32, two column ranges", conv(512, 256, 1, 1, 14), 64),
     ("3x3 s1 odd width 7", conv(72, 136, 3, 1, 7), 5),
     ("3x3 s2 odd width 15->8", conv(16, 80, 3, 2, 15), 3),
     ("stride 3", Layer("conv", 6, 10, 14, 17, 3, 3, 3, 1, False), 2),

@@ -30,7 +30,10 @@ def test_resnet50_layers_go_to_the_expected_kernels(wl):
     assert per_example["s2b1.c2"].startswith("conv_contract<bf16,")
     assert weighted["s4b1.c2"].startswith("conv_contract<bf16,")
     # 1x1 convs: general kernel; the classifier: the dense kernels
-    assert per_example["s3b2.c3"] == "conv_contract<bf16,256x128,per_example>"     # 256 -> 1024 on 14x14: whole wide tiles, short K
+    assert per_example["s3b2.c3"] == "conv_contract<bf16,256x256rows,per_example>"  # 256 -> 1024 on 14x14: whole rows in blocks of 32
+    from workloads import conv
+    d = dp.make_desc(conv(256, 256, 1, 1, 10), 64, "bf16")
+    assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD) == "conv_contract<bf16,256x128,per_example>"   # 10x10: chunked K
     d = dp.make_desc([l for l in wl.layers if l.name == "s2b2.c3"][0], wl.n, wl.dtype)
     assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD | dp.DP_VARIANT_SHARED) == \
         "conv_contract<bf16,128x128,per_example>"                                          # 28x28: K too long for the wide tile
