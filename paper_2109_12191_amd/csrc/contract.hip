@@ -1561,8 +1561,8 @@ static FullPlan full_plan(const Geo &g, int mode)
     } else {
         const long long units = (long long)g.n * tiles;
         if (p.shape == T256rows) {
-            // a unit (example, tile) is sixteen blocks; two or more in a row hide the filling of the ring
-            long long e = crowd ? 2 : (units + 511) / 512;
+            // a unit (example, tile) is sixteen blocks; several in a row hide the filling of the ring (measured: 1, 2, 4 within 4 %)
+            long long e = crowd ? 4 : (units + 511) / 512;
             if (e > 4) e = 4;
             if (e > g.n) e = g.n;
             p.ex_per_wg = (int)(e < 1 ? 1 : e);
