@@ -664,6 +664,36 @@ def test_batch_call_matches_the_single_layer_calls_and_the_oracle(n, materialise
             assert_close(host(gws[k]), gw1, 2e-5, f"layer {k} against the single-layer call")
 
 
+@pytest.mark.parametrize("materialise", [False, True])
+def test_batch_call_of_whole_row_blocks_with_a_ragged_last_group_of_examples(materialise):
+    """Two 1x1 layers on 14x14 maps in one batch call: the kernel that moves whole rows in blocks of 32, several examples
+    per workgroup (66 examples: the last group is short), gradients and norms against the oracle."""
+    dtype, n = "bf16", 66
+    layers = [conv(256, 512, 1, 1, 14), conv(512, 256, 1, 1, 14)]
+    descs = [dp.make_desc(l, n, dtype) for l in layers]
+    for d in descs:
+        assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD | dp.DP_VARIANT_SHARED) == "conv_contract<bf16,256x256rows,per_example>"
+    ins = [_inputs(l, n, 1300 + k, dtype) for k, l in enumerate(layers)]
+    xs = [dev(x, dtype) for x, _ in ins]
+    dys = [dev(dy, dtype) for _, dy in ins]
+    wss = [torch.empty(max(16, dp.dp_workspace_bytes(d)), dtype=torch.uint8, device="cuda:0") for d in descs]
+    sq = torch.full((2, n), -1.0, device="cuda:0")
+    gws = [torch.full((n, l.pw), 7.0, device="cuda:0") for l in layers]
+    batch = dp.LayerBatch(descs, [w.data_ptr() for w in wss], [w.numel() for w in wss])
+    dp.dp_per_example_grad_batch(batch, batch.ptrs([t.data_ptr() for t in xs]), batch.ptrs([t.data_ptr() for t in dys]),
+                                 batch.ptrs([t.data_ptr() for t in gws]) if materialise else None, None,
+                                 batch.ptrs([sq[k].data_ptr() for k in range(2)]))
+    torch.cuda.synchronize()
+    for k, l in enumerate(layers):
+        ref_w, _, ref_n2 = _oracle_grads(l, *ins[k])
+        assert np.allclose(host(sq[k]), ref_n2, rtol=BF16_TOL, atol=0), (k, host(sq[k]), ref_n2)
+        if materialise:
+            for i in (0, 3, 4, 63, 64, 65):
+                assert_close(host(gws[k][i]), ref_w[i], BF16_TOL, f"layer {k} dW[{i}]")
+        else:
+            assert torch.all(gws[k] == 7.0)
+
+
 @pytest.mark.parametrize("n", [1, 5])
 def test_batch_calls_with_the_reduction_left_to_one_launch(n):
     """Two batch calls that leave their partial sums in the workspaces (sqnorm NULL), then ONE
