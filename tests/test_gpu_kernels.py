@@ -83,6 +83,7 @@ CONV_CASES = [
     ("256 x 128 tiles eight waves short K with tail", conv(256, 256, 1, 1, 10), 64),
     ("whole rows in blocks of 32, 14 x 14 maps", conv(256, 512, 1, 1, 14), 64),
     ("whole rows in blocks of 32, two column ranges", conv(512, 256, 1, 1, 14), 64),
+    ("whole rows in blocks of 32, rows of 204", Layer("conv", 256, 256, 12, 17, 1, 1, 1, 0, False), 128),
     ("3x3 s1 odd width 7", conv(72, 136, 3, 1, 7), 5),
     ("3x3 s2 odd width 15->8", conv(16, 80, 3, 2, 15), 3),
     ("stride 3", Layer("conv", 6, 10, 14, 17, 3, 3, 3, 1, False), 2),
