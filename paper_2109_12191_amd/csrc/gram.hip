@@ -32,7 +32,8 @@ struct GramArgs {
     float *part;                                   // [n][sa + sb][4096]: slices of the dY Gram, then of the X Gram
     float *out;                                    // [n][GR_PARTS] partial squared norms
     int n, ca, cb, S;
-    int sa, sb;                                    // channel slices (of at most 256 channels) of dY and of X
+    int sa, sb;                                    // channel slices (of at most `slice` channels) of dY and of X
+    int slice;                                     // channels a workgroup takes: a multiple of 256
     int total_a, total_b;                          // elements in each tensor
     // 3x3 pad-1 convolutions: the rows of the second operand are im2col rows (ci, kh, kw) gathered from the
     // image X [n][cin][h][w]; cb = cin * 9 then.  taps == 1: X is the operand itself.
@@ -141,14 +142,14 @@ __global__ void __launch_bounds__(GR_THREADS) gram_partial_kernel(const Grouped<
     f32x16 gm;
 #pragma unroll
     for (int r = 0; r < 16; ++r) gm[r] = 0.0f;
-    // one slice of one operand per workgroup: a single block of channels, one memory round trip
+    // one slice of one operand per workgroup: one to four blocks of 256 channels (one memory round trip each)
     if (s < a.sa)
-        gram_part(gm, a.a, i * a.ca * a.S, a.total_a, s * GR_CB, min(a.ca, (s + 1) * GR_CB), a.S, lds, kb, kb2, lane);
+        gram_part(gm, a.a, i * a.ca * a.S, a.total_a, s * a.slice, min(a.ca, (s + 1) * a.slice), a.S, lds, kb, kb2, lane);
     else if (a.taps == 1)
-        gram_part(gm, a.b, i * a.cb * a.S, a.total_b, (s - a.sa) * GR_CB, min(a.cb, (s - a.sa + 1) * GR_CB), a.S, lds, kb, kb2,
+        gram_part(gm, a.b, i * a.cb * a.S, a.total_b, (s - a.sa) * a.slice, min(a.cb, (s - a.sa + 1) * a.slice), a.S, lds, kb, kb2,
                   lane);
     else
-        gram_part_im2col(gm, a, i, (s - a.sa) * GR_CB, min(a.cb, (s - a.sa + 1) * GR_CB), lds, kb, kb2, lane);
+        gram_part_im2col(gm, a, i, (s - a.sa) * a.slice, min(a.cb, (s - a.sa + 1) * a.slice), lds, kb, kb2, lane);
     float *mine = a.part + (size_t)bid * 4096;
 #pragma unroll
     for (int r = 0; r < 16; ++r) mine[r * GR_THREADS + threadIdx.x] = gm[r];
@@ -181,6 +182,11 @@ __global__ void __launch_bounds__(GR_THREADS) gram_combine_kernel(const Grouped<
 }
 
 int gram_rows_b(const Geo &g) { return g.cin * g.kh * g.kw; }
+// Channels per workgroup: every slice leaves a 16 KB partial Gram in the workspace, which the second kernel reads back --
+// with 256-channel slices that is more bytes than the operands themselves.  Inside a batch call (the launch is shared
+// with other layers and has thousands of workgroups) a workgroup takes four blocks; a layer alone keeps one block per
+// workgroup, for the parallelism.  Workspace sizes cover the one-block plan, the larger of the two.
+int gram_slice(const Geo &g) { return (crowd_hint() > 0 && g.n >= 8) ? 4 * GR_CB : GR_CB; }
 int gram_slots(const Geo &g) { return (g.cout + GR_CB - 1) / GR_CB + (gram_rows_b(g) + GR_CB - 1) / GR_CB; }
 
 size_t gram_align16(size_t b) { return (b + 15) & ~(size_t)15; }
@@ -212,7 +218,8 @@ dp_status launch_gram_norm(const Geo &g, const void *x, const void *dy, float *s
     a.a = static_cast<const uint16_t *>(dy);
     a.b = static_cast<const uint16_t *>(x);
     a.n = g.n; a.ca = g.cout; a.cb = gram_rows_b(g); a.S = g.oh * g.ow;
-    a.sa = (g.cout + GR_CB - 1) / GR_CB; a.sb = (a.cb + GR_CB - 1) / GR_CB;
+    a.slice = gram_slice(g);
+    a.sa = (g.cout + a.slice - 1) / a.slice; a.sb = (a.cb + a.slice - 1) / a.slice;
     a.taps = g.kh * g.kw; a.cin = g.cin; a.h = g.h; a.w = g.w; a.ow = g.ow; a.stride = g.stride;
     a.total_a = g.n * g.cout * a.S;
     a.total_b = g.n * g.cin * g.h * g.w;

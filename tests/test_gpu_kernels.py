@@ -695,6 +695,30 @@ def test_batch_call_of_whole_row_blocks_with_a_ragged_last_group_of_examples(mat
             assert torch.all(gws[k] == 7.0)
 
 
+def test_gram_route_norms_in_a_batch_call_with_several_blocks_per_workgroup():
+    """Norm-only batch call on 7x7 maps with a dozen examples: the Gram-route kernel takes four blocks of 256 channels
+    per workgroup there (one block when a layer is alone); the norms against the oracle and against the single calls."""
+    dtype, n = "bf16", 12
+    layers = [conv(2048, 512, 1, 1, 7), conv(512, 1280, 1, 1, 7), conv(512, 256, 3, 1, 7), conv(256, 256, 3, 2, 14)]
+    descs = [dp.make_desc(l, n, dtype) for l in layers]
+    for d in descs:
+        assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD) == "conv_gram_norm<bf16>"
+    ins = [_inputs(l, n, 1500 + k, dtype) for k, l in enumerate(layers)]
+    xs = [dev(x, dtype) for x, _ in ins]
+    dys = [dev(dy, dtype) for _, dy in ins]
+    wss = [torch.empty(max(16, dp.dp_workspace_bytes(d)), dtype=torch.uint8, device="cuda:0") for d in descs]
+    sq = torch.full((len(layers), n), -1.0, device="cuda:0")
+    batch = dp.LayerBatch(descs, [w.data_ptr() for w in wss], [w.numel() for w in wss])
+    dp.dp_per_example_grad_batch(batch, batch.ptrs([t.data_ptr() for t in xs]), batch.ptrs([t.data_ptr() for t in dys]), None, None,
+                                 batch.ptrs([sq[k].data_ptr() for k in range(len(layers))]))
+    torch.cuda.synchronize()
+    for k, l in enumerate(layers):
+        ref_n2 = _oracle_grads(l, *ins[k])[2]
+        assert np.allclose(host(sq[k]), ref_n2, rtol=BF16_TOL, atol=0), (k, host(sq[k]), ref_n2)
+        sq1 = _run_per_example(l, *ins[k], dtype, materialise=False)[2]
+        assert np.allclose(host(sq[k]), sq1, rtol=3e-5, atol=0), k
+
+
 @pytest.mark.parametrize("n", [1, 5])
 def test_batch_calls_with_the_reduction_left_to_one_launch(n):
     """Two batch calls that leave their partial sums in the workspaces (sqnorm NULL), then ONE
