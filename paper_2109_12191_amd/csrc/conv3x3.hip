@@ -659,7 +659,9 @@ C3Plan c3_plan(const Geo &g, int mode)
         return p;
     }
     const long long units = (long long)g.n * tiles;
-    if (p.chunks > 1 && (crowd ? p.chunks > tgt + tgt / 2 : units < 128)) {
+    // (measured in the replayed step, where other streams fill the compute units a narrow launch leaves free: the 56-wide
+    // layers run 14 chunks per workgroup unsliced rather than in three slices + a slice-sum launch)
+    if (p.chunks > 1 && (crowd ? p.chunks > 3 * tgt : units < 128)) {
         long long want = (128 + units - 1) / units;
         if (crowd) want = (p.chunks + tgt - 1) / tgt;
         if (want > p.chunks) want = p.chunks;
