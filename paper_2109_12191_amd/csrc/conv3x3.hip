@@ -647,9 +647,11 @@ C3Plan c3_plan(const Geo &g, int mode)
     if (crowd && mode != MODE_WEIGHTED && (long long)g.n * tiles * p.chunks <= 128) tgt = 1;
     if (mode == MODE_WEIGHTED) {
         // example ranges: about 256 workgroups, partial blocks in the workspace kept below ~100 MB; in a launch
-        // shared with other layers, ranges of about 96 chunks
+        // shared with other layers, ranges of at most 48 chunks
         long long want = (256 + tiles - 1) / tiles;
-        if (crowd) want = ((long long)g.n * p.chunks + 2 * tgt - 1) / (2 * tgt);
+        // (measured in the replayed step: one range -- no partial blocks, no slice-sum launch, a narrow launch that the
+        // other streams overlap -- beats four ranges by 4 % of the whole step; a walk is still capped at 48 chunks)
+        if (crowd) want = ((long long)g.n * p.chunks + 47) / 48;
         const long long cap = (long long)(96.0e6 / (4.0 * 9 * 16 * C3_THREADS * (double)tiles));
         if (want > cap) want = cap;
         if (want > g.n) want = g.n;
