@@ -651,7 +651,11 @@ C3Plan c3_plan(const Geo &g, int mode)
         long long want = (256 + tiles - 1) / tiles;
         // (measured in the replayed step: one range -- no partial blocks, no slice-sum launch, a narrow launch that the
         // other streams overlap -- beats four ranges by 4 % of the whole step; a walk is still capped at 48 chunks)
-        if (crowd) want = ((long long)g.n * p.chunks + 47) / 48;
+        // and a layer of few tiles still brings 32 workgroups
+        if (crowd) {
+            want = ((long long)g.n * p.chunks + 47) / 48;
+            if (want * tiles < 32) want = (32 + tiles - 1) / tiles;
+        }
         const long long cap = (long long)(96.0e6 / (4.0 * 9 * 16 * C3_THREADS * (double)tiles));
         if (want > cap) want = cap;
         if (want > g.n) want = g.n;

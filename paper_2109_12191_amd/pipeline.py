@@ -170,7 +170,7 @@ class PrivatiseStep:
         constant pointer arrays)."""
         by_name = {}
         for li in layer_ids:
-            key = self.variant[li][1 if use == 2 else use] + ("|mat" if (use == 0 and self.form[li] == "materialise") else "")
+            key = self.variant[li][1 if use == 2 else use]      # same name, same kernel: storing and norm-only layers share a launch
             if self.batching == "all":
                 key = "all layers"
             elif self.wl.n <= 2:
@@ -230,16 +230,19 @@ class PrivatiseStep:
             return mode
         if mode != "auto":
             raise ValueError(mode)
-        # Cost model fitted to measured kernel times on MI355X (micro-batch n, layers launched in groups):
+        # Cost model fitted to the measured throughput of whole replayed steps on MI355X (micro-batch n, layers launched
+        # in groups, kernels of several streams overlapping):
         #   materialise: the [n, P] fp32 gradients are written by the contraction's epilogue and read back by the
         #     streaming accumulate -- 8 n P bytes at ~5 TB/s;
-        #   recompute: a second (clip-weighted) contraction -- ~10 us of fixed cost (packing, slice sums), the
-        #     layer's inputs once more at ~4 TB/s and its flops at ~300 TFLOP/s sustained.
-        # Layers with more than about half a million parameters (stage 4, the classifier) recompute.
+        #   recompute: a second (clip-weighted) contraction -- the layer's inputs once more at ~4 TB/s and its flops
+        #     at ~300 TFLOP/s sustained (no fixed cost any more: the weighted kernels run one example range per tile
+        #     inside batch calls, without partial blocks or slice sums).
+        # ResNet-50 at n = 32: the 3x3 layers of stage 3, stage 4 and the classifier recompute (17 layers, 20.6 M
+        # parameters); sweeping the two rates around these values moved whole-step throughput by -5 % .. 0.
         p = layer.pw + layer.pb
         esize = 2 if self.wl.dtype == "bf16" else 4
         materialise = 8.0 * p * self.n / 5.0e12
-        recompute = 10.0e-6 + layer.in_bytes(esize) * self.n / 4.0e12 + layer.flops * self.n / 300.0e12
+        recompute = layer.in_bytes(esize) * self.n / 4.0e12 + layer.flops * self.n / 300.0e12
         return "materialise" if materialise <= recompute else "recompute"
 
     # ---- views of one layer's tensors in the flat vectors
