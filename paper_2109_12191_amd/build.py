@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdp_privatise.so")
-SOURCES = ["api.hip", "stream_kernels.hip", "small_layers.hip", "contract.hip", "conv3x3.hip", "pack.hip", "gram.hip", "noalloc.hip"]
+SOURCES = ["api.hip", "stream_kernels.hip", "small_layers.hip", "contract.hip", "conv3x3.hip", "pack.hip", "gram.hip", "stem.hip", "noalloc.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

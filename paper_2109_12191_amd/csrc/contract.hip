@@ -1690,6 +1690,7 @@ size_t conv_ws_bytes(const Geo &g, int mode)
 
 static size_t conv_ws_bytes_mode(const Geo &g, int mode)
 {
+    if (stem_applicable(g, mode)) return stem_ws_bytes(g);
     if (gram_norm_applicable(g, mode)) return gram_ws_bytes(g);
     if (conv3x3_applicable(g, mode)) return conv3x3_ws_bytes(g, mode);
     PackPlan pp;
@@ -1708,6 +1709,7 @@ static size_t conv_ws_bytes_mode(const Geo &g, int mode)
 
 size_t conv_norm_partial_count(const Geo &g, int mode)
 {
+    if (stem_applicable(g, mode)) return stem_norm_partial_count();
     if (gram_norm_applicable(g, mode)) return gram_norm_partial_count();
     if (conv3x3_applicable(g, mode)) return conv3x3_norm_partial_count(g);
     Geo g2;
@@ -1731,6 +1733,7 @@ const char *conv_variant_name(const Geo &g, int mode, bool shared)
     struct Restore { int v; ~Restore() { tl_forced_crowd = v; } } restore{saved};
     c3_set_forced_crowd(shared ? 32 : 0);
     struct Restore3 { ~Restore3() { c3_set_forced_crowd(-1); } } restore3;
+    if (stem_applicable(g, mode)) return "conv_stem7x7<bf16,per_example>";
     if (gram_norm_applicable(g, mode)) return "conv_gram_norm<bf16>";
     if (conv3x3_applicable(g, mode)) return conv3x3_variant_name(g, mode);
     struct Names {
@@ -1843,6 +1846,7 @@ dp_status launch_conv(const Geo &g, int mode, const void *x, const void *dy, flo
                       size_t out_stride, float *sqnorm, const float *group_sqnorm, float clip_c, void *ws,
                       hipStream_t s)
 {
+    if (stem_applicable(g, mode)) return launch_stem(g, x, dy, out_w, out_stride, sqnorm, ws, s);
     if (gram_norm_applicable(g, mode)) return launch_gram_norm(g, x, dy, sqnorm, ws, s);
     if (conv3x3_applicable(g, mode))
         return launch_conv3x3(g, mode, x, dy, out_w, out_stride, sqnorm, group_sqnorm, clip_c, ws, s);

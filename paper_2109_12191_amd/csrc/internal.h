@@ -86,6 +86,12 @@ dp_status launch_to_channels_first(const void *in, void *out, int n, int positio
 dp_status launch_subsample(const Geo &g, const void *x, void *out, hipStream_t s);
 
 // Norm-only calls of 1x1 convolutions on small feature maps through two Gram matrices (gram.hip).
+// the network's first convolution (7x7, stride 2, pad 3, few input channels): stem.hip
+bool stem_applicable(const Geo &g, int mode);
+size_t stem_ws_bytes(const Geo &g);
+size_t stem_norm_partial_count(void);
+dp_status launch_stem(const Geo &g, const void *x, const void *dy, float *out_w, size_t out_stride, float *sqnorm, void *ws,
+                      hipStream_t s);
 bool gram_norm_applicable(const Geo &g, int mode);
 size_t gram_ws_bytes(const Geo &g);
 size_t gram_norm_partial_count(void);

@@ -141,6 +141,33 @@ def test_conv3x3_raw_row_kernel(name, layer, n, sample):
         assert math.isclose(sq[i], oracle.sqnorm(w), rel_tol=BF16_TOL), (i, sq[i], oracle.sqnorm(w))
 
 
+# The network's first convolution (7x7, stride 2, pad 3, 64 output channels, a few input channels, bf16) has a kernel of
+# its own: output rows split over workgroups two at a time (odd last range), one to three input channels, wide and narrow maps.
+STEM_CASES = [
+    ("64x64 three channels", conv(3, 64, 7, 2, 64), 3),
+    ("224x224 three channels", conv(3, 64, 7, 2, 224), 2),
+    ("38x96 last range of one row", Layer("conv", 3, 64, 38, 96, 7, 7, 2, 3, False), 2),
+    ("one channel 32x32", conv(1, 64, 7, 2, 32), 5),
+    ("two channels 8x32 one range", Layer("conv", 2, 64, 8, 32, 7, 7, 2, 3, False), 4),
+]
+
+
+@pytest.mark.parametrize("name,layer,n", STEM_CASES, ids=[c[0] for c in STEM_CASES])
+def test_conv_stem_kernel(name, layer, n):
+    d = dp.make_desc(layer, n, "bf16")
+    assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD) == "conv_stem7x7<bf16,per_example>"
+    x, dy = _inputs(layer, n, 223, "bf16")
+    gw, _, sq = _run_per_example(layer, x, dy, "bf16")
+    _, _, sq2 = _run_per_example(layer, x, dy, "bf16", materialise=False)
+    assert np.array_equal(sq, sq2)
+    gws, _, sq3 = _run_per_example(layer, x, dy, "bf16", g_stride=layer.pw + 12)
+    assert np.array_equal(gws, gw) and np.array_equal(sq3, sq)
+    for i in range(n):
+        w, _ = oracle.example_grad(layer, x[i], dy[i])
+        assert_close(gw[i], w.reshape(-1), BF16_TOL, f"{name} dW[{i}]")
+        assert math.isclose(sq[i], oracle.sqnorm(w), rel_tol=BF16_TOL), (i, sq[i], oracle.sqnorm(w))
+
+
 def test_conv_strided_gradient_matrix_layout():
     layer = Layer("conv", 5, 9, 8, 8, 3, 3, 1, 1, True)
     x, dy = _inputs(layer, 3, 103, "f32")
