@@ -127,7 +127,7 @@ def main():
                     help="examples per clipping unit (1: every example is clipped; 2, 4: the micro-batch clipping of the GPU baseline)")
     ap.add_argument("--fork", default=None, choices=("micro_step", "step"),
                     help="whether the side streams wait for the main stream every micro-step or once per step (default: by micro-batch size)")
-    ap.add_argument("--lanes", default="balanced", choices=("round_robin", "balanced"),
+    ap.add_argument("--lanes", default="balanced", choices=("round_robin", "balanced", "flops"),
                     help="how the batch calls of a phase are dealt to the side streams")
     ap.add_argument("--batching", default="variant", choices=("variant", "all"),
                     help="layers per batch call: those of one kernel variant, or all layers of a phase")

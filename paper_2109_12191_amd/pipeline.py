@@ -36,7 +36,7 @@ class PrivatiseStep:
         # launches are long and overlap); "all": one batch call per phase with every layer in it, so that also the
         # pre-passes and slice sums of all layers share launches (one-example micro-steps: launches are what costs)
         self.batching = batching
-        if lanes not in ("round_robin", "balanced"):
+        if lanes not in ("round_robin", "balanced", "flops"):
             raise ValueError(lanes)
         self.lanes = lanes                     # how the batch calls of a phase are dealt to the side streams
         # "micro_step": the side streams of the per-example phase start every micro-step behind everything issued so
@@ -133,6 +133,14 @@ class PrivatiseStep:
         self._partials = [(ctypes.c_void_p * L)(*[self._ws[c][i].data_ptr() for i in range(L)]) for c in range(self.copies)]
         self._layer_sqnorm_ptrs = [(ctypes.c_void_p * L)(*[self._layer_sqnorm[c][i].data_ptr() for i in range(L)])
                                    for c in range(self.copies)]
+        esize = 2 if wl.dtype == "bf16" else 4
+        # algorithmic work of one call per layer: (flop, HBM bytes of the per-example call, HBM bytes of the
+        # recomputing clipped-sum call).  Bytes = the operands read once, plus the per-example gradients
+        # written when the layer materialises them, or the accumulator read and written by form (b).
+        self.work = [(l.flops * wl.n,
+                      l.in_bytes(esize) * wl.n + (4 * wl.n * (pw + pb) if form == "materialise" else 0),
+                      l.in_bytes(esize) * wl.n + 8 * (pw + pb))
+                     for l, pw, pb, form in zip(self.layers, self.pw, self.pb, self.form)]
         self._groups_a = self._make_groups(range(L), 0)
         self._groups_b = self._make_groups([i for i in range(L) if self.form[i] == "recompute"], 1)
         self._groups_u = self._make_groups(range(L), 2) if self.clip_unit > 1 else []
@@ -156,14 +164,6 @@ class PrivatiseStep:
         # optional timing probe (bench.py): an object with arm(variant, flops, bytes) that asks the
         # library to bracket the next contraction kernel with a pair of events
         self.probe = None
-        esize = 2 if wl.dtype == "bf16" else 4
-        # algorithmic work of one call per layer: (flop, HBM bytes of the per-example call, HBM bytes of the
-        # recomputing clipped-sum call).  Bytes = the operands read once, plus the per-example gradients
-        # written when the layer materialises them, or the accumulator read and written by form (b).
-        self.work = [(l.flops * wl.n,
-                      l.in_bytes(esize) * wl.n + (4 * wl.n * (pw + pb) if form == "materialise" else 0),
-                      l.in_bytes(esize) * wl.n + 8 * (pw + pb))
-                     for l, pw, pb, form in zip(self.layers, self.pw, self.pb, self.form)]
 
     def _make_groups(self, layer_ids, use: int):
         """Groups of at most 16 layers with the same kernel variant for phase `use` (0: per-example gradients,
@@ -210,16 +210,32 @@ class PrivatiseStep:
                     g["acc_b"] = g["batch"][0].ptrs([self.acc[self.off_b[i]:].data_ptr() if self.pb[i] else None
                                                      for i in part])
                 g["flops"] = sum(self.layers[i].flops for i in part) * self.n
+                g["bytes"] = sum(self.work[i][2 if use == 1 else 1] for i in part)
+                g["seconds"] = self._estimate(g)
                 groups.append(g)
-        groups.sort(key=lambda g: -g["flops"])
-        # side stream of each group: longest first onto the least loaded stream (a launch costs a few microseconds
-        # however small it is)
+        groups.sort(key=lambda g: -g["seconds"])
+        # side stream of each group: longest first onto the least loaded stream
         load = [0.0] * max(1, self.n_streams)
         for gi, g in enumerate(groups):
-            k = load.index(min(load)) if self.lanes == "balanced" else gi % max(1, self.n_streams)
+            k = load.index(min(load)) if self.lanes != "round_robin" else gi % max(1, self.n_streams)
             g["lane"] = k
-            load[k] += g["flops"] / 150.0e12 + 8.0e-6
+            load[k] += g["seconds"]
         return groups
+
+    def _estimate(self, g) -> float:
+        """Duration of a group's launch for the lane balance: its work at the rates its kernel family sustains on
+        MI355X when it has the chip to itself (measured call by call on ResNet-50 at n = 32), plus a few
+        microseconds per launch however small it is."""
+        if self.lanes == "flops":
+            return g["flops"] / 150.0e12 + 8.0e-6
+        name = g["name"]
+        if name.startswith("conv3x3_rows"):
+            rate = 130.0e12 if ("w56" in name or "w7,weighted" in name) else 300.0e12
+        elif "gather" in name:
+            rate = 130.0e12
+        else:
+            rate = 400.0e12
+        return max(g["flops"] / rate, g["bytes"] / 4.5e12) + 8.0e-6
 
     def _arm(self, group, use: int):
         if self.probe is not None and group["conv"]:
