@@ -226,7 +226,9 @@ class PrivatiseStep:
         """Duration of a group's launch for the lane balance: its work at the rates its kernel family sustains on
         MI355X when it has the chip to itself (measured call by call on ResNet-50 at n = 32), plus a few
         microseconds per launch however small it is."""
-        if self.lanes == "flops":
+        if self.lanes == "flops" or self.wl.n <= 2:
+            # micro-steps of one or two examples: launches are bound by the walk along K of a few workgroups, not by
+            # the chip's rates; flops alone order them better (measured: 5.6 k against 5.1 k examples/s)
             return g["flops"] / 150.0e12 + 8.0e-6
         name = g["name"]
         if name.startswith("conv3x3_rows"):
