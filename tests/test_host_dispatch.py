@@ -45,6 +45,29 @@ def test_resnet50_layers_go_to_the_expected_kernels(wl):
     assert sum(v.startswith("conv3x3_rows") for v in per_example.values()) == 12
 
 
+def test_the_first_convolution_has_a_kernel_of_its_own_where_its_shape_allows(wl):
+    from workloads import Layer, conv
+    stem = "conv_stem7x7<bf16,per_example>"
+    d = dp.make_desc(wl.layers[0], wl.n, wl.dtype)
+    assert wl.layers[0].name == "conv1" and dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD) == stem
+    assert dp.dp_kernel_variant(d, dp.DP_WS_PER_EXAMPLE_GRAD | dp.DP_VARIANT_SHARED | dp.DP_VARIANT_MATERIALISE) == stem
+    assert dp.dp_norm_partial_count(d, True) == dp.dp_norm_partial_count(d, False) == 40
+    # partial norms + one 64 x 160 block per range of output rows (eight ranges of 14 rows at 32 examples)
+    assert dp.dp_workspace_bytes(d, dp.DP_WS_PER_EXAMPLE_GRAD) == 32 * 40 * 4 + 32 * 8 * 64 * 160 * 4
+    # the clip-weighted form, fp32 inputs, a bias, odd images, other channel counts and widths that are no multiple
+    # of 16 stay in the general kernel
+    assert not dp.dp_kernel_variant(d, dp.DP_WS_RECOMPUTE).startswith("conv_stem")
+    others = [(conv(3, 64, 7, 2, 224), "f32"), (conv(3, 64, 7, 2, 224, bias=True), "bf16"), (conv(3, 64, 7, 2, 225), "bf16"),
+              (conv(3, 32, 7, 2, 224), "bf16"), (conv(4, 64, 7, 2, 224), "bf16"), (conv(3, 64, 7, 2, 24), "bf16"),
+              (Layer("conv", 3, 64, 224, 224, 7, 7, 2, 2, False), "bf16"), (conv(3, 64, 7, 1, 32), "bf16")]
+    for layer, dtype in others:
+        name = dp.dp_kernel_variant(dp.make_desc(layer, 4, dtype), dp.DP_WS_PER_EXAMPLE_GRAD)
+        assert name.startswith("conv_contract<"), (layer, dtype, name)
+    # one to three input channels and any even image whose output width is a multiple of 16 do
+    for layer in (conv(1, 64, 7, 2, 32), conv(2, 64, 7, 2, 64), Layer("conv", 3, 64, 38, 96, 7, 7, 2, 3, False)):
+        assert dp.dp_kernel_variant(dp.make_desc(layer, 4, "bf16"), dp.DP_WS_PER_EXAMPLE_GRAD) == stem
+
+
 def test_workspace_queries_are_consistent(wl):
     total = 0
     for l in wl.layers:
