@@ -49,7 +49,7 @@ static thread_local LaunchQueue *g_queue = nullptr;
 LaunchQueue *open_queue() { return g_queue; }
 void set_open_queue(LaunchQueue *q) { g_queue = q; }
 int crowd_hint() { return g_queue ? g_queue->crowd : 0; }
-bool fuse_hint() { return g_queue && g_queue->fuse; }
+int fuse_hint() { return g_queue ? g_queue->fuse : 0; }
 
 dp_status flush_queue(LaunchQueue &q)
 {
@@ -469,7 +469,7 @@ dp_status dp_per_example_grad_batch(const dp_layer_desc *descs, const void *cons
     LaunchQueue q;
     q.stream = s;
     q.crowd = batch_target(geo);
-    q.fuse = geo[0].n <= 2;
+    q.fuse = geo[0].n <= 2 ? 2 : 1;
     set_open_queue(&q);
     std::vector<const float *> parts((size_t)n_layers);
     std::vector<int32_t> counts((size_t)n_layers);
@@ -529,7 +529,7 @@ dp_status dp_unit_grad_batch(const dp_layer_desc *descs, int clip_unit, const vo
     LaunchQueue q;
     q.stream = s;
     q.crowd = batch_target(geo);
-    q.fuse = geo[0].n <= 2;
+    q.fuse = geo[0].n <= 2 ? 2 : 1;
     set_open_queue(&q);
     std::vector<const float *> parts((size_t)n_layers);
     std::vector<int32_t> counts((size_t)n_layers);
@@ -602,7 +602,7 @@ dp_status dp_clip_accumulate_recompute_batch(const dp_layer_desc *descs, const v
     LaunchQueue q;
     q.stream = s;
     q.crowd = batch_target(geo);
-    q.fuse = geo[0].n <= 2;
+    q.fuse = geo[0].n <= 2 ? 2 : 1;
     set_open_queue(&q);
     dp_status st = DP_OK;
     for (int l = 0; l < n_layers && st == DP_OK; ++l) {

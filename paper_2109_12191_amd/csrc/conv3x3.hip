@@ -454,27 +454,47 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3
     conv3x3_body<W, MODE, STRIDE>(a, bid);
 }
 
-// The per-example variants a ResNet of 224 x 224 images needs, in ONE kernel that dispatches on the layer's variant:
-// for micro-steps of one or two examples, where every launch is a few dozen workgroups and costs more than its work.
-// Registers and LDS are those of the largest variant.
+// The variants a ResNet of 224 x 224 images needs, in ONE kernel that dispatches on the layer's variant, so that all
+// 3x3 layers of a batch call share a launch: at most four kernels run at a time on the chip, and the few workgroups of
+// a narrow layer cost none of those four when they sit inside a wide launch.  Two sets (a body that is not needed is
+// not compiled in: registers and LDS are those of the largest body of a set, and the finely sliced 56-wide body
+// spills a few registers): set 0 for micro-steps of one or two examples (sliced variants: every launch is a few dozen
+// workgroups and costs more than its work), set 1 for larger micro-steps (unsliced and clip-weighted variants).
 enum { C3_ANY_56_SLICED = 0, C3_ANY_28_SLICED, C3_ANY_28_FULL, C3_ANY_14_FULL, C3_ANY_14_SLICED, C3_ANY_7_FULL,
-       C3_ANY_14S2_SLICED, C3_ANY_14S2_FULL, C3_ANY_7S2_FULL, C3_ANY_COUNT };
+       C3_ANY_14S2_SLICED, C3_ANY_14S2_FULL, C3_ANY_7S2_FULL, C3_ANY_56_FULL, C3_ANY_28_WEIGHTED, C3_ANY_14_WEIGHTED,
+       C3_ANY_7_WEIGHTED, C3_ANY_COUNT };
 
+constexpr bool c3_any_in_set(int variant, int set)
+{
+    if (variant < 0) return false;
+    if (set == 0) return variant <= C3_ANY_7S2_FULL;
+    return variant != C3_ANY_56_SLICED;
+}
+
+template <int SET>
 __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_any_kernel(const Grouped<C3Args> grp)
 {
     unsigned bid;
     const C3Args &a = grp.a[group_pick(grp, bid)];
-    switch (__builtin_amdgcn_readfirstlane(a.variant)) {
-    case C3_ANY_56_SLICED: conv3x3_body<56, C3_SLICED, 1>(a, bid); break;
-    case C3_ANY_28_SLICED: conv3x3_body<28, C3_SLICED, 1>(a, bid); break;
-    case C3_ANY_28_FULL: conv3x3_body<28, C3_FULL, 1>(a, bid); break;
-    case C3_ANY_14_FULL: conv3x3_body<14, C3_FULL, 1>(a, bid); break;
-    case C3_ANY_14_SLICED: conv3x3_body<14, C3_SLICED, 1>(a, bid); break;
-    case C3_ANY_7_FULL: conv3x3_body<7, C3_FULL, 1>(a, bid); break;
-    case C3_ANY_14S2_SLICED: conv3x3_body<14, C3_SLICED, 2>(a, bid); break;
-    case C3_ANY_14S2_FULL: conv3x3_body<14, C3_FULL, 2>(a, bid); break;
-    default: conv3x3_body<7, C3_FULL, 2>(a, bid); break;
+    const int v = __builtin_amdgcn_readfirstlane(a.variant);
+#define C3_ANY_CASE(ID, W, MODE, STRIDE)                                                  \
+    if constexpr (c3_any_in_set(ID, SET)) {                                               \
+        if (v == ID) { conv3x3_body<W, MODE, STRIDE>(a, bid); return; }                   \
     }
+    C3_ANY_CASE(C3_ANY_56_SLICED, 56, C3_SLICED, 1)
+    C3_ANY_CASE(C3_ANY_28_SLICED, 28, C3_SLICED, 1)
+    C3_ANY_CASE(C3_ANY_28_FULL, 28, C3_FULL, 1)
+    C3_ANY_CASE(C3_ANY_14_FULL, 14, C3_FULL, 1)
+    C3_ANY_CASE(C3_ANY_14_SLICED, 14, C3_SLICED, 1)
+    C3_ANY_CASE(C3_ANY_7_FULL, 7, C3_FULL, 1)
+    C3_ANY_CASE(C3_ANY_14S2_SLICED, 14, C3_SLICED, 2)
+    C3_ANY_CASE(C3_ANY_14S2_FULL, 14, C3_FULL, 2)
+    C3_ANY_CASE(C3_ANY_7S2_FULL, 7, C3_FULL, 2)
+    C3_ANY_CASE(C3_ANY_56_FULL, 56, C3_FULL, 1)
+    C3_ANY_CASE(C3_ANY_28_WEIGHTED, 28, C3_WEIGHTED, 1)
+    C3_ANY_CASE(C3_ANY_14_WEIGHTED, 14, C3_WEIGHTED, 1)
+    C3_ANY_CASE(C3_ANY_7_WEIGHTED, 7, C3_WEIGHTED, 1)
+#undef C3_ANY_CASE
 }
 
 constexpr int c3_max(int a, int b) { return a > b ? a : b; }
@@ -484,10 +504,10 @@ constexpr int C3_ANY_LDS = c3_max(c3_max(c3_max(C3Cfg<56, 1>::LDS, C3Cfg<28, 1>:
 template <int W, int MODE, int STRIDE> constexpr int c3_any_variant()
 {
     if (STRIDE == 1) {
-        if (W == 56 && MODE == C3_SLICED) return C3_ANY_56_SLICED;
-        if (W == 28) return MODE == C3_SLICED ? C3_ANY_28_SLICED : (MODE == C3_FULL ? C3_ANY_28_FULL : -1);
-        if (W == 14) return MODE == C3_SLICED ? C3_ANY_14_SLICED : (MODE == C3_FULL ? C3_ANY_14_FULL : -1);
-        if (W == 7 && MODE == C3_FULL) return C3_ANY_7_FULL;
+        if (W == 56) return MODE == C3_SLICED ? C3_ANY_56_SLICED : (MODE == C3_FULL ? C3_ANY_56_FULL : -1);
+        if (W == 28) return MODE == C3_SLICED ? C3_ANY_28_SLICED : (MODE == C3_FULL ? C3_ANY_28_FULL : C3_ANY_28_WEIGHTED);
+        if (W == 14) return MODE == C3_SLICED ? C3_ANY_14_SLICED : (MODE == C3_FULL ? C3_ANY_14_FULL : C3_ANY_14_WEIGHTED);
+        if (W == 7) return MODE == C3_FULL ? C3_ANY_7_FULL : (MODE == C3_WEIGHTED ? C3_ANY_7_WEIGHTED : -1);
         return -1;
     }
     if (W == 14) return MODE == C3_SLICED ? C3_ANY_14S2_SLICED : (MODE == C3_FULL ? C3_ANY_14S2_FULL : -1);
@@ -687,14 +707,16 @@ dp_status c3_launch_mode(const C3Args &a, unsigned blocks, hipStream_t s)
 {
     using C = C3Cfg<W, STRIDE>;
     constexpr int any = c3_any_variant<W, MODE, STRIDE>();
-    if (any >= 0 && fuse_hint()) {
-        // tiny micro-steps: every row width in one launch
-        const void *fn = reinterpret_cast<const void *>(&conv3x3_any_kernel);
-        static std::atomic<bool> any_attr_done;
-        if (!any_attr_done.load()) {
+    const int set = fuse_hint() == 2 ? 0 : 1;
+    if (fuse_hint() && (set == 0 ? c3_any_in_set(any, 0) : c3_any_in_set(any, 1))) {
+        // inside a batch call: every row width in one launch
+        const void *fn = set == 0 ? reinterpret_cast<const void *>(&conv3x3_any_kernel<0>)
+                                  : reinterpret_cast<const void *>(&conv3x3_any_kernel<1>);
+        static std::atomic<bool> any_attr_done[2];
+        if (!any_attr_done[set].load()) {
             if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C3_ANY_LDS) != hipSuccess)
                 return fail(DP_ERR_DEVICE, "conv3x3: cannot reserve %d bytes of LDS", C3_ANY_LDS);
-            any_attr_done.store(true);
+            any_attr_done[set].store(true);
         }
         C3Args b = a;
         b.variant = any;

@@ -69,9 +69,11 @@ struct LaunchQueue {
     hipStream_t stream = nullptr;
     int crowd = 0;                      // > 0: launches are shared with other layers; the work a workgroup should
                                         // get, in units of one 128x128x64 chunk (about a million multiply-adds)
-    bool fuse = false;                  // micro-steps of one or two examples: a launch costs more than the work in it, so
-                                        // launchers hand in the kernels that dispatch on the variant INSIDE the kernel
-                                        // (one launch for all row widths of the 3x3 kernel, all tile shapes of the slice sums)
+    int fuse = 0;                       // > 0: launchers hand in the kernels that dispatch on the variant INSIDE the kernel
+                                        // (one launch for all row widths of the 3x3 kernel): only four kernels run at a
+                                        // time, and a narrow launch inside a wide one costs none of them.  2: micro-steps
+                                        // of one or two examples (a launch costs more than the work in it; finely sliced
+                                        // variants), 1: larger ones (unsliced and clip-weighted variants)
 };
 
 // The queue open on this thread (nullptr: launches are issued at once).
@@ -79,8 +81,8 @@ LaunchQueue *open_queue();
 void set_open_queue(LaunchQueue *q);
 // 0, or inside a batch call of several layers the work per workgroup to plan for (see LaunchQueue::crowd)
 int crowd_hint();
-// whether the open batch wants variant-dispatching kernels (see LaunchQueue::fuse)
-bool fuse_hint();
+// which variant-dispatching kernels the open batch wants (see LaunchQueue::fuse); 0: none
+int fuse_hint();
 // Launch the held main kernels grouped by kernel, then the deferred follow-ups.
 dp_status flush_queue(LaunchQueue &q);
 

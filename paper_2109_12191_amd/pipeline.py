@@ -170,19 +170,20 @@ class PrivatiseStep:
         1: recomputing clipped sum), largest total work first.  Each group: dict(layers, name, batch per copy,
         constant pointer arrays)."""
         by_name = {}
+        family = "conv3x3_rows<bf16,all widths,%s>" % ("weighted" if use else "per_example")
         for li in layer_ids:
             key = self.variant[li][1 if use == 2 else use]      # same name, same kernel: storing and norm-only layers share a launch
             if self.batching == "all":
                 key = "all layers"
-            elif self.wl.n <= 2:
-                # micro-steps of one or two examples: the library runs all variants of a kernel family in one launch,
-                # so a family is one batch call
-                if key.startswith("conv3x3_rows<"):
-                    key = "conv3x3_rows"
+            elif key.startswith("conv3x3_rows<"):
+                # inside a batch call the library runs all variants of the raw-row 3x3 kernel in one launch (only
+                # four kernels run at a time on the chip: the few workgroups of a narrow layer cost none of the
+                # four inside a wide launch), so the family is one batch call
+                key = family
             by_name.setdefault(key, []).append(li)
         groups = []
         for key, ids in by_name.items():
-            width = len(ids) if (self.batching == "all" or key == "conv3x3_rows") else 16
+            width = len(ids) if (self.batching == "all" or key == family) else 16
             for k in range(0, len(ids), width):
                 part = ids[k: k + width]
                 name = key.split("|")[0]
