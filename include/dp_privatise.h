@@ -115,7 +115,9 @@ size_t dp_workspace_bytes(const dp_layer_desc *desc /*[host]*/, int use /*dp_ws_
  * "conv_contract<bf16,128x128,per_example>"; "" on a bad descriptor.  With DP_VARIANT_SHARED or-ed
  * into `use`: the variant the layer runs as inside a batch call of several layers (tiling is chosen
  * differently when a launch is shared); layers with equal names then share one launch, at most 16
- * per launch.  Pure host; lets a profiler's per-kernel rows be tied to layers.  The string is static. */
+ * per launch, and so do all layers whose names begin with "conv3x3_rows<" (every row width, stride
+ * and K slicing of that kernel runs in one launch inside a batch call).  Pure host; lets a profiler's
+ * per-kernel rows be tied to layers.  The string is static.                                     */
 #define DP_VARIANT_SHARED 2
 #define DP_VARIANT_MATERIALISE 4   /* or-ed into DP_WS_PER_EXAMPLE_GRAD: the variant of a call that stores the gradients
                                       (g_w given); without it the norm-only call, which may take another route */
