@@ -64,7 +64,7 @@ constexpr int C3_STORE_LDS = 4 * 8 * C3_RP * 4;      // bytes the store epilogue
 template <int W, int STRIDE> struct C3Cfg {
     static constexpr int OWP = (W + 7) / 8 * 8;
     static constexpr int R = (STRIDE == 1) ? ((OWP == 8) ? 8 : 224 / OWP)            // output rows per chunk
-                                           : ((OWP == 16) ? 5 : 8);
+                                           : ((OWP == 16) ? 5 : (OWP == 32 ? 3 : 8));
     static constexpr int KSTEPS = R * OWP / 16;
     static constexpr int WP = (STRIDE == 1) ? OWP + 8 : 2 * OWP + 8;                  // elements per staged X row
     static constexpr int E_OFF = OWP + 8;                                           // stride 2: where E starts in a row
@@ -462,12 +462,12 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_kernel(const Grouped<C3
 // workgroups and costs more than its work), set 1 for larger micro-steps (unsliced and clip-weighted variants).
 enum { C3_ANY_56_SLICED = 0, C3_ANY_28_SLICED, C3_ANY_28_FULL, C3_ANY_14_FULL, C3_ANY_14_SLICED, C3_ANY_7_FULL,
        C3_ANY_14S2_SLICED, C3_ANY_14S2_FULL, C3_ANY_7S2_FULL, C3_ANY_56_FULL, C3_ANY_28_WEIGHTED, C3_ANY_14_WEIGHTED,
-       C3_ANY_7_WEIGHTED, C3_ANY_COUNT };
+       C3_ANY_7_WEIGHTED, C3_ANY_28S2_FULL, C3_ANY_28S2_SLICED, C3_ANY_COUNT };
 
 constexpr bool c3_any_in_set(int variant, int set)
 {
     if (variant < 0) return false;
-    if (set == 0) return variant <= C3_ANY_7S2_FULL;
+    if (set == 0) return variant <= C3_ANY_7S2_FULL || variant >= C3_ANY_28S2_FULL;
     return variant != C3_ANY_56_SLICED;
 }
 
@@ -494,12 +494,14 @@ __global__ void __launch_bounds__(C3_THREADS, 2) conv3x3_any_kernel(const Groupe
     C3_ANY_CASE(C3_ANY_28_WEIGHTED, 28, C3_WEIGHTED, 1)
     C3_ANY_CASE(C3_ANY_14_WEIGHTED, 14, C3_WEIGHTED, 1)
     C3_ANY_CASE(C3_ANY_7_WEIGHTED, 7, C3_WEIGHTED, 1)
+    C3_ANY_CASE(C3_ANY_28S2_FULL, 28, C3_FULL, 2)
+    C3_ANY_CASE(C3_ANY_28S2_SLICED, 28, C3_SLICED, 2)
 #undef C3_ANY_CASE
 }
 
 constexpr int c3_max(int a, int b) { return a > b ? a : b; }
 constexpr int C3_ANY_LDS = c3_max(c3_max(c3_max(C3Cfg<56, 1>::LDS, C3Cfg<28, 1>::LDS), c3_max(C3Cfg<14, 1>::LDS, C3Cfg<7, 1>::LDS)),
-                                  c3_max(C3Cfg<14, 2>::LDS, C3Cfg<7, 2>::LDS));
+                                  c3_max(C3Cfg<28, 2>::LDS, c3_max(C3Cfg<14, 2>::LDS, C3Cfg<7, 2>::LDS)));
 
 template <int W, int MODE, int STRIDE> constexpr int c3_any_variant()
 {
@@ -511,6 +513,7 @@ template <int W, int MODE, int STRIDE> constexpr int c3_any_variant()
         return -1;
     }
     if (W == 14) return MODE == C3_SLICED ? C3_ANY_14S2_SLICED : (MODE == C3_FULL ? C3_ANY_14S2_FULL : -1);
+    if (W == 28) return MODE == C3_SLICED ? C3_ANY_28S2_SLICED : (MODE == C3_FULL ? C3_ANY_28S2_FULL : -1);
     if (W == 7 && MODE == C3_FULL) return C3_ANY_7S2_FULL;
     return -1;
 }
@@ -632,7 +635,7 @@ struct C3Plan {
 int rows_of_width(int ow, int stride)
 {
     const int owp = (ow + 7) / 8 * 8;
-    if (stride == 2) return owp == 16 ? 5 : 8;
+    if (stride == 2) return owp == 16 ? 5 : (owp == 32 ? 3 : 8);
     return owp == 8 ? 8 : 224 / owp;
 }
 
@@ -759,9 +762,12 @@ bool conv3x3_applicable(const Geo &g, int mode)
     } else if (g.stride == 2) {
         // even images only (rows split by column parity, output exactly half the size)
         if (g.h % 2 || g.w % 2 || g.oh * 2 != g.h || g.ow * 2 != g.w) return false;
-        // measured: worthwhile for the per-example calls on 14- and 7-wide outputs; wider outputs (short chunks,
-        // K slicing) and the clip-weighted form do better in the general kernel / on packed operands
-        if (mode == MODE_WEIGHTED || (g.ow != 7 && g.ow != 14)) return false;
+        // measured: worthwhile for the per-example calls on 14- and 7-wide outputs, and on 28-wide ones (chunks of
+        // three rows) once a micro-step holds more than two examples: the layer then rides in the launch of the other
+        // 3x3 layers (+ 0.4 % for the step; - 0.9 % with one example per micro-step); the clip-weighted form does
+        // better in the general kernel / on packed operands
+        if (mode == MODE_WEIGHTED || (g.ow != 7 && g.ow != 14 && g.ow != 28)) return false;
+        if (g.ow == 28 && g.n <= 2) return false;
         if ((long long)g.n * g.cin * g.h * (2 * ((g.ow + 7) / 8 * 8) + 8) >= (1ll << 31)) return false;
     } else {
         return false;
@@ -884,6 +890,7 @@ dp_status launch_conv3x3(const Geo &g, int mode, const void *x, const void *dy, 
     }
     if (g.stride == 2) {
         if (g.ow == 7) st = c3_launch_w<7, 2>(a, weighted, blocks, s);
+        else if (g.ow == 28) st = c3_launch_w<28, 2>(a, weighted, blocks, s);
         else st = c3_launch_w<14, 2>(a, weighted, blocks, s);
     } else {
         switch (g.w) {

@@ -119,11 +119,13 @@ ROWS_CASES = [
     ("w8 one chunk", Layer("conv", 64, 64, 8, 8, 3, 3, 1, 1, False), 3, None),
     ("w7 tall image", Layer("conv", 64, 70, 19, 7, 3, 3, 1, 1, False), 2, None),
     ("w8 two chunks unsliced many examples", Layer("conv", 64, 64, 11, 8, 3, 3, 1, 1, False), 520, [0, 1, 259, 518, 519]),
-    # stride 2 (rows of X split by column parity first): output widths 14 and 7
+    # stride 2 (rows of X split by column parity first): output widths 28, 14 and 7
     ("s2 28->14 ragged channels", Layer("conv", 80, 72, 28, 28, 3, 3, 2, 1, False), 3, None),
     ("s2 14->7", Layer("conv", 128, 64, 14, 14, 3, 3, 2, 1, False), 3, None),
     ("s2 short image 12x28 -> 6x14", Layer("conv", 64, 96, 12, 28, 3, 3, 2, 1, False), 2, None),
     ("s2 14->7 unsliced many examples", Layer("conv", 64, 64, 14, 14, 3, 3, 2, 1, False), 515, [0, 1, 300, 513, 514]),
+    ("s2 56->28 last chunk of one row", Layer("conv", 64, 96, 20, 56, 3, 3, 2, 1, False), 3, None),
+    ("s2 56->28 ragged channels", Layer("conv", 80, 72, 56, 56, 3, 3, 2, 1, False), 3, None),
 ]
 
 

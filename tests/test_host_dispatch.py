@@ -23,11 +23,12 @@ def test_resnet50_layers_go_to_the_expected_kernels(wl):
         assert per_example[name] == f"conv3x3_rows<bf16,w{width},per_example>"
         assert weighted[name] == f"conv3x3_rows<bf16,w{width},weighted>"
     assert weighted["s4b2.c2"] == "conv3x3_rows<bf16,w7,weighted>"
-    # the strided 3x3 convs onto 14- and 7-wide outputs too; the one onto 28 stays in the general kernel
+    # the strided 3x3 convs too (per-example calls only)
     assert per_example["s3b1.c2"] == "conv3x3_rows<bf16,w14,s2,per_example>"
+    assert per_example["s2b1.c2"] == "conv3x3_rows<bf16,w28,s2,per_example>"
     # norm-only calls on 7x7 maps take the Gram route (3x3 convs included); their materialising calls do not
     assert per_example["s4b1.c2"] == "conv_gram_norm<bf16>" and per_example["s4b2.c2"] == "conv_gram_norm<bf16>"
-    assert per_example["s2b1.c2"].startswith("conv_contract<bf16,")
+    assert weighted["s2b1.c2"].startswith("conv_contract<bf16,")
     assert weighted["s4b1.c2"].startswith("conv_contract<bf16,")
     # 1x1 convs: general kernel; the classifier: the dense kernels
     assert per_example["s3b2.c3"] == "conv_contract<bf16,256x256rows,per_example>"  # 256 -> 1024 on 14x14: whole rows in blocks of 32
@@ -42,7 +43,7 @@ def test_resnet50_layers_go_to_the_expected_kernels(wl):
         assert per_example[name] == "conv_gram_norm<bf16>", name
     assert per_example["s1b1.c1"] == "conv_contract<bf16,64x64,per_example>"
     assert per_example["fc"] == "dense<bf16>"
-    assert sum(v.startswith("conv3x3_rows") for v in per_example.values()) == 12
+    assert sum(v.startswith("conv3x3_rows") for v in per_example.values()) == 13
 
 
 def test_the_first_convolution_has_a_kernel_of_its_own_where_its_shape_allows(wl):
