@@ -35,10 +35,10 @@ HBM_PEAK = 8.0e12
 # per lane like the contraction's loads: FETCH_SIZE reads half of their bytes, WRITE_SIZE all of them).
 PMC_FETCH_SCALE, PMC_WRITE_SCALE = 2.0, 1.0
 PMC_KIB_PER_LAUNCH = {          # variant -> (FETCH_SIZE, WRITE_SIZE)
-    "conv_contract<bf16,256x256rows,per_example>": (105128.1, 426223.8),
-    "conv_contract<bf16,128x128,per_example>": (194834.0, 98327.7),
-    "conv_contract<bf16,64x64,per_example>": (201287.9, 12813.4),
-    "conv_contract<bf16,128x128,weighted>": (221896.5, 48640.0),
+    "conv_contract<bf16,256x256rows,per_example>": (105134.5, 491793.3),
+    "conv_contract<bf16,128x128,per_example>": (194900.0, 98327.9),
+    "conv_contract<bf16,64x64,per_example>": (201359.4, 12813.6),
+    "conv_contract<bf16,128x128,weighted>": (137733.2, 37888.0),
 }
 
 

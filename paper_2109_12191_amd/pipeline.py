@@ -255,14 +255,16 @@ class PrivatiseStep:
         #   materialise: the [n, P] fp32 gradients are written by the contraction's epilogue and read back by the
         #     streaming accumulate -- 8 n P bytes at ~5 TB/s;
         #   recompute: a second (clip-weighted) contraction -- the layer's inputs once more at ~4 TB/s and its flops
-        #     at ~300 TFLOP/s sustained (no fixed cost any more: the weighted kernels run one example range per tile
-        #     inside batch calls, without partial blocks or slice sums).
-        # ResNet-50 at n = 32: the 3x3 layers of stage 3, stage 4 and the classifier recompute (17 layers, 20.6 M
-        # parameters); sweeping the two rates around these values moved whole-step throughput by -5 % .. 0.
+        #     at ~275 TFLOP/s sustained (no fixed cost: the weighted kernels run one example range per tile inside
+        #     batch calls, without partial blocks or slice sums).
+        # ResNet-50 at n = 32: the stride-1 3x3 layers of stage 3, stage 4 but its first 1x1 layer, and the classifier
+        # recompute (15 layers, 19.4 M parameters).  Whole-step throughput around this split: 37/17 (300 TFLOP/s: the
+        # strided 3x3 layer of stage 3, whose weighted form has no raw-row kernel, and the first 1x1 of stage 4 recompute
+        # too) - 2 %, 44/10 (250) - 9 %, 26/28 (360) - 3 %.
         p = layer.pw + layer.pb
         esize = 2 if self.wl.dtype == "bf16" else 4
         materialise = 8.0 * p * self.n / 5.0e12
-        recompute = layer.in_bytes(esize) * self.n / 4.0e12 + layer.flops * self.n / 300.0e12
+        recompute = layer.in_bytes(esize) * self.n / 4.0e12 + layer.flops * self.n / 275.0e12
         return "materialise" if materialise <= recompute else "recompute"
 
     # ---- views of one layer's tensors in the flat vectors
