@@ -651,6 +651,7 @@ BATCH_LAYERS = [
     conv(64, 64, 3, 1, 28), conv(64, 128, 3, 1, 28), conv(128, 64, 3, 1, 14),          # raw-row 3x3 kernels
     conv(48, 80, 1, 2, 14), conv(128, 128, 3, 2, 28), conv(3, 64, 7, 2, 64),           # strided, long K
     conv(256, 512, 1, 1, 7), conv(512, 256, 3, 1, 7),                                  # Gram-route norms
+    conv(64, 64, 3, 1, 56), conv(64, 64, 3, 2, 56),                                    # raw-row 3x3: 56-wide rows, stride 2 onto 28-wide rows
     dense(100, 36), gn_affine(32, 10, 8),
 ]
 
